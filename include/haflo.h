@@ -1,0 +1,214 @@
+/*
+ * haflo.h - C boundary of the MI355X Paillier operator library.
+ *
+ * The library implements the homomorphic operators that federated logistic
+ * regression runs every iteration under additive Paillier encryption (the
+ * operator set of the paper's Table 1 and Table 2: encoding, decoding,
+ * encryption, decryption, ciphertext addition, ciphertext-by-plaintext
+ * multiplication, summation and matrix multiplication), over arrays that stay
+ * resident in GPU memory between calls (the paper's "cached results" workflow,
+ * Section 3.3, reduced to "the caller keeps the device pointer").
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * Return value: 0 on success, a negative HAFLO_E* code otherwise. No exception
+ *   crosses the boundary and there is no global state besides loaded code.
+ * "host" pointers are ordinary process memory; "device" pointers are HIP device
+ *   memory on the current device. The caller owns every buffer it passes; the
+ *   library owns only the haflo_ctx (which holds small per-key constant tables
+ *   in device memory) and frees it in haflo_ctx_destroy.
+ * Streams: `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *   Device work is enqueued on it and the call returns without synchronising.
+ * Workspace: operators that need temporary device memory take a caller-supplied
+ *   workspace pointer and its size; haflo_workspace_bytes says how much is
+ *   needed. The library never allocates device memory inside an operator call.
+ *   Contents of the workspace are undefined afterwards; two calls that share a
+ *   workspace must be ordered on one stream.
+ *
+ * Interchange format (what a framework serialises, the paper's Section 3.2):
+ *   a big integer is an array of little-endian uint32 limbs, item-major:
+ *   element i of an array occupies words [i*L, (i+1)*L).
+ *   - plaintext residue: Lp = n_bits/32 limbs, value in [0, n).
+ *   - canonical ciphertext: Lc = n_bits/16 limbs, value in [0, n^2).
+ * Internal ciphertext format ("cipher" below): opaque, fixed size per element
+ *   (haflo_ctx_info reports it); it is the Montgomery form modulo n^2 held in
+ *   29-bit limbs. Every operator consumes and produces this format, so chains
+ *   of operators need no conversion; haflo_import_cipher / haflo_export_cipher
+ *   convert from / to the canonical interchange format.
+ * Ciphertexts that are not units modulo n^2 are the caller's error: they give
+ *   an unspecified plaintext, never a fault.
+ */
+#ifndef HAFLO_H
+#define HAFLO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HAFLO_OK 0
+#define HAFLO_EINVAL (-1)  /* null pointer, bad count / size / scale, workspace too small */
+#define HAFLO_EKEY (-2)    /* unusable key material */
+#define HAFLO_ENOPRIV (-3) /* private-key operation on a public-only context */
+#define HAFLO_EHIP (-4)    /* the HIP runtime reported an error */
+#define HAFLO_ENOMEM (-5)  /* host or device allocation for the context failed */
+
+/* Per-element status bits written by encode / decode / import. */
+#define HAFLO_ST_OK 0u
+#define HAFLO_ST_RANGE 1u /* value not representable: non-finite or out of range */
+
+typedef struct haflo_ctx haflo_ctx;
+
+/* Operator selector for haflo_workspace_bytes. */
+enum haflo_op {
+  HAFLO_OP_ENCRYPT = 1,
+  HAFLO_OP_DECRYPT = 2,
+  HAFLO_OP_SCALAR_MUL = 3,
+  HAFLO_OP_MATVEC_XT_D = 4, /* orientation 0 */
+  HAFLO_OP_MATVEC_X_W = 5   /* orientation 1 */
+};
+
+/* Text for an error code; never NULL. */
+const char* haflo_strerror(int code);
+
+/*
+ * Deterministic key generation (host only). The paper takes the Paillier key
+ * pair as given (Section 2.1); this is the seeded procedure the benchmark
+ * configurations ask for: one SplitMix64 stream seeded with `seed`; a prime
+ * candidate is n_bits/128 stream words (first word least significant) with the
+ * two top bits and the low bit set; candidates divisible by a prime below 2000
+ * are dropped; survivors take up to 40 Miller-Rabin rounds with bases
+ * (words mod (cand-3)) + 2 drawn from the same stream; the first survivor is p,
+ * the stream continues for q until q != p and gcd(pq,(p-1)(q-1)) = 1.
+ * n_bits must be 512, 1024, 2048 or 4096. p_le and q_le are host buffers of
+ * n_bits/16 bytes each (little-endian bytes).
+ */
+int haflo_keygen(uint32_t n_bits, uint64_t seed, uint8_t* p_le, uint8_t* q_le);
+
+/*
+ * Key contexts. g = n + 1 always. A private context (p, q given) can run every
+ * operator; a public one (n only) everything except haflo_decrypt.
+ * p_le / q_le: host, n_bits/16 little-endian bytes each; n_le: host, n_bits/8
+ * bytes. p and q must be distinct odd numbers of exactly n_bits/2 bits whose
+ * product has exactly n_bits bits and is coprime to (p-1)(q-1); primality is
+ * the caller's responsibility. n_bits in {512, 1024, 2048, 4096}.
+ * Context creation synchronises with the device (it uploads constant tables).
+ */
+int haflo_ctx_create_private(const uint8_t* p_le, const uint8_t* q_le, uint32_t n_bits, haflo_ctx** out);
+int haflo_ctx_create_public(const uint8_t* n_le, uint32_t n_bits, haflo_ctx** out);
+int haflo_ctx_destroy(haflo_ctx* ctx);
+
+/* Sizes for a context: key bits, canonical ciphertext limbs Lc, plaintext
+ * limbs Lp, bytes of one internal ciphertext element, bytes of one plaintext
+ * element (= 4*Lp). Any output pointer may be NULL. */
+int haflo_ctx_info(const haflo_ctx* ctx, uint32_t* n_bits, uint32_t* cipher_limbs, uint32_t* plain_limbs,
+                   size_t* cipher_bytes_internal, size_t* plain_bytes);
+
+/* Workspace needed by an operator call of the given shape. For element-wise
+ * operators `rows` is the element count and `cols` is ignored; for the matvecs
+ * they are the matrix shape. Returns 0 for operators that need none and
+ * (size_t)-1 on bad arguments. */
+size_t haflo_workspace_bytes(const haflo_ctx* ctx, int op, size_t rows, size_t cols);
+
+/*
+ * Serialisation boundary (paper Section 3.2, "Data Preprocessing" /
+ * "Postprocessing"): canonical ciphertexts <-> internal ciphertexts.
+ * d_canon: device, count*Lc uint32. d_cipher: device, count internal elements.
+ * d_status: device, one uint32 OR-ed with HAFLO_ST_RANGE when any imported
+ * value is >= n^2 (that element is imported as 0); may be NULL.
+ */
+int haflo_import_cipher(const haflo_ctx* ctx, const uint32_t* d_canon, void* d_cipher, uint32_t* d_status,
+                        size_t count, void* stream);
+int haflo_export_cipher(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_canon, size_t count, void* stream);
+
+/*
+ * "Encoding" (paper Table 2, first row; defined by the benchmark
+ * configurations as signed fixed point): q = rint(v * 2^scale_bits) with ties
+ * to even, computed in binary64; the plaintext residue is q mod n (a negative
+ * q is stored as n - |q|). d_v: device float[count]; d_plain: device
+ * count*Lp uint32; d_status: device uint32[count] or NULL, HAFLO_ST_RANGE
+ * (and residue 0) when v is not finite or q leaves int64. scale_bits <= 62.
+ */
+int haflo_encode_f32(const haflo_ctx* ctx, const float* d_v, uint32_t scale_bits, uint32_t* d_plain,
+                     uint32_t* d_status, size_t count, void* stream);
+
+/* The same quantisation for matrix entries, kept as signed 32-bit exponents
+ * for the matvecs. d_x: device float[count]; d_e: device int32[count];
+ * d_status as above (HAFLO_ST_RANGE and exponent 0 when q leaves int32). */
+int haflo_encode_exponents_f32(const float* d_x, uint32_t scale_bits, int32_t* d_e, uint32_t* d_status,
+                               size_t count, void* stream);
+
+/*
+ * "Decoding" (paper Table 2, second row): signed lift (m > floor(n/2) means
+ * m - n) to q, then value = q / 2^scale_bits in binary64 (q converted with
+ * round-to-nearest-even). d_plain: device count*Lp uint32; d_q: device
+ * int64[count] or NULL; d_v: device double[count] or NULL; d_status: device
+ * uint32[count] or NULL, HAFLO_ST_RANGE (q = 0, value = 0) when the lifted
+ * integer leaves int64. scale_bits <= 1000.
+ */
+int haflo_decode(const haflo_ctx* ctx, const uint32_t* d_plain, uint32_t scale_bits, int64_t* d_q, double* d_v,
+                 uint32_t* d_status, size_t count, void* stream);
+
+/*
+ * "Homomorphic Encryption" (paper Table 1): E(m) = g^m * r^n mod n^2.
+ * d_plain: device count*Lp uint32, residues in [0, n). d_r: device count*Lp
+ * uint32, the caller's random units in [1, n) (the library draws no random
+ * numbers). d_cipher: device, count internal elements (may not alias inputs).
+ * Workspace: haflo_workspace_bytes(ctx, HAFLO_OP_ENCRYPT, count, 0).
+ */
+int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t* d_r, void* d_cipher, size_t count,
+                  void* d_workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * "Homomorphic Decryption" (paper Table 2; the scheme of the paper's reference
+ * for Paillier): m = L(c^lambda mod n^2) * mu mod n, L(x) = (x-1)/n, evaluated
+ * through the factors p^2 and q^2 and recombined (same plaintext). Private
+ * context only. d_cipher: device, count internal elements; d_plain: device
+ * count*Lp uint32. Workspace: HAFLO_OP_DECRYPT.
+ */
+int haflo_decrypt(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain, size_t count, void* d_workspace,
+                  size_t workspace_bytes, void* stream);
+
+/* "Homomorphic Addition" (paper Table 1): out = c1 * c2 mod n^2, element-wise.
+ * All three device arrays hold count internal elements; out may alias c1 or c2. */
+int haflo_add(const haflo_ctx* ctx, const void* d_c1, const void* d_c2, void* d_out, size_t count, void* stream);
+
+/*
+ * "Homomorphic Multiplication" (paper Table 1): out = c^k mod n^2.
+ * _u64: one unsigned 64-bit scalar per element (d_k: device uint64[count]).
+ * _i64_bcast: one signed scalar for the whole array; k < 0 raises the inverse
+ * of c to |k|. d_out may alias d_c. Workspace: HAFLO_OP_SCALAR_MUL.
+ */
+int haflo_scalar_mul_u64(const haflo_ctx* ctx, const void* d_c, const uint64_t* d_k, void* d_out, size_t count,
+                         void* d_workspace, size_t workspace_bytes, void* stream);
+int haflo_scalar_mul_i64_bcast(const haflo_ctx* ctx, const void* d_c, int64_t k, void* d_out, size_t count,
+                               void* d_workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * "Homomorphic Matrix Multiplication" (paper Table 2; multiplication followed
+ * by summation, Table 1) with a plaintext matrix of signed 32-bit exponents,
+ * row-major X[rows][cols]; a negative exponent is a power of the inverse.
+ *   orientation 0, the encrypted gradient X^T [[d]] (paper Section 2.1):
+ *     d_c holds `rows` elements, d_out receives `cols` elements,
+ *     out[j] = prod_i c[i]^X[i][j] mod n^2.
+ *   orientation 1, the encrypted forward pass X [[w]]:
+ *     d_c holds `cols` elements, d_out receives `rows` elements,
+ *     out[i] = prod_j c[j]^X[i][j] mod n^2.
+ * An empty or all-zero product is an encryption-free 1. d_out may not alias
+ * d_c. Workspace: HAFLO_OP_MATVEC_XT_D / HAFLO_OP_MATVEC_X_W with the shape.
+ */
+int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, const int32_t* d_X, size_t rows,
+                        size_t cols, void* d_out, void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* "Homomorphic Summation" (paper Table 1): out[0] = prod_i c[i] mod n^2 over
+ * count internal elements (1 for count = 0). Workspace: the same as
+ * HAFLO_OP_MATVEC_XT_D with rows = count, cols = 1. */
+int haflo_cipher_sum(const haflo_ctx* ctx, const void* d_c, size_t count, void* d_out, void* d_workspace,
+                     size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HAFLO_H */

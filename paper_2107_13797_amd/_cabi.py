@@ -1,0 +1,52 @@
+"""ctypes prototypes of the C boundary declared in include/haflo.h.
+
+Argument marshalling only: this module declares argument and result types for
+every exported entry point and holds no arithmetic.
+"""
+import ctypes as C
+
+c_void_p = C.c_void_p
+c_size_t = C.c_size_t
+c_int = C.c_int
+c_u32 = C.c_uint32
+c_u64 = C.c_uint64
+c_i64 = C.c_int64
+
+# name -> (restype, argtypes)
+PROTOTYPES = {
+    "haflo_strerror": (C.c_char_p, [c_int]),
+    "haflo_keygen": (c_int, [c_u32, c_u64, c_void_p, c_void_p]),
+    "haflo_ctx_create_private": (c_int, [c_void_p, c_void_p, c_u32, C.POINTER(c_void_p)]),
+    "haflo_ctx_create_public": (c_int, [c_void_p, c_u32, C.POINTER(c_void_p)]),
+    "haflo_ctx_destroy": (c_int, [c_void_p]),
+    "haflo_ctx_info": (c_int, [c_void_p, C.POINTER(c_u32), C.POINTER(c_u32), C.POINTER(c_u32),
+                               C.POINTER(c_size_t), C.POINTER(c_size_t)]),
+    "haflo_workspace_bytes": (c_size_t, [c_void_p, c_int, c_size_t, c_size_t]),
+    "haflo_import_cipher": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "haflo_export_cipher": (c_int, [c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "haflo_encode_f32": (c_int, [c_void_p, c_void_p, c_u32, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "haflo_encode_exponents_f32": (c_int, [c_void_p, c_u32, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "haflo_decode": (c_int, [c_void_p, c_void_p, c_u32, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "haflo_encrypt": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]),
+    "haflo_decrypt": (c_int, [c_void_p, c_void_p, c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]),
+    "haflo_add": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "haflo_scalar_mul_u64": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]),
+    "haflo_scalar_mul_i64_bcast": (c_int, [c_void_p, c_void_p, c_i64, c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]),
+    "haflo_cipher_matvec": (c_int, [c_void_p, c_int, c_void_p, c_void_p, c_size_t, c_size_t, c_void_p, c_void_p,
+                                    c_size_t, c_void_p]),
+    "haflo_cipher_sum": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_size_t, c_void_p]),
+}
+
+OP_ENCRYPT, OP_DECRYPT, OP_SCALAR_MUL, OP_MATVEC_XT_D, OP_MATVEC_X_W = 1, 2, 3, 4, 5
+
+
+def bind(lib, names=None):
+    """Attach the prototypes to a loaded library; raises AttributeError when a
+    declared symbol is missing."""
+    for name, (res, args) in PROTOTYPES.items():
+        if names is not None and name not in names:
+            continue
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    return lib

@@ -1,0 +1,340 @@
+// Device-side big-integer core for gfx950: cooperative multi-limb arithmetic
+// with one big integer spread over T consecutive lanes of a 64-wide wavefront.
+//
+// Representation. A big integer of NL = T*LPT limbs is held in radix 2^29:
+// lane k of the group (k = 0 least significant) keeps limbs [k*LPT, (k+1)*LPT)
+// in registers. 29-bit limbs leave 6 spare bits in a 64-bit accumulator, so a
+// column sum of up to 62 limb products needs no carry handling: the inner loops
+// are pure v_mad_u64_u32 streams (32x32+64 multiply-add issues at full VALU
+// rate on this chip, so every carry instruction saved is a multiply gained).
+//
+// "Lazy" operands: limbs may exceed 2^29 by a few units (< 2^29 + 2^8) and the
+// value may reach a small multiple of the modulus; the radix 2^(29*NL) exceeds
+// every modulus by at least 2^10, which keeps Montgomery products below twice
+// the modulus without a final subtraction. Only values that are stored or
+// compared are brought to canonical form (limbs < 2^29, value < modulus).
+//
+// Cross-lane traffic: ds_bpermute for broadcasts inside a group, DPP row
+// shifts by one lane for neighbour exchange (groups never straddle a 16-lane
+// DPP row, so T <= 16).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace haflo {
+namespace dev {
+
+typedef uint32_t u32;
+typedef uint64_t u64;
+typedef int32_t s32;
+typedef int64_t s64;
+
+constexpr int LIMB_BITS = 29;
+constexpr u32 LIMB_MASK = (1u << LIMB_BITS) - 1u;
+constexpr int WAVE = 64;
+
+__device__ __forceinline__ u64 mad64(u32 a, u32 b, u64 c) { return (u64)a * (u64)b + c; }
+
+// Geometry of the lane group that owns one big integer.
+template <int T>
+struct Grp {
+  static_assert(T == 1 || T == 2 || T == 4 || T == 8 || T == 16, "group must fit one DPP row");
+  int k;          // this lane's chunk index inside the group
+  int base_addr;  // ds_bpermute byte address of the group's lane 0
+  __device__ __forceinline__ Grp() {
+    int lane = (int)(threadIdx.x & (WAVE - 1));
+    k = lane & (T - 1);
+    base_addr = (lane - k) << 2;
+  }
+  // value of `v` held by lane `src_k` of this group
+  __device__ __forceinline__ u32 bcast(u32 v, int src_k) const {
+    if (T == 1) return v;
+    return (u32)__builtin_amdgcn_ds_bpermute(base_addr + (src_k << 2), (int)v);
+  }
+  // v of the next-higher lane; 0 past the end of the 16-lane row. The top lane
+  // of a group that is not at a row end sees lane 0 of the next group.
+  __device__ __forceinline__ u32 from_upper_raw(u32 v) const {
+    if (T == 1) return 0u;
+    return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x101 /* row_shl:1 */, 0xf, 0xf, true);
+  }
+  __device__ __forceinline__ u32 from_upper(u32 v) const {
+    if (T == 1) return 0u;
+    u32 r = from_upper_raw(v);
+    return (k == T - 1) ? 0u : r;
+  }
+  // v of the next-lower lane; 0 for the group's lane 0
+  __device__ __forceinline__ u32 from_lower(u32 v) const {
+    if (T == 1) return 0u;
+    u32 r = (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x111 /* row_shr:1 */, 0xf, 0xf, true);
+    return (k == 0) ? 0u : r;
+  }
+};
+
+__device__ __forceinline__ bool wave_any(bool p) { return __builtin_amdgcn_ballot_w64(p) != 0ull; }
+
+// Push the upper 32 bits of every column accumulator one column up
+// (A[j+1] += 8 * hi(A[j]), radix 2^29 vs word 2^32), leaving each column below
+// 2^32 (column 0 below 2^36). The top lane's top column is bounded by the value
+// bound of the caller and is left alone.
+template <int LPT, int T>
+__device__ __forceinline__ void hi_normalise(u64 (&A)[LPT], const Grp<T>& g) {
+#pragma unroll
+  for (int j = 0; j + 1 < LPT; ++j) {
+    A[j + 1] = mad64((u32)(A[j] >> 32), 8u, A[j + 1]);
+    A[j] = (u64)(u32)A[j];
+  }
+  if (T > 1) {
+    u32 hi = (u32)(A[LPT - 1] >> 32);
+    u32 send = (g.k == T - 1) ? 0u : hi;
+    u32 recv = g.from_lower(send);
+    if (g.k != T - 1) A[LPT - 1] = (u64)(u32)A[LPT - 1];
+    A[0] = mad64(recv, 8u, A[0]);
+  }
+}
+
+// Montgomery product out = a * b / 2^(29*NL) mod n, lazy in and out.
+//   a, b: limbs < 2^29 + 2^8, values < 4n.  n: canonical limbs of the odd
+//   modulus.  n0inv = -n^-1 mod 2^29.  out: limbs < 2^29 + 2^5, value < 2n.
+// Word-serial with a sliding accumulator window: step i adds a*b_i, then q*n
+// with q chosen so the lowest column vanishes mod 2^29, then drops that column;
+// every lane hands the low 29 bits of its lowest column to the lane below and
+// keeps the rest as a carry, so no lane is special-cased.
+// NORM = number of steps between hi_normalise passes (<= 31).
+template <int LPT, int T>
+__device__ __forceinline__ void montmul(u32 (&out)[LPT], const u32 (&a)[LPT], const u32 (&b)[LPT],
+                                        const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
+  constexpr int NORM = (LPT <= 31) ? LPT : (LPT / 2);
+  static_assert(NORM <= 31 && LPT % NORM == 0, "normalisation interval");
+  u64 A[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) A[j] = 0;
+#pragma unroll 1
+  for (int o = 0; o < T; ++o) {
+    const int src = g.base_addr + (o << 2);
+#pragma unroll
+    for (int r = 0; r < LPT; ++r) {
+      u32 bi = (T == 1) ? b[r] : (u32)__builtin_amdgcn_ds_bpermute(src, (int)b[r]);
+      A[0] = mad64(a[0], bi, A[0]);
+      u32 qv = ((u32)A[0] * n0inv) & LIMB_MASK;
+      u32 q = g.bcast(qv, 0);
+#pragma unroll
+      for (int j = 1; j < LPT; ++j) A[j] = mad64(a[j], bi, A[j]);
+      u64 t0 = mad64(q, n[0], A[0]);
+      u32 low = (u32)t0 & LIMB_MASK;  // 0 on lane 0 of every group, by the choice of q
+      u32 recv = g.from_upper_raw(low);
+      u64 carry = t0 >> LIMB_BITS;
+      if (LPT > 1) {
+        A[0] = mad64(q, n[1], A[1]) + carry;
+#pragma unroll
+        for (int j = 2; j < LPT; ++j) A[j - 1] = mad64(q, n[j], A[j]);
+        A[LPT - 1] = (u64)recv;
+      } else {
+        A[0] = (u64)recv + carry;
+      }
+      if ((r + 1) % NORM == 0) hi_normalise<LPT, T>(A, g);
+    }
+  }
+  // Compress the columns to 32-bit limbs: ripple inside the lane, then hand the
+  // lane's carry to the lane above (which absorbs it lazily in its limb 0).
+  u64 c = 0;
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) {
+    u64 v = A[j] + c;
+    out[j] = (u32)v & LIMB_MASK;
+    c = v >> LIMB_BITS;
+  }
+  if (T > 1) out[0] += g.from_lower((u32)c);
+}
+
+// Full carry propagation of signed lazy limbs (|x[j]| < 2^30): afterwards every
+// limb is in [0, 2^29) and the return value (the same on all lanes of the
+// group) is the carry out of the top limb: 0 for a value in [0, 2^(29*NL)),
+// -1 for a negative value (then the limbs hold value + 2^(29*NL)).
+template <int LPT, int T>
+__device__ __forceinline__ int resolve(s32 (&x)[LPT], const Grp<T>& g) {
+  int top = 0;
+  bool more;
+  do {
+    s32 c = 0;
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+      s32 v = x[j] + c;
+      x[j] = v & (s32)LIMB_MASK;
+      c = v >> LIMB_BITS;  // arithmetic
+    }
+    if (T == 1) {
+      top += c;
+      more = false;
+    } else {
+      if (g.k == T - 1) top += c;
+      s32 cin = (s32)g.from_lower((u32)c);
+      x[0] += cin;
+      more = wave_any(cin != 0);
+    }
+  } while (more);
+  if (T > 1) top = (int)g.bcast((u32)top, T - 1);
+  return top;
+}
+
+template <int LPT, int T>
+__device__ __forceinline__ int resolve(u32 (&x)[LPT], const Grp<T>& g) {
+  s32 t[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) t[j] = (s32)x[j];
+  int top = resolve<LPT, T>(t, g);
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) x[j] = (u32)t[j];
+  return top;
+}
+
+// x mod n for a lazy x < 2n: canonical limbs, value in [0, n).
+template <int LPT, int T>
+__device__ __forceinline__ void canonicalise(u32 (&x)[LPT], const u32 (&n)[LPT], const Grp<T>& g) {
+  resolve<LPT, T>(x, g);
+  s32 d[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) d[j] = (s32)x[j] - (s32)n[j];
+  int top = resolve<LPT, T>(d, g);
+  if (top >= 0) {
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) x[j] = (u32)d[j];
+  }
+}
+
+// out = (a - b) mod n for canonical a, b in [0, n).
+template <int LPT, int T>
+__device__ __forceinline__ void sub_mod(u32 (&out)[LPT], const u32 (&a)[LPT], const u32 (&b)[LPT],
+                                        const u32 (&n)[LPT], const Grp<T>& g) {
+  s32 d[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) d[j] = (s32)a[j] - (s32)b[j];
+  int top = resolve<LPT, T>(d, g);
+  // every group of the wave takes the same path through the cross-lane code
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) d[j] += (top < 0) ? (s32)n[j] : 0;
+  resolve<LPT, T>(d, g);
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) out[j] = (u32)d[j];
+}
+
+// Plain product of canonical a and b (2*NL limbs): lo = low NL limbs, and when
+// WANT_HI also hi = high NL limbs, both canonical. Same sliding window as
+// montmul without the modulus: step i emits result limb i from lane 0's
+// lowest column; what is left in the window at the end is the high half.
+template <int LPT, int T, bool WANT_HI>
+__device__ __forceinline__ void mul_plain(u32 (&lo)[LPT], u32 (&hi)[LPT], const u32 (&a)[LPT], const u32 (&b)[LPT],
+                                          const Grp<T>& g) {
+  constexpr int NORM = (LPT <= 31) ? LPT : (LPT / 2);
+  u64 A[LPT];
+  u32 res[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) {
+    A[j] = 0;
+    res[j] = 0;
+  }
+#pragma unroll 1
+  for (int o = 0; o < T; ++o) {
+    const int src = g.base_addr + (o << 2);
+#pragma unroll
+    for (int r = 0; r < LPT; ++r) {
+      u32 bi = (T == 1) ? b[r] : (u32)__builtin_amdgcn_ds_bpermute(src, (int)b[r]);
+#pragma unroll
+      for (int j = 0; j < LPT; ++j) A[j] = mad64(a[j], bi, A[j]);
+      u32 low = (u32)A[0] & LIMB_MASK;
+      u64 carry = A[0] >> LIMB_BITS;
+      u32 digit = g.bcast(low, 0);
+      if (g.k == o) res[r] = digit;
+      u32 recv = g.from_upper(low);  // nothing enters above the top lane
+      if (LPT > 1) {
+        A[0] = A[1] + carry;
+#pragma unroll
+        for (int j = 2; j < LPT; ++j) A[j - 1] = A[j];
+        A[LPT - 1] = (u64)recv;
+      } else {
+        A[0] = (u64)recv + carry;
+      }
+      if ((r + 1) % NORM == 0) hi_normalise<LPT, T>(A, g);
+    }
+  }
+  if (WANT_HI) {
+    u64 c = 0;
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+      u64 v = A[j] + c;
+      hi[j] = (u32)v & LIMB_MASK;
+      c = v >> LIMB_BITS;
+    }
+    if (T > 1) hi[0] += g.from_lower((u32)c);
+    resolve<LPT, T>(hi, g);
+  }
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) lo[j] = res[j];
+}
+
+// out = a * b mod 2^(29*NL)
+template <int LPT, int T>
+__device__ __forceinline__ void mullo(u32 (&out)[LPT], const u32 (&a)[LPT], const u32 (&b)[LPT], const Grp<T>& g) {
+  u32 unused[LPT];
+  mul_plain<LPT, T, false>(out, unused, a, b, g);
+}
+
+// (hi, lo) = a * b
+template <int LPT, int T>
+__device__ __forceinline__ void mulwide(u32 (&lo)[LPT], u32 (&hi)[LPT], const u32 (&a)[LPT], const u32 (&b)[LPT],
+                                        const Grp<T>& g) {
+  mul_plain<LPT, T, true>(lo, hi, a, b, g);
+}
+
+// ---------------------------------------------------------------------------
+// memory <-> registers
+// ---------------------------------------------------------------------------
+
+// limbs [k*LPT, (k+1)*LPT) of a limb array (internal format)
+template <int LPT, int T>
+__device__ __forceinline__ void load_limbs(u32 (&x)[LPT], const u32* p, const Grp<T>& g) {
+  const u32* q = p + g.k * LPT;
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) x[j] = q[j];
+}
+template <int LPT, int T>
+__device__ __forceinline__ void store_limbs(u32* p, const u32 (&x)[LPT], const Grp<T>& g) {
+  u32* q = p + g.k * LPT;
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) q[j] = x[j];
+}
+template <int LPT>
+__device__ __forceinline__ void zero_limbs(u32 (&x)[LPT]) {
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) x[j] = 0;
+}
+
+// This lane's 29-bit limbs cut out of an array of `nwords` little-endian 32-bit
+// words (bits past the array read as zero).
+template <int LPT, int T>
+__device__ __forceinline__ void load_words_as_limbs(u32 (&x)[LPT], const u32* wp, int nwords, const Grp<T>& g) {
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) {
+    int bitpos = (g.k * LPT + j) * LIMB_BITS;
+    int wi = bitpos >> 5;
+    int sh = bitpos & 31;
+    u32 lo = (wi < nwords) ? wp[wi] : 0u;
+    u32 hi = (wi + 1 < nwords) ? wp[wi + 1] : 0u;
+    u64 v = ((u64)hi << 32) | lo;
+    x[j] = (u32)(v >> sh) & LIMB_MASK;
+  }
+}
+
+// 32-bit word `wi` of the integer whose canonical 29-bit limbs are limbs[0..nl)
+__device__ __forceinline__ u32 word_from_limbs(const u32* limbs, int nl, int wi) {
+  int bitpos = wi << 5;
+  int li = bitpos / LIMB_BITS;
+  int sh = bitpos - li * LIMB_BITS;  // 0..28
+  u64 v = 0;
+  if (li < nl) v = (u64)limbs[li] >> sh;
+  if (li + 1 < nl) v |= (u64)limbs[li + 1] << (LIMB_BITS - sh);
+  if (li + 2 < nl) v |= (u64)limbs[li + 2] << (2 * LIMB_BITS - sh);
+  return (u32)v;
+}
+
+}  // namespace dev
+}  // namespace haflo

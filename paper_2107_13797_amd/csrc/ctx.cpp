@@ -1,0 +1,385 @@
+// Host side of libhaflo: deterministic key generation, key contexts and the
+// per-key constant tables the kernels read (Montgomery constants in radix
+// 2^29, exponent schedules, constants of decryption through p^2 and q^2).
+#include <cstdio>
+#include <cstdlib>
+#include <new>
+
+#include "haflo_internal.hpp"
+
+namespace haflo {
+
+std::vector<uint32_t> to_limbs29(const Big& x, int nl) {
+  std::vector<uint32_t> r(nl, 0);
+  for (int i = 0; i < nl; ++i) r[i] = x.extract((size_t)i * kLimbBits, kLimbBits);
+  return r;
+}
+
+// Sliding-window plan for a fixed exponent (left to right, odd-power table).
+static HostSched plan_with_window(const Big& e, int w) {
+  HostSched s;
+  if (e.is_zero()) {
+    s.is_zero = 1;
+    return s;
+  }
+  long i = (long)e.bits() - 1;
+  auto take_window = [&](long hi, long& lo_out) -> uint32_t {
+    long lo = hi - w + 1;
+    if (lo < 0) lo = 0;
+    while (!e.bit((size_t)lo)) ++lo;
+    lo_out = lo;
+    return e.extract((size_t)lo, (unsigned)(hi - lo + 1));
+  };
+  long lo;
+  uint32_t v = take_window(i, lo);
+  s.first = (int)((v - 1) / 2);
+  int max_idx = s.first;
+  // bits below the leading window that it skipped over (trailing zeros of the
+  // window were excluded, so none) - continue below `lo`
+  i = lo - 1;
+  uint32_t pending = 0;
+  while (i >= 0) {
+    if (!e.bit((size_t)i)) {
+      ++pending;
+      --i;
+      continue;
+    }
+    v = take_window(i, lo);
+    uint32_t nsq = pending + (uint32_t)(i - lo + 1);
+    int idx = (int)((v - 1) / 2);
+    if (idx > max_idx) max_idx = idx;
+    s.steps.push_back((nsq << 16) | (uint32_t)idx);
+    s.nsquare += nsq;
+    s.nmul += 1;
+    pending = 0;
+    i = lo - 1;
+  }
+  if (pending) {
+    s.steps.push_back((pending << 16) | kNoMul);
+    s.nsquare += pending;
+  }
+  s.table_len = max_idx + 1;
+  if (s.table_len > 1) {
+    s.nsquare += 1;                 // x^2
+    s.nmul += s.table_len - 1;      // x^3, x^5, ...
+  }
+  return s;
+}
+
+HostSched make_schedule(const Big& e, int window) {
+  if (window > 0) return plan_with_window(e, window);
+  HostSched best = plan_with_window(e, 1);
+  for (int w = 2; w <= 7; ++w) {
+    HostSched c = plan_with_window(e, w);
+    if (c.nsquare + c.nmul < best.nsquare + best.nmul) best = c;
+  }
+  return best;
+}
+
+static const std::vector<uint32_t>& small_primes() {
+  static std::vector<uint32_t> pr;
+  if (pr.empty()) {
+    for (uint32_t c = 2; c < 2000; ++c) {
+      bool ok = true;
+      for (uint32_t d = 2; d * d <= c; ++d)
+        if (c % d == 0) {
+          ok = false;
+          break;
+        }
+      if (ok) pr.push_back(c);
+    }
+  }
+  return pr;
+}
+
+// one strong-probable-prime round of odd cand to `base`
+static bool mr_round(const MontHost& mh, const Big& cand, const Big& cm1, const Big& d, size_t s, const Big& base) {
+  Big x = mh.powmod(base, d);
+  if (x == Big(1) || x == cm1) return true;
+  for (size_t i = 1; i < s; ++i) {
+    x = mh.from_mont(mh.mul(mh.to_mont(x), mh.to_mont(x)));
+    if (x == cm1) return true;
+  }
+  (void)cand;
+  return false;
+}
+
+static Big next_prime_from_stream(SplitMix64& rng, size_t half_bits) {
+  size_t nwords = half_bits / 64;
+  for (;;) {
+    Big cand = rng.words(nwords);
+    cand.w.resize(half_bits / 32, 0);
+    cand.w[half_bits / 32 - 1] |= 0xC0000000u;
+    cand.w[0] |= 1u;
+    cand.trim();
+    bool divisible = false;
+    for (uint32_t sp : small_primes())
+      if (cand.mod_small(sp) == 0) {
+        divisible = true;
+        break;
+      }
+    if (divisible) continue;
+    MontHost mh(cand);
+    Big cm1 = Big::sub(cand, Big(1));
+    Big d = cm1;
+    size_t s = 0;
+    while (!d.is_odd()) {
+      d = d.shr1();
+      ++s;
+    }
+    Big cm3 = Big::sub(cand, Big(3));
+    bool ok = true;
+    for (int round = 0; round < 40; ++round) {
+      Big base = rng.words(nwords);
+      // base < 2^half_bits < 2*(cand-3): one conditional subtraction reduces it
+      if (base >= cm3) base = Big::sub(base, cm3);
+      base = Big::add(base, Big(2));
+      if (!mr_round(mh, cand, cm1, d, s, base)) {
+        ok = false;
+        break;
+      }
+    }
+    if (ok) return cand;
+  }
+}
+
+static bool valid_bits(uint32_t n_bits) { return n_bits == 512 || n_bits == 1024 || n_bits == 2048 || n_bits == 4096; }
+
+static bool choose_geometry(ModHost& m) {
+  if (m.nl % 18 == 0) {
+    m.lpt = 18;
+    m.t = m.nl / 18;
+  } else if (m.nl == 9) {
+    m.lpt = 9;
+    m.t = 1;
+  } else {
+    return false;
+  }
+  return m.t == 1 || m.t == 2 || m.t == 4 || m.t == 8 || m.t == 16;
+}
+
+struct Uploader {
+  haflo_ctx* ctx;
+  bool ok = true;
+  uint32_t* put(const std::vector<uint32_t>& v) {
+    if (!ok) return nullptr;
+    void* d = nullptr;
+    size_t bytes = v.size() * sizeof(uint32_t);
+    if (bytes == 0) bytes = 4;
+    if (hipMalloc(&d, bytes) != hipSuccess) {
+      ok = false;
+      return nullptr;
+    }
+    ctx->dev_allocs.push_back(d);
+    if (!v.empty() && hipMemcpy(d, v.data(), v.size() * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess) {
+      ok = false;
+      return nullptr;
+    }
+    return (uint32_t*)d;
+  }
+};
+
+static void build_modulus(ModHost& m, const Big& mod, int nl, Uploader& up) {
+  m.mod = mod;
+  m.nl = nl;
+  if (!choose_geometry(m)) {
+    up.ok = false;
+    return;
+  }
+  m.n0inv = neg_inv32(mod.w[0]) & ((1u << kLimbBits) - 1u);
+  Big r1 = Big::mod(Big::pow2((size_t)kLimbBits * nl), mod);
+  Big r2 = Big::mod(Big::mul(r1, r1), mod);
+  Big r3 = Big::mod(Big::mul(r2, r1), mod);
+  std::vector<uint32_t> tab;
+  for (const Big* b : {(const Big*)&mod, (const Big*)&r1, (const Big*)&r2, (const Big*)&r3}) {
+    std::vector<uint32_t> l = to_limbs29(*b, nl);
+    tab.insert(tab.end(), l.begin(), l.end());
+  }
+  m.d_tab = up.put(tab);
+}
+
+static void build_schedule(DevSched& s, const Big& e, Uploader& up) {
+  s.h = make_schedule(e, 0);
+  s.d_steps = up.put(s.h.steps);
+}
+
+static std::vector<uint32_t> to_words(const Big& x, int nw) {
+  std::vector<uint32_t> r(nw, 0);
+  for (int i = 0; i < nw; ++i) r[i] = x.word(i);
+  return r;
+}
+
+static int ctx_build(haflo_ctx* ctx, const Big& n, const Big* p, const Big* q, uint32_t n_bits) {
+  ctx->n_bits = n_bits;
+  ctx->lc = (int)(n_bits / 16);
+  ctx->lp = (int)(n_bits / 32);
+  ctx->n = n;
+  ctx->nsq = Big::mul(n, n);
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return HAFLO_EHIP;
+  ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+
+  Uploader up{ctx};
+  const int nl_n2 = (int)(n_bits * 9 / 128);
+  build_modulus(ctx->N, ctx->nsq, nl_n2, up);
+  if (!up.ok) return HAFLO_ENOMEM;
+  build_schedule(ctx->sched_n, n, up);
+  {
+    // k1 = n * R^2 mod n^2
+    Big r1 = Big::mod(Big::pow2((size_t)kLimbBits * nl_n2), ctx->nsq);
+    Big r2 = Big::mod(Big::mul(r1, r1), ctx->nsq);
+    Big k1 = Big::mod(Big::mul(n, r2), ctx->nsq);
+    ctx->d_k1 = up.put(to_limbs29(k1, nl_n2));
+  }
+  ctx->d_n_words = up.put(to_words(n, ctx->lp));
+  ctx->d_halfn_words = up.put(to_words(n.shr1(), ctx->lp));
+
+  if (p && q) {
+    ctx->has_priv = true;
+    ctx->p = *p;
+    ctx->q = *q;
+    const int nl_h = nl_n2 / 2, nl_q = nl_n2 / 4;
+    build_modulus(ctx->P2, Big::mul(*p, *p), nl_h, up);
+    build_modulus(ctx->Q2, Big::mul(*q, *q), nl_h, up);
+    build_modulus(ctx->P, *p, nl_q, up);
+    build_modulus(ctx->Q, *q, nl_q, up);
+    if (!up.ok) return HAFLO_ENOMEM;
+    build_schedule(ctx->sched_pm1, Big::sub(*p, Big(1)), up);
+    build_schedule(ctx->sched_qm1, Big::sub(*q, Big(1)), up);
+    // With g = n + 1: g^(p-1) mod p^2 = 1 + (p-1)*n mod p^2, so
+    // L_p(g^(p-1) mod p^2) = -q mod p and h_p = -(q^-1) mod p (p, q prime).
+    MontHost mp(*p), mq(*q);
+    Big q_mod_p = (*q >= *p) ? Big::sub(*q, *p) : *q;
+    Big p_mod_q = (*p >= *q) ? Big::sub(*p, *q) : *p;
+    Big qinv_p = mp.powmod(q_mod_p, Big::sub(*p, Big(2)));
+    Big pinv_q = mq.powmod(p_mod_q, Big::sub(*q, Big(2)));
+    Big hp = Big::sub(*p, qinv_p);
+    Big hq = Big::sub(*q, pinv_q);
+    Big rp = Big::mod(Big::pow2((size_t)kLimbBits * nl_q), *p);
+    Big rq = Big::mod(Big::pow2((size_t)kLimbBits * nl_q), *q);
+    Big hpR = Big::mod(Big::mul(hp, rp), *p);
+    Big hqR = Big::mod(Big::mul(hq, rq), *q);
+    Big pinvqR = Big::mod(Big::mul(pinv_q, rq), *q);
+    Big pinv2 = inv_mod_pow2(*p, (size_t)kLimbBits * nl_q);
+    Big qinv2 = inv_mod_pow2(*q, (size_t)kLimbBits * nl_q);
+    std::vector<uint32_t> tab;
+    for (const Big* b : {(const Big*)&pinv2, (const Big*)&qinv2, (const Big*)&hpR, (const Big*)&hqR, (const Big*)&pinvqR}) {
+      std::vector<uint32_t> l = to_limbs29(*b, nl_q);
+      tab.insert(tab.end(), l.begin(), l.end());
+    }
+    ctx->d_priv = up.put(tab);
+    if (!up.ok) return HAFLO_ENOMEM;
+    ctx->d_pinv = ctx->d_priv;
+    ctx->d_qinv = ctx->d_priv + nl_q;
+    ctx->d_hp = ctx->d_priv + 2 * nl_q;
+    ctx->d_hq = ctx->d_priv + 3 * nl_q;
+    ctx->d_pinvq = ctx->d_priv + 4 * nl_q;
+  }
+  if (!up.ok) return HAFLO_ENOMEM;
+  if (hipDeviceSynchronize() != hipSuccess) return HAFLO_EHIP;
+  return HAFLO_OK;
+}
+
+}  // namespace haflo
+
+using namespace haflo;
+
+extern "C" {
+
+const char* haflo_strerror(int code) {
+  switch (code) {
+    case HAFLO_OK: return "ok";
+    case HAFLO_EINVAL: return "invalid argument";
+    case HAFLO_EKEY: return "unusable key material";
+    case HAFLO_ENOPRIV: return "operation needs the private key";
+    case HAFLO_EHIP: return "HIP runtime error";
+    case HAFLO_ENOMEM: return "allocation failed";
+    default: return "unknown error";
+  }
+}
+
+int haflo_keygen(uint32_t n_bits, uint64_t seed, uint8_t* p_le, uint8_t* q_le) {
+  if (!valid_bits(n_bits) || !p_le || !q_le) return HAFLO_EINVAL;
+  try {
+    SplitMix64 rng(seed);
+    size_t half = n_bits / 2;
+    Big p = next_prime_from_stream(rng, half);
+    for (;;) {
+      Big q = next_prime_from_stream(rng, half);
+      if (q == p) continue;
+      Big n = Big::mul(p, q);
+      Big phi = Big::mul(Big::sub(p, Big(1)), Big::sub(q, Big(1)));
+      if (Big::gcd(n, phi) != Big(1)) continue;
+      p.to_bytes_le(p_le, n_bits / 16);
+      q.to_bytes_le(q_le, n_bits / 16);
+      return HAFLO_OK;
+    }
+  } catch (const std::bad_alloc&) {
+    return HAFLO_ENOMEM;
+  }
+}
+
+int haflo_ctx_destroy(haflo_ctx* ctx) {
+  if (!ctx) return HAFLO_EINVAL;
+  int rc = HAFLO_OK;
+  for (void* d : ctx->dev_allocs)
+    if (hipFree(d) != hipSuccess) rc = HAFLO_EHIP;
+  delete ctx;
+  return rc;
+}
+
+int haflo_ctx_create_private(const uint8_t* p_le, const uint8_t* q_le, uint32_t n_bits, haflo_ctx** out) {
+  if (!p_le || !q_le || !out || !valid_bits(n_bits)) return HAFLO_EINVAL;
+  *out = nullptr;
+  try {
+    Big p = Big::from_bytes_le(p_le, n_bits / 16), q = Big::from_bytes_le(q_le, n_bits / 16);
+    if (!p.is_odd() || !q.is_odd() || p == q || p.bits() != n_bits / 2 || q.bits() != n_bits / 2) return HAFLO_EKEY;
+    Big n = Big::mul(p, q);
+    if (n.bits() != n_bits) return HAFLO_EKEY;
+    Big phi = Big::mul(Big::sub(p, Big(1)), Big::sub(q, Big(1)));
+    if (Big::gcd(n, phi) != Big(1)) return HAFLO_EKEY;
+    haflo_ctx* ctx = new haflo_ctx();
+    int rc = ctx_build(ctx, n, &p, &q, n_bits);
+    if (rc != HAFLO_OK) {
+      haflo_ctx_destroy(ctx);
+      return rc;
+    }
+    *out = ctx;
+    return HAFLO_OK;
+  } catch (const std::bad_alloc&) {
+    return HAFLO_ENOMEM;
+  }
+}
+
+int haflo_ctx_create_public(const uint8_t* n_le, uint32_t n_bits, haflo_ctx** out) {
+  if (!n_le || !out || !valid_bits(n_bits)) return HAFLO_EINVAL;
+  *out = nullptr;
+  try {
+    Big n = Big::from_bytes_le(n_le, n_bits / 8);
+    if (!n.is_odd() || n.bits() != n_bits) return HAFLO_EKEY;
+    haflo_ctx* ctx = new haflo_ctx();
+    int rc = ctx_build(ctx, n, nullptr, nullptr, n_bits);
+    if (rc != HAFLO_OK) {
+      haflo_ctx_destroy(ctx);
+      return rc;
+    }
+    *out = ctx;
+    return HAFLO_OK;
+  } catch (const std::bad_alloc&) {
+    return HAFLO_ENOMEM;
+  }
+}
+
+int haflo_ctx_info(const haflo_ctx* ctx, uint32_t* n_bits, uint32_t* cipher_limbs, uint32_t* plain_limbs,
+                   size_t* cipher_bytes_internal, size_t* plain_bytes) {
+  if (!ctx) return HAFLO_EINVAL;
+  if (n_bits) *n_bits = ctx->n_bits;
+  if (cipher_limbs) *cipher_limbs = (uint32_t)ctx->lc;
+  if (plain_limbs) *plain_limbs = (uint32_t)ctx->lp;
+  if (cipher_bytes_internal) *cipher_bytes_internal = (size_t)ctx->N.nl * 4;
+  if (plain_bytes) *plain_bytes = (size_t)ctx->lp * 4;
+  return HAFLO_OK;
+}
+
+}  // extern "C"

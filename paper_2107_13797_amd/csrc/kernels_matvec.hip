@@ -1,0 +1,725 @@
+// Ciphertext matrix-vector products, ciphertext summation and the modular
+// inverse they need for negative exponents. Kernels and C entry points.
+//
+// X^T [[d]] (orientation 0): the bases c_i are shared by every output column,
+//   so each base gets a table of its first 2^w powers; output column j then is
+//   prod_s ( prod_i table_i[digit_s(|x_ij|)] )^(2^(w s)), with positive and
+//   negative entries collected separately and one inversion per column.
+// X [[w]] (orientation 1): the few bases c_j are shared by every output row,
+//   so each base (and its inverse) gets positional tables c_j^(d 2^(w s)); an
+//   output row is a plain product of table entries over its non-zero entries,
+//   which are compacted per row first.
+#include "kernels_common.hpp"
+
+using namespace haflo;
+using namespace haflo::dev;
+
+namespace {
+
+constexpr int kWin = 4;                    // window width of the exponent digits
+constexpr int kWinEntries = 1 << kWin;     // table entries per base (entry 0 = 1)
+constexpr int kMaxPos = (32 + kWin - 1) / kWin;  // digit positions of a 32-bit magnitude
+
+// ---------------------------------------------------------------------------
+// modular inverse by batched division steps
+// ---------------------------------------------------------------------------
+
+// 29 division steps of the Bernstein-Yang 2-adic gcd recurrence on the low
+// bits of (f, g), f odd:
+//   g odd and delta > 0:  (delta, f, g) <- (1 - delta, g, (g - f) / 2)
+//   g odd otherwise:      (delta, f, g) <- (1 + delta, f, (g + f) / 2)
+//   g even:               (delta, f, g) <- (1 + delta, f, g / 2)
+// Returns the integer matrix with 2^29 (f', g') = (u f + v g, q f + r g); every
+// entry has magnitude at most 2^29 and each row sums to at most 2^29 in
+// magnitude.
+__device__ __forceinline__ void divsteps29(int& delta, u32 f0, u32 g0, s32& u, s32& v, s32& q, s32& r) {
+  u = 1;
+  v = 0;
+  q = 0;
+  r = 1;
+#pragma unroll 1
+  for (int i = 0; i < LIMB_BITS; ++i) {
+    bool odd = (g0 & 1u) != 0u;
+    bool swp = odd && (delta > 0);
+    u32 nf = swp ? g0 : f0;
+    s32 nu = swp ? q : u;
+    s32 nv = swp ? r : v;
+    u32 ng = odd ? (swp ? g0 - f0 : g0 + f0) : g0;
+    s32 nq = odd ? (swp ? q - u : q + u) : q;
+    s32 nr = odd ? (swp ? r - v : r + v) : r;
+    delta = swp ? 1 - delta : 1 + delta;
+    f0 = nf;
+    g0 = ng >> 1;
+    u = nu * 2;
+    v = nv * 2;
+    q = nq;
+    r = nr;
+  }
+}
+
+// Shared tail of the two linear updates: absorb the carry of the lane below,
+// then drop the (vanished) lowest limb; the top lane's carry becomes the new,
+// signed, top limb.
+template <int LPT, int T>
+__device__ __forceinline__ void shift_down(s32 (&x)[LPT], s32 (&nx)[LPT], s64 carry, const Grp<T>& g) {
+  if (T > 1) {
+    s32 cin = (s32)g.from_lower((u32)(s32)carry);
+    s64 v0 = (s64)nx[0] + (s64)cin;
+    nx[0] = (s32)(v0 & (s64)LIMB_MASK);
+    nx[1] += (s32)(v0 >> LIMB_BITS);
+  }
+  s32 down = (s32)g.from_upper((u32)nx[0]);
+#pragma unroll
+  for (int j = 0; j + 1 < LPT; ++j) x[j] = nx[j + 1];
+  x[LPT - 1] = (g.k == T - 1) ? (s32)carry : down;
+}
+
+// out = in^-1 * R^2 ... precisely: for `a` the Montgomery form x R of a unit x
+// modulo the odd modulus m, returns the Montgomery form x^-1 R (canonical).
+// Works on signed numbers in radix 2^29 whose top limb carries the sign:
+// (f, g) start at (m, a) and are driven to (+-1, 0) by batches of 29 division
+// steps, (d, e) start at (0, 1) and follow the same matrices modulo m, so that
+// d * a = f (mod m) throughout; |d| grows by at most m per batch, which the
+// head-room of the radix above m absorbs. nbatch bounds the number of batches.
+template <int LPT, int T>
+__device__ __forceinline__ void invert_mont(u32 (&out)[LPT], const u32 (&a)[LPT], const ModRegs<LPT>& M,
+                                            const u32* r3, int nbatch, const Grp<T>& g) {
+  s32 f[LPT], gg[LPT], d[LPT], e[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) {
+    f[j] = (s32)M.n[j];
+    gg[j] = (s32)a[j];
+    d[j] = 0;
+    e[j] = 0;
+  }
+  if (g.k == 0) e[0] = 1;
+  int delta = 1;
+#pragma unroll 1
+  for (int b = 0; b < nbatch; ++b) {
+    s32 any = 0;
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) any |= gg[j];
+    if (!wave_any(any != 0)) break;
+    u32 f0 = g.bcast((u32)f[0], 0), g0 = g.bcast((u32)gg[0], 0);
+    s32 u, v, q, r;
+    divsteps29(delta, f0, g0, u, v, q, r);
+    {
+      s64 cf = 0, cg = 0;
+      s32 nf[LPT], ng[LPT];
+#pragma unroll
+      for (int j = 0; j < LPT; ++j) {
+        s64 tf = (s64)u * f[j] + (s64)v * gg[j] + cf;
+        s64 tg = (s64)q * f[j] + (s64)r * gg[j] + cg;
+        nf[j] = (s32)(tf & (s64)LIMB_MASK);
+        cf = tf >> LIMB_BITS;
+        ng[j] = (s32)(tg & (s64)LIMB_MASK);
+        cg = tg >> LIMB_BITS;
+      }
+      shift_down<LPT, T>(f, nf, cf, g);
+      shift_down<LPT, T>(gg, ng, cg, g);
+    }
+    {
+      // multiples of m that clear the lowest limb of each combination
+      u32 lowd = (u32)u * (u32)d[0] + (u32)v * (u32)e[0];
+      u32 lowe = (u32)q * (u32)d[0] + (u32)r * (u32)e[0];
+      u32 kd = g.bcast((lowd * M.n0inv) & LIMB_MASK, 0);
+      u32 ke = g.bcast((lowe * M.n0inv) & LIMB_MASK, 0);
+      s64 cd = 0, ce = 0;
+      s32 nd[LPT], ne[LPT];
+#pragma unroll
+      for (int j = 0; j < LPT; ++j) {
+        s64 td = (s64)u * d[j] + (s64)v * e[j] + (s64)((u64)kd * M.n[j]) + cd;
+        s64 te = (s64)q * d[j] + (s64)r * e[j] + (s64)((u64)ke * M.n[j]) + ce;
+        nd[j] = (s32)(td & (s64)LIMB_MASK);
+        cd = td >> LIMB_BITS;
+        ne[j] = (s32)(te & (s64)LIMB_MASK);
+        ce = te >> LIMB_BITS;
+      }
+      shift_down<LPT, T>(d, nd, cd, g);
+      shift_down<LPT, T>(e, ne, ce, g);
+    }
+  }
+  // f = +-1 now; the inverse is sign(f) * d modulo m
+  u32 f0 = g.bcast((u32)f[0], 0) & LIMB_MASK;
+  bool fneg = (f0 != 1u);
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) d[j] = fneg ? -d[j] : d[j];
+  int top = resolve<LPT, T>(d, g);
+  bool neg = top < 0;
+  // from here on every group of the wave runs the same cross-lane code and
+  // only selects differ
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) d[j] = neg ? -d[j] : d[j];
+  resolve<LPT, T>(d, g);
+  u32 x[LPT], t[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) x[j] = (u32)d[j];
+  load_limbs<LPT, T>(t, r3, g);
+  montmul<LPT, T>(x, x, t, M.n, M.n0inv, g);  // |d| R^-1 * R^3 / R = |d| R
+  canonicalise<LPT, T>(x, M.n, g);
+  s32 y[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) y[j] = neg ? (s32)M.n[j] - (s32)x[j] : (s32)x[j];
+  resolve<LPT, T>(y, g);
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) x[j] = (u32)y[j];
+  canonicalise<LPT, T>(x, M.n, g);  // m - 0 = m folds back to 0
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) out[j] = x[j];
+}
+
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_invert(ModRef M, const u32* in, u32* out, size_t count, int nbatch) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    size_t item = base + bt.gib;
+    bool active = item < count;
+    u32 x[LPT];
+    if (active) load_limbs<LPT, T>(x, in + item * (size_t)NL, g);
+    else zero_limbs<LPT>(x);
+    invert_mont<LPT, T>(x, x, mod, M.r3, nbatch, g);
+    if (active) store_limbs<LPT, T>(out + item * (size_t)NL, x, g);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// shared pieces
+// ---------------------------------------------------------------------------
+
+// bit length of the largest |x| in the matrix (atomicMax into a zeroed word)
+__global__ __launch_bounds__(kBlockThreads) void k_zero_word(u32* p) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) *p = 0u;
+}
+__global__ __launch_bounds__(kBlockThreads) void k_maxbits(const int* __restrict__ X, size_t total, u32* maxbits) {
+  u32 m = 0;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    int x = X[i];
+    u32 mag = x < 0 ? 0u - (u32)x : (u32)x;
+    m |= mag;
+  }
+  // OR preserves the highest set bit; reduce across the wave with ballots
+  u32 bits = 0;
+#pragma unroll 1
+  for (int b = 31; b >= 0; --b) {
+    if (__builtin_amdgcn_ballot_w64(((m >> b) & 1u) != 0u) != 0ull) {
+      bits = (u32)b + 1u;
+      break;
+    }
+  }
+  if ((threadIdx.x & (WAVE - 1)) == 0 && bits) atomicMax(maxbits, bits);
+}
+
+// product of the per-group accumulators of a block, left in group 0.
+// lds: (groups per block / 2) * NL limbs.
+template <int LPT, int T>
+__device__ __forceinline__ void block_product(u32 (&acc)[LPT], u32* lds, const ModRegs<LPT>& mod, const Batch<T>& bt,
+                                              const Grp<T>& g) {
+  constexpr int NL = LPT * T;
+  for (int stride = bt.gpb >> 1; stride >= 1; stride >>= 1) {
+    if (bt.gib >= stride && bt.gib < 2 * stride) {
+      u32* dst = lds + (bt.gib - stride) * NL + g.k * LPT;
+#pragma unroll
+      for (int j = 0; j < LPT; ++j) dst[j] = acc[j];
+    }
+    __syncthreads();
+    u32 t[LPT], r[LPT];
+    bool take = bt.gib < stride;
+    const u32* src = lds + (take ? bt.gib : 0) * NL + g.k * LPT;
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) t[j] = src[j];
+    montmul<LPT, T>(r, acc, t, mod.n, mod.n0inv, g);
+    if (take) {
+#pragma unroll
+      for (int j = 0; j < LPT; ++j) acc[j] = r[j];
+    }
+    __syncthreads();
+  }
+}
+
+// table[i][d] = c_i^d for d < 2^w (Montgomery form, lazy), one group per base
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_pow_tables(ModRef M, const u32* __restrict__ bases,
+                                                              u32* __restrict__ tables, size_t count) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    size_t item = base + bt.gib;
+    bool active = item < count;
+    u32 x[LPT], cur[LPT];
+    if (active) load_limbs<LPT, T>(x, bases + item * (size_t)NL, g);
+    else zero_limbs<LPT>(x);
+    load_limbs<LPT, T>(cur, M.r1, g);
+    u32* tb = tables + item * (size_t)kWinEntries * NL;
+    if (active) {
+      store_limbs<LPT, T>(tb, cur, g);
+      store_limbs<LPT, T>(tb + NL, x, g);
+    }
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) cur[j] = x[j];
+#pragma unroll 1
+    for (int dgt = 2; dgt < kWinEntries; ++dgt) {
+      montmul<LPT, T>(cur, cur, x, mod.n, mod.n0inv, g);
+      if (active) store_limbs<LPT, T>(tb + (size_t)dgt * NL, cur, g);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// orientation 0: out[j] = prod_i c_i^X[i][j]
+// ---------------------------------------------------------------------------
+
+// block (j, s, rs): product over the rows of slice rs of table_i[digit s of
+// |X[i][j]|], positive and negative entries apart -> partials[j][s][sign][rs]
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_xtd_main(ModRef M, const int* __restrict__ X, size_t rows,
+                                                            size_t cols, const u32* __restrict__ tables, int rsplit,
+                                                            u32* __restrict__ partials,
+                                                            const u32* __restrict__ maxbits) {
+  constexpr int NL = LPT * T;
+  __shared__ u32 lds[(kBlockThreads / 2) * LPT];
+  Grp<T> g;
+  Batch<T> bt;
+  const size_t b = blockIdx.x;
+  const size_t j = b % cols;
+  const int rs = (int)((b / cols) % (size_t)rsplit);
+  const int s = (int)(b / (cols * (size_t)rsplit));
+  if ((u32)(s * kWin) >= *maxbits) return;  // no digit at this position anywhere
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  const size_t r0 = rows * (size_t)rs / (size_t)rsplit, r1 = rows * (size_t)(rs + 1) / (size_t)rsplit;
+  u32 accp[LPT], accn[LPT];
+  load_limbs<LPT, T>(accp, M.r1, g);
+#pragma unroll
+  for (int jj = 0; jj < LPT; ++jj) accn[jj] = accp[jj];
+  for (size_t base = r0; base < r1; base += (size_t)bt.gpb) {
+    size_t i = base + bt.gib;
+    bool active = i < r1;
+    int x = active ? X[i * cols + j] : 0;
+    u32 mag = x < 0 ? 0u - (u32)x : (u32)x;
+    u32 dgt = (mag >> (s * kWin)) & (u32)(kWinEntries - 1);
+    const u32* entry = active ? tables + (i * (size_t)kWinEntries + dgt) * NL : M.r1;
+    u32 t[LPT], cur[LPT];
+    load_limbs<LPT, T>(t, entry, g);
+    bool neg = x < 0;
+#pragma unroll
+    for (int jj = 0; jj < LPT; ++jj) cur[jj] = neg ? accn[jj] : accp[jj];
+    montmul<LPT, T>(cur, cur, t, mod.n, mod.n0inv, g);
+#pragma unroll
+    for (int jj = 0; jj < LPT; ++jj) {
+      if (neg) accn[jj] = cur[jj];
+      else accp[jj] = cur[jj];
+    }
+  }
+  block_product<LPT, T>(accp, lds, mod, bt, g);
+  block_product<LPT, T>(accn, lds, mod, bt, g);
+  if (bt.gib == 0) {
+    size_t slot = ((j * (size_t)kMaxPos + (size_t)s) * 2) * (size_t)rsplit + (size_t)rs;
+    store_limbs<LPT, T>(partials + slot * NL, accp, g);
+    store_limbs<LPT, T>(partials + (slot + (size_t)rsplit) * NL, accn, g);
+  }
+}
+
+// one group per (j, sign): P = prod_s (prod_rs partial[j][s][sign][rs])^(2^(w s)), top position first
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_xtd_horner(ModRef M, size_t cols, int rsplit,
+                                                              const u32* __restrict__ partials, u32* __restrict__ P,
+                                                              const u32* __restrict__ maxbits) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  const int npos = (int)((*maxbits + (u32)kWin - 1u) / (u32)kWin);
+  const size_t count = cols * 2;
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    size_t item = base + bt.gib;
+    bool active = item < count;
+    size_t j = active ? item >> 1 : 0;
+    size_t sign = item & 1;
+    u32 acc[LPT], t[LPT];
+    load_limbs<LPT, T>(acc, M.r1, g);
+#pragma unroll 1
+    for (int s = npos - 1; s >= 0; --s) {
+      if (s != npos - 1) {
+#pragma unroll 1
+        for (int i = 0; i < kWin; ++i) montmul<LPT, T>(acc, acc, acc, mod.n, mod.n0inv, g);
+      }
+#pragma unroll 1
+      for (int rs = 0; rs < rsplit; ++rs) {
+        size_t slot = ((j * (size_t)kMaxPos + (size_t)s) * 2 + sign) * (size_t)rsplit + (size_t)rs;
+        load_limbs<LPT, T>(t, partials + slot * NL, g);
+        montmul<LPT, T>(acc, acc, t, mod.n, mod.n0inv, g);
+      }
+    }
+    if (active) store_limbs<LPT, T>(P + item * (size_t)NL, acc, g);
+  }
+}
+
+// out[j] = P[j][+] * (P[j][-])^-1
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_xtd_finish(ModRef M, size_t cols, const u32* __restrict__ P,
+                                                              u32* __restrict__ out, int nbatch) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  for (size_t base = bt.first(); base < cols; base += bt.stride()) {
+    size_t j = base + bt.gib;
+    bool active = j < cols;
+    u32 pos[LPT], neg[LPT];
+    if (active) {
+      load_limbs<LPT, T>(pos, P + (2 * j) * (size_t)NL, g);
+      load_limbs<LPT, T>(neg, P + (2 * j + 1) * (size_t)NL, g);
+    } else {
+      load_limbs<LPT, T>(pos, M.r1, g);
+      load_limbs<LPT, T>(neg, M.r1, g);
+    }
+    canonicalise<LPT, T>(neg, mod.n, g);
+    invert_mont<LPT, T>(neg, neg, mod, M.r3, nbatch, g);
+    montmul<LPT, T>(pos, pos, neg, mod.n, mod.n0inv, g);
+    canonicalise<LPT, T>(pos, mod.n, g);
+    if (active) store_limbs<LPT, T>(out + j * (size_t)NL, pos, g);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// orientation 1: out[i] = prod_j c_j^X[i][j]
+// ---------------------------------------------------------------------------
+
+// positional tables: group (j, sign): T[j][sign][s][d] = b^(d 2^(w s)), b = c_j or its inverse
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_xw_tables(ModRef M, const u32* __restrict__ bases,
+                                                             const u32* __restrict__ invbases, size_t cols,
+                                                             u32* __restrict__ tables,
+                                                             const u32* __restrict__ maxbits) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  const int npos = (int)((*maxbits + (u32)kWin - 1u) / (u32)kWin);
+  const size_t count = cols * 2;
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    size_t item = base + bt.gib;
+    bool active = item < count;
+    size_t j = active ? item >> 1 : 0;
+    const u32* src = (item & 1) ? invbases : bases;
+    u32 b[LPT], cur[LPT], one[LPT], half[LPT];
+    load_limbs<LPT, T>(b, src + j * (size_t)NL, g);
+    load_limbs<LPT, T>(one, M.r1, g);
+#pragma unroll 1
+    for (int s = 0; s < npos; ++s) {
+      u32* tb = tables + ((item * (size_t)kMaxPos + (size_t)s) * (size_t)kWinEntries) * NL;
+      if (active) {
+        store_limbs<LPT, T>(tb, one, g);
+        store_limbs<LPT, T>(tb + NL, b, g);
+      }
+#pragma unroll
+      for (int jj = 0; jj < LPT; ++jj) cur[jj] = b[jj];
+#pragma unroll 1
+      for (int dgt = 2; dgt < kWinEntries; ++dgt) {
+        montmul<LPT, T>(cur, cur, b, mod.n, mod.n0inv, g);
+        if (active) store_limbs<LPT, T>(tb + (size_t)dgt * NL, cur, g);
+        if (dgt == kWinEntries / 2) {
+#pragma unroll
+          for (int jj = 0; jj < LPT; ++jj) half[jj] = cur[jj];
+        }
+      }
+      montmul<LPT, T>(b, half, half, mod.n, mod.n0inv, g);  // b^(2^w) for the next position
+    }
+  }
+}
+
+// per row: the (column, value) pairs of its non-zero entries, in column order.
+// One wave per row; nz: rows*cols pairs of ints, nzcount: rows.
+__global__ __launch_bounds__(kBlockThreads) void k_xw_compact(const int* __restrict__ X, size_t rows, size_t cols,
+                                                              int* __restrict__ nz, u32* __restrict__ nzcount) {
+  const int lane = (int)(threadIdx.x & (WAVE - 1));
+  const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+  const size_t nwaves = ((size_t)gridDim.x * blockDim.x) / WAVE;
+  for (size_t row = wave; row < rows; row += nwaves) {
+    u32 written = 0;
+    for (size_t c0 = 0; c0 < cols; c0 += WAVE) {
+      size_t c = c0 + (size_t)lane;
+      int x = (c < cols) ? X[row * cols + c] : 0;
+      u64 mask = __builtin_amdgcn_ballot_w64(x != 0);
+      if (x != 0) {
+        u32 before = (u32)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
+        size_t o = (row * cols + written + before) * 2;
+        nz[o] = (int)c;
+        nz[o + 1] = x;
+      }
+      written += (u32)__builtin_popcountll(mask);
+    }
+    if (lane == 0) nzcount[row] = written;
+  }
+}
+
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_xw_main(ModRef M, size_t rows, size_t cols,
+                                                           const int* __restrict__ nz, const u32* __restrict__ nzcount,
+                                                           const u32* __restrict__ tables, u32* __restrict__ out,
+                                                           const u32* __restrict__ maxbits) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  const int npos = (int)((*maxbits + (u32)kWin - 1u) / (u32)kWin);
+  for (size_t base = bt.first(); base < rows; base += bt.stride()) {
+    size_t row = base + bt.gib;
+    bool active = row < rows;
+    u32 cnt = active ? nzcount[row] : 0u;
+    u32 acc[LPT], t[LPT];
+    load_limbs<LPT, T>(acc, M.r1, g);
+    for (u32 e = 0; wave_any(e < cnt); ++e) {
+      bool live = e < cnt;
+      int col = 0, x = 0;
+      if (live) {
+        col = nz[(row * cols + e) * 2];
+        x = nz[(row * cols + e) * 2 + 1];
+      }
+      u32 mag = x < 0 ? 0u - (u32)x : (u32)x;
+      size_t tsel = (size_t)col * 2 + (x < 0 ? 1 : 0);
+#pragma unroll 1
+      for (int s = 0; s < npos; ++s) {
+        u32 dgt = (mag >> (s * kWin)) & (u32)(kWinEntries - 1);
+        const u32* entry =
+            live ? tables + ((tsel * (size_t)kMaxPos + (size_t)s) * (size_t)kWinEntries + dgt) * NL : M.r1;
+        load_limbs<LPT, T>(t, entry, g);
+        montmul<LPT, T>(acc, acc, t, mod.n, mod.n0inv, g);
+      }
+    }
+    canonicalise<LPT, T>(acc, mod.n, g);
+    if (active) store_limbs<LPT, T>(out + row * (size_t)NL, acc, g);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// summation
+// ---------------------------------------------------------------------------
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_sum(ModRef M, const u32* __restrict__ in, size_t count,
+                                                       u32* __restrict__ out, int canonical) {
+  constexpr int NL = LPT * T;
+  __shared__ u32 lds[(kBlockThreads / 2) * LPT];
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  u32 acc[LPT], t[LPT];
+  load_limbs<LPT, T>(acc, M.r1, g);
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    size_t item = base + bt.gib;
+    const u32* src = item < count ? in + item * (size_t)NL : M.r1;
+    load_limbs<LPT, T>(t, src, g);
+    montmul<LPT, T>(acc, acc, t, mod.n, mod.n0inv, g);
+  }
+  block_product<LPT, T>(acc, lds, mod, bt, g);
+  if (canonical) canonicalise<LPT, T>(acc, mod.n, g);
+  if (bt.gib == 0) store_limbs<LPT, T>(out + (size_t)blockIdx.x * NL, acc, g);
+}
+
+int inverse_batches(const haflo_ctx* ctx) {
+  size_t bits = ctx->N.mod.bits();
+  size_t steps = (49 * bits + 57) / 17;
+  return (int)((steps + LIMB_BITS - 1) / LIMB_BITS);
+}
+
+struct XtdPlan {
+  int rsplit;
+  size_t off_tables, off_partials, off_P, total;  // in u32 words; word 0 holds maxbits
+};
+XtdPlan xtd_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
+  XtdPlan p;
+  const int gpb = kBlockThreads / ctx->N.t;
+  // aim at ~4 blocks per compute unit assuming 5 live digit positions, keep >= 2 rows per group
+  size_t want = ((size_t)ctx->num_cu * 4 + cols * 5 - 1) / (cols * 5 ? cols * 5 : 1);
+  size_t maxsplit = rows / ((size_t)gpb * 2);
+  if (want > maxsplit) want = maxsplit;
+  if (want < 1) want = 1;
+  if (want > 64) want = 64;
+  p.rsplit = (int)want;
+  const size_t nl = (size_t)ctx->N.nl;
+  p.off_tables = 64;
+  p.off_partials = p.off_tables + rows * kWinEntries * nl;
+  p.off_P = p.off_partials + cols * kMaxPos * 2 * (size_t)p.rsplit * nl;
+  p.total = p.off_P + cols * 2 * nl;
+  return p;
+}
+
+struct XwPlan {
+  size_t off_inv, off_tables, off_nz, off_cnt, total;  // in u32 words; word 0 holds maxbits
+};
+XwPlan xw_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
+  XwPlan p;
+  const size_t nl = (size_t)ctx->N.nl;
+  p.off_inv = 64;
+  p.off_tables = p.off_inv + cols * nl;
+  p.off_nz = p.off_tables + cols * 2 * kMaxPos * kWinEntries * nl;
+  p.off_cnt = p.off_nz + rows * cols * 2;
+  p.total = p.off_cnt + rows;
+  return p;
+}
+
+int sum_blocks(const haflo_ctx* ctx, size_t count) {
+  const int gpb = kBlockThreads / ctx->N.t;
+  size_t need = (count + (size_t)gpb * 4 - 1) / ((size_t)gpb * 4);
+  size_t cap = (size_t)ctx->num_cu * 4;
+  if (need < 1) need = 1;
+  return (int)(need < cap ? need : cap);
+}
+
+int launch_maxbits(const haflo_ctx* ctx, const int32_t* X, size_t total, u32* word, hipStream_t st) {
+  LaunchShape one;
+  one.blocks = 1;
+  one.threads = 64;
+  one.gpb = 64;
+  HAFLO_LAUNCH(k_zero_word, one, st, word);
+  if (total) {
+    LaunchShape sh = launch_shape(ctx, total, 1, 8);
+    HAFLO_LAUNCH(k_maxbits, sh, st, X, total, word);
+  }
+  return hip_status(hipGetLastError());
+}
+
+}  // namespace
+
+namespace haflo {
+
+int invert_batch(const haflo_ctx* ctx, const uint32_t* in, uint32_t* out, size_t count, hipStream_t st) {
+  const ModHost& m = ctx->N;
+  const LaunchShape sh = launch_shape(ctx, count, m.t, 8);
+  const int nbatch = inverse_batches(ctx);
+#define CALL(LPT, T) HAFLO_LAUNCH((k_invert<LPT, T>), sh, st, m.ref(), in, out, count, nbatch)
+  HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+  return hip_status(hipGetLastError());
+}
+
+}  // namespace haflo
+
+extern "C" {
+
+size_t haflo_workspace_bytes(const haflo_ctx* ctx, int op, size_t rows, size_t cols) {
+  if (!ctx) return (size_t)-1;
+  switch (op) {
+    case HAFLO_OP_ENCRYPT: return ws_encrypt(ctx, rows);
+    case HAFLO_OP_DECRYPT: return ctx->has_priv ? ws_decrypt(ctx, rows) : (size_t)-1;
+    case HAFLO_OP_SCALAR_MUL: return ws_scalar_mul(ctx, rows);
+    case HAFLO_OP_MATVEC_XT_D: return cols ? xtd_plan(ctx, rows, cols).total * 4 : 0;
+    case HAFLO_OP_MATVEC_X_W: return xw_plan(ctx, rows, cols).total * 4;
+    default: return (size_t)-1;
+  }
+}
+
+int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, const int32_t* d_X, size_t rows,
+                        size_t cols, void* d_out, void* d_workspace, size_t workspace_bytes, void* stream) {
+  if (!ctx || (orientation != 0 && orientation != 1)) return HAFLO_EINVAL;
+  const size_t nin = orientation == 0 ? rows : cols;
+  const size_t nout = orientation == 0 ? cols : rows;
+  if (nout == 0) return HAFLO_OK;
+  if (!d_out || (nin && (!d_c || !d_X))) return HAFLO_EINVAL;
+  const ModHost& m = ctx->N;
+  hipStream_t st = (hipStream_t)stream;
+  const size_t need = haflo_workspace_bytes(ctx, orientation == 0 ? HAFLO_OP_MATVEC_XT_D : HAFLO_OP_MATVEC_X_W, rows, cols);
+  if (!d_workspace || workspace_bytes < need) return HAFLO_EINVAL;
+  u32* ws = (u32*)d_workspace;
+  int rc = launch_maxbits(ctx, d_X, rows * cols, ws, st);
+  if (rc != HAFLO_OK) return rc;
+  const int nbatch = inverse_batches(ctx);
+  if (orientation == 0) {
+    const XtdPlan p = xtd_plan(ctx, rows, cols);
+    u32* tables = ws + p.off_tables;
+    u32* partials = ws + p.off_partials;
+    u32* P = ws + p.off_P;
+    if (rows) {
+      const LaunchShape sh = launch_shape(ctx, rows, m.t, 8);
+#define CALL(LPT, T) HAFLO_LAUNCH((k_pow_tables<LPT, T>), sh, st, m.ref(), (const u32*)d_c, tables, rows)
+      HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+      LaunchShape mainsh;
+      mainsh.threads = kBlockThreads;
+      mainsh.gpb = kBlockThreads / m.t;
+      mainsh.blocks = (int)(cols * (size_t)p.rsplit * kMaxPos);
+#define CALL(LPT, T) \
+  HAFLO_LAUNCH((k_xtd_main<LPT, T>), mainsh, st, m.ref(), d_X, rows, cols, (const u32*)tables, p.rsplit, partials, (const u32*)ws)
+      HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+    }
+    {
+      const LaunchShape sh = launch_shape(ctx, cols * 2, m.t, 8);
+#define CALL(LPT, T) \
+  HAFLO_LAUNCH((k_xtd_horner<LPT, T>), sh, st, m.ref(), cols, p.rsplit, (const u32*)partials, P, (const u32*)ws)
+      HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+    }
+    {
+      const LaunchShape sh = launch_shape(ctx, cols, m.t, 8);
+#define CALL(LPT, T) HAFLO_LAUNCH((k_xtd_finish<LPT, T>), sh, st, m.ref(), cols, (const u32*)P, (u32*)d_out, nbatch)
+      HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+    }
+  } else {
+    const XwPlan p = xw_plan(ctx, rows, cols);
+    u32* inv = ws + p.off_inv;
+    u32* tables = ws + p.off_tables;
+    int* nz = (int*)(ws + p.off_nz);
+    u32* cnt = ws + p.off_cnt;
+    if (cols) {
+      rc = invert_batch(ctx, (const u32*)d_c, inv, cols, st);
+      if (rc != HAFLO_OK) return rc;
+      const LaunchShape sh = launch_shape(ctx, cols * 2, m.t, 8);
+#define CALL(LPT, T) \
+  HAFLO_LAUNCH((k_xw_tables<LPT, T>), sh, st, m.ref(), (const u32*)d_c, (const u32*)inv, cols, tables, (const u32*)ws)
+      HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+    }
+    {
+      LaunchShape sh = launch_shape(ctx, rows, 64, 8);
+      if (cols == 0) {
+        // nothing to compact: every row is the empty product
+      }
+      HAFLO_LAUNCH(k_xw_compact, sh, st, d_X, rows, cols, nz, cnt);
+    }
+    {
+      const LaunchShape sh = launch_shape(ctx, rows, m.t, 8);
+#define CALL(LPT, T) \
+  HAFLO_LAUNCH((k_xw_main<LPT, T>), sh, st, m.ref(), rows, cols, (const int*)nz, (const u32*)cnt, (const u32*)tables, (u32*)d_out, (const u32*)ws)
+      HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+    }
+  }
+  return hip_status(hipGetLastError());
+}
+
+int haflo_cipher_sum(const haflo_ctx* ctx, const void* d_c, size_t count, void* d_out, void* d_workspace,
+                     size_t workspace_bytes, void* stream) {
+  if (!ctx || !d_out || (count && !d_c)) return HAFLO_EINVAL;
+  const ModHost& m = ctx->N;
+  hipStream_t st = (hipStream_t)stream;
+  const int nb = sum_blocks(ctx, count);
+  if (!d_workspace || workspace_bytes < (size_t)nb * m.nl * 4) return HAFLO_EINVAL;
+  LaunchShape sh;
+  sh.threads = kBlockThreads;
+  sh.gpb = kBlockThreads / m.t;
+  sh.blocks = nb;
+  LaunchShape fin = sh;
+  fin.blocks = 1;
+#define CALL(LPT, T)                                                                                   \
+  HAFLO_LAUNCH((k_sum<LPT, T>), sh, st, m.ref(), (const u32*)d_c, count, (u32*)d_workspace, 0);        \
+  HAFLO_LAUNCH((k_sum<LPT, T>), fin, st, m.ref(), (const u32*)d_workspace, (size_t)nb, (u32*)d_out, 1)
+  HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+  return hip_status(hipGetLastError());
+}
+
+}  // extern "C"

@@ -1,0 +1,193 @@
+// Fiber scheduler behind the CPU stand-in for the HIP runtime (tests only).
+#include <hip/hip_runtime.h>
+#include <sys/mman.h>
+#include <ucontext.h>
+#include <unistd.h>
+
+#include <map>
+#include <vector>
+
+namespace hipemu {
+
+namespace {
+constexpr int kWave = 64;
+constexpr size_t kStack = 256 * 1024;
+
+struct Lane {
+  LaneState st;
+  ucontext_t ctx;
+  bool done = false;
+  int wave = 0, lane = 0;
+  uint64_t ops = 0;  // cross-lane operations issued so far
+  char* stack = nullptr;
+};
+struct WaveSlots {
+  uint32_t val[2][kWave];
+  uint64_t op[2][kWave];
+};
+
+std::vector<Lane> lanes;
+std::vector<WaveSlots> waves;
+Lane* cur = nullptr;
+ucontext_t sched;
+const std::function<void()>* body = nullptr;
+int live = 0;
+int bar_arrived = 0;
+uint64_t bar_gen = 0;
+
+void die(const char* msg) {
+  fprintf(stderr, "hipemu: %s\n", msg);
+  fflush(stderr);
+  abort();
+}
+
+void yield() { swapcontext(&cur->ctx, &sched); }
+
+void trampoline() {
+  (*body)();
+  cur->done = true;
+  --live;
+}
+
+// publish v for this wave-wide operation, switch away, and return the table of
+// the values all 64 lanes published for the same operation
+const uint32_t* exchange(uint32_t v) {
+  Lane* me = cur;
+  WaveSlots& w = waves[me->wave];
+  int par = (int)(me->ops & 1);
+  uint64_t id = me->ops++;
+  w.val[par][me->lane] = v;
+  w.op[par][me->lane] = id;
+  yield();
+  int nl = (int)lanes.size();
+  for (int l = 0; l < kWave; ++l) {
+    int gl = me->wave * kWave + l;
+    if (gl >= nl) die("wave not fully populated");
+    if (w.op[par][l] != id) die("divergent cross-lane operation inside a wave (or a lane exited early)");
+  }
+  return w.val[par];
+}
+}  // namespace
+
+LaneState* current() { return &cur->st; }
+
+uint32_t bpermute(int byte_addr, uint32_t v) {
+  const uint32_t* t = exchange(v);
+  return t[((unsigned)byte_addr >> 2) & (kWave - 1)];
+}
+
+uint32_t dpp(uint32_t old, uint32_t src, int ctrl, bool bound_ctrl) {
+  int lane = cur->lane;
+  const uint32_t* t = exchange(src);
+  int row = lane & ~15, pos = lane & 15;
+  int from = -1;
+  if (ctrl >= 0x101 && ctrl <= 0x10f) {  // row_shl:n - lane i reads lane i+n
+    int s = pos + (ctrl - 0x100);
+    if (s < 16) from = row + s;
+  } else if (ctrl >= 0x111 && ctrl <= 0x11f) {  // row_shr:n - lane i reads lane i-n
+    int s = pos - (ctrl - 0x110);
+    if (s >= 0) from = row + s;
+  } else if (ctrl >= 0 && ctrl <= 0xff) {  // quad_perm
+    from = (lane & ~3) + ((ctrl >> (2 * (lane & 3))) & 3);
+  } else {
+    die("unsupported DPP control");
+  }
+  if (from < 0) return bound_ctrl ? 0u : old;
+  return t[from];
+}
+
+uint64_t ballot(bool p) {
+  const uint32_t* t = exchange(p ? 1u : 0u);
+  uint64_t m = 0;
+  for (int l = 0; l < kWave; ++l)
+    if (t[l]) m |= 1ull << l;
+  return m;
+}
+
+void barrier() {
+  uint64_t gen = bar_gen;
+  ++bar_arrived;
+  if (bar_arrived == live) {
+    bar_arrived = 0;
+    ++bar_gen;
+    return;
+  }
+  while (bar_gen == gen) yield();
+}
+
+void launch(dim3 grid, dim3 block, const std::function<void()>& fn) {
+  if (block.y != 1 || block.z != 1 || grid.y != 1 || grid.z != 1) die("only 1-D launches are emulated");
+  if (block.x == 0 || block.x % kWave) die("block size must be a multiple of 64");
+  if (cur) die("nested launch");
+  size_t nthreads = block.x;
+  if (lanes.size() != nthreads) {
+    for (Lane& l : lanes) free(l.stack);
+    lanes.assign(nthreads, Lane());
+    for (Lane& l : lanes) l.stack = (char*)malloc(kStack);
+  }
+  waves.assign(nthreads / kWave, WaveSlots());
+  body = &fn;
+  for (unsigned b = 0; b < grid.x; ++b) {
+    for (size_t t = 0; t < nthreads; ++t) {
+      Lane& l = lanes[t];
+      l.st.tid = dim3((unsigned)t);
+      l.st.bid = dim3(b);
+      l.st.bdim = block;
+      l.st.gdim = grid;
+      l.done = false;
+      l.ops = 0;
+      l.wave = (int)(t / kWave);
+      l.lane = (int)(t % kWave);
+      getcontext(&l.ctx);
+      l.ctx.uc_stack.ss_sp = l.stack;
+      l.ctx.uc_stack.ss_size = kStack;
+      l.ctx.uc_link = &sched;
+      makecontext(&l.ctx, trampoline, 0);
+    }
+    for (WaveSlots& w : waves) memset(&w, 0xff, sizeof(w));
+    live = (int)nthreads;
+    bar_arrived = 0;
+    while (live > 0) {
+      for (size_t t = 0; t < nthreads; ++t) {
+        if (lanes[t].done) continue;
+        cur = &lanes[t];
+        swapcontext(&sched, &lanes[t].ctx);
+      }
+    }
+    cur = nullptr;
+  }
+  body = nullptr;
+}
+
+// device memory: the buffer ends right at an inaccessible page
+namespace {
+std::map<void*, std::pair<void*, size_t>> allocs;
+}
+void* dev_alloc(size_t bytes) {
+  size_t page = (size_t)sysconf(_SC_PAGESIZE);
+  size_t want = (bytes + 15) & ~(size_t)15;
+  if (want == 0) want = 16;
+  size_t body_pages = (want + page - 1) / page;
+  size_t total = (body_pages + 1) * page;
+  char* base = (char*)mmap(nullptr, total, PROT_READ | PROT_WRITE, MAP_PRIVATE | MAP_ANONYMOUS, -1, 0);
+  if (base == MAP_FAILED) return nullptr;
+  mprotect(base + body_pages * page, page, PROT_NONE);
+  char* p = base + body_pages * page - want;
+  memset(base, 0xCD, body_pages * page);
+  allocs[p] = std::make_pair((void*)base, total);
+  return p;
+}
+void dev_free(void* p) {
+  auto it = allocs.find(p);
+  if (it == allocs.end()) return;
+  munmap(it->second.first, it->second.second);
+  allocs.erase(it);
+}
+
+}  // namespace hipemu
+
+// test harness entry points: guarded "device" buffers for the Python side
+extern "C" {
+void* hipemu_alloc(size_t bytes) { return hipemu::dev_alloc(bytes); }
+void hipemu_free(void* p) { hipemu::dev_free(p); }
+}
