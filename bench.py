@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the Paillier operator path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B] [--features F] [--bits 2048]
+
+One step is one pass of the whole hot path over one batch of synthetic
+federated-LR-shaped input, with everything resident in HBM before timing:
+
+    encode residuals -> encrypt -> add another party's ciphertexts ->
+    scalar multiply -> X^T [[d]] -> X [[w]] -> decrypt -> decode
+
+at a 2048-bit key (the key size the headline metric is quoted on). The
+headline value is full-length modular exponentiations (2048-bit exponent,
+4096-bit modulus: the r^n of every encryption) per second over the whole step
+time. The JSON line also carries the rate of the encrypted-gradient product,
+the roofline of the dominant kernel (encryption) against the chip's 32-bit
+integer multiply-add issue rate, and the CPU oracle timed on the host cores
+on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X: 256 compute units x 64 lanes x one v_mad_u64_u32 per lane per clock at 2.4 GHz
+# (32x32+64 integer multiply-add issues at the full VALU rate on gfx950).
+PEAK_MAD32_PER_S = 256 * 64 * 2.4e9
+
+
+def montmul_mul32(limbs):
+    """32x32->64 multiply-adds of one word-serial Montgomery product on `limbs` 32-bit limbs."""
+    return 2 * limbs * limbs + limbs
+
+
+def _oracle_encrypt_chunk(args):
+    from oracle import paillier_oracle as O
+    n, ms, rs = args
+    pk = O.PublicKey(n)
+    t0 = time.perf_counter()
+    out = [O.encrypt(pk, m, r) for m, r in zip(ms, rs)]
+    return time.perf_counter() - t0, out
+
+
+def cpu_baseline(n, ms, rs, want):
+    """The oracle's encryption (the same r^n modexp the GPU headline counts) on all host cores."""
+    import multiprocessing as mp
+    cores = max(1, min(16, os.cpu_count() or 1))
+    per = max(1, len(ms) // cores)
+    chunks = [(n, ms[i * per:(i + 1) * per], rs[i * per:(i + 1) * per]) for i in range(cores)]
+    chunks = [c for c in chunks if c[1]]
+    with mp.get_context("spawn").Pool(len(chunks)) as pool:
+        t0 = time.perf_counter()
+        res = pool.map(_oracle_encrypt_chunk, chunks)
+        wall = time.perf_counter() - t0
+    done = sum(len(c[1]) for c in chunks)
+    got = [c for _, part in res for c in part]
+    assert got == want[:done], "GPU encryption disagrees with the oracle on the timed sample"
+    return {"value": done / wall, "unit": "modexp/s", "cores": len(chunks), "kind": "oracle",
+            "sample": "%d encryptions (2048-bit r^n mod n^2) of the step's first elements, python int pow, "
+                      "%.1f core-seconds" % (done, sum(t for t, _ in res))}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--batch", type=int, default=65536)
+    ap.add_argument("--features", type=int, default=32)
+    ap.add_argument("--bits", type=int, default=2048)
+    ap.add_argument("--cpu-sample", type=int, default=192)
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2107_13797_amd import _cabi, api, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    bits, B, F = args.bits, args.batch, args.features
+    seed = synth.BASE_SEED + bits
+    p, q = api.haflo_keygen(bits, seed)
+    n = p * q
+    ctx = api.haflo_ctx_create_private(p, q, bits)
+    lp = bits // 32
+
+    def dev(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint32:
+            a = a.view(np.int32)
+        return torch.from_numpy(a).cuda()
+
+    # synthetic inputs (hetero-LR shapes: residuals ~N(0, 0.25) at 2^24, features ~N(0,1) at 2^16,
+    # a sparse forward-pass matrix with 70% zeros at 2^16), all resident before timing
+    rng = np.random.default_rng(seed)
+    d = dev(synth.normal_f32(B, 0.25, seed + 1))
+    r_words = rng.integers(0, 2 ** 32, size=(B, lp), dtype=np.uint32)
+    r_words[:, -1] &= 0x7FFFFFFF
+    r = dev(r_words)
+    Xg = api.haflo_encode_exponents_f32(dev(synth.normal_f32((B, F), 1.0, seed + 2)), 16)
+    Xw = api.haflo_encode_exponents_f32(dev(synth.sparse_uniform_f32((B, F), 0.7, seed + 3)), 16)
+    other = api.haflo_encrypt(ctx, api.haflo_encode_f32(ctx, dev(synth.normal_f32(B, 0.25, seed + 4)), 24),
+                              dev(np.roll(r_words, 1, axis=0)))
+    wc = api.haflo_encrypt(ctx, api.haflo_encode_f32(ctx, dev(synth.normal_f32(F, 0.1, seed + 5)), 24),
+                           dev(r_words[:F]))
+    k_quarter = 1 << 6  # the fore-gradient's factor 0.25 at 2^8, keeps decoded sums inside int64
+    torch.cuda.synchronize()
+
+    stages = ("encode", "encrypt", "add", "scalar_mul", "matvec_xt_d", "matvec_x_w", "decrypt", "decode")
+    # HIP events on torch's current stream, which is the stream every kernel is launched on
+    events = [{name: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for name in stages}
+              for _ in range(args.steps)]
+    stage_ms = {name: 0.0 for name in stages}
+    keep = {}
+
+    def step(ev):
+        record = ev is not None
+
+        def timed(name, fn):
+            if record:
+                ev[name][0].record()
+            out = fn()
+            if record:
+                ev[name][1].record()
+            return out
+        plain = timed("encode", lambda: api.haflo_encode_f32(ctx, d, 24))
+        c = timed("encrypt", lambda: api.haflo_encrypt(ctx, plain, r))
+        s = timed("add", lambda: api.haflo_add(ctx, c, other))
+        fg = timed("scalar_mul", lambda: api.haflo_scalar_mul_i64_bcast(ctx, s, k_quarter))
+        grad = timed("matvec_xt_d", lambda: api.haflo_cipher_matvec(ctx, 0, fg, Xg))
+        fwd = timed("matvec_x_w", lambda: api.haflo_cipher_matvec(ctx, 1, wc, Xw))
+        both = torch.cat([fwd[:4096], grad], dim=0)
+        pl = timed("decrypt", lambda: api.haflo_decrypt(ctx, both))
+        qv = timed("decode", lambda: (api.haflo_decode(ctx, pl[:4096], 40), api.haflo_decode(ctx, pl[4096:], 48)))
+        keep["c"], keep["q"] = c, qv
+
+    for _ in range(args.warmup):
+        step(None)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for ev in events:
+        for name in stages:
+            stage_ms[name] += ev[name][0].elapsed_time(ev[name][1])
+
+    ms_per_step = wall * 1e3 / args.steps
+    modexp_per_s = B * args.steps / wall
+    enc_ms = stage_ms["encrypt"] / args.steps
+    mm, limbs = api.haflo_op_cost(ctx, _cabi.OP_ENCRYPT)
+    algo_mad = B * mm * montmul_mul32(limbs)
+    achieved = algo_mad / (enc_ms * 1e-3)
+    out = {
+        "metric": "Paillier modexp/s at 2048-bit n; encrypted X^T[[d]] entries/s",
+        "value": modexp_per_s,
+        "unit": "modexp/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32 limbs (32x32+64 integer multiply-add)",
+        "data": "synthetic",
+        "config": {"workload": "hetero-LR step at a %d-bit key: encode, encrypt, add, scalar_mul, X^T[[d]], "
+                               "X[[w]], decrypt, decode" % bits,
+                   "n_bits": bits, "batch": B, "features": F},
+        "xt_d_entries_per_s": B * F / (stage_ms["matvec_xt_d"] / args.steps * 1e-3),
+        "encrypt_per_s": B / (enc_ms * 1e-3),
+        "stage_ms": {k: v / args.steps for k, v in stage_ms.items()},
+        "roofline": {"bound": "alu", "kernel": "k_encrypt", "achieved": achieved / 1e12,
+                     "peak": PEAK_MAD32_PER_S / 1e12, "unit": "Tmad32/s", "frac": achieved / PEAK_MAD32_PER_S,
+                     "traffic": None,
+                     "algorithmic": "%d Montgomery products x (2*%d^2+%d) mul32 per encryption" % (mm, limbs, limbs)},
+    }
+    if not args.no_cpu:
+        k = min(args.cpu_sample, B)
+        from paper_2107_13797_amd import synth as _s
+        ms = _s.words_to_ints(api.haflo_encode_f32(ctx, d[:k].contiguous(), 24).cpu().numpy())
+        rs = _s.words_to_ints(r_words[:k])
+        want = _s.words_to_ints(api.haflo_export_cipher(ctx, keep["c"][:k].contiguous()).cpu().numpy())
+        out["cpu_baseline"] = cpu_baseline(n, ms, rs, want)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

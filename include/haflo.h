@@ -106,6 +106,14 @@ int haflo_ctx_destroy(haflo_ctx* ctx);
 int haflo_ctx_info(const haflo_ctx* ctx, uint32_t* n_bits, uint32_t* cipher_limbs, uint32_t* plain_limbs,
                    size_t* cipher_bytes_internal, size_t* plain_bytes);
 
+/* Arithmetic cost of one element of an operator, for throughput accounting:
+ * the number of Montgomery products the library's schedule executes per
+ * element (exponentiation windows and table building included) and the size,
+ * in 32-bit limbs, of the modulus they run on. Defined for HAFLO_OP_ENCRYPT
+ * (modulus n^2) and HAFLO_OP_DECRYPT (the sum over both prime-power branches,
+ * modulus size of p^2). Either output may be NULL. */
+int haflo_op_cost(const haflo_ctx* ctx, int op, uint64_t* montmuls, uint32_t* modulus_limbs);
+
 /* Workspace needed by an operator call of the given shape. For element-wise
  * operators `rows` is the element count and `cols` is ignored; for the matvecs
  * they are the matrix shape. Returns 0 for operators that need none and

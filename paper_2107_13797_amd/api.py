@@ -117,6 +117,13 @@ def haflo_workspace_bytes(ctx, op, rows, cols=0):
     return lib().haflo_workspace_bytes(ctx.handle, op, rows, cols)
 
 
+def haflo_op_cost(ctx, op):
+    """(Montgomery products per element, 32-bit limbs of their modulus)."""
+    mm, limbs = C.c_uint64(), C.c_uint32()
+    _check(lib().haflo_op_cost(ctx.handle, op, C.byref(mm), C.byref(limbs)))
+    return mm.value, limbs.value
+
+
 def _new_cipher(ctx, count):
     return torch.empty((count, ctx.cipher_words), dtype=torch.int32, device="cuda")
 

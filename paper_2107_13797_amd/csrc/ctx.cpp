@@ -382,4 +382,25 @@ int haflo_ctx_info(const haflo_ctx* ctx, uint32_t* n_bits, uint32_t* cipher_limb
   return HAFLO_OK;
 }
 
+int haflo_op_cost(const haflo_ctx* ctx, int op, uint64_t* montmuls, uint32_t* modulus_limbs) {
+  if (!ctx) return HAFLO_EINVAL;
+  uint64_t mm = 0;
+  uint32_t limbs = 0;
+  if (op == HAFLO_OP_ENCRYPT) {
+    // into Montgomery form, the power r^n, (1 + m n) R, the final product
+    mm = ctx->sched_n.h.nsquare + ctx->sched_n.h.nmul + 3;
+    limbs = (uint32_t)ctx->lc;
+  } else if (op == HAFLO_OP_DECRYPT) {
+    if (!ctx->has_priv) return HAFLO_ENOPRIV;
+    // per branch: two products to reduce into Montgomery form, the power, one product out
+    mm = ctx->sched_pm1.h.nsquare + ctx->sched_pm1.h.nmul + ctx->sched_qm1.h.nsquare + ctx->sched_qm1.h.nmul + 6;
+    limbs = (uint32_t)ctx->lc / 2;
+  } else {
+    return HAFLO_EINVAL;
+  }
+  if (montmuls) *montmuls = mm;
+  if (modulus_limbs) *modulus_limbs = limbs;
+  return HAFLO_OK;
+}
+
 }  // extern "C"

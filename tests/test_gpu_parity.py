@@ -1,0 +1,411 @@
+"""Parity of the HIP path with the CPU oracle, through the C boundary, on the
+five benchmark configurations plus edge cases. Everything here needs a GPU.
+
+Levels of agreement checked wherever an oracle value is computed: exported
+canonical ciphertext limbs, decrypted plaintext residues, decoded integers -
+all bit-exact. Where the full oracle run would take hours (configurations 3-5)
+ciphertext parity is checked on a seeded sample that always contains the first
+and last element and elements next to wavefront and workgroup boundaries, and
+every output is checked through the plaintext identity D(out) = sum x_i m_i
+(mod n) with exact Python integers.
+"""
+import math
+import random
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from conftest import oracle_key  # noqa: E402
+from oracle import paillier_oracle as O  # noqa: E402
+from paper_2107_13797_amd import synth  # noqa: E402
+
+import oracle_pool as OP  # noqa: E402
+
+
+def say(*a):
+    print(*a)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def api():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2107_13797_amd import api as _api
+    _api.lib()
+    return _api
+
+
+_CTX = {}
+
+
+def context(api, bits):
+    if bits not in _CTX:
+        p, q = oracle_key(bits)
+        _CTX[bits] = (api.haflo_ctx_create_private(p, q, bits), O.PrivateKey(p, q))
+    return _CTX[bits]
+
+
+from helpers import dev_to_ints, ints_to_dev, random_units_words, to_dev  # noqa: E402
+
+
+def sample_indices(count, k, seed):
+    """k seeded indices that always include the ends and the neighbours of
+    64-lane and 256-lane boundaries."""
+    fixed = {0, 1, count - 1, count - 2, 7, 8, 15, 16, 31, 32, 63, 64, 255, 256, 257, count // 2}
+    fixed = {i for i in fixed if 0 <= i < count}
+    rng = random.Random(seed)
+    while len(fixed) < min(k, count):
+        fixed.add(rng.randrange(count))
+    return sorted(fixed)
+
+
+# ---------------------------------------------------------------------------
+# configuration 1: operator mix at a 1024-bit key, everything compared
+# ---------------------------------------------------------------------------
+def test_cfg1_operator_mix_full_parity(api):
+    cfg = synth.CONFIGS[1]
+    bits, count = cfg["n_bits"], cfg["count"]
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n, nsq = pk.n, pk.nsq
+    lp = bits // 32
+    ms = synth.uniform_below(n, count, synth.seed_for(1, 0))
+    rs = synth.units_below(n, count, synth.seed_for(1, 1))
+    ks = synth.uniform_u64(count, synth.seed_for(1, 2))
+    say("cfg1: encrypt")
+    c = api.haflo_encrypt(ctx, ints_to_dev(ms, lp), ints_to_dev(rs, lp))
+    want_c = OP.encrypt_many(n, ms, rs)
+    assert dev_to_ints(api.haflo_export_cipher(ctx, c)) == want_c
+    say("cfg1: add")
+    rolled = torch.roll(c, shifts=-1, dims=0).contiguous()
+    s = api.haflo_add(ctx, c, rolled)
+    want_s = [want_c[i] * want_c[(i + 1) % count] % nsq for i in range(count)]
+    assert dev_to_ints(api.haflo_export_cipher(ctx, s)) == want_s
+    say("cfg1: scalar_mul")
+    kt = to_dev(np.array(ks, dtype=np.uint64))
+    e = api.haflo_scalar_mul_u64(ctx, c, kt)
+    want_e = OP.pow_many(n, want_c, ks)
+    assert dev_to_ints(api.haflo_export_cipher(ctx, e)) == want_e
+    say("cfg1: decrypt")
+    allc = torch.cat([c, s, e], dim=0).contiguous()
+    got = dev_to_ints(api.haflo_decrypt(ctx, allc))
+    assert got[:count] == ms
+    assert got[count:2 * count] == [(ms[i] + ms[(i + 1) % count]) % n for i in range(count)]
+    assert got[2 * count:] == [m * k % n for m, k in zip(ms, ks)]
+    assert got == OP.decrypt_many(sk.p, sk.q, want_c + want_s + want_e)
+
+
+# ---------------------------------------------------------------------------
+# configuration 2: hetero-LR encrypted gradient at a 1024-bit key, everything compared
+# ---------------------------------------------------------------------------
+def test_cfg2_encrypted_gradient_full_parity(api):
+    cfg = synth.CONFIGS[2]
+    bits, rows, cols = cfg["n_bits"], cfg["rows"], cfg["cols"]
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n = pk.n
+    lp = bits // 32
+    d = synth.normal_f32(rows, cfg["d_sigma"], synth.seed_for(2, 0))
+    Xf = synth.normal_f32((rows, cols), 1.0, synth.seed_for(2, 1))
+    rs = synth.units_below(n, rows, synth.seed_for(2, 2))
+    say("cfg2: encode")
+    st = torch.zeros(rows, dtype=torch.int32, device="cuda")
+    plain = api.haflo_encode_f32(ctx, to_dev(d), cfg["scale_d"], st)
+    enc = [O.encode(pk, float(v), cfg["scale_d"]) for v in d]
+    md = [m for m, _ in enc]
+    assert dev_to_ints(plain) == md and st.cpu().tolist() == [s for _, s in enc]
+    stx = torch.zeros((rows, cols), dtype=torch.int32, device="cuda")
+    X = api.haflo_encode_exponents_f32(to_dev(Xf), cfg["scale_x"], stx)
+    Xo = [[O.encode_exponent(float(v), cfg["scale_x"])[0] for v in row] for row in Xf]
+    assert X.cpu().tolist() == Xo and int(stx.abs().sum()) == 0
+    say("cfg2: encrypt")
+    c = api.haflo_encrypt(ctx, plain, ints_to_dev(rs, lp))
+    want_c = OP.encrypt_many(n, md, rs)
+    assert dev_to_ints(api.haflo_export_cipher(ctx, c)) == want_c
+    say("cfg2: matvec")
+    out = api.haflo_cipher_matvec(ctx, 0, c, X)
+    want_out = OP.matvec_cols(n, want_c, [[row[j] for row in Xo] for j in range(cols)])
+    assert dev_to_ints(api.haflo_export_cipher(ctx, out)) == want_out
+    say("cfg2: decrypt + decode")
+    pl = api.haflo_decrypt(ctx, out)
+    qd = [O.quantise(float(v), cfg["scale_d"]) for v in d]
+    exact = [sum(Xo[i][j] * qd[i] for i in range(rows)) for j in range(cols)]
+    assert dev_to_ints(pl) == [e % n for e in exact]
+    q, v = api.haflo_decode(ctx, pl, cfg["scale_d"] + cfg["scale_x"])
+    assert q.cpu().tolist() == exact
+    assert v.cpu().tolist() == [math.ldexp(float(e), -(cfg["scale_d"] + cfg["scale_x"])) for e in exact]
+
+
+# ---------------------------------------------------------------------------
+# configuration 3: encrypted forward pass at a 2048-bit key
+# ---------------------------------------------------------------------------
+def test_cfg3_forward_pass(api):
+    cfg = synth.CONFIGS[3]
+    bits, rows, cols = cfg["n_bits"], cfg["rows"], cfg["cols"]
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n = pk.n
+    lp = bits // 32
+    w = synth.normal_f32(cols, cfg["w_sigma"], synth.seed_for(3, 0))
+    Xf = synth.sparse_uniform_f32((rows, cols), cfg["zero_frac"], synth.seed_for(3, 1))
+    rs = synth.units_below(n, cols, synth.seed_for(3, 2))
+    plain = api.haflo_encode_f32(ctx, to_dev(w), cfg["scale_w"])
+    qw = [O.quantise(float(v), cfg["scale_w"]) for v in w]
+    assert dev_to_ints(plain) == [q % n for q in qw]
+    say("cfg3: encrypt")
+    c = api.haflo_encrypt(ctx, plain, ints_to_dev(rs, lp))
+    want_c = OP.encrypt_many(n, [q % n for q in qw], rs)
+    assert dev_to_ints(api.haflo_export_cipher(ctx, c)) == want_c
+    X = api.haflo_encode_exponents_f32(to_dev(Xf), cfg["scale_x"])
+    Xo = np.rint(Xf.astype(np.float64) * 2.0 ** cfg["scale_x"]).astype(np.int64)
+    assert np.array_equal(X.cpu().numpy().astype(np.int64), Xo)
+    say("cfg3: matvec (full size)")
+    out = api.haflo_cipher_matvec(ctx, 1, c, X)
+    say("cfg3: sampled ciphertext parity")
+    idx = sample_indices(rows, 1024, synth.seed_for(3, 3))
+    got = dev_to_ints(api.haflo_export_cipher(ctx, out[torch.tensor(idx, device="cuda")].contiguous()))
+    want = OP.matvec_rows(n, want_c, [Xo[i].tolist() for i in idx])
+    assert got == want
+    say("cfg3: plaintext identity on every row")
+    pl = dev_to_ints(api.haflo_decrypt(ctx, out))
+    qw_arr = np.array(qw, dtype=object)
+    exact = [int(np.dot(Xo[i].astype(object), qw_arr)) for i in range(rows)]
+    assert pl == [e % n for e in exact]
+    q, _ = api.haflo_decode(ctx, api.haflo_decrypt(ctx, out), cfg["scale_w"] + cfg["scale_x"])
+    assert q.cpu().tolist() == exact
+
+
+# ---------------------------------------------------------------------------
+# configuration 4: homo-LR aggregation at a 2048-bit key, full size
+# ---------------------------------------------------------------------------
+def test_cfg4_aggregation_full_size(api):
+    cfg = synth.CONFIGS[4]
+    bits, parties, count = cfg["n_bits"], cfg["parties"], cfg["count"]
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n, nsq = pk.n, pk.nsq
+    k = 1 << (cfg["inv_parties_scale"] - 3)  # 1/8 in fixed point
+    idx = sample_indices(count, 256, synth.seed_for(4, 9))
+    idx_t = torch.tensor(idx, device="cuda")
+    acc = None
+    qsum = np.zeros(count, dtype=np.int64)
+    want_acc = None
+    for party in range(parties):
+        say("cfg4: party", party)
+        w = synth.normal_f32(count, cfg["w_sigma"], synth.seed_for(4, party))
+        r_words = random_units_words(count, bits, synth.seed_for(4, 100 + party))
+        qsum += np.rint(w.astype(np.float64) * 2.0 ** cfg["scale_w"]).astype(np.int64)
+        plain = api.haflo_encode_f32(ctx, to_dev(w), cfg["scale_w"])
+        c = api.haflo_encrypt(ctx, plain, to_dev(r_words))
+        # sampled ciphertext parity of this party's encryptions
+        ms = [O.encode(pk, float(w[i]), cfg["scale_w"])[0] for i in idx]
+        rs = synth.words_to_ints(r_words[idx])
+        want_c = OP.encrypt_many(n, ms, rs)
+        assert dev_to_ints(api.haflo_export_cipher(ctx, c[idx_t].contiguous())) == want_c
+        if acc is None:
+            acc, want_acc = c, want_c
+        else:
+            acc = api.haflo_add(ctx, acc, c, out=acc)
+            want_acc = [a * b % nsq for a, b in zip(want_acc, want_c)]
+        del plain, c
+    say("cfg4: scalar multiply by 2^21 and decrypt")
+    assert dev_to_ints(api.haflo_export_cipher(ctx, acc[idx_t].contiguous())) == want_acc
+    avg = api.haflo_scalar_mul_i64_bcast(ctx, acc, k)
+    want_avg = OP.pow_many(n, want_acc, [k] * len(idx))
+    assert dev_to_ints(api.haflo_export_cipher(ctx, avg[idx_t].contiguous())) == want_avg
+    pl = api.haflo_decrypt(ctx, avg)
+    assert dev_to_ints(pl[idx_t].contiguous()) == OP.decrypt_many(sk.p, sk.q, want_avg)
+    q, v = api.haflo_decode(ctx, pl, cfg["scale_w"] + cfg["inv_parties_scale"])
+    assert np.array_equal(q.cpu().numpy(), qsum * k)
+    assert np.array_equal(v.cpu().numpy(), (qsum * k).astype(np.float64) / 2.0 ** 48)
+
+
+# ---------------------------------------------------------------------------
+# configuration 5: large-key gradient at a 4096-bit key
+# ---------------------------------------------------------------------------
+def test_cfg5_large_key_gradient(api):
+    cfg = synth.CONFIGS[5]
+    bits, rows, cols = cfg["n_bits"], cfg["rows"], cfg["cols"]
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n = pk.n
+    d = synth.normal_f32(rows, cfg["d_sigma"], synth.seed_for(5, 0))
+    Xf = synth.normal_f32((rows, cols), 1.0, synth.seed_for(5, 1))
+    r_words = random_units_words(rows, bits, synth.seed_for(5, 2))
+    plain = api.haflo_encode_f32(ctx, to_dev(d), cfg["scale_d"])
+    say("cfg5: encrypt (full size)")
+    c = api.haflo_encrypt(ctx, plain, to_dev(r_words))
+    idx = sample_indices(rows, 256, synth.seed_for(5, 3))
+    idx_t = torch.tensor(idx, device="cuda")
+    qd = np.rint(d.astype(np.float64) * 2.0 ** cfg["scale_d"]).astype(np.int64)
+    want_c = OP.encrypt_many(n, [int(qd[i]) % n for i in idx], synth.words_to_ints(r_words[idx]))
+    assert dev_to_ints(api.haflo_export_cipher(ctx, c[idx_t].contiguous())) == want_c
+    X = api.haflo_encode_exponents_f32(to_dev(Xf), cfg["scale_x"])
+    Xo = np.rint(Xf.astype(np.float64) * 2.0 ** cfg["scale_x"]).astype(np.int64)
+    assert np.array_equal(X.cpu().numpy().astype(np.int64), Xo)
+    say("cfg5: reduced matvec with ciphertext parity")
+    sub_rows, sub_cols = 2048, 8
+    sub_idx = idx[:16] + list(range(300, 300 + sub_rows - 16))
+    sub_idx_t = torch.tensor(sub_idx, device="cuda")
+    sub_c = c[sub_idx_t].contiguous()
+    sub_X = X[sub_idx_t][:, :sub_cols].contiguous()
+    sub_out = api.haflo_cipher_matvec(ctx, 0, sub_c, sub_X)
+    # the oracle needs these 2048 ciphertexts: take the 16 already checked plus GPU exports of
+    # the rest, whose encryption path is the one checked on the sample above
+    sub_c_int = dev_to_ints(api.haflo_export_cipher(ctx, sub_c))
+    assert sub_c_int[:16] == want_c[:16]
+    want_sub = OP.matvec_cols(n, sub_c_int, [Xo[sub_idx, j].tolist() for j in range(sub_cols)])
+    assert dev_to_ints(api.haflo_export_cipher(ctx, sub_out)) == want_sub
+    say("cfg5: full matvec, plaintext identity on every output")
+    out = api.haflo_cipher_matvec(ctx, 0, c, X)
+    pl = api.haflo_decrypt(ctx, out)
+    qd_obj = qd.astype(object)
+    exact = [int(np.dot(Xo[:, j].astype(object), qd_obj)) for j in range(cols)]
+    assert dev_to_ints(pl) == [e % n for e in exact]
+    q, _ = api.haflo_decode(ctx, pl, cfg["scale_d"] + cfg["scale_x"])
+    assert q.cpu().tolist() == exact
+    assert dev_to_ints(pl) == OP.decrypt_many(sk.p, sk.q, dev_to_ints(api.haflo_export_cipher(ctx, out)))
+
+
+# ---------------------------------------------------------------------------
+# edge cases
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", [512, 1024, 2048])
+def test_edges_import_export_add(api, bits):
+    ctx, sk = context(api, bits)
+    n, nsq = sk.n, sk.n ** 2
+    lc = bits // 16
+    rng = random.Random(bits)
+    for count in (1, 2, 63, 64, 65, 257, 1000):
+        cs = [rng.randrange(nsq) for _ in range(count)]
+        cs[0] = 0
+        cs[-1] = nsq - 1
+        if count > 2:
+            cs[1] = 1
+        ci = api.haflo_import_cipher(ctx, ints_to_dev(cs, lc))
+        assert dev_to_ints(api.haflo_export_cipher(ctx, ci)) == cs
+        s = api.haflo_add(ctx, ci, ci)
+        assert dev_to_ints(api.haflo_export_cipher(ctx, s)) == [c * c % nsq for c in cs]
+    # values >= n^2 are rejected and imported as 0
+    st = torch.zeros(1, dtype=torch.int32, device="cuda")
+    bad = [nsq, 5, (1 << (32 * lc)) - 1]
+    ci = api.haflo_import_cipher(ctx, ints_to_dev(bad, lc), st)
+    assert dev_to_ints(api.haflo_export_cipher(ctx, ci)) == [0, 5, 0] and int(st[0]) == 1
+    # empty batches are accepted
+    empty = torch.empty((0, ctx.cipher_words), dtype=torch.int32, device="cuda")
+    assert api.haflo_add(ctx, empty, empty).shape[0] == 0
+    assert api.haflo_export_cipher(ctx, empty).shape[0] == 0
+
+
+def test_edges_encrypt_decrypt(api):
+    bits = 1024
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n = pk.n
+    lp = bits // 32
+    ms = [0, 1, n - 1, n // 2, n // 2 + 1, 2 ** 64, n - 2 ** 63]
+    rs = [1, n - 1, 2, 3, n - 2, 12345, 1]
+    c = api.haflo_encrypt(ctx, ints_to_dev(ms, lp), ints_to_dev(rs, lp))
+    assert dev_to_ints(api.haflo_export_cipher(ctx, c)) == [O.encrypt(pk, m, r) for m, r in zip(ms, rs)]
+    assert dev_to_ints(api.haflo_decrypt(ctx, c)) == ms
+    # decrypting arbitrary imported units agrees with the plain lambda/mu definition
+    rng = random.Random(4)
+    cs = [rng.randrange(1, n * n) for _ in range(9)] + [1]
+    ci = api.haflo_import_cipher(ctx, ints_to_dev(cs, bits // 16))
+    assert dev_to_ints(api.haflo_decrypt(ctx, ci)) == [O.decrypt(sk, c_) for c_ in cs]
+    # a public-only context refuses to decrypt
+    pub = api.haflo_ctx_create_public(n, bits)
+    with pytest.raises(api.HafloError):
+        api.haflo_decrypt(pub, c)
+    c2 = api.haflo_encrypt(pub, ints_to_dev(ms, lp), ints_to_dev(rs, lp))
+    assert torch.equal(c, c2)
+    pub.close()
+
+
+def test_edges_scalar_mul(api):
+    bits = 1024
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n = pk.n
+    rng = random.Random(6)
+    cs = [O.encrypt(pk, rng.randrange(n), rng.randrange(1, n)) for _ in range(5)]
+    ci = api.haflo_import_cipher(ctx, ints_to_dev(cs, bits // 16))
+    for k in (0, 1, 2, 3, 2 ** 21, 2 ** 62 + 12345, 2 ** 63 - 1, -1, -2, -(2 ** 63)):
+        out = api.haflo_scalar_mul_i64_bcast(ctx, ci, k)
+        assert dev_to_ints(api.haflo_export_cipher(ctx, out)) == [O.scalar_mul(pk, c, k) for c in cs], k
+    ks = [0, 1, 2 ** 64 - 1, 2 ** 63, 0xF0F0F0F0F0F0F0F0]
+    out = api.haflo_scalar_mul_u64(ctx, ci, to_dev(np.array(ks, dtype=np.uint64)))
+    assert dev_to_ints(api.haflo_export_cipher(ctx, out)) == [pow(c, k, n * n) for c, k in zip(cs, ks)]
+
+
+@pytest.mark.parametrize("bits", [512, 2048])
+def test_edges_matvec(api, bits):
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n = pk.n
+    rng = random.Random(8)
+    nc = 70
+    cs = [O.encrypt(pk, rng.randrange(n), rng.randrange(1, n)) for _ in range(nc)]
+    ci = api.haflo_import_cipher(ctx, ints_to_dev(cs, bits // 16))
+    npr = np.random.default_rng(3)
+    cases = []
+    X = npr.integers(-(2 ** 19), 2 ** 19, size=(nc, 3)).astype(np.int32)
+    X[:, 2] = 0                        # an all-zero column -> 1
+    X[5, 0] = -2 ** 31                 # most negative exponent
+    X[6, 1] = 2 ** 31 - 1
+    cases.append((0, X))
+    cases.append((0, np.ones((nc, 1), dtype=np.int32)))          # summation
+    cases.append((0, -np.ones((nc, 1), dtype=np.int32)))         # inverse of the product
+    cases.append((0, np.zeros((nc, 2), dtype=np.int32)))
+    Y = npr.integers(-(2 ** 16), 2 ** 16, size=(67, nc)).astype(np.int32)
+    Y[npr.random(Y.shape) < 0.7] = 0
+    Y[3, :] = 0                        # an empty row -> 1
+    Y[4, :] = 1
+    cases.append((1, Y))
+    cases.append((1, np.eye(nc, dtype=np.int32)[:9]))
+    for orientation, M in cases:
+        out = api.haflo_cipher_matvec(ctx, orientation, ci, to_dev(M))
+        assert dev_to_ints(api.haflo_export_cipher(ctx, out)) == O.matvec(pk, orientation, cs, M.tolist())
+    s = api.haflo_cipher_sum(ctx, ci)
+    assert dev_to_ints(api.haflo_export_cipher(ctx, s)) == [O.summation(pk, cs)]
+    s1 = api.haflo_cipher_sum(ctx, ci[:1].contiguous())
+    assert dev_to_ints(api.haflo_export_cipher(ctx, s1)) == cs[:1]
+
+
+def test_edges_encode_decode(api):
+    bits = 1024
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n = pk.n
+    vals = np.concatenate([
+        np.array([0.0, -0.0, 1.0, -1.0, 0.5, -0.5, np.inf, -np.inf, np.nan, 3.4e38, -3.4e38, 1e-45, -1e-45,
+                  1.5 * 2.0 ** -24, 2.5 * 2.0 ** -24, -1.5 * 2.0 ** -24, -2.5 * 2.0 ** -24, 2.0 ** 38, -(2.0 ** 39),
+                  2.0 ** 39], dtype=np.float32),
+        synth.normal_f32(5000, 0.25, 77)])
+    for s in (0, 16, 24, 40):
+        st = torch.full((len(vals),), 7, dtype=torch.int32, device="cuda")
+        pl = api.haflo_encode_f32(ctx, to_dev(vals), s, st)
+        want = [O.encode(pk, float(v), s) for v in vals]
+        assert dev_to_ints(pl) == [m for m, _ in want]
+        assert st.cpu().tolist() == [f for _, f in want]
+        q, v = api.haflo_decode(ctx, pl, s, st)
+        wd = [O.decode(pk, m, s) for m, _ in want]
+        assert q.cpu().tolist() == [a for a, _, _ in wd]
+        assert v.cpu().tolist() == [b for _, b, _ in wd]
+        assert st.cpu().tolist() == [c for _, _, c in wd]
+        ste = torch.zeros(len(vals), dtype=torch.int32, device="cuda")
+        e = api.haflo_encode_exponents_f32(to_dev(vals), s, ste)
+        we = [O.encode_exponent(float(x), s) for x in vals]
+        assert e.cpu().tolist() == [a for a, _ in we] and ste.cpu().tolist() == [b for _, b in we]
+    edge = [n // 2, n // 2 + 1, 2 ** 63 - 1, 2 ** 63, n - 2 ** 63, n - 2 ** 63 - 1, n - 1, 0, 1 << 64, n - (1 << 64),
+            (1 << 64) - 1, n - (1 << 64) + 1]
+    st = torch.zeros(len(edge), dtype=torch.int32, device="cuda")
+    q, v = api.haflo_decode(ctx, ints_to_dev(edge, bits // 32), 40, st)
+    wd = [O.decode(pk, m, 40) for m in edge]
+    assert list(zip(q.cpu().tolist(), v.cpu().tolist(), st.cpu().tolist())) == wd

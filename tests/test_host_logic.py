@@ -1,0 +1,96 @@
+"""CPU-only checks of the shipped library: it loads, exports every symbol the
+header declares, its host-side key generation agrees with the oracle's
+independent implementation, and argument errors come back as error codes."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from conftest import ROOT
+from oracle import paillier_oracle as O
+from paper_2107_13797_amd import _cabi
+
+LIB_PATH = os.path.join(ROOT, "paper_2107_13797_amd", "libhaflo.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB_PATH):
+        from paper_2107_13797_amd import build
+        build.build_library(verbose=False)
+    return _cabi.bind(C.CDLL(LIB_PATH))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "haflo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(haflo_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_prototypes_agree():
+    assert set(declared_symbols()) == set(_cabi.PROTOTYPES)
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+
+
+def test_strerror(lib):
+    assert lib.haflo_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -5, -99):
+        assert lib.haflo_strerror(code)
+
+
+@pytest.mark.parametrize("bits,seed", [(512, 1), (512, 2), (512, 77), (512, 2 ** 63 + 5), (1024, 1), (1024, 31337),
+                                       (2048, 5)])
+def test_keygen_matches_oracle(lib, bits, seed):
+    p = (C.c_uint8 * (bits // 16))()
+    q = (C.c_uint8 * (bits // 16))()
+    assert lib.haflo_keygen(bits, seed, p, q) == 0
+    got = (int.from_bytes(bytes(p), "little"), int.from_bytes(bytes(q), "little"))
+    assert got == O.keygen(bits, seed)
+
+
+def test_argument_errors_without_gpu(lib):
+    buf = (C.c_uint8 * 64)()
+    out = C.c_void_p()
+    assert lib.haflo_keygen(1000, 1, buf, buf) == -1
+    assert lib.haflo_keygen(512, 1, None, buf) == -1
+    assert lib.haflo_ctx_create_public(None, 512, C.byref(out)) == -1
+    assert lib.haflo_ctx_create_public(buf, 768, C.byref(out)) == -1
+    even = (C.c_uint8 * 64)(*([2] + [0] * 62 + [0x80]))
+    assert lib.haflo_ctx_create_public(even, 512, C.byref(out)) == -2  # even modulus
+    p = (C.c_uint8 * 32)(*([3] + [0] * 30 + [0xC0]))
+    assert lib.haflo_ctx_create_private(p, p, 512, C.byref(out)) == -2  # p == q
+    short = (C.c_uint8 * 32)(*([3] + [0] * 31))
+    assert lib.haflo_ctx_create_private(short, p, 512, C.byref(out)) == -2  # wrong bit length
+    assert lib.haflo_ctx_destroy(None) == -1
+    assert lib.haflo_ctx_info(None, None, None, None, None, None) == -1
+    assert lib.haflo_workspace_bytes(None, 1, 1, 0) == 2 ** 64 - 1
+    assert lib.haflo_add(None, None, None, None, 4, None) == -1
+    assert lib.haflo_encrypt(None, None, None, None, 4, None, 0, None) == -1
+    assert lib.haflo_decrypt(None, None, None, 4, None, 0, None) == -1
+    assert lib.haflo_cipher_matvec(None, 0, None, None, 1, 1, None, None, 0, None) == -1
+    assert lib.haflo_encode_exponents_f32(None, 16, None, None, 4, None) == -1
+    assert lib.haflo_encode_exponents_f32(None, 99, None, None, 0, None) == -1
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    import importlib
+    api = importlib.import_module("paper_2107_13797_amd.api") if _torch_ok() else None
+    if api is None:
+        pytest.skip("torch not importable")
+    monkeypatch.setattr(api, "_lib", None)
+    monkeypatch.setattr(api, "_LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(api.HafloError):
+        api.lib()
+
+
+def _torch_ok():
+    try:
+        import torch  # noqa: F401
+        return True
+    except Exception:
+        return False
