@@ -72,15 +72,24 @@ struct Grp {
 
 __device__ __forceinline__ bool wave_any(bool p) { return __builtin_amdgcn_ballot_w64(p) != 0ull; }
 
+// The constant 8 = 2^32 / 2^29 behind an optimisation barrier: hi * 8 + acc then
+// stays a single v_mad_u64_u32 instead of being strength-reduced into a 64-bit
+// shift, two masks and an add.
+__device__ __forceinline__ u32 opaque_eight() {
+  u32 e = 8u;
+  asm volatile("" : "+r"(e));
+  return e;
+}
+
 // Push the upper 32 bits of every column accumulator one column up
 // (A[j+1] += 8 * hi(A[j]), radix 2^29 vs word 2^32), leaving each column below
 // 2^32 (column 0 below 2^36). The top lane's top column is bounded by the value
-// bound of the caller and is left alone.
+// bound of the caller and is left alone. `eight` comes from opaque_eight().
 template <int LPT, int T>
-__device__ __forceinline__ void hi_normalise(u64 (&A)[LPT], const Grp<T>& g) {
+__device__ __forceinline__ void hi_normalise(u64 (&A)[LPT], const Grp<T>& g, u32 eight) {
 #pragma unroll
   for (int j = 0; j + 1 < LPT; ++j) {
-    A[j + 1] = mad64((u32)(A[j] >> 32), 8u, A[j + 1]);
+    A[j + 1] = mad64((u32)(A[j] >> 32), eight, A[j + 1]);
     A[j] = (u64)(u32)A[j];
   }
   if (T > 1) {
@@ -88,7 +97,7 @@ __device__ __forceinline__ void hi_normalise(u64 (&A)[LPT], const Grp<T>& g) {
     u32 send = (g.k == T - 1) ? 0u : hi;
     u32 recv = g.from_lower(send);
     if (g.k != T - 1) A[LPT - 1] = (u64)(u32)A[LPT - 1];
-    A[0] = mad64(recv, 8u, A[0]);
+    A[0] = mad64(recv, eight, A[0]);
   }
 }
 
@@ -105,6 +114,7 @@ __device__ __forceinline__ void montmul(u32 (&out)[LPT], const u32 (&a)[LPT], co
                                         const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
   constexpr int NORM = (LPT <= 31) ? LPT : (LPT / 2);
   static_assert(NORM <= 31 && LPT % NORM == 0, "normalisation interval");
+  const u32 eight = opaque_eight();
   u64 A[LPT];
 #pragma unroll
   for (int j = 0; j < LPT; ++j) A[j] = 0;
@@ -131,7 +141,7 @@ __device__ __forceinline__ void montmul(u32 (&out)[LPT], const u32 (&a)[LPT], co
       } else {
         A[0] = (u64)recv + carry;
       }
-      if ((r + 1) % NORM == 0) hi_normalise<LPT, T>(A, g);
+      if ((r + 1) % NORM == 0) hi_normalise<LPT, T>(A, g, eight);
     }
   }
   // Compress the columns to 32-bit limbs: ripple inside the lane, then hand the
@@ -225,6 +235,7 @@ template <int LPT, int T, bool WANT_HI>
 __device__ __forceinline__ void mul_plain(u32 (&lo)[LPT], u32 (&hi)[LPT], const u32 (&a)[LPT], const u32 (&b)[LPT],
                                           const Grp<T>& g) {
   constexpr int NORM = (LPT <= 31) ? LPT : (LPT / 2);
+  const u32 eight = opaque_eight();
   u64 A[LPT];
   u32 res[LPT];
 #pragma unroll
@@ -253,7 +264,7 @@ __device__ __forceinline__ void mul_plain(u32 (&lo)[LPT], u32 (&hi)[LPT], const 
       } else {
         A[0] = (u64)recv + carry;
       }
-      if ((r + 1) % NORM == 0) hi_normalise<LPT, T>(A, g);
+      if ((r + 1) % NORM == 0) hi_normalise<LPT, T>(A, g, eight);
     }
   }
   if (WANT_HI) {

@@ -76,6 +76,33 @@ HostSched make_schedule(const Big& e, int window) {
   return best;
 }
 
+void append_modexp(std::vector<uint32_t>& prog, const HostSched& h) {
+  if (h.is_zero) {
+    prog.push_back(eng_ins(ENG_LOAD_C, kConstR1));
+    return;
+  }
+  const uint32_t tmp = (uint32_t)h.table_len;
+  prog.push_back(eng_ins(ENG_STORE_T, 0));
+  if (h.table_len > 1) {
+    prog.push_back(eng_ins(ENG_SQ));
+    prog.push_back(eng_ins(ENG_STORE_T, tmp));
+    prog.push_back(eng_ins(ENG_LOAD_T, 0));
+    for (int i = 1; i < h.table_len; ++i) prog.push_back(eng_ins(ENG_MUL_T_ST, tmp, (uint32_t)i));
+  }
+  prog.push_back(eng_ins(ENG_LOAD_T, (uint32_t)h.first));
+  for (uint32_t st : h.steps) {
+    for (uint32_t i = 0; i < (st >> 16); ++i) prog.push_back(eng_ins(ENG_SQ));
+    if ((st & 0xFFFFu) != kNoMul) prog.push_back(eng_ins(ENG_MUL_T, st & 0xFFFFu));
+  }
+}
+
+void append_power_table16(std::vector<uint32_t>& prog) {
+  prog.push_back(eng_ins(ENG_STORE_T, 1));
+  for (uint32_t d = 2; d < 16; ++d) prog.push_back(eng_ins(ENG_MUL_T_ST, 1, d));
+  prog.push_back(eng_ins(ENG_LOAD_C, kConstR1));
+  prog.push_back(eng_ins(ENG_STORE_T, 0));
+}
+
 static const std::vector<uint32_t>& small_primes() {
   static std::vector<uint32_t> pr;
   if (pr.empty()) {
@@ -190,17 +217,47 @@ static void build_modulus(ModHost& m, const Big& mod, int nl, Uploader& up) {
   Big r1 = Big::mod(Big::pow2((size_t)kLimbBits * nl), mod);
   Big r2 = Big::mod(Big::mul(r1, r1), mod);
   Big r3 = Big::mod(Big::mul(r2, r1), mod);
+  Big one(1);
   std::vector<uint32_t> tab;
-  for (const Big* b : {(const Big*)&mod, (const Big*)&r1, (const Big*)&r2, (const Big*)&r3}) {
+  for (const Big* b : {(const Big*)&mod, (const Big*)&r1, (const Big*)&r2, (const Big*)&r3, (const Big*)&one}) {
     std::vector<uint32_t> l = to_limbs29(*b, nl);
     tab.insert(tab.end(), l.begin(), l.end());
   }
   m.d_tab = up.put(tab);
 }
 
-static void build_schedule(DevSched& s, const Big& e, Uploader& up) {
-  s.h = make_schedule(e, 0);
-  s.d_steps = up.put(s.h.steps);
+// encryption: acc = r (word input 1) -> r R -> (r R)^n -> times ((m n) R + R), m = word input 0
+static void build_prog_encrypt(DevProg& p, const Big& n, Uploader& up) {
+  p.sched = make_schedule(n, 0);
+  p.host.clear();
+  p.host.push_back(eng_ins(ENG_LOAD_W, 1));
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstR2));
+  append_modexp(p.host, p.sched);
+  p.host.push_back(eng_ins(ENG_STORE_T, 0));
+  p.host.push_back(eng_ins(ENG_LOAD_W, 0));
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstExtra));  // montmul(m, n R^2) = m n R
+  p.host.push_back(eng_ins(ENG_ADD_C, kConstR1));
+  p.host.push_back(eng_ins(ENG_MUL_T, 0));
+  p.table_entries = p.sched.table_len + 1;
+  p.d_ins = up.put(p.host);
+}
+
+// decryption branch for a prime s: the canonical residue c = c_hi R + c_lo (two halves of the
+// limb input) goes to Montgomery form mod s^2 as montmul(c_lo, R^2) + montmul(c_hi, R^3),
+// is raised to s - 1 and leaves the Montgomery domain
+static void build_prog_decrypt(DevProg& p, const Big& e, Uploader& up) {
+  p.sched = make_schedule(e, 0);
+  p.host.clear();
+  p.host.push_back(eng_ins(ENG_LOAD_L, 0));
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstR2));
+  p.host.push_back(eng_ins(ENG_STORE_T, 0));
+  p.host.push_back(eng_ins(ENG_LOAD_L, 1));
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstR3));
+  p.host.push_back(eng_ins(ENG_ADD_T, 0));
+  append_modexp(p.host, p.sched);
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstOne));
+  p.table_entries = p.sched.table_len + 1;
+  p.d_ins = up.put(p.host);
 }
 
 static std::vector<uint32_t> to_words(const Big& x, int nw) {
@@ -224,7 +281,7 @@ static int ctx_build(haflo_ctx* ctx, const Big& n, const Big* p, const Big* q, u
   const int nl_n2 = (int)(n_bits * 9 / 128);
   build_modulus(ctx->N, ctx->nsq, nl_n2, up);
   if (!up.ok) return HAFLO_ENOMEM;
-  build_schedule(ctx->sched_n, n, up);
+  build_prog_encrypt(ctx->prog_enc, n, up);
   {
     // k1 = n * R^2 mod n^2
     Big r1 = Big::mod(Big::pow2((size_t)kLimbBits * nl_n2), ctx->nsq);
@@ -245,8 +302,8 @@ static int ctx_build(haflo_ctx* ctx, const Big& n, const Big* p, const Big* q, u
     build_modulus(ctx->P, *p, nl_q, up);
     build_modulus(ctx->Q, *q, nl_q, up);
     if (!up.ok) return HAFLO_ENOMEM;
-    build_schedule(ctx->sched_pm1, Big::sub(*p, Big(1)), up);
-    build_schedule(ctx->sched_qm1, Big::sub(*q, Big(1)), up);
+    build_prog_decrypt(ctx->prog_dec_p, Big::sub(*p, Big(1)), up);
+    build_prog_decrypt(ctx->prog_dec_q, Big::sub(*q, Big(1)), up);
     // With g = n + 1: g^(p-1) mod p^2 = 1 + (p-1)*n mod p^2, so
     // L_p(g^(p-1) mod p^2) = -q mod p and h_p = -(q^-1) mod p (p, q prime).
     MontHost mp(*p), mq(*q);
@@ -388,12 +445,13 @@ int haflo_op_cost(const haflo_ctx* ctx, int op, uint64_t* montmuls, uint32_t* mo
   uint32_t limbs = 0;
   if (op == HAFLO_OP_ENCRYPT) {
     // into Montgomery form, the power r^n, (1 + m n) R, the final product
-    mm = ctx->sched_n.h.nsquare + ctx->sched_n.h.nmul + 3;
+    mm = ctx->prog_enc.sched.nsquare + ctx->prog_enc.sched.nmul + 3;
     limbs = (uint32_t)ctx->lc;
   } else if (op == HAFLO_OP_DECRYPT) {
     if (!ctx->has_priv) return HAFLO_ENOPRIV;
     // per branch: two products to reduce into Montgomery form, the power, one product out
-    mm = ctx->sched_pm1.h.nsquare + ctx->sched_pm1.h.nmul + ctx->sched_qm1.h.nsquare + ctx->sched_qm1.h.nmul + 6;
+    mm = ctx->prog_dec_p.sched.nsquare + ctx->prog_dec_p.sched.nmul + ctx->prog_dec_q.sched.nsquare +
+         ctx->prog_dec_q.sched.nmul + 6;
     limbs = (uint32_t)ctx->lc / 2;
   } else {
     return HAFLO_EINVAL;

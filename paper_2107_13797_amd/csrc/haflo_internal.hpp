@@ -21,6 +21,7 @@ struct ModRef {
   const uint32_t* r1;  // R mod n, R = 2^(29*NL): the Montgomery form of 1
   const uint32_t* r2;  // R^2 mod n
   const uint32_t* r3;  // R^3 mod n
+  const uint32_t* one; // the integer 1
   uint32_t n0inv;      // -n^-1 mod 2^29
   int nl;              // limbs
 };
@@ -30,16 +31,8 @@ struct ModRef {
 // x^(2*table_len-1). Execution: acc = table[first]; then for each step square
 // `nsq` times and, unless idx == kNoMul, multiply by table[idx].
 constexpr uint32_t kNoMul = 0xFFFFu;
-struct SchedRef {
-  const uint32_t* steps;  // device: (nsq << 16) | idx
-  int nsteps;
-  int first;      // table index of the leading window
-  int table_len;  // entries to precompute (>= 1)
-  int is_zero;    // exponent == 0: result is 1
-};
-
 struct HostSched {
-  std::vector<uint32_t> steps;
+  std::vector<uint32_t> steps;  // (nsq << 16) | idx
   int first = 0;
   int table_len = 1;
   int is_zero = 0;
@@ -47,35 +40,59 @@ struct HostSched {
 };
 HostSched make_schedule(const Big& e, int window);
 
+// The exponentiation kernels run a small batch-uniform program, one
+// instruction per Montgomery product or register/table move, so that the whole
+// operator goes through a single unrolled product loop. An instruction is
+// op | a << 8 | b << 20. `acc` is the running value (lazy Montgomery form),
+// table[] the group's scratch slots of NL limbs, constant[] per-modulus limb
+// arrays (kConst*), k the element's own 64-bit exponent where one is given.
+enum EngOp : uint32_t {
+  ENG_SQ = 0,        // acc = acc * acc
+  ENG_MUL_T = 1,     // acc = acc * table[a]
+  ENG_MUL_T_ST = 2,  // acc = acc * table[a]; table[b] = acc
+  ENG_MUL_C = 3,     // acc = acc * constant[a]
+  ENG_MUL_TD = 4,    // acc = acc * table[(k >> a) & 15]
+  // no product below this line
+  ENG_LOAD_T = 8,    // acc = table[a]
+  ENG_STORE_T = 9,   // table[a] = acc
+  ENG_LOAD_C = 10,   // acc = constant[a]
+  ENG_ADD_C = 11,    // acc += constant[a]  (lazy, limbs renormalised)
+  ENG_ADD_T = 12,    // acc += table[a]
+  ENG_LOAD_W = 13,   // acc = the element's 32-bit-word input a (0 or 1), cut into limbs
+  ENG_LOAD_L = 14,   // acc = limbs [a*NL, (a+1)*NL) of the element's limb input
+  ENG_LOAD_TD = 15   // acc = table[(k >> a) & 15]
+};
+enum { kConstR1 = 0, kConstR2 = 1, kConstR3 = 2, kConstOne = 3, kConstExtra = 4, kNumConst = 5 };
+inline uint32_t eng_ins(uint32_t op, uint32_t a = 0, uint32_t b = 0) { return op | (a << 8) | (b << 20); }
+
+// acc = acc^e for the plan `h`, using table slots [0, h.table_len] (the last one as scratch)
+void append_modexp(std::vector<uint32_t>& prog, const HostSched& h);
+// table[d] = x^d for d < 16 from acc = x (leaves acc = x^15)
+void append_power_table16(std::vector<uint32_t>& prog);
+
+struct DevProg {
+  std::vector<uint32_t> host;
+  uint32_t* d_ins = nullptr;
+  int table_entries = 1;  // table slots the program touches
+  HostSched sched;        // the exponent plan inside it, for cost accounting
+};
+
 struct ModHost {
   Big mod;
   int nl = 0;   // 29-bit limbs
   int lpt = 0;  // limbs per lane
   int t = 0;    // lanes per big integer
   uint32_t n0inv = 0;
-  uint32_t* d_tab = nullptr;  // device: n | r1 | r2 | r3, nl limbs each
+  uint32_t* d_tab = nullptr;  // device: n | r1 | r2 | r3 | one, nl limbs each
   ModRef ref() const {
     ModRef r;
     r.n = d_tab;
     r.r1 = d_tab + nl;
     r.r2 = d_tab + 2 * nl;
     r.r3 = d_tab + 3 * nl;
+    r.one = d_tab + 4 * nl;
     r.n0inv = n0inv;
     r.nl = nl;
-    return r;
-  }
-};
-
-struct DevSched {
-  HostSched h;
-  uint32_t* d_steps = nullptr;
-  SchedRef ref() const {
-    SchedRef r;
-    r.steps = d_steps;
-    r.nsteps = (int)h.steps.size();
-    r.first = h.first;
-    r.table_len = h.table_len;
-    r.is_zero = h.is_zero;
     return r;
   }
 };
@@ -91,9 +108,9 @@ struct haflo_ctx {
   haflo::ModHost N;            // n^2
   haflo::ModHost P2, Q2;       // p^2, q^2 (private)
   haflo::ModHost P, Q;         // p, q (private)
-  haflo::DevSched sched_n;     // exponent n modulo n^2 (encryption)
-  haflo::DevSched sched_pm1;   // exponent p-1 modulo p^2
-  haflo::DevSched sched_qm1;   // exponent q-1 modulo q^2
+  haflo::DevProg prog_enc;     // encryption: r^n modulo n^2 and the (1 + m n) factor
+  haflo::DevProg prog_dec_p;   // decryption branch: c^(p-1) modulo p^2
+  haflo::DevProg prog_dec_q;   // decryption branch: c^(q-1) modulo q^2
   // device constants
   uint32_t* d_k1 = nullptr;      // n * R^2 mod n^2 (N.nl limbs): montmul(m, k1) = m*n*R
   uint32_t* d_n_words = nullptr; // n as lp 32-bit words
@@ -141,6 +158,9 @@ std::vector<uint32_t> to_limbs29(const Big& x, int nl);
 size_t ws_encrypt(const haflo_ctx* ctx, size_t count);
 size_t ws_scalar_mul(const haflo_ctx* ctx, size_t count);
 size_t ws_decrypt(const haflo_ctx* ctx, size_t count);
+
+// tables[i][d] = c_i^d for d < 16 (kernels_modexp.hip)
+int power_tables16(const haflo_ctx* ctx, const uint32_t* d_c, uint32_t* d_tables, size_t count, hipStream_t st);
 
 // out[i] = in[i]^-1 mod n^2 on internal ciphertexts; out may alias in (kernels_matvec.hip)
 int invert_batch(const haflo_ctx* ctx, const uint32_t* in, uint32_t* out, size_t count, hipStream_t st);

@@ -49,52 +49,103 @@ __device__ __forceinline__ void partial_norm(u32 (&x)[LPT], const Grp<T>& g) {
   if (T > 1) x[0] += g.from_lower(c);
 }
 
-struct SchedInline {
-  u32 steps[64];
-  int nsteps;
-  int first;
-  int table_len;
-  int is_zero;
+// Program storage for the exponentiation engine: a device array for long
+// programs (key-length exponents), an array inside the kernel arguments for
+// short ones (64-bit exponents), so that no device memory has to be allocated
+// or written for a per-call exponent.
+struct ProgPtr {
+  const u32* ins;
+  int len;
+  __device__ __forceinline__ u32 at(int pc) const { return ins[pc]; }
 };
-__device__ __forceinline__ u32 sched_step(const SchedRef& s, int i) { return s.steps[i]; }
-__device__ __forceinline__ u32 sched_step(const SchedInline& s, int i) { return s.steps[i]; }
+constexpr int kInlineProgMax = 192;
+struct ProgInline {
+  u32 ins[kInlineProgMax];
+  int len;
+  __device__ __forceinline__ u32 at(int pc) const { return ins[pc]; }
+};
 
-// acc = x^e in Montgomery form for the fixed exponent described by `S`
-// (sliding windows over a table of odd powers kept in this group's workspace
-// slot: table_len entries of NL limbs, each lane reading back only the limbs
-// it wrote itself). xbar: Montgomery form of x, lazy. acc: lazy, < 2n.
-template <int LPT, int T, class Sched>
-__device__ __forceinline__ void modexp_fixed(u32 (&acc)[LPT], const u32 (&xbar)[LPT], const ModRegs<LPT>& M,
-                                             const Sched& S, u32* table, const u32* r1, const Grp<T>& g) {
+// Operands of one engine launch (all device pointers; unused ones may be null).
+struct EngineIO {
+  const u32* constant[kNumConst];  // per-modulus limb arrays, see kConst*
+  const u32* in_words[2];          // per-element arrays of in_nwords 32-bit words
+  int in_nwords;
+  const u32* in_limbs;             // per-element limb arrays, in_limbs_stride limbs apart
+  int in_limbs_stride;
+  const unsigned long long* k64;   // per-element exponent for the *_TD instructions
+  u32* out;                        // NL limbs per element (canonical) or null
+  u32* tables;                     // table_entries * NL limbs per slot
+  int table_entries;
+  int table_per_item;              // 1: slot = element index (tables are an output), 0: slot = lane group
+};
+
+// The exponentiation engine: every lane group runs the batch-uniform program
+// `P` on its element. All Montgomery products of all operators built on it go
+// through the one unrolled loop instantiated here, which keeps the register
+// footprint at what a single product needs.
+template <int LPT, int T, class Prog>
+__global__ __launch_bounds__(kBlockThreads, 4) void k_engine(ModRef M, Prog P, EngineIO io, size_t count) {
   constexpr int NL = LPT * T;
-  if (S.is_zero) {
-    load_limbs<LPT, T>(acc, r1, g);
-    return;
-  }
-  store_limbs<LPT, T>(table, xbar, g);
-  if (S.table_len > 1) {
-    u32 x2[LPT], cur[LPT];
-    montmul<LPT, T>(x2, xbar, xbar, M.n, M.n0inv, g);
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    const size_t item = base + bt.gib;
+    const bool active = item < count;
+    const bool tab_ok = active || !io.table_per_item;
+    u32* table = io.tables + (io.table_per_item ? (active ? item : 0) : bt.slot()) * (size_t)io.table_entries * NL;
+    const u64 k = (io.k64 && active) ? io.k64[item] : 0ull;
+    u32 acc[LPT];
+    zero_limbs<LPT>(acc);
+#pragma unroll 1
+    for (int pc = 0; pc < P.len; ++pc) {
+      const u32 ins = P.at(pc);
+      const u32 op = ins & 0xFFu, a = (ins >> 8) & 0xFFFu, b = ins >> 20;
+      if (op >= ENG_LOAD_T) {
+        if (op == ENG_STORE_T) {
+          if (tab_ok) store_limbs<LPT, T>(table + (size_t)a * NL, acc, g);
+        } else if (op == ENG_LOAD_W) {
+          if (active) load_words_as_limbs<LPT, T>(acc, io.in_words[a] + item * (size_t)io.in_nwords, io.in_nwords, g);
+          else zero_limbs<LPT>(acc);
+        } else if (op == ENG_LOAD_L) {
+          if (active) load_limbs<LPT, T>(acc, io.in_limbs + item * (size_t)io.in_limbs_stride + (size_t)a * NL, g);
+          else zero_limbs<LPT>(acc);
+        } else {
+          const u32* src;
+          if (op == ENG_LOAD_C || op == ENG_ADD_C) src = io.constant[a];
+          else src = table + (size_t)(op == ENG_LOAD_TD ? (u32)(k >> a) & 15u : a) * NL;
+          u32 t[LPT];
+          if (tab_ok || op == ENG_LOAD_C || op == ENG_ADD_C) load_limbs<LPT, T>(t, src, g);
+          else zero_limbs<LPT>(t);
+          if (op == ENG_ADD_C || op == ENG_ADD_T) {
 #pragma unroll
-    for (int j = 0; j < LPT; ++j) cur[j] = xbar[j];
-#pragma unroll 1
-    for (int i = 1; i < S.table_len; ++i) {
-      montmul<LPT, T>(cur, cur, x2, M.n, M.n0inv, g);
-      store_limbs<LPT, T>(table + (size_t)i * NL, cur, g);
+            for (int j = 0; j < LPT; ++j) acc[j] += t[j];
+            partial_norm<LPT, T>(acc, g);
+          } else {
+#pragma unroll
+            for (int j = 0; j < LPT; ++j) acc[j] = t[j];
+          }
+        }
+        continue;
+      }
+      u32 y[LPT];
+      if (op == ENG_SQ) {
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) y[j] = acc[j];
+      } else {
+        const u32* src;
+        if (op == ENG_MUL_C) src = io.constant[a];
+        else src = table + (size_t)(op == ENG_MUL_TD ? (u32)(k >> a) & 15u : a) * NL;
+        if (tab_ok || op == ENG_MUL_C) load_limbs<LPT, T>(y, src, g);
+        else zero_limbs<LPT>(y);
+      }
+      montmul<LPT, T>(acc, acc, y, mod.n, mod.n0inv, g);
+      if (op == ENG_MUL_T_ST && tab_ok) store_limbs<LPT, T>(table + (size_t)b * NL, acc, g);
     }
-  }
-  load_limbs<LPT, T>(acc, table + (size_t)S.first * NL, g);
-#pragma unroll 1
-  for (int s = 0; s < S.nsteps; ++s) {
-    u32 st = sched_step(S, s);
-    int nsq = (int)(st >> 16);
-    u32 idx = st & 0xFFFFu;
-#pragma unroll 1
-    for (int i = 0; i < nsq; ++i) montmul<LPT, T>(acc, acc, acc, M.n, M.n0inv, g);
-    if (idx != kNoMul) {
-      u32 t[LPT];
-      load_limbs<LPT, T>(t, table + (size_t)idx * NL, g);
-      montmul<LPT, T>(acc, acc, t, M.n, M.n0inv, g);
+    if (io.out) {
+      canonicalise<LPT, T>(acc, mod.n, g);
+      if (active) store_limbs<LPT, T>(io.out + item * (size_t)NL, acc, g);
     }
   }
 }

@@ -240,37 +240,6 @@ __device__ __forceinline__ void block_product(u32 (&acc)[LPT], u32* lds, const M
   }
 }
 
-// table[i][d] = c_i^d for d < 2^w (Montgomery form, lazy), one group per base
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_pow_tables(ModRef M, const u32* __restrict__ bases,
-                                                              u32* __restrict__ tables, size_t count) {
-  constexpr int NL = LPT * T;
-  Grp<T> g;
-  Batch<T> bt;
-  ModRegs<LPT> mod;
-  load_mod<LPT, T>(mod, M, g);
-  for (size_t base = bt.first(); base < count; base += bt.stride()) {
-    size_t item = base + bt.gib;
-    bool active = item < count;
-    u32 x[LPT], cur[LPT];
-    if (active) load_limbs<LPT, T>(x, bases + item * (size_t)NL, g);
-    else zero_limbs<LPT>(x);
-    load_limbs<LPT, T>(cur, M.r1, g);
-    u32* tb = tables + item * (size_t)kWinEntries * NL;
-    if (active) {
-      store_limbs<LPT, T>(tb, cur, g);
-      store_limbs<LPT, T>(tb + NL, x, g);
-    }
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) cur[j] = x[j];
-#pragma unroll 1
-    for (int dgt = 2; dgt < kWinEntries; ++dgt) {
-      montmul<LPT, T>(cur, cur, x, mod.n, mod.n0inv, g);
-      if (active) store_limbs<LPT, T>(tb + (size_t)dgt * NL, cur, g);
-    }
-  }
-}
-
 // ---------------------------------------------------------------------------
 // orientation 0: out[j] = prod_i c_i^X[i][j]
 // ---------------------------------------------------------------------------
@@ -278,7 +247,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_pow_tables(ModRef M, const u3
 // block (j, s, rs): product over the rows of slice rs of table_i[digit s of
 // |X[i][j]|], positive and negative entries apart -> partials[j][s][sign][rs]
 template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_xtd_main(ModRef M, const int* __restrict__ X, size_t rows,
+__global__ __launch_bounds__(kBlockThreads, 2) void k_xtd_main(ModRef M, const int* __restrict__ X, size_t rows,
                                                             size_t cols, const u32* __restrict__ tables, int rsplit,
                                                             u32* __restrict__ partials,
                                                             const u32* __restrict__ maxbits) {
@@ -464,7 +433,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_compact(const int* __restr
 }
 
 template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_xw_main(ModRef M, size_t rows, size_t cols,
+__global__ __launch_bounds__(kBlockThreads, 4) void k_xw_main(ModRef M, size_t rows, size_t cols,
                                                            const int* __restrict__ nz, const u32* __restrict__ nzcount,
                                                            const u32* __restrict__ tables, u32* __restrict__ out,
                                                            const u32* __restrict__ maxbits) {
@@ -642,10 +611,9 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
     u32* partials = ws + p.off_partials;
     u32* P = ws + p.off_P;
     if (rows) {
-      const LaunchShape sh = launch_shape(ctx, rows, m.t, 8);
-#define CALL(LPT, T) HAFLO_LAUNCH((k_pow_tables<LPT, T>), sh, st, m.ref(), (const u32*)d_c, tables, rows)
-      HAFLO_DISPATCH_GEOMETRY(m, CALL);
-#undef CALL
+      static_assert(kWinEntries == 16, "the shared table builder makes 16 entries");
+      rc = power_tables16(ctx, (const u32*)d_c, tables, rows, st);
+      if (rc != HAFLO_OK) return rc;
       LaunchShape mainsh;
       mainsh.threads = kBlockThreads;
       mainsh.gpb = kBlockThreads / m.t;

@@ -9,116 +9,6 @@ namespace {
 
 constexpr int kModexpBlocksPerCu = 4;  // resident blocks assumed when sizing window-table workspace
 
-// E(m) = (1 + m n) r^n mod n^2, output in internal form.
-//   r^n: fixed-exponent sliding-window power in Montgomery form.
-//   (1 + m n) R = montmul(m, n R^2) + R, formed lazily and folded in with one
-//   more Montgomery product.
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_encrypt(ModRef M, SchedRef S, const u32* __restrict__ k1,
-                                                           const u32* __restrict__ plain, const u32* __restrict__ rnd,
-                                                           int lp, u32* __restrict__ out, u32* __restrict__ tables,
-                                                           size_t count) {
-  constexpr int NL = LPT * T;
-  Grp<T> g;
-  Batch<T> bt;
-  ModRegs<LPT> mod;
-  load_mod<LPT, T>(mod, M, g);
-  u32* table = tables + bt.slot() * (size_t)S.table_len * NL;
-  for (size_t base = bt.first(); base < count; base += bt.stride()) {
-    size_t item = base + bt.gib;
-    bool active = item < count;
-    u32 x[LPT], acc[LPT], t[LPT];
-    if (active) load_words_as_limbs<LPT, T>(x, rnd + item * (size_t)lp, lp, g);
-    else zero_limbs<LPT>(x);
-    load_limbs<LPT, T>(t, M.r2, g);
-    montmul<LPT, T>(x, x, t, mod.n, mod.n0inv, g);
-    modexp_fixed<LPT, T>(acc, x, mod, S, table, M.r1, g);
-    if (active) load_words_as_limbs<LPT, T>(x, plain + item * (size_t)lp, lp, g);
-    else zero_limbs<LPT>(x);
-    load_limbs<LPT, T>(t, k1, g);
-    montmul<LPT, T>(x, x, t, mod.n, mod.n0inv, g);
-    load_limbs<LPT, T>(t, M.r1, g);
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) x[j] += t[j];
-    partial_norm<LPT, T>(x, g);
-    montmul<LPT, T>(acc, acc, x, mod.n, mod.n0inv, g);
-    canonicalise<LPT, T>(acc, mod.n, g);
-    if (active) store_limbs<LPT, T>(out + item * (size_t)NL, acc, g);
-  }
-}
-
-// c^k mod n^2 with one exponent plan for the whole batch
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_pow_bcast(ModRef M, SchedInline S, const u32* __restrict__ in,
-                                                             u32* __restrict__ out, u32* __restrict__ tables,
-                                                             size_t count) {
-  constexpr int NL = LPT * T;
-  Grp<T> g;
-  Batch<T> bt;
-  ModRegs<LPT> mod;
-  load_mod<LPT, T>(mod, M, g);
-  u32* table = tables + bt.slot() * (size_t)S.table_len * NL;
-  for (size_t base = bt.first(); base < count; base += bt.stride()) {
-    size_t item = base + bt.gib;
-    bool active = item < count;
-    u32 x[LPT], acc[LPT];
-    if (active) load_limbs<LPT, T>(x, in + item * (size_t)NL, g);
-    else zero_limbs<LPT>(x);
-    modexp_fixed<LPT, T>(acc, x, mod, S, table, M.r1, g);
-    canonicalise<LPT, T>(acc, mod.n, g);
-    if (active) store_limbs<LPT, T>(out + item * (size_t)NL, acc, g);
-  }
-}
-
-// c^k mod n^2 with one unsigned 64-bit exponent per element: fixed 4-bit
-// windows over a 16-entry table (entry 0 is the Montgomery one, so every
-// window multiplies and lanes never diverge on the digit).
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_pow_u64(ModRef M, const u32* __restrict__ in,
-                                                           const unsigned long long* __restrict__ kk,
-                                                           u32* __restrict__ out, u32* __restrict__ tables,
-                                                           size_t count) {
-  constexpr int NL = LPT * T;
-  Grp<T> g;
-  Batch<T> bt;
-  ModRegs<LPT> mod;
-  load_mod<LPT, T>(mod, M, g);
-  u32* table = tables + bt.slot() * (size_t)16 * NL;
-  for (size_t base = bt.first(); base < count; base += bt.stride()) {
-    size_t item = base + bt.gib;
-    bool active = item < count;
-    u32 x[LPT], acc[LPT], t[LPT];
-    u64 k = 0;
-    if (active) {
-      load_limbs<LPT, T>(x, in + item * (size_t)NL, g);
-      k = kk[item];
-    } else {
-      zero_limbs<LPT>(x);
-    }
-    load_limbs<LPT, T>(t, M.r1, g);
-    store_limbs<LPT, T>(table, t, g);
-    store_limbs<LPT, T>(table + NL, x, g);
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) t[j] = x[j];
-#pragma unroll 1
-    for (int i = 2; i < 16; ++i) {
-      montmul<LPT, T>(t, t, x, mod.n, mod.n0inv, g);
-      store_limbs<LPT, T>(table + (size_t)i * NL, t, g);
-    }
-    load_limbs<LPT, T>(acc, table + (size_t)(k >> 60) * NL, g);
-#pragma unroll 1
-    for (int wi = 14; wi >= 0; --wi) {
-#pragma unroll 1
-      for (int s = 0; s < 4; ++s) montmul<LPT, T>(acc, acc, acc, mod.n, mod.n0inv, g);
-      u32 d = (u32)(k >> (4 * wi)) & 15u;
-      load_limbs<LPT, T>(t, table + (size_t)d * NL, g);
-      montmul<LPT, T>(acc, acc, t, mod.n, mod.n0inv, g);
-    }
-    canonicalise<LPT, T>(acc, mod.n, g);
-    if (active) store_limbs<LPT, T>(out + item * (size_t)NL, acc, g);
-  }
-}
-
 // Decryption stage A: internal ciphertext -> canonical residue mod n^2 in
 // 29-bit limbs (workspace), ready to be split in halves.
 template <int LPT, int T>
@@ -141,47 +31,6 @@ __global__ __launch_bounds__(kBlockThreads) void k_dec_unmont(ModRef M, const u3
     montmul<LPT, T>(x, x, one, mod.n, mod.n0inv, g);
     canonicalise<LPT, T>(x, mod.n, g);
     if (active) store_limbs<LPT, T>(canon29 + item * (size_t)NL, x, g);
-  }
-}
-
-// Decryption stage B for one prime s (modulus s^2 of NL limbs): reduce the
-// 2*NL-limb residue c = c_hi * R + c_lo into Montgomery form mod s^2
-// (c R = c_lo R + c_hi R^2 = montmul(c_lo, R^2) + montmul(c_hi, R^3)), raise
-// to s - 1, leave the Montgomery domain and store the canonical result.
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_dec_pow(ModRef M, SchedRef S, const u32* __restrict__ canon29,
-                                                           u32* __restrict__ ypow, u32* __restrict__ tables,
-                                                           size_t count) {
-  constexpr int NL = LPT * T;
-  Grp<T> g;
-  Batch<T> bt;
-  ModRegs<LPT> mod;
-  load_mod<LPT, T>(mod, M, g);
-  u32* table = tables + bt.slot() * (size_t)S.table_len * NL;
-  for (size_t base = bt.first(); base < count; base += bt.stride()) {
-    size_t item = base + bt.gib;
-    bool active = item < count;
-    u32 lo[LPT], hi[LPT], t[LPT], acc[LPT];
-    if (active) {
-      load_limbs<LPT, T>(lo, canon29 + item * (size_t)(2 * NL), g);
-      load_limbs<LPT, T>(hi, canon29 + item * (size_t)(2 * NL) + NL, g);
-    } else {
-      zero_limbs<LPT>(lo);
-      zero_limbs<LPT>(hi);
-    }
-    load_limbs<LPT, T>(t, M.r2, g);
-    montmul<LPT, T>(lo, lo, t, mod.n, mod.n0inv, g);
-    load_limbs<LPT, T>(t, M.r3, g);
-    montmul<LPT, T>(hi, hi, t, mod.n, mod.n0inv, g);
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) lo[j] += hi[j];
-    partial_norm<LPT, T>(lo, g);
-    modexp_fixed<LPT, T>(acc, lo, mod, S, table, M.r1, g);
-    zero_limbs<LPT>(t);
-    if (g.k == 0) t[0] = 1u;
-    montmul<LPT, T>(acc, acc, t, mod.n, mod.n0inv, g);
-    canonicalise<LPT, T>(acc, mod.n, g);
-    if (active) store_limbs<LPT, T>(ypow + item * (size_t)NL, acc, g);
   }
 }
 
@@ -258,24 +107,43 @@ __global__ __launch_bounds__(kBlockThreads) void k_dec_crt(ModRef MP, ModRef MQ,
   }
 }
 
-void inline_schedule(SchedInline& si, const HostSched& h) {
-  si.nsteps = (int)h.steps.size();
-  for (int i = 0; i < si.nsteps && i < 64; ++i) si.steps[i] = h.steps[i];
-  si.first = h.first;
-  si.table_len = h.table_len;
-  si.is_zero = h.is_zero;
-}
-
 LaunchShape modexp_shape(const haflo_ctx* ctx, size_t count, int t) {
   return launch_shape(ctx, count, t, kModexpBlocksPerCu);
+}
+
+EngineIO engine_io(const ModHost& m) {
+  EngineIO io = {};
+  const ModRef r = m.ref();
+  io.constant[kConstR1] = r.r1;
+  io.constant[kConstR2] = r.r2;
+  io.constant[kConstR3] = r.r3;
+  io.constant[kConstOne] = r.one;
+  io.constant[kConstExtra] = nullptr;
+  return io;
+}
+
+bool to_inline(ProgInline& pi, const std::vector<uint32_t>& prog) {
+  if (prog.size() > (size_t)kInlineProgMax) return false;
+  pi.len = (int)prog.size();
+  for (size_t i = 0; i < prog.size(); ++i) pi.ins[i] = prog[i];
+  return true;
+}
+
+template <class Prog>
+int launch_engine(const ModHost& m, const LaunchShape& sh, hipStream_t st, const Prog& prog, const EngineIO& io,
+                  size_t count) {
+#define CALL(LPT, T) HAFLO_LAUNCH((k_engine<LPT, T, Prog>), sh, st, m.ref(), prog, io, count)
+  HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+  return hip_status(hipGetLastError());
 }
 
 }  // namespace
 
 namespace haflo {
-// window tables: one slot per resident lane group
+// table slots: one set per resident lane group
 size_t ws_encrypt(const haflo_ctx* ctx, size_t count) {
-  return modexp_shape(ctx, count, ctx->N.t).slots() * (size_t)ctx->sched_n.h.table_len * ctx->N.nl * 4;
+  return modexp_shape(ctx, count, ctx->N.t).slots() * (size_t)ctx->prog_enc.table_entries * ctx->N.nl * 4;
 }
 // sized for the per-element variant (16 entries); the broadcast variant never needs more
 size_t ws_scalar_mul(const haflo_ctx* ctx, size_t count) {
@@ -284,9 +152,26 @@ size_t ws_scalar_mul(const haflo_ctx* ctx, size_t count) {
 // layout: [canon29: count*N.nl][yp: count*P2.nl][yq: count*Q2.nl][tables]
 size_t ws_decrypt(const haflo_ctx* ctx, size_t count) {
   if (!ctx->has_priv) return 0;
-  size_t tl = (size_t)std::max(ctx->sched_pm1.h.table_len, ctx->sched_qm1.h.table_len);
+  size_t tl = (size_t)std::max(ctx->prog_dec_p.table_entries, ctx->prog_dec_q.table_entries);
   return (count * (size_t)ctx->N.nl + 2 * count * (size_t)ctx->P2.nl +
           modexp_shape(ctx, count, ctx->P2.t).slots() * tl * ctx->P2.nl) * 4;
+}
+
+// tables[i][d] = c_i^d, d < 16, for `count` internal ciphertexts (used by the matvec)
+int power_tables16(const haflo_ctx* ctx, const uint32_t* d_c, uint32_t* d_tables, size_t count, hipStream_t st) {
+  const ModHost& m = ctx->N;
+  std::vector<uint32_t> prog;
+  prog.push_back(eng_ins(ENG_LOAD_L, 0));
+  append_power_table16(prog);
+  ProgInline pi;
+  if (!to_inline(pi, prog)) return HAFLO_EINVAL;
+  EngineIO io = engine_io(m);
+  io.in_limbs = d_c;
+  io.in_limbs_stride = m.nl;
+  io.tables = d_tables;
+  io.table_entries = 16;
+  io.table_per_item = 1;
+  return launch_engine(m, launch_shape(ctx, count, m.t, 8), st, pi, io, count);
 }
 }  // namespace haflo
 
@@ -298,14 +183,16 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
   if (count == 0) return HAFLO_OK;
   if (!d_workspace || workspace_bytes < ws_encrypt(ctx, count)) return HAFLO_EINVAL;
   const ModHost& m = ctx->N;
-  const LaunchShape sh = modexp_shape(ctx, count, m.t);
-  hipStream_t st = (hipStream_t)stream;
-#define CALL(LPT, T)                                                                                          \
-  HAFLO_LAUNCH((k_encrypt<LPT, T>), sh, st, m.ref(), ctx->sched_n.ref(), ctx->d_k1, d_plain, d_r, ctx->lp,    \
-               (u32*)d_cipher, (u32*)d_workspace, count)
-  HAFLO_DISPATCH_GEOMETRY(m, CALL);
-#undef CALL
-  return hip_status(hipGetLastError());
+  EngineIO io = engine_io(m);
+  io.constant[kConstExtra] = ctx->d_k1;
+  io.in_words[0] = d_plain;
+  io.in_words[1] = d_r;
+  io.in_nwords = ctx->lp;
+  io.out = (u32*)d_cipher;
+  io.tables = (u32*)d_workspace;
+  io.table_entries = ctx->prog_enc.table_entries;
+  ProgPtr prog = {ctx->prog_enc.d_ins, (int)ctx->prog_enc.host.size()};
+  return launch_engine(m, modexp_shape(ctx, count, m.t), (hipStream_t)stream, prog, io, count);
 }
 
 int haflo_scalar_mul_u64(const haflo_ctx* ctx, const void* d_c, const uint64_t* d_k, void* d_out, size_t count,
@@ -314,14 +201,26 @@ int haflo_scalar_mul_u64(const haflo_ctx* ctx, const void* d_c, const uint64_t* 
   if (count == 0) return HAFLO_OK;
   if (!d_workspace || workspace_bytes < ws_scalar_mul(ctx, count)) return HAFLO_EINVAL;
   const ModHost& m = ctx->N;
-  const LaunchShape sh = modexp_shape(ctx, count, m.t);
-  hipStream_t st = (hipStream_t)stream;
-#define CALL(LPT, T)                                                                                   \
-  HAFLO_LAUNCH((k_pow_u64<LPT, T>), sh, st, m.ref(), (const u32*)d_c, (const unsigned long long*)d_k,  \
-               (u32*)d_out, (u32*)d_workspace, count)
-  HAFLO_DISPATCH_GEOMETRY(m, CALL);
-#undef CALL
-  return hip_status(hipGetLastError());
+  // fixed 4-bit windows over the table c^0..c^15: every window multiplies (by 1 for a zero
+  // digit), so the instruction stream is the same for every element
+  std::vector<uint32_t> prog;
+  prog.push_back(eng_ins(ENG_LOAD_L, 0));
+  append_power_table16(prog);
+  prog.push_back(eng_ins(ENG_LOAD_TD, 60));
+  for (int wi = 14; wi >= 0; --wi) {
+    for (int s = 0; s < 4; ++s) prog.push_back(eng_ins(ENG_SQ));
+    prog.push_back(eng_ins(ENG_MUL_TD, (uint32_t)(4 * wi)));
+  }
+  ProgInline pi;
+  if (!to_inline(pi, prog)) return HAFLO_EINVAL;
+  EngineIO io = engine_io(m);
+  io.in_limbs = (const u32*)d_c;
+  io.in_limbs_stride = m.nl;
+  io.k64 = (const unsigned long long*)d_k;
+  io.out = (u32*)d_out;
+  io.tables = (u32*)d_workspace;
+  io.table_entries = 16;
+  return launch_engine(m, modexp_shape(ctx, count, m.t), (hipStream_t)stream, pi, io, count);
 }
 
 int haflo_scalar_mul_i64_bcast(const haflo_ctx* ctx, const void* d_c, int64_t k, void* d_out, size_t count,
@@ -339,14 +238,19 @@ int haflo_scalar_mul_i64_bcast(const haflo_ctx* ctx, const void* d_c, int64_t k,
     if (rc != HAFLO_OK) return rc;
     src = (const u32*)d_out;
   }
-  SchedInline si;
-  inline_schedule(si, make_schedule(Big(mag), 4));
-  const LaunchShape sh = modexp_shape(ctx, count, m.t);
-#define CALL(LPT, T) \
-  HAFLO_LAUNCH((k_pow_bcast<LPT, T>), sh, st, m.ref(), si, src, (u32*)d_out, (u32*)d_workspace, count)
-  HAFLO_DISPATCH_GEOMETRY(m, CALL);
-#undef CALL
-  return hip_status(hipGetLastError());
+  const HostSched plan = make_schedule(Big(mag), 4);
+  std::vector<uint32_t> prog;
+  prog.push_back(eng_ins(ENG_LOAD_L, 0));
+  append_modexp(prog, plan);
+  ProgInline pi;
+  if (!to_inline(pi, prog)) return HAFLO_EINVAL;
+  EngineIO io = engine_io(m);
+  io.in_limbs = src;
+  io.in_limbs_stride = m.nl;
+  io.out = (u32*)d_out;
+  io.tables = (u32*)d_workspace;
+  io.table_entries = plan.table_len + 1;
+  return launch_engine(m, modexp_shape(ctx, count, m.t), st, pi, io, count);
 }
 
 int haflo_decrypt(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain, size_t count, void* d_workspace,
@@ -369,12 +273,16 @@ int haflo_decrypt(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain,
   }
   for (int side = 0; side < 2; ++side) {
     const ModHost& m = side ? ctx->Q2 : ctx->P2;
-    const DevSched& s = side ? ctx->sched_qm1 : ctx->sched_pm1;
-    u32* y = side ? yq : yp;
-    const LaunchShape sh = modexp_shape(ctx, count, m.t);
-#define CALL(LPT, T) HAFLO_LAUNCH((k_dec_pow<LPT, T>), sh, st, m.ref(), s.ref(), (const u32*)canon29, y, tables, count)
-    HAFLO_DISPATCH_GEOMETRY(m, CALL);
-#undef CALL
+    const DevProg& dp = side ? ctx->prog_dec_q : ctx->prog_dec_p;
+    EngineIO io = engine_io(m);
+    io.in_limbs = canon29;
+    io.in_limbs_stride = 2 * m.nl;
+    io.out = side ? yq : yp;
+    io.tables = tables;
+    io.table_entries = dp.table_entries;
+    ProgPtr prog = {dp.d_ins, (int)dp.host.size()};
+    int rc = launch_engine(m, modexp_shape(ctx, count, m.t), st, prog, io, count);
+    if (rc != HAFLO_OK) return rc;
   }
   {
     const ModHost& m = ctx->P;

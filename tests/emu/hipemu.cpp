@@ -4,6 +4,9 @@
 #include <ucontext.h>
 #include <unistd.h>
 
+#include <execinfo.h>
+#include <signal.h>
+
 #include <map>
 #include <vector>
 
@@ -162,6 +165,41 @@ void launch(dim3 grid, dim3 block, const std::function<void()>& fn) {
 // device memory: the buffer ends right at an inaccessible page
 namespace {
 std::map<void*, std::pair<void*, size_t>> allocs;
+std::map<void*, size_t> alloc_bytes;
+
+// an out-of-bounds access: say which lane did it and which buffer it ran off
+void on_fault(int, siginfo_t* si, void*) {
+  char* addr = (char*)si->si_addr;
+  fprintf(stderr, "hipemu: memory fault at %p", (void*)addr);
+  if (cur) fprintf(stderr, " in block %u thread %u", cur->st.bid.x, cur->st.tid.x);
+  for (auto& kv : allocs) {
+    char* base = (char*)kv.second.first;
+    if (addr >= base && addr < base + kv.second.second)
+      fprintf(stderr, ": %ld bytes past the start of a %zu-byte buffer", (long)(addr - (char*)kv.first),
+              alloc_bytes[kv.first]);
+  }
+  fprintf(stderr, "\n");
+  void* frames[32];
+  int nf = backtrace(frames, 32);
+  backtrace_symbols_fd(frames, nf, 2);
+  _exit(139);
+}
+void install_handler() {
+  static bool done = false;
+  if (done) return;
+  done = true;
+  static char altstack[1 << 16];
+  stack_t ss;
+  ss.ss_sp = altstack;
+  ss.ss_size = sizeof(altstack);
+  ss.ss_flags = 0;
+  sigaltstack(&ss, nullptr);
+  struct sigaction sa;
+  memset(&sa, 0, sizeof(sa));
+  sa.sa_sigaction = on_fault;
+  sa.sa_flags = SA_SIGINFO | SA_ONSTACK;
+  sigaction(SIGSEGV, &sa, nullptr);
+}
 }
 void* dev_alloc(size_t bytes) {
   size_t page = (size_t)sysconf(_SC_PAGESIZE);
@@ -175,12 +213,15 @@ void* dev_alloc(size_t bytes) {
   char* p = base + body_pages * page - want;
   memset(base, 0xCD, body_pages * page);
   allocs[p] = std::make_pair((void*)base, total);
+  alloc_bytes[p] = bytes;
+  install_handler();
   return p;
 }
 void dev_free(void* p) {
   auto it = allocs.find(p);
   if (it == allocs.end()) return;
   munmap(it->second.first, it->second.second);
+  alloc_bytes.erase(p);
   allocs.erase(it);
 }
 
