@@ -75,6 +75,9 @@ def main():
     ap.add_argument("--bits", type=int, default=2048)
     ap.add_argument("--cpu-sample", type=int, default=192)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy: the known-size kernel that scales "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, sharding); "
@@ -116,6 +119,13 @@ def main():
                            dev(r_words[:F]))
     k_quarter = 1 << 6  # the fore-gradient's factor 0.25 at 2^8, keeps decoded sums inside int64
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.int32, device="cuda").fill_(7)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)  # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     stages = ("encode", "encrypt", "add", "scalar_mul", "matvec_xt_d", "matvec_x_w", "decrypt", "decode")
     # HIP events on torch's current stream, which is the stream every kernel is launched on

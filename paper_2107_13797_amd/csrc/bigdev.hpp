@@ -101,6 +101,26 @@ __device__ __forceinline__ void hi_normalise(u64 (&A)[LPT], const Grp<T>& g, u32
   }
 }
 
+// Where the word-serial operand b of a product comes from: the lanes' own
+// registers (limb i sits on lane i / LPT and is broadcast with ds_bpermute), or
+// an NL-limb array in memory that every lane of the group reads directly.
+template <int LPT, int T>
+struct BRegs {
+  const u32 (&b)[LPT];
+  __device__ __forceinline__ u32 limb(int o, int r, int src_addr) const {
+    (void)o;
+    return (T == 1) ? b[r] : (u32)__builtin_amdgcn_ds_bpermute(src_addr, (int)b[r]);
+  }
+};
+template <int LPT, int T>
+struct BMem {
+  const u32* p;
+  __device__ __forceinline__ u32 limb(int o, int r, int src_addr) const {
+    (void)src_addr;
+    return p[o * LPT + r];
+  }
+};
+
 // Montgomery product out = a * b / 2^(29*NL) mod n, lazy in and out.
 //   a, b: limbs < 2^29 + 2^8, values < 4n.  n: canonical limbs of the odd
 //   modulus.  n0inv = -n^-1 mod 2^29.  out: limbs < 2^29 + 2^5, value < 2n.
@@ -109,9 +129,9 @@ __device__ __forceinline__ void hi_normalise(u64 (&A)[LPT], const Grp<T>& g, u32
 // every lane hands the low 29 bits of its lowest column to the lane below and
 // keeps the rest as a carry, so no lane is special-cased.
 // NORM = number of steps between hi_normalise passes (<= 31).
-template <int LPT, int T>
-__device__ __forceinline__ void montmul(u32 (&out)[LPT], const u32 (&a)[LPT], const u32 (&b)[LPT],
-                                        const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
+template <int LPT, int T, class BSrc>
+__device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT], const BSrc& bsrc,
+                                             const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
   constexpr int NORM = (LPT <= 31) ? LPT : (LPT / 2);
   static_assert(NORM <= 31 && LPT % NORM == 0, "normalisation interval");
   const u32 eight = opaque_eight();
@@ -123,7 +143,7 @@ __device__ __forceinline__ void montmul(u32 (&out)[LPT], const u32 (&a)[LPT], co
     const int src = g.base_addr + (o << 2);
 #pragma unroll
     for (int r = 0; r < LPT; ++r) {
-      u32 bi = (T == 1) ? b[r] : (u32)__builtin_amdgcn_ds_bpermute(src, (int)b[r]);
+      u32 bi = bsrc.limb(o, r, src);
       A[0] = mad64(a[0], bi, A[0]);
       u32 qv = ((u32)A[0] * n0inv) & LIMB_MASK;
       u32 q = g.bcast(qv, 0);
@@ -154,6 +174,22 @@ __device__ __forceinline__ void montmul(u32 (&out)[LPT], const u32 (&a)[LPT], co
     c = v >> LIMB_BITS;
   }
   if (T > 1) out[0] += g.from_lower((u32)c);
+}
+
+// b in registers (out may alias a and b)
+template <int LPT, int T>
+__device__ __forceinline__ void montmul(u32 (&out)[LPT], const u32 (&a)[LPT], const u32 (&b)[LPT],
+                                        const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
+  BRegs<LPT, T> src = {b};
+  montmul_core<LPT, T>(out, a, src, n, n0inv, g);
+}
+
+// b = NL limbs at `bmem`, the same array for every lane of the group
+template <int LPT, int T>
+__device__ __forceinline__ void montmul_mem(u32 (&out)[LPT], const u32 (&a)[LPT], const u32* bmem,
+                                            const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
+  BMem<LPT, T> src = {bmem};
+  montmul_core<LPT, T>(out, a, src, n, n0inv, g);
 }
 
 // Full carry propagation of signed lazy limbs (|x[j]| < 2^30): afterwards every

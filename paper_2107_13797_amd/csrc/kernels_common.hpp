@@ -129,18 +129,16 @@ __global__ __launch_bounds__(kBlockThreads, 4) void k_engine(ModRef M, Prog P, E
         }
         continue;
       }
-      u32 y[LPT];
       if (op == ENG_SQ) {
-#pragma unroll
-        for (int j = 0; j < LPT; ++j) y[j] = acc[j];
+        montmul<LPT, T>(acc, acc, acc, mod.n, mod.n0inv, g);
       } else {
+        // the multiplier is read limb by limb straight from its table slot or constant array
         const u32* src;
         if (op == ENG_MUL_C) src = io.constant[a];
         else src = table + (size_t)(op == ENG_MUL_TD ? (u32)(k >> a) & 15u : a) * NL;
-        if (tab_ok || op == ENG_MUL_C) load_limbs<LPT, T>(y, src, g);
-        else zero_limbs<LPT>(y);
+        if (!(tab_ok || op == ENG_MUL_C)) src = io.constant[kConstR1];
+        montmul_mem<LPT, T>(acc, acc, src, mod.n, mod.n0inv, g);
       }
-      montmul<LPT, T>(acc, acc, y, mod.n, mod.n0inv, g);
       if (op == ENG_MUL_T_ST && tab_ok) store_limbs<LPT, T>(table + (size_t)b * NL, acc, g);
     }
     if (io.out) {

@@ -1,0 +1,197 @@
+"""The library's kernel sources, compiled for the CPU against a stand-in for the
+HIP runtime (tests/emu), run through the same C entry points and compared with
+the oracle. This is a host-side check of indexing, bounds (device buffers end
+at a guard page) and lock-step convergence of the cross-lane code; it is not a
+parity claim for the GPU build, which tests/test_gpu_parity.py covers.
+"""
+import ctypes as C
+import random
+
+import numpy as np
+import pytest
+
+from conftest import oracle_key
+from oracle import paillier_oracle as O
+from paper_2107_13797_amd import _cabi, synth
+
+BITS = 512
+
+
+@pytest.fixture(scope="module")
+def emu():
+    import sys, os
+    sys.path.insert(0, os.path.join(os.path.dirname(__file__), "emu"))
+    import build_emu
+    lib = _cabi.bind(C.CDLL(build_emu.build()))
+    lib.hipemu_alloc.restype = C.c_void_p
+    lib.hipemu_alloc.argtypes = [C.c_size_t]
+    lib.hipemu_free.argtypes = [C.c_void_p]
+    return lib
+
+
+class Dev:
+    """A 'device' buffer of the emulated runtime holding a numpy array."""
+
+    def __init__(self, lib, arr):
+        arr = np.ascontiguousarray(arr)
+        self.lib, self.n, self.dtype, self.shape = lib, arr.nbytes, arr.dtype, arr.shape
+        self.p = lib.hipemu_alloc(max(self.n, 1))
+        C.memmove(self.p, arr.ctypes.data, self.n)
+
+    def get(self):
+        out = np.empty(self.shape, self.dtype)
+        C.memmove(out.ctypes.data, self.p, self.n)
+        return out
+
+    def __del__(self):
+        self.lib.hipemu_free(self.p)
+
+
+@pytest.fixture(scope="module")
+def env(emu):
+    p, q = oracle_key(BITS)
+    sk = O.PrivateKey(p, q)
+    ctx = C.c_void_p()
+
+    def le(x, nbytes):
+        return (C.c_uint8 * nbytes).from_buffer_copy(x.to_bytes(nbytes, "little"))
+
+    assert emu.haflo_ctx_create_private(le(p, BITS // 16), le(q, BITS // 16), BITS, C.byref(ctx)) == 0
+    cb = C.c_size_t()
+    emu.haflo_ctx_info(ctx, None, None, None, C.byref(cb), None)
+    yield emu, ctx, sk, cb.value // 4
+    emu.haflo_ctx_destroy(ctx)
+
+
+def words(lib, xs, nl):
+    return Dev(lib, synth.ints_to_words(xs, nl))
+
+
+def zeros(lib, shape, dtype=np.uint32):
+    return Dev(lib, np.zeros(shape, dtype))
+
+
+def export(lib, ctx, d_cipher, count):
+    out = zeros(lib, (count, BITS // 16))
+    assert lib.haflo_export_cipher(ctx, d_cipher.p, out.p, count, None) == 0
+    return synth.words_to_ints(out.get())
+
+
+def ws(lib, ctx, op, rows, cols=0):
+    nb = lib.haflo_workspace_bytes(ctx, op, rows, cols)
+    assert nb != 2 ** 64 - 1
+    return zeros(lib, (nb // 4 + 1,)), nb
+
+
+def test_import_export_add_and_montgomery_form(env):
+    lib, ctx, sk, nlw = env
+    n, nsq = sk.n, sk.n ** 2
+    rng = random.Random(1)
+    cs = [rng.randrange(nsq) for _ in range(5)] + [0, 1, nsq - 1]
+    d_int, st = zeros(lib, (len(cs), nlw)), zeros(lib, (1,))
+    assert lib.haflo_import_cipher(ctx, words(lib, cs, BITS // 16).p, d_int.p, st.p, len(cs), None) == 0
+    assert export(lib, ctx, d_int, len(cs)) == cs and st.get()[0] == 0
+    # the internal form is the Montgomery form in 29-bit limbs (textbook identity x*R mod N)
+    R = 1 << (29 * nlw)
+    internal = d_int.get()
+    assert [sum(int(v) << (29 * i) for i, v in enumerate(row)) for row in internal] == [c * R % nsq for c in cs]
+    d_sum = zeros(lib, (len(cs), nlw))
+    assert lib.haflo_add(ctx, d_int.p, d_int.p, d_sum.p, len(cs), None) == 0
+    assert export(lib, ctx, d_sum, len(cs)) == [c * c % nsq for c in cs]
+    bad = [nsq, 3]
+    assert lib.haflo_import_cipher(ctx, words(lib, bad, BITS // 16).p, d_int.p, st.p, 2, None) == 0
+    assert export(lib, ctx, d_int, 2) == [0, 3] and st.get()[0] == 1
+
+
+def test_encrypt_decrypt_scalar_mul(env):
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    n = pk.n
+    lp = BITS // 32
+    rng = random.Random(2)
+    ms = [rng.randrange(n) for _ in range(3)] + [0, 1, n - 1]
+    rs = [rng.randrange(1, n) for _ in range(3)] + [1, n - 1, 2]
+    d_c = zeros(lib, (len(ms), nlw))
+    w, nb = ws(lib, ctx, _cabi.OP_ENCRYPT, len(ms))
+    assert lib.haflo_encrypt(ctx, words(lib, ms, lp).p, words(lib, rs, lp).p, d_c.p, len(ms), w.p, nb, None) == 0
+    want = [O.encrypt(pk, m, r) for m, r in zip(ms, rs)]
+    assert export(lib, ctx, d_c, len(ms)) == want
+    d_pl = zeros(lib, (len(ms), lp))
+    w, nb = ws(lib, ctx, _cabi.OP_DECRYPT, len(ms))
+    assert lib.haflo_decrypt(ctx, d_c.p, d_pl.p, len(ms), w.p, nb, None) == 0
+    assert synth.words_to_ints(d_pl.get()) == ms
+    ks = [rng.getrandbits(64) for _ in range(3)] + [0, 1, 2 ** 64 - 1]
+    d_o = zeros(lib, (len(ms), nlw))
+    w, nb = ws(lib, ctx, _cabi.OP_SCALAR_MUL, len(ms))
+    assert lib.haflo_scalar_mul_u64(ctx, d_c.p, Dev(lib, np.array(ks, dtype=np.uint64)).p, d_o.p, len(ms), w.p, nb,
+                                    None) == 0
+    assert export(lib, ctx, d_o, len(ms)) == [pow(c, k, n * n) for c, k in zip(want, ks)]
+    for k in (0, 1, 5, -1, -7, 2 ** 21, -(2 ** 40) + 3):
+        assert lib.haflo_scalar_mul_i64_bcast(ctx, d_c.p, k, d_o.p, len(ms), w.p, nb, None) == 0
+        assert export(lib, ctx, d_o, len(ms)) == [O.scalar_mul(pk, c, k) for c in want], k
+
+
+def test_matvec_sum(env):
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    n = pk.n
+    rng = random.Random(3)
+    cs = [O.encrypt(pk, rng.randrange(n), rng.randrange(1, n)) for _ in range(7)]
+    d_c = zeros(lib, (len(cs), nlw))
+    assert lib.haflo_import_cipher(ctx, words(lib, cs, BITS // 16).p, d_c.p, None, len(cs), None) == 0
+    npr = np.random.default_rng(5)
+    X = npr.integers(-(1 << 19), 1 << 19, size=(7, 3)).astype(np.int32)
+    X[0, 0], X[1, 1], X[2, 2] = 0, -1, -2 ** 31
+    w, nb = ws(lib, ctx, _cabi.OP_MATVEC_XT_D, 7, 3)
+    d_o = zeros(lib, (3, nlw))
+    assert lib.haflo_cipher_matvec(ctx, 0, d_c.p, Dev(lib, X).p, 7, 3, d_o.p, w.p, nb, None) == 0
+    assert export(lib, ctx, d_o, 3) == O.matvec(pk, 0, cs, X.tolist())
+    Y = npr.integers(-(1 << 16), 1 << 16, size=(5, 7)).astype(np.int32)
+    Y[npr.random(Y.shape) < 0.5] = 0
+    Y[3, :] = 0
+    w, nb = ws(lib, ctx, _cabi.OP_MATVEC_X_W, 5, 7)
+    d_o = zeros(lib, (5, nlw))
+    assert lib.haflo_cipher_matvec(ctx, 1, d_c.p, Dev(lib, Y).p, 5, 7, d_o.p, w.p, nb, None) == 0
+    assert export(lib, ctx, d_o, 5) == O.matvec(pk, 1, cs, Y.tolist())
+    w, nb = ws(lib, ctx, _cabi.OP_MATVEC_XT_D, 7, 1)
+    d_s = zeros(lib, (1, nlw))
+    assert lib.haflo_cipher_sum(ctx, d_c.p, 7, d_s.p, w.p, nb, None) == 0
+    assert export(lib, ctx, d_s, 1) == [O.summation(pk, cs)]
+
+
+def test_encode_decode(env):
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    n = pk.n
+    lp = BITS // 32
+    vals = np.concatenate([np.array([0.0, 1.0, -1.0, 0.5, -0.25, np.inf, np.nan, 1e30, -1e30, 1.5 * 2.0 ** -24,
+                                     2.5 * 2.0 ** -24, -3.4e38], dtype=np.float32), synth.normal_f32(300, 0.25, 9)])
+    d_pl, d_st = zeros(lib, (len(vals), lp)), zeros(lib, (len(vals),))
+    assert lib.haflo_encode_f32(ctx, Dev(lib, vals).p, 24, d_pl.p, d_st.p, len(vals), None) == 0
+    want = [O.encode(pk, float(v), 24) for v in vals]
+    assert list(zip(synth.words_to_ints(d_pl.get()), d_st.get().tolist())) == want
+    d_q, d_v = zeros(lib, (len(vals),), np.int64), zeros(lib, (len(vals),), np.float64)
+    assert lib.haflo_decode(ctx, d_pl.p, 24, d_q.p, d_v.p, d_st.p, len(vals), None) == 0
+    assert list(zip(d_q.get().tolist(), d_v.get().tolist(), d_st.get().tolist())) == [O.decode(pk, m, 24)
+                                                                                     for m, _ in want]
+    edge = [n // 2, n // 2 + 1, 2 ** 63 - 1, 2 ** 63, n - 2 ** 63, n - 2 ** 63 - 1, n - 1, 0, 1 << 64, n - (1 << 64)]
+    d_q, d_v, d_st = zeros(lib, (len(edge),), np.int64), zeros(lib, (len(edge),), np.float64), zeros(lib, (len(edge),))
+    assert lib.haflo_decode(ctx, words(lib, edge, lp).p, 40, d_q.p, d_v.p, d_st.p, len(edge), None) == 0
+    assert list(zip(d_q.get().tolist(), d_v.get().tolist(), d_st.get().tolist())) == [O.decode(pk, m, 40) for m in edge]
+    d_e, d_st = zeros(lib, (len(vals),), np.int32), zeros(lib, (len(vals),))
+    assert lib.haflo_encode_exponents_f32(Dev(lib, vals).p, 16, d_e.p, d_st.p, len(vals), None) == 0
+    assert list(zip(d_e.get().tolist(), d_st.get().tolist())) == [O.encode_exponent(float(v), 16) for v in vals]
+
+
+def test_op_cost_and_workspace_queries(env):
+    lib, ctx, sk, nlw = env
+    mm, limbs = C.c_uint64(), C.c_uint32()
+    assert lib.haflo_op_cost(ctx, _cabi.OP_ENCRYPT, C.byref(mm), C.byref(limbs)) == 0
+    # a 512-bit exponent needs at least 511 squarings and fewer than 1.5 products per bit
+    assert 511 < mm.value < 768 and limbs.value == BITS // 16
+    assert lib.haflo_op_cost(ctx, 99, None, None) == -1
+    assert lib.haflo_workspace_bytes(ctx, 99, 1, 1) == 2 ** 64 - 1
+    assert lib.haflo_encrypt(ctx, None, None, None, 4, None, 0, None) == -1
+    small = zeros(lib, (4,))
+    d = zeros(lib, (1, nlw))
+    assert lib.haflo_encrypt(ctx, small.p, small.p, d.p, 1, small.p, 16, None) == -1  # workspace too small
