@@ -96,9 +96,9 @@ void append_modexp(std::vector<uint32_t>& prog, const HostSched& h) {
   }
 }
 
-void append_power_table16(std::vector<uint32_t>& prog) {
+void append_power_table(std::vector<uint32_t>& prog, int entries) {
   prog.push_back(eng_ins(ENG_STORE_T, 1));
-  for (uint32_t d = 2; d < 16; ++d) prog.push_back(eng_ins(ENG_MUL_T_ST, 1, d));
+  for (uint32_t d = 2; d < (uint32_t)entries; ++d) prog.push_back(eng_ins(ENG_MUL_T_ST, 1, d));
   prog.push_back(eng_ins(ENG_LOAD_C, kConstR1));
   prog.push_back(eng_ins(ENG_STORE_T, 0));
 }

@@ -67,8 +67,8 @@ inline uint32_t eng_ins(uint32_t op, uint32_t a = 0, uint32_t b = 0) { return op
 
 // acc = acc^e for the plan `h`, using table slots [0, h.table_len] (the last one as scratch)
 void append_modexp(std::vector<uint32_t>& prog, const HostSched& h);
-// table[d] = x^d for d < 16 from acc = x (leaves acc = x^15)
-void append_power_table16(std::vector<uint32_t>& prog);
+// table[d] = x^d for d < entries from acc = x (leaves acc = 1 in Montgomery form)
+void append_power_table(std::vector<uint32_t>& prog, int entries);
 
 struct DevProg {
   std::vector<uint32_t> host;
@@ -159,8 +159,9 @@ size_t ws_encrypt(const haflo_ctx* ctx, size_t count);
 size_t ws_scalar_mul(const haflo_ctx* ctx, size_t count);
 size_t ws_decrypt(const haflo_ctx* ctx, size_t count);
 
-// tables[i][d] = c_i^d for d < 16 (kernels_modexp.hip)
-int power_tables16(const haflo_ctx* ctx, const uint32_t* d_c, uint32_t* d_tables, size_t count, hipStream_t st);
+// tables[i][d] = c_i^d for d < entries (kernels_modexp.hip)
+int power_tables(const haflo_ctx* ctx, const uint32_t* d_c, uint32_t* d_tables, int entries, size_t count,
+                 hipStream_t st);
 
 // out[i] = in[i]^-1 mod n^2 on internal ciphertexts; out may alias in (kernels_matvec.hip)
 int invert_batch(const haflo_ctx* ctx, const uint32_t* in, uint32_t* out, size_t count, hipStream_t st);

@@ -26,14 +26,16 @@ template <int T>
 struct Batch {
   int gpb;  // groups per block
   int gib;  // this lane's group inside the block
-  __device__ __forceinline__ Batch() {
+  unsigned block, nblocks;  // this block's index among the blocks that share the batch
+  __device__ __forceinline__ Batch() : Batch(blockIdx.x, gridDim.x) {}
+  __device__ __forceinline__ Batch(unsigned block_, unsigned nblocks_) : block(block_), nblocks(nblocks_) {
     gpb = (int)blockDim.x / T;
     gib = (int)threadIdx.x / T;
   }
-  __device__ __forceinline__ size_t first() const { return (size_t)blockIdx.x * gpb; }
-  __device__ __forceinline__ size_t stride() const { return (size_t)gridDim.x * gpb; }
+  __device__ __forceinline__ size_t first() const { return (size_t)block * gpb; }
+  __device__ __forceinline__ size_t stride() const { return (size_t)nblocks * gpb; }
   // index of this group's private slot in a per-launch workspace
-  __device__ __forceinline__ size_t slot() const { return (size_t)blockIdx.x * gpb + gib; }
+  __device__ __forceinline__ size_t slot() const { return (size_t)block * gpb + gib; }
 };
 
 // One cheap carry pass for a lazy sum: limbs end below 2^29 + 2^4.
@@ -84,10 +86,11 @@ struct EngineIO {
 // through the one unrolled loop instantiated here, which keeps the register
 // footprint at what a single product needs.
 template <int LPT, int T, class Prog>
-__global__ __launch_bounds__(kBlockThreads, 4) void k_engine(ModRef M, Prog P, EngineIO io, size_t count) {
+__device__ __forceinline__ void engine_run(const ModRef& M, const Prog& P, const EngineIO& io, size_t count,
+                                           unsigned block, unsigned nblocks) {
   constexpr int NL = LPT * T;
   Grp<T> g;
-  Batch<T> bt;
+  Batch<T> bt(block, nblocks);
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
   for (size_t base = bt.first(); base < count; base += bt.stride()) {
@@ -146,6 +149,25 @@ __global__ __launch_bounds__(kBlockThreads, 4) void k_engine(ModRef M, Prog P, E
       if (active) store_limbs<LPT, T>(io.out + item * (size_t)NL, acc, g);
     }
   }
+}
+
+template <int LPT, int T, class Prog>
+__global__ __launch_bounds__(kBlockThreads, 4) void k_engine(ModRef M, Prog P, EngineIO io, size_t count) {
+  engine_run<LPT, T, Prog>(M, P, io, count, blockIdx.x, gridDim.x);
+}
+
+// Two independent jobs of the same geometry in one launch (the two prime-power
+// branches of decryption): the first `split` blocks run job 0, the rest job 1.
+struct EngineJob {
+  ModRef M;
+  ProgPtr P;
+  EngineIO io;
+};
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads, 4) void k_engine_pair(EngineJob j0, EngineJob j1, unsigned split,
+                                                                  size_t count) {
+  if (blockIdx.x < split) engine_run<LPT, T, ProgPtr>(j0.M, j0.P, j0.io, count, blockIdx.x, split);
+  else engine_run<LPT, T, ProgPtr>(j1.M, j1.P, j1.io, count, blockIdx.x - split, gridDim.x - split);
 }
 
 }  // namespace dev

@@ -16,9 +16,29 @@ using namespace haflo::dev;
 
 namespace {
 
+// Orientation 1: unsigned 4-bit digits of |x|, positional tables.
 constexpr int kWin = 4;                    // window width of the exponent digits
 constexpr int kWinEntries = 1 << kWin;     // table entries per base (entry 0 = 1)
 constexpr int kMaxPos = (32 + kWin - 1) / kWin;  // digit positions of a 32-bit magnitude
+
+// Orientation 0: signed 5-bit digits. |x| + c, c = 16 (32^S - 1) / 31, is read in base 32 and
+// each digit e is taken as d = e - 16 in [-16, 15], so |x| = sum d_s 32^s: the table holds only
+// c^0..c^16 and a negative digit sends the term to the accumulator of the opposite sign.
+constexpr int kSWin = 5;
+constexpr int kSEntries = 17;
+constexpr int kSMaxPos = 7;  // 32^7 - c_7 > 2^31
+__host__ __device__ inline unsigned long long signed_digit_offset(int npos) {
+  unsigned long long c = 0;
+  for (int s = 0; s < npos; ++s) c = c * 32ull + 16ull;
+  return c;
+}
+// positions needed so that maxmag + c_S < 32^S (0 for an all-zero matrix)
+__host__ __device__ inline int signed_digit_positions(unsigned maxmag) {
+  if (maxmag == 0) return 0;
+  for (int s = 1; s < kSMaxPos; ++s)
+    if ((unsigned long long)maxmag + signed_digit_offset(s) < (1ull << (kSWin * s))) return s;
+  return kSMaxPos;
+}
 
 // ---------------------------------------------------------------------------
 // modular inverse by batched division steps
@@ -190,28 +210,31 @@ __global__ __launch_bounds__(kBlockThreads) void k_invert(ModRef M, const u32* i
 // shared pieces
 // ---------------------------------------------------------------------------
 
-// bit length of the largest |x| in the matrix (atomicMax into a zeroed word)
+// largest |x| in the matrix (atomicMax into a zeroed word)
 __global__ __launch_bounds__(kBlockThreads) void k_zero_word(u32* p) {
   if (blockIdx.x == 0 && threadIdx.x == 0) *p = 0u;
 }
-__global__ __launch_bounds__(kBlockThreads) void k_maxbits(const int* __restrict__ X, size_t total, u32* maxbits) {
+__global__ __launch_bounds__(kBlockThreads) void k_maxmag(const int* __restrict__ X, size_t total, u32* maxmag) {
   u32 m = 0;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     int x = X[i];
     u32 mag = x < 0 ? 0u - (u32)x : (u32)x;
-    m |= mag;
+    m = mag > m ? mag : m;
   }
-  // OR preserves the highest set bit; reduce across the wave with ballots
-  u32 bits = 0;
+  // wave maximum, bit by bit from the top: keep the lanes that still can hold it
+  u32 best = 0;
+  bool cand = true;
 #pragma unroll 1
   for (int b = 31; b >= 0; --b) {
-    if (__builtin_amdgcn_ballot_w64(((m >> b) & 1u) != 0u) != 0ull) {
-      bits = (u32)b + 1u;
-      break;
+    bool has = cand && ((m >> b) & 1u);
+    if (__builtin_amdgcn_ballot_w64(has) != 0ull) {
+      best |= 1u << b;
+      cand = has;
     }
   }
-  if ((threadIdx.x & (WAVE - 1)) == 0 && bits) atomicMax(maxbits, bits);
+  if ((threadIdx.x & (WAVE - 1)) == 0 && best) atomicMax(maxmag, best);
 }
+__device__ __forceinline__ int bit_length(u32 v) { return v ? 32 - __builtin_clz(v) : 0; }
 
 // product of the per-group accumulators of a block, left in group 0.
 // lds: (groups per block / 2) * NL limbs.
@@ -250,7 +273,7 @@ template <int LPT, int T>
 __global__ __launch_bounds__(kBlockThreads, 2) void k_xtd_main(ModRef M, const int* __restrict__ X, size_t rows,
                                                             size_t cols, const u32* __restrict__ tables, int rsplit,
                                                             u32* __restrict__ partials,
-                                                            const u32* __restrict__ maxbits) {
+                                                            const u32* __restrict__ maxmag) {
   constexpr int NL = LPT * T;
   __shared__ u32 lds[(kBlockThreads / 2) * LPT];
   Grp<T> g;
@@ -259,7 +282,9 @@ __global__ __launch_bounds__(kBlockThreads, 2) void k_xtd_main(ModRef M, const i
   const size_t j = b % cols;
   const int rs = (int)((b / cols) % (size_t)rsplit);
   const int s = (int)(b / (cols * (size_t)rsplit));
-  if ((u32)(s * kWin) >= *maxbits) return;  // no digit at this position anywhere
+  const int npos = signed_digit_positions(*maxmag);
+  if (s >= npos) return;  // no digit at this position anywhere
+  const u64 offset = signed_digit_offset(npos);
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
   const size_t r0 = rows * (size_t)rs / (size_t)rsplit, r1 = rows * (size_t)(rs + 1) / (size_t)rsplit;
@@ -272,11 +297,12 @@ __global__ __launch_bounds__(kBlockThreads, 2) void k_xtd_main(ModRef M, const i
     bool active = i < r1;
     int x = active ? X[i * cols + j] : 0;
     u32 mag = x < 0 ? 0u - (u32)x : (u32)x;
-    u32 dgt = (mag >> (s * kWin)) & (u32)(kWinEntries - 1);
-    const u32* entry = active ? tables + (i * (size_t)kWinEntries + dgt) * NL : M.r1;
+    int d = (int)((((u64)mag + offset) >> (s * kSWin)) & 31ull) - 16;
+    u32 dgt = (u32)(d < 0 ? -d : d);
+    const u32* entry = active ? tables + (i * (size_t)kSEntries + dgt) * NL : M.r1;
     u32 t[LPT], cur[LPT];
     load_limbs<LPT, T>(t, entry, g);
-    bool neg = x < 0;
+    bool neg = (x < 0) != (d < 0);
 #pragma unroll
     for (int jj = 0; jj < LPT; ++jj) cur[jj] = neg ? accn[jj] : accp[jj];
     montmul<LPT, T>(cur, cur, t, mod.n, mod.n0inv, g);
@@ -289,7 +315,7 @@ __global__ __launch_bounds__(kBlockThreads, 2) void k_xtd_main(ModRef M, const i
   block_product<LPT, T>(accp, lds, mod, bt, g);
   block_product<LPT, T>(accn, lds, mod, bt, g);
   if (bt.gib == 0) {
-    size_t slot = ((j * (size_t)kMaxPos + (size_t)s) * 2) * (size_t)rsplit + (size_t)rs;
+    size_t slot = ((j * (size_t)kSMaxPos + (size_t)s) * 2) * (size_t)rsplit + (size_t)rs;
     store_limbs<LPT, T>(partials + slot * NL, accp, g);
     store_limbs<LPT, T>(partials + (slot + (size_t)rsplit) * NL, accn, g);
   }
@@ -299,13 +325,13 @@ __global__ __launch_bounds__(kBlockThreads, 2) void k_xtd_main(ModRef M, const i
 template <int LPT, int T>
 __global__ __launch_bounds__(kBlockThreads) void k_xtd_horner(ModRef M, size_t cols, int rsplit,
                                                               const u32* __restrict__ partials, u32* __restrict__ P,
-                                                              const u32* __restrict__ maxbits) {
+                                                              const u32* __restrict__ maxmag) {
   constexpr int NL = LPT * T;
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
-  const int npos = (int)((*maxbits + (u32)kWin - 1u) / (u32)kWin);
+  const int npos = signed_digit_positions(*maxmag);
   const size_t count = cols * 2;
   for (size_t base = bt.first(); base < count; base += bt.stride()) {
     size_t item = base + bt.gib;
@@ -318,11 +344,11 @@ __global__ __launch_bounds__(kBlockThreads) void k_xtd_horner(ModRef M, size_t c
     for (int s = npos - 1; s >= 0; --s) {
       if (s != npos - 1) {
 #pragma unroll 1
-        for (int i = 0; i < kWin; ++i) montmul<LPT, T>(acc, acc, acc, mod.n, mod.n0inv, g);
+        for (int i = 0; i < kSWin; ++i) montmul<LPT, T>(acc, acc, acc, mod.n, mod.n0inv, g);
       }
 #pragma unroll 1
       for (int rs = 0; rs < rsplit; ++rs) {
-        size_t slot = ((j * (size_t)kMaxPos + (size_t)s) * 2 + sign) * (size_t)rsplit + (size_t)rs;
+        size_t slot = ((j * (size_t)kSMaxPos + (size_t)s) * 2 + sign) * (size_t)rsplit + (size_t)rs;
         load_limbs<LPT, T>(t, partials + slot * NL, g);
         montmul<LPT, T>(acc, acc, t, mod.n, mod.n0inv, g);
       }
@@ -368,13 +394,13 @@ template <int LPT, int T>
 __global__ __launch_bounds__(kBlockThreads) void k_xw_tables(ModRef M, const u32* __restrict__ bases,
                                                              const u32* __restrict__ invbases, size_t cols,
                                                              u32* __restrict__ tables,
-                                                             const u32* __restrict__ maxbits) {
+                                                             const u32* __restrict__ maxmag) {
   constexpr int NL = LPT * T;
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
-  const int npos = (int)((*maxbits + (u32)kWin - 1u) / (u32)kWin);
+  const int npos = (bit_length(*maxmag) + kWin - 1) / kWin;
   const size_t count = cols * 2;
   for (size_t base = bt.first(); base < count; base += bt.stride()) {
     size_t item = base + bt.gib;
@@ -436,13 +462,13 @@ template <int LPT, int T>
 __global__ __launch_bounds__(kBlockThreads, 4) void k_xw_main(ModRef M, size_t rows, size_t cols,
                                                            const int* __restrict__ nz, const u32* __restrict__ nzcount,
                                                            const u32* __restrict__ tables, u32* __restrict__ out,
-                                                           const u32* __restrict__ maxbits) {
+                                                           const u32* __restrict__ maxmag) {
   constexpr int NL = LPT * T;
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
-  const int npos = (int)((*maxbits + (u32)kWin - 1u) / (u32)kWin);
+  const int npos = (bit_length(*maxmag) + kWin - 1) / kWin;
   for (size_t base = bt.first(); base < rows; base += bt.stride()) {
     size_t row = base + bt.gib;
     bool active = row < rows;
@@ -505,13 +531,13 @@ int inverse_batches(const haflo_ctx* ctx) {
 
 struct XtdPlan {
   int rsplit;
-  size_t off_tables, off_partials, off_P, total;  // in u32 words; word 0 holds maxbits
+  size_t off_tables, off_partials, off_P, total;  // in u32 words; word 0 holds the largest |x|
 };
 XtdPlan xtd_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
   XtdPlan p;
   const int gpb = kBlockThreads / ctx->N.t;
-  // aim at ~4 blocks per compute unit assuming 5 live digit positions, keep >= 2 rows per group
-  size_t want = ((size_t)ctx->num_cu * 4 + cols * 5 - 1) / (cols * 5 ? cols * 5 : 1);
+  // aim at ~4 blocks per compute unit assuming 4 live digit positions, keep >= 2 rows per group
+  size_t want = ((size_t)ctx->num_cu * 4 + cols * 4 - 1) / (cols ? cols * 4 : 1);
   size_t maxsplit = rows / ((size_t)gpb * 2);
   if (want > maxsplit) want = maxsplit;
   if (want < 1) want = 1;
@@ -519,14 +545,14 @@ XtdPlan xtd_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
   p.rsplit = (int)want;
   const size_t nl = (size_t)ctx->N.nl;
   p.off_tables = 64;
-  p.off_partials = p.off_tables + rows * kWinEntries * nl;
-  p.off_P = p.off_partials + cols * kMaxPos * 2 * (size_t)p.rsplit * nl;
+  p.off_partials = p.off_tables + rows * kSEntries * nl;
+  p.off_P = p.off_partials + cols * kSMaxPos * 2 * (size_t)p.rsplit * nl;
   p.total = p.off_P + cols * 2 * nl;
   return p;
 }
 
 struct XwPlan {
-  size_t off_inv, off_tables, off_nz, off_cnt, total;  // in u32 words; word 0 holds maxbits
+  size_t off_inv, off_tables, off_nz, off_cnt, total;  // in u32 words; word 0 holds the largest |x|
 };
 XwPlan xw_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
   XwPlan p;
@@ -547,7 +573,7 @@ int sum_blocks(const haflo_ctx* ctx, size_t count) {
   return (int)(need < cap ? need : cap);
 }
 
-int launch_maxbits(const haflo_ctx* ctx, const int32_t* X, size_t total, u32* word, hipStream_t st) {
+int launch_maxmag(const haflo_ctx* ctx, const int32_t* X, size_t total, u32* word, hipStream_t st) {
   LaunchShape one;
   one.blocks = 1;
   one.threads = 64;
@@ -555,7 +581,7 @@ int launch_maxbits(const haflo_ctx* ctx, const int32_t* X, size_t total, u32* wo
   HAFLO_LAUNCH(k_zero_word, one, st, word);
   if (total) {
     LaunchShape sh = launch_shape(ctx, total, 1, 8);
-    HAFLO_LAUNCH(k_maxbits, sh, st, X, total, word);
+    HAFLO_LAUNCH(k_maxmag, sh, st, X, total, word);
   }
   return hip_status(hipGetLastError());
 }
@@ -602,7 +628,7 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
   const size_t need = haflo_workspace_bytes(ctx, orientation == 0 ? HAFLO_OP_MATVEC_XT_D : HAFLO_OP_MATVEC_X_W, rows, cols);
   if (!d_workspace || workspace_bytes < need) return HAFLO_EINVAL;
   u32* ws = (u32*)d_workspace;
-  int rc = launch_maxbits(ctx, d_X, rows * cols, ws, st);
+  int rc = launch_maxmag(ctx, d_X, rows * cols, ws, st);
   if (rc != HAFLO_OK) return rc;
   const int nbatch = inverse_batches(ctx);
   if (orientation == 0) {
@@ -611,13 +637,12 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
     u32* partials = ws + p.off_partials;
     u32* P = ws + p.off_P;
     if (rows) {
-      static_assert(kWinEntries == 16, "the shared table builder makes 16 entries");
-      rc = power_tables16(ctx, (const u32*)d_c, tables, rows, st);
+      rc = power_tables(ctx, (const u32*)d_c, tables, kSEntries, rows, st);
       if (rc != HAFLO_OK) return rc;
       LaunchShape mainsh;
       mainsh.threads = kBlockThreads;
       mainsh.gpb = kBlockThreads / m.t;
-      mainsh.blocks = (int)(cols * (size_t)p.rsplit * kMaxPos);
+      mainsh.blocks = (int)(cols * (size_t)p.rsplit * kSMaxPos);
 #define CALL(LPT, T) \
   HAFLO_LAUNCH((k_xtd_main<LPT, T>), mainsh, st, m.ref(), d_X, rows, cols, (const u32*)tables, p.rsplit, partials, (const u32*)ws)
       HAFLO_DISPATCH_GEOMETRY(m, CALL);

@@ -154,22 +154,23 @@ size_t ws_decrypt(const haflo_ctx* ctx, size_t count) {
   if (!ctx->has_priv) return 0;
   size_t tl = (size_t)std::max(ctx->prog_dec_p.table_entries, ctx->prog_dec_q.table_entries);
   return (count * (size_t)ctx->N.nl + 2 * count * (size_t)ctx->P2.nl +
-          modexp_shape(ctx, count, ctx->P2.t).slots() * tl * ctx->P2.nl) * 4;
+          2 * modexp_shape(ctx, count, ctx->P2.t).slots() * tl * ctx->P2.nl) * 4;
 }
 
-// tables[i][d] = c_i^d, d < 16, for `count` internal ciphertexts (used by the matvec)
-int power_tables16(const haflo_ctx* ctx, const uint32_t* d_c, uint32_t* d_tables, size_t count, hipStream_t st) {
+// tables[i][d] = c_i^d, d < entries, for `count` internal ciphertexts (used by the matvec)
+int power_tables(const haflo_ctx* ctx, const uint32_t* d_c, uint32_t* d_tables, int entries, size_t count,
+                 hipStream_t st) {
   const ModHost& m = ctx->N;
   std::vector<uint32_t> prog;
   prog.push_back(eng_ins(ENG_LOAD_L, 0));
-  append_power_table16(prog);
+  append_power_table(prog, entries);
   ProgInline pi;
   if (!to_inline(pi, prog)) return HAFLO_EINVAL;
   EngineIO io = engine_io(m);
   io.in_limbs = d_c;
   io.in_limbs_stride = m.nl;
   io.tables = d_tables;
-  io.table_entries = 16;
+  io.table_entries = entries;
   io.table_per_item = 1;
   return launch_engine(m, launch_shape(ctx, count, m.t, 8), st, pi, io, count);
 }
@@ -205,7 +206,7 @@ int haflo_scalar_mul_u64(const haflo_ctx* ctx, const void* d_c, const uint64_t* 
   // digit), so the instruction stream is the same for every element
   std::vector<uint32_t> prog;
   prog.push_back(eng_ins(ENG_LOAD_L, 0));
-  append_power_table16(prog);
+  append_power_table(prog, 16);
   prog.push_back(eng_ins(ENG_LOAD_TD, 60));
   for (int wi = 14; wi >= 0; --wi) {
     for (int s = 0; s < 4; ++s) prog.push_back(eng_ins(ENG_SQ));
@@ -264,6 +265,7 @@ int haflo_decrypt(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain,
   u32* yp = canon29 + count * (size_t)ctx->N.nl;
   u32* yq = yp + count * (size_t)ctx->P2.nl;
   u32* tables = yq + count * (size_t)ctx->Q2.nl;
+  const int dp_table_entries = std::max(ctx->prog_dec_p.table_entries, ctx->prog_dec_q.table_entries);
   {
     const ModHost& m = ctx->N;
     const LaunchShape sh = launch_shape(ctx, count, m.t, 8);
@@ -271,18 +273,29 @@ int haflo_decrypt(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain,
     HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
   }
-  for (int side = 0; side < 2; ++side) {
-    const ModHost& m = side ? ctx->Q2 : ctx->P2;
-    const DevProg& dp = side ? ctx->prog_dec_q : ctx->prog_dec_p;
-    EngineIO io = engine_io(m);
-    io.in_limbs = canon29;
-    io.in_limbs_stride = 2 * m.nl;
-    io.out = side ? yq : yp;
-    io.tables = tables;
-    io.table_entries = dp.table_entries;
-    ProgPtr prog = {dp.d_ins, (int)dp.host.size()};
-    int rc = launch_engine(m, modexp_shape(ctx, count, m.t), st, prog, io, count);
-    if (rc != HAFLO_OK) return rc;
+  {
+    // both prime-power branches in one launch: the first half of the grid works modulo p^2,
+    // the second half modulo q^2, each half with its own table slots
+    const ModHost& m = ctx->P2;
+    LaunchShape sh = modexp_shape(ctx, count, m.t);
+    EngineJob job[2];
+    for (int side = 0; side < 2; ++side) {
+      const ModHost& ms = side ? ctx->Q2 : ctx->P2;
+      const DevProg& dp = side ? ctx->prog_dec_q : ctx->prog_dec_p;
+      job[side].M = ms.ref();
+      job[side].P = ProgPtr{dp.d_ins, (int)dp.host.size()};
+      job[side].io = engine_io(ms);
+      job[side].io.in_limbs = canon29;
+      job[side].io.in_limbs_stride = 2 * ms.nl;
+      job[side].io.out = side ? yq : yp;
+      job[side].io.tables = tables + (side ? sh.slots() * (size_t)dp_table_entries * ms.nl : 0);
+      job[side].io.table_entries = dp_table_entries;
+    }
+    const unsigned split = (unsigned)sh.blocks;
+    sh.blocks *= 2;
+#define CALL(LPT, T) HAFLO_LAUNCH((k_engine_pair<LPT, T>), sh, st, job[0], job[1], split, count)
+    HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
   }
   {
     const ModHost& m = ctx->P;

@@ -159,6 +159,23 @@ def test_matvec_sum(env):
     assert export(lib, ctx, d_s, 1) == [O.summation(pk, cs)]
 
 
+@pytest.mark.parametrize("top", [15, 16, 17, 495, 496, 507375, 507376, 2 ** 31 - 1])
+def test_matvec_signed_digit_boundaries(env, top):
+    """Exponent magnitudes around the points where the signed base-32 recoding of
+    orientation 0 needs one more digit position."""
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    rng = random.Random(top)
+    cs = [O.encrypt(pk, rng.randrange(pk.n), rng.randrange(1, pk.n)) for _ in range(4)]
+    d_c = zeros(lib, (4, nlw))
+    assert lib.haflo_import_cipher(ctx, words(lib, cs, BITS // 16).p, d_c.p, None, 4, None) == 0
+    X = np.array([[top, -top], [top - 1, 1], [-(top // 2), top // 3], [16, -17]], dtype=np.int64).astype(np.int32)
+    w, nb = ws(lib, ctx, _cabi.OP_MATVEC_XT_D, 4, 2)
+    d_o = zeros(lib, (2, nlw))
+    assert lib.haflo_cipher_matvec(ctx, 0, d_c.p, Dev(lib, X).p, 4, 2, d_o.p, w.p, nb, None) == 0
+    assert export(lib, ctx, d_o, 2) == O.matvec(pk, 0, cs, X.tolist())
+
+
 def test_encode_decode(env):
     lib, ctx, sk, nlw = env
     pk = sk.public
