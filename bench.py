@@ -31,6 +31,11 @@ if ROOT not in sys.path:
 # (32x32+64 integer multiply-add issues at the full VALU rate on gfx950).
 PEAK_MAD32_PER_S = 256 * 64 * 2.4e9
 
+# HBM bytes per 2048-bit encryption measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this
+# launch shape, each scaled by what the counter reads for a 1 GiB device copy
+# (profiles/k_engine_encrypt_2048bit_b65536_pmc.md): (12455427 + 4566665) KiB per 65536 encryptions.
+TRAFFIC_BYTES_PER_ENCRYPT_2048 = (12455427 + 4566665) * 1024 / 65536
+
 
 def montmul_mul32(limbs):
     """32x32->64 multiply-adds of one word-serial Montgomery product on `limbs` 32-bit limbs."""
@@ -194,7 +199,8 @@ def main():
         "stage_ms": {k: v / args.steps for k, v in stage_ms.items()},
         "roofline": {"bound": "alu", "kernel": "k_encrypt", "achieved": achieved / 1e12,
                      "peak": PEAK_MAD32_PER_S / 1e12, "unit": "Tmad32/s", "frac": achieved / PEAK_MAD32_PER_S,
-                     "traffic": None,
+                     "traffic": (TRAFFIC_BYTES_PER_ENCRYPT_2048 * B if bits == 2048 else None),
+                     "traffic_unit": "bytes per launch (rocprofv3 counters, see profiles/)",
                      "algorithmic": "%d Montgomery products x (2*%d^2+%d) mul32 per encryption" % (mm, limbs, limbs)},
     }
     if not args.no_cpu:
