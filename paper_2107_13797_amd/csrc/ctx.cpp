@@ -242,6 +242,20 @@ static void build_prog_encrypt(DevProg& p, const Big& n, Uploader& up) {
   p.d_ins = up.put(p.host);
 }
 
+// Key owner's encryption, one prime-power branch: r^n mod s^2 with the exponent reduced modulo
+// the group order s (s - 1). r (word input 1, below n < 2 s^2) needs no reduction first: the
+// Montgomery product accepts it as it is. The result leaves the Montgomery domain.
+static void build_prog_encrypt_branch(DevProg& p, const Big& e, Uploader& up) {
+  p.sched = make_schedule(e, 0);
+  p.host.clear();
+  p.host.push_back(eng_ins(ENG_LOAD_W, 1));
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstR2));
+  append_modexp(p.host, p.sched);
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstOne));
+  p.table_entries = p.sched.table_len + 1;
+  p.d_ins = up.put(p.host);
+}
+
 // decryption branch for a prime s: the canonical residue c = c_hi R + c_lo (two halves of the
 // limb input) goes to Montgomery form mod s^2 as montmul(c_lo, R^2) + montmul(c_hi, R^3),
 // is raised to s - 1 and leaves the Montgomery domain
@@ -304,6 +318,19 @@ static int ctx_build(haflo_ctx* ctx, const Big& n, const Big* p, const Big* q, u
     if (!up.ok) return HAFLO_ENOMEM;
     build_prog_decrypt(ctx->prog_dec_p, Big::sub(*p, Big(1)), up);
     build_prog_decrypt(ctx->prog_dec_q, Big::sub(*q, Big(1)), up);
+    {
+      // r^n mod s^2 only depends on n modulo |(Z/s^2)*| = s (s - 1)
+      Big ordp = Big::mul(*p, Big::sub(*p, Big(1))), ordq = Big::mul(*q, Big::sub(*q, Big(1)));
+      build_prog_encrypt_branch(ctx->prog_enc_p, Big::mod(n, ordp), up);
+      build_prog_encrypt_branch(ctx->prog_enc_q, Big::mod(n, ordq), up);
+      // (p^2)^-1 mod q^2 = (p^2)^(q(q-1)-1) mod q^2 (p is a unit there), kept in Montgomery form
+      const Big& q2 = ctx->Q2.mod;
+      MontHost mq2(q2);
+      Big p2_mod_q2 = Big::mod(ctx->P2.mod, q2);
+      Big inv = mq2.powmod(p2_mod_q2, Big::sub(ordq, Big(1)));
+      Big rq2 = Big::mod(Big::pow2((size_t)kLimbBits * nl_h), q2);
+      ctx->d_p2inv = up.put(to_limbs29(Big::mod(Big::mul(inv, rq2), q2), nl_h));
+    }
     // With g = n + 1: g^(p-1) mod p^2 = 1 + (p-1)*n mod p^2, so
     // L_p(g^(p-1) mod p^2) = -q mod p and h_p = -(q^-1) mod p (p, q prime).
     MontHost mp(*p), mq(*q);
@@ -444,9 +471,18 @@ int haflo_op_cost(const haflo_ctx* ctx, int op, uint64_t* montmuls, uint32_t* mo
   uint64_t mm = 0;
   uint32_t limbs = 0;
   if (op == HAFLO_OP_ENCRYPT) {
-    // into Montgomery form, the power r^n, (1 + m n) R, the final product
-    mm = ctx->prog_enc.sched.nsquare + ctx->prog_enc.sched.nmul + 3;
-    limbs = (uint32_t)ctx->lc;
+    if (ctx->has_priv) {
+      // through p^2 and q^2: per branch into Montgomery form, the power, out of it; then one
+      // half-size product and one plain product to recombine and three full-size products
+      // (= 12 half-size ones) for the (1 + m n) factor and the Montgomery form of the result
+      mm = ctx->prog_enc_p.sched.nsquare + ctx->prog_enc_p.sched.nmul + ctx->prog_enc_q.sched.nsquare +
+           ctx->prog_enc_q.sched.nmul + 4 + 2 + 12;
+      limbs = (uint32_t)ctx->lc / 2;
+    } else {
+      // into Montgomery form, the power r^n, (1 + m n) R, the final product
+      mm = ctx->prog_enc.sched.nsquare + ctx->prog_enc.sched.nmul + 3;
+      limbs = (uint32_t)ctx->lc;
+    }
   } else if (op == HAFLO_OP_DECRYPT) {
     if (!ctx->has_priv) return HAFLO_ENOPRIV;
     // per branch: two products to reduce into Montgomery form, the power, one product out

@@ -111,6 +111,9 @@ struct haflo_ctx {
   haflo::DevProg prog_enc;     // encryption: r^n modulo n^2 and the (1 + m n) factor
   haflo::DevProg prog_dec_p;   // decryption branch: c^(p-1) modulo p^2
   haflo::DevProg prog_dec_q;   // decryption branch: c^(q-1) modulo q^2
+  haflo::DevProg prog_enc_p;   // key owner's encryption: r^(n mod p(p-1)) modulo p^2
+  haflo::DevProg prog_enc_q;   // key owner's encryption: r^(n mod q(q-1)) modulo q^2
+  uint32_t* d_p2inv = nullptr; // ((p^2)^-1 mod q^2) * R mod q^2 (P2.nl limbs)
   // device constants
   uint32_t* d_k1 = nullptr;      // n * R^2 mod n^2 (N.nl limbs): montmul(m, k1) = m*n*R
   uint32_t* d_n_words = nullptr; // n as lp 32-bit words

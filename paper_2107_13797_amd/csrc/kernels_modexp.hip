@@ -107,6 +107,52 @@ __global__ __launch_bounds__(kBlockThreads) void k_dec_crt(ModRef MP, ModRef MQ,
   }
 }
 
+// Key owner's encryption, recombination: from y_p = r^n mod p^2 and y_q = r^n mod q^2
+// (canonical) to r^n mod n^2 = y_p + p^2 ((y_q - y_p) (p^2)^-1 mod q^2), written as the
+// 2*NL limbs of a residue modulo n^2 (low half, high half).
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_enc_crt(ModRef MP2, ModRef MQ2, const u32* __restrict__ p2invR,
+                                                           const u32* __restrict__ yp, const u32* __restrict__ yq,
+                                                           u32* __restrict__ rn, size_t count) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mp, mq;
+  load_mod<LPT, T>(mp, MP2, g);
+  load_mod<LPT, T>(mq, MQ2, g);
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    size_t item = base + bt.gib;
+    bool active = item < count;
+    u32 a[LPT], b[LPT], t[LPT], u[LPT];
+    if (active) {
+      load_limbs<LPT, T>(a, yp + item * (size_t)NL, g);
+      load_limbs<LPT, T>(b, yq + item * (size_t)NL, g);
+    } else {
+      zero_limbs<LPT>(a);
+      zero_limbs<LPT>(b);
+    }
+    // y_p < p^2 < 2 q^2: one conditional subtraction reduces it modulo q^2
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) t[j] = a[j];
+    canonicalise<LPT, T>(t, mq.n, g);
+    sub_mod<LPT, T>(u, b, t, mq.n, g);
+    load_limbs<LPT, T>(t, p2invR, g);
+    montmul<LPT, T>(u, u, t, mq.n, mq.n0inv, g);
+    canonicalise<LPT, T>(u, mq.n, g);
+    u32 lo[LPT], hi[LPT];
+    mulwide<LPT, T>(lo, hi, mp.n, u, g);
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) lo[j] += a[j];
+    int carry = resolve<LPT, T>(lo, g);
+    if (g.k == 0) hi[0] += (u32)carry;
+    resolve<LPT, T>(hi, g);
+    if (active) {
+      store_limbs<LPT, T>(rn + item * (size_t)(2 * NL), lo, g);
+      store_limbs<LPT, T>(rn + item * (size_t)(2 * NL) + NL, hi, g);
+    }
+  }
+}
+
 LaunchShape modexp_shape(const haflo_ctx* ctx, size_t count, int t) {
   return launch_shape(ctx, count, t, kModexpBlocksPerCu);
 }
@@ -143,7 +189,14 @@ int launch_engine(const ModHost& m, const LaunchShape& sh, hipStream_t st, const
 namespace haflo {
 // table slots: one set per resident lane group
 size_t ws_encrypt(const haflo_ctx* ctx, size_t count) {
-  return modexp_shape(ctx, count, ctx->N.t).slots() * (size_t)ctx->prog_enc.table_entries * ctx->N.nl * 4;
+  if (!ctx->has_priv)
+    return modexp_shape(ctx, count, ctx->N.t).slots() * (size_t)ctx->prog_enc.table_entries * ctx->N.nl * 4;
+  // key owner: [y_p, y_q: count*P2.nl each][r^n: count*N.nl][branch tables, both halves of the grid]
+  // and, for the last stage, one table slot of N.nl limbs per lane group (placed over the branch tables)
+  size_t tl = (size_t)std::max(ctx->prog_enc_p.table_entries, ctx->prog_enc_q.table_entries);
+  size_t branch = 2 * modexp_shape(ctx, count, ctx->P2.t).slots() * tl * ctx->P2.nl;
+  size_t last = modexp_shape(ctx, count, ctx->N.t).slots() * (size_t)ctx->N.nl;
+  return (2 * count * (size_t)ctx->P2.nl + count * (size_t)ctx->N.nl + std::max(branch, last)) * 4;
 }
 // sized for the per-element variant (16 entries); the broadcast variant never needs more
 size_t ws_scalar_mul(const haflo_ctx* ctx, size_t count) {
@@ -184,16 +237,79 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
   if (count == 0) return HAFLO_OK;
   if (!d_workspace || workspace_bytes < ws_encrypt(ctx, count)) return HAFLO_EINVAL;
   const ModHost& m = ctx->N;
+  hipStream_t st = (hipStream_t)stream;
+  if (!ctx->has_priv) {
+    // public key: r^n with the full exponent modulo n^2
+    EngineIO io = engine_io(m);
+    io.constant[kConstExtra] = ctx->d_k1;
+    io.in_words[0] = d_plain;
+    io.in_words[1] = d_r;
+    io.in_nwords = ctx->lp;
+    io.out = (u32*)d_cipher;
+    io.tables = (u32*)d_workspace;
+    io.table_entries = ctx->prog_enc.table_entries;
+    ProgPtr prog = {ctx->prog_enc.d_ins, (int)ctx->prog_enc.host.size()};
+    return launch_engine(m, modexp_shape(ctx, count, m.t), st, prog, io, count);
+  }
+  // key owner: r^n through p^2 and q^2 (half-size moduli: a quarter of the multiplications per
+  // branch), Chinese remainder, then the (1 + m n) factor and the Montgomery form modulo n^2.
+  // Bit-identical to the public path: the residue r^n mod n^2 is unique.
+  const ModHost& h = ctx->P2;
+  u32* yp = (u32*)d_workspace;
+  u32* yq = yp + count * (size_t)h.nl;
+  u32* rn = yq + count * (size_t)h.nl;
+  u32* tables = rn + count * (size_t)m.nl;
+  {
+    const int tl = std::max(ctx->prog_enc_p.table_entries, ctx->prog_enc_q.table_entries);
+    LaunchShape sh = modexp_shape(ctx, count, h.t);
+    EngineJob job[2];
+    for (int side = 0; side < 2; ++side) {
+      const ModHost& ms = side ? ctx->Q2 : ctx->P2;
+      const DevProg& dp = side ? ctx->prog_enc_q : ctx->prog_enc_p;
+      job[side].M = ms.ref();
+      job[side].P = ProgPtr{dp.d_ins, (int)dp.host.size()};
+      job[side].io = engine_io(ms);
+      job[side].io.in_words[1] = d_r;
+      job[side].io.in_nwords = ctx->lp;
+      job[side].io.out = side ? yq : yp;
+      job[side].io.tables = tables + (side ? sh.slots() * (size_t)tl * ms.nl : 0);
+      job[side].io.table_entries = tl;
+    }
+    const unsigned split = (unsigned)sh.blocks;
+    sh.blocks *= 2;
+#define CALL(LPT, T) HAFLO_LAUNCH((k_engine_pair<LPT, T>), sh, st, job[0], job[1], split, count)
+    HAFLO_DISPATCH_GEOMETRY(h, CALL);
+#undef CALL
+  }
+  {
+    const LaunchShape sh = launch_shape(ctx, count, h.t, 8);
+#define CALL(LPT, T)                                                                                  \
+  HAFLO_LAUNCH((k_enc_crt<LPT, T>), sh, st, ctx->P2.ref(), ctx->Q2.ref(), (const u32*)ctx->d_p2inv,   \
+               (const u32*)yp, (const u32*)yq, rn, count)
+    HAFLO_DISPATCH_GEOMETRY(h, CALL);
+#undef CALL
+  }
+  // acc = m -> (m n) R + R = (1 + m n) R -> times r^n (plain) -> times R^2: Montgomery form of E(m)
+  std::vector<uint32_t> prog;
+  prog.push_back(eng_ins(ENG_LOAD_L, 0));
+  prog.push_back(eng_ins(ENG_STORE_T, 0));
+  prog.push_back(eng_ins(ENG_LOAD_W, 0));
+  prog.push_back(eng_ins(ENG_MUL_C, kConstExtra));
+  prog.push_back(eng_ins(ENG_ADD_C, kConstR1));
+  prog.push_back(eng_ins(ENG_MUL_T, 0));
+  prog.push_back(eng_ins(ENG_MUL_C, kConstR2));
+  ProgInline pi;
+  if (!to_inline(pi, prog)) return HAFLO_EINVAL;
   EngineIO io = engine_io(m);
   io.constant[kConstExtra] = ctx->d_k1;
   io.in_words[0] = d_plain;
-  io.in_words[1] = d_r;
   io.in_nwords = ctx->lp;
+  io.in_limbs = rn;
+  io.in_limbs_stride = m.nl;
   io.out = (u32*)d_cipher;
-  io.tables = (u32*)d_workspace;
-  io.table_entries = ctx->prog_enc.table_entries;
-  ProgPtr prog = {ctx->prog_enc.d_ins, (int)ctx->prog_enc.host.size()};
-  return launch_engine(m, modexp_shape(ctx, count, m.t), (hipStream_t)stream, prog, io, count);
+  io.tables = tables;
+  io.table_entries = 1;
+  return launch_engine(m, modexp_shape(ctx, count, m.t), st, pi, io, count);
 }
 
 int haflo_scalar_mul_u64(const haflo_ctx* ctx, const void* d_c, const uint64_t* d_k, void* d_out, size_t count,

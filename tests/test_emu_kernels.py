@@ -131,6 +131,35 @@ def test_encrypt_decrypt_scalar_mul(env):
         assert export(lib, ctx, d_o, len(ms)) == [O.scalar_mul(pk, c, k) for c in want], k
 
 
+def test_public_context_encrypts_identically(env):
+    """The public-key path (full exponent modulo n^2) and the key owner's path (through p^2 and
+    q^2) must produce the same ciphertext bits; a public context cannot decrypt."""
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    n = pk.n
+    lp = BITS // 32
+    pub = C.c_void_p()
+    buf = (C.c_uint8 * (BITS // 8)).from_buffer_copy(n.to_bytes(BITS // 8, "little"))
+    assert lib.haflo_ctx_create_public(buf, BITS, C.byref(pub)) == 0
+    rng = random.Random(21)
+    ms = [rng.randrange(n) for _ in range(3)] + [0, n - 1]
+    rs = [rng.randrange(1, n) for _ in range(3)] + [n - 1, 1]
+    want = [O.encrypt(pk, m, r) for m, r in zip(ms, rs)]
+    for handle in (pub, ctx):
+        d_c = zeros(lib, (len(ms), nlw))
+        w, nb = ws(lib, handle, _cabi.OP_ENCRYPT, len(ms))
+        assert lib.haflo_encrypt(handle, words(lib, ms, lp).p, words(lib, rs, lp).p, d_c.p, len(ms), w.p, nb,
+                                 None) == 0
+        assert export(lib, handle, d_c, len(ms)) == want
+    mm, limbs = C.c_uint64(), C.c_uint32()
+    assert lib.haflo_op_cost(pub, _cabi.OP_ENCRYPT, C.byref(mm), C.byref(limbs)) == 0
+    assert 511 < mm.value < 768 and limbs.value == BITS // 16
+    d_pl = zeros(lib, (len(ms), lp))
+    assert lib.haflo_decrypt(pub, d_c.p, d_pl.p, len(ms), w.p, nb, None) == -3
+    assert lib.haflo_workspace_bytes(pub, _cabi.OP_DECRYPT, 4, 0) == 2 ** 64 - 1
+    lib.haflo_ctx_destroy(pub)
+
+
 def test_matvec_sum(env):
     lib, ctx, sk, nlw = env
     pk = sk.public
@@ -204,8 +233,9 @@ def test_op_cost_and_workspace_queries(env):
     lib, ctx, sk, nlw = env
     mm, limbs = C.c_uint64(), C.c_uint32()
     assert lib.haflo_op_cost(ctx, _cabi.OP_ENCRYPT, C.byref(mm), C.byref(limbs)) == 0
-    # a 512-bit exponent needs at least 511 squarings and fewer than 1.5 products per bit
-    assert 511 < mm.value < 768 and limbs.value == BITS // 16
+    # key owner: two branches with ~512-bit exponents on half-size moduli; each needs at least
+    # one squaring per bit and fewer than 1.5 products per bit
+    assert 2 * 500 < mm.value < 2 * 768 + 18 and limbs.value == BITS // 32
     assert lib.haflo_op_cost(ctx, 99, None, None) == -1
     assert lib.haflo_workspace_bytes(ctx, 99, 1, 1) == 2 ** 64 - 1
     assert lib.haflo_encrypt(ctx, None, None, None, 4, None, 0, None) == -1
