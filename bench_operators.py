@@ -1,0 +1,110 @@
+#!/usr/bin/env python3
+"""Per-operator throughput table in the shape of the paper's Table 2.
+
+    python bench_operators.py [--bits 1024] [--instances 100000] [--json out.json]
+
+For each operator of the paper's Table 2 (encoding, decoding, encryption,
+decryption, multiplication, addition, matrix multiplication, summation) this
+times `instances` elements at the given key size on one MI355X, inputs resident
+in HBM, and prints instances per second next to the V100 figures the paper
+reports for a 1024-bit key (context only: other hardware, unknown whether host
+transfers were inside the paper's timings). `bench.py` remains the contract
+benchmark; this is the operator-level view.
+"""
+import argparse
+import json
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# paper Table 2, GPU column (V100, 1024-bit key, 10^5 instances), instances per second
+PAPER_V100_1024 = {
+    "encoding": 15108620, "decoding": 22343405, "encryption": 83909, "decryption": 287273,
+    "multiplication": 991946, "addition": 1226803, "matrix multiplication": 931942, "summation": 19575768,
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--bits", type=int, default=1024)
+    ap.add_argument("--instances", type=int, default=100000)
+    ap.add_argument("--features", type=int, default=32)
+    ap.add_argument("--reps", type=int, default=3)
+    ap.add_argument("--json", default=None)
+    args = ap.parse_args()
+
+    import numpy as np
+    import torch
+
+    from paper_2107_13797_amd import api, synth
+
+    assert torch.cuda.is_available(), "needs a GPU"
+    bits, N, F = args.bits, args.instances, args.features
+    seed = synth.BASE_SEED + bits
+    p, q = api.haflo_keygen(bits, seed)
+    own = api.haflo_ctx_create_private(p, q, bits)
+    pub = api.haflo_ctx_create_public(p * q, bits)
+    lp = bits // 32
+
+    def dev(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint32:
+            a = a.view(np.int32)
+        elif a.dtype == np.uint64:
+            a = a.view(np.int64)
+        return torch.from_numpy(a).cuda()
+
+    rng = np.random.default_rng(seed)
+    v = dev(synth.normal_f32(N, 0.25, seed + 1))
+    r_words = rng.integers(0, 2 ** 32, size=(N, lp), dtype=np.uint32)
+    r_words[:, -1] &= 0x7FFFFFFF
+    r = dev(r_words)
+    k64 = dev(rng.integers(0, 2 ** 63, size=N, dtype=np.uint64) * 2 + 1)
+    rows = max(1, N // F)
+    X = api.haflo_encode_exponents_f32(dev(synth.normal_f32((rows, F), 1.0, seed + 2)), 16)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.reps):
+            out = fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.reps * 1e-3, out
+
+    res = {}
+    t, plain = timed(lambda: api.haflo_encode_f32(pub, v, 24))
+    res["encoding"] = N / t
+    t, c = timed(lambda: api.haflo_encrypt(pub, plain, r))
+    res["encryption"] = N / t
+    t, _ = timed(lambda: api.haflo_encrypt(own, plain, r))
+    res["encryption (key owner)"] = N / t
+    t, pl = timed(lambda: api.haflo_decrypt(own, c))
+    res["decryption"] = N / t
+    t, _ = timed(lambda: api.haflo_decode(own, pl, 24))
+    res["decoding"] = N / t
+    t, _ = timed(lambda: api.haflo_scalar_mul_u64(pub, c, k64))
+    res["multiplication"] = N / t
+    t, _ = timed(lambda: api.haflo_add(pub, c, c))
+    res["addition"] = N / t
+    t, _ = timed(lambda: api.haflo_cipher_matvec(pub, 0, c[:rows].contiguous(), X))
+    res["matrix multiplication"] = rows * F / t
+    t, _ = timed(lambda: api.haflo_cipher_sum(pub, c))
+    res["summation"] = N / t
+
+    print("%-26s %16s %16s %8s" % ("operator (%d-bit key)" % bits, "MI355X inst/s", "paper V100 inst/s", "ratio"))
+    for name, rate in res.items():
+        ref = PAPER_V100_1024.get(name) if bits == 1024 else None
+        print("%-26s %16.0f %16s %8s" % (name, rate, ref if ref else "-", ("%.1f" % (rate / ref)) if ref else "-"))
+    if args.json:
+        with open(args.json, "w") as fh:
+            json.dump({"n_bits": bits, "instances": N, "features": F, "instances_per_s": res}, fh, indent=1)
+
+
+if __name__ == "__main__":
+    main()
