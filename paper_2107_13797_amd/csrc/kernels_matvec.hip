@@ -270,7 +270,7 @@ __device__ __forceinline__ void block_product(u32 (&acc)[LPT], u32* lds, const M
 // block (j, s, rs): product over the rows of slice rs of table_i[digit s of
 // |X[i][j]|], positive and negative entries apart -> partials[j][s][sign][rs]
 template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads, 2) void k_xtd_main(ModRef M, const int* __restrict__ X, size_t rows,
+__global__ __launch_bounds__(kBlockThreads, 3) void k_xtd_main(ModRef M, const int* __restrict__ X, size_t rows,
                                                             size_t cols, const u32* __restrict__ tables, int rsplit,
                                                             u32* __restrict__ partials,
                                                             const u32* __restrict__ maxmag) {
@@ -278,7 +278,11 @@ __global__ __launch_bounds__(kBlockThreads, 2) void k_xtd_main(ModRef M, const i
   __shared__ u32 lds[(kBlockThreads / 2) * LPT];
   Grp<T> g;
   Batch<T> bt;
-  const size_t b = blockIdx.x;
+  // Blocks are handed to the 8 XCDs round-robin; the blocks of all columns j of one (s, rs)
+  // slice read the same table entries, so renumber them to put a slice's column blocks on one
+  // XCD and let its L2 serve the re-reads (identity when the grid is not a multiple of 8).
+  size_t b = blockIdx.x;
+  if (gridDim.x % 8u == 0u) b = (size_t)(blockIdx.x % 8u) * (gridDim.x / 8u) + blockIdx.x / 8u;
   const size_t j = b % cols;
   const int rs = (int)((b / cols) % (size_t)rsplit);
   const int s = (int)(b / (cols * (size_t)rsplit));
@@ -300,12 +304,11 @@ __global__ __launch_bounds__(kBlockThreads, 2) void k_xtd_main(ModRef M, const i
     int d = (int)((((u64)mag + offset) >> (s * kSWin)) & 31ull) - 16;
     u32 dgt = (u32)(d < 0 ? -d : d);
     const u32* entry = active ? tables + (i * (size_t)kSEntries + dgt) * NL : M.r1;
-    u32 t[LPT], cur[LPT];
-    load_limbs<LPT, T>(t, entry, g);
+    u32 cur[LPT];
     bool neg = (x < 0) != (d < 0);
 #pragma unroll
     for (int jj = 0; jj < LPT; ++jj) cur[jj] = neg ? accn[jj] : accp[jj];
-    montmul<LPT, T>(cur, cur, t, mod.n, mod.n0inv, g);
+    montmul_mem<LPT, T>(cur, cur, entry, mod.n, mod.n0inv, g);
 #pragma unroll
     for (int jj = 0; jj < LPT; ++jj) {
       if (neg) accn[jj] = cur[jj];
@@ -433,65 +436,61 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_tables(ModRef M, const u32
   }
 }
 
-// per row: the (column, value) pairs of its non-zero entries, in column order.
-// One wave per row; nz: rows*cols pairs of ints, nzcount: rows.
-__global__ __launch_bounds__(kBlockThreads) void k_xw_compact(const int* __restrict__ X, size_t rows, size_t cols,
-                                                              int* __restrict__ nz, u32* __restrict__ nzcount) {
+// Per row: the list of table entries its product consists of, one per non-zero 4-bit digit
+// of every non-zero |X[row][c]|: entry index ((c*2 + sign)*kMaxPos + s)*16 + digit, in units of
+// one table entry. One wave per row; lists: rows * cols * kMaxPos words, counts: rows.
+__global__ __launch_bounds__(kBlockThreads) void k_xw_lists(const int* __restrict__ X, size_t rows, size_t cols,
+                                                            u32* __restrict__ lists, u32* __restrict__ counts,
+                                                            const u32* __restrict__ maxmag) {
   const int lane = (int)(threadIdx.x & (WAVE - 1));
   const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
   const size_t nwaves = ((size_t)gridDim.x * blockDim.x) / WAVE;
+  const int npos = (bit_length(*maxmag) + kWin - 1) / kWin;
   for (size_t row = wave; row < rows; row += nwaves) {
+    u32* mine = lists + row * cols * (size_t)kMaxPos;
     u32 written = 0;
     for (size_t c0 = 0; c0 < cols; c0 += WAVE) {
       size_t c = c0 + (size_t)lane;
       int x = (c < cols) ? X[row * cols + c] : 0;
-      u64 mask = __builtin_amdgcn_ballot_w64(x != 0);
-      if (x != 0) {
-        u32 before = (u32)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
-        size_t o = (row * cols + written + before) * 2;
-        nz[o] = (int)c;
-        nz[o + 1] = x;
+      u32 mag = x < 0 ? 0u - (u32)x : (u32)x;
+      u32 tsel = (u32)c * 2u + (x < 0 ? 1u : 0u);
+      for (int s = 0; s < npos; ++s) {
+        u32 dgt = (mag >> (s * kWin)) & (u32)(kWinEntries - 1);
+        u64 mask = __builtin_amdgcn_ballot_w64(dgt != 0u);
+        if (dgt != 0u) {
+          u32 before = (u32)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
+          mine[written + before] = (tsel * (u32)kMaxPos + (u32)s) * (u32)kWinEntries + dgt;
+        }
+        written += (u32)__builtin_popcountll(mask);
       }
-      written += (u32)__builtin_popcountll(mask);
     }
-    if (lane == 0) nzcount[row] = written;
+    if (lane == 0) counts[row] = written;
   }
 }
 
+// one group per output row: the product of the listed table entries
 template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads, 4) void k_xw_main(ModRef M, size_t rows, size_t cols,
-                                                           const int* __restrict__ nz, const u32* __restrict__ nzcount,
-                                                           const u32* __restrict__ tables, u32* __restrict__ out,
-                                                           const u32* __restrict__ maxmag) {
+__global__ __launch_bounds__(kBlockThreads, 3) void k_xw_main(ModRef M, size_t rows, size_t list_stride,
+                                                           const u32* __restrict__ lists,
+                                                           const u32* __restrict__ counts,
+                                                           const u32* __restrict__ tables, u32* __restrict__ out) {
   constexpr int NL = LPT * T;
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
-  const int npos = (bit_length(*maxmag) + kWin - 1) / kWin;
   for (size_t base = bt.first(); base < rows; base += bt.stride()) {
     size_t row = base + bt.gib;
     bool active = row < rows;
-    u32 cnt = active ? nzcount[row] : 0u;
-    u32 acc[LPT], t[LPT];
+    u32 cnt = active ? counts[row] : 0u;
+    const u32* mine = lists + (active ? row : 0) * list_stride;
+    u32 acc[LPT];
     load_limbs<LPT, T>(acc, M.r1, g);
-    for (u32 e = 0; wave_any(e < cnt); ++e) {
-      bool live = e < cnt;
-      int col = 0, x = 0;
-      if (live) {
-        col = nz[(row * cols + e) * 2];
-        x = nz[(row * cols + e) * 2 + 1];
-      }
-      u32 mag = x < 0 ? 0u - (u32)x : (u32)x;
-      size_t tsel = (size_t)col * 2 + (x < 0 ? 1 : 0);
 #pragma unroll 1
-      for (int s = 0; s < npos; ++s) {
-        u32 dgt = (mag >> (s * kWin)) & (u32)(kWinEntries - 1);
-        const u32* entry =
-            live ? tables + ((tsel * (size_t)kMaxPos + (size_t)s) * (size_t)kWinEntries + dgt) * NL : M.r1;
-        load_limbs<LPT, T>(t, entry, g);
-        montmul<LPT, T>(acc, acc, t, mod.n, mod.n0inv, g);
-      }
+    for (u32 e = 0; wave_any(e < cnt); ++e) {
+      // a group that has run out of entries multiplies by one and stays in step with its wave
+      const u32* entry = (e < cnt) ? tables + (size_t)mine[e] * NL : M.r1;
+      montmul_mem<LPT, T>(acc, acc, entry, mod.n, mod.n0inv, g);
     }
     canonicalise<LPT, T>(acc, mod.n, g);
     if (active) store_limbs<LPT, T>(out + row * (size_t)NL, acc, g);
@@ -560,7 +559,7 @@ XwPlan xw_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
   p.off_inv = 64;
   p.off_tables = p.off_inv + cols * nl;
   p.off_nz = p.off_tables + cols * 2 * kMaxPos * kWinEntries * nl;
-  p.off_cnt = p.off_nz + rows * cols * 2;
+  p.off_cnt = p.off_nz + rows * cols * kMaxPos;
   p.total = p.off_cnt + rows;
   return p;
 }
@@ -665,7 +664,7 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
     const XwPlan p = xw_plan(ctx, rows, cols);
     u32* inv = ws + p.off_inv;
     u32* tables = ws + p.off_tables;
-    int* nz = (int*)(ws + p.off_nz);
+    u32* lists = ws + p.off_nz;
     u32* cnt = ws + p.off_cnt;
     if (cols) {
       rc = invert_batch(ctx, (const u32*)d_c, inv, cols, st);
@@ -677,16 +676,14 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
 #undef CALL
     }
     {
-      LaunchShape sh = launch_shape(ctx, rows, 64, 8);
-      if (cols == 0) {
-        // nothing to compact: every row is the empty product
-      }
-      HAFLO_LAUNCH(k_xw_compact, sh, st, d_X, rows, cols, nz, cnt);
+      const LaunchShape sh = launch_shape(ctx, rows, 64, 8);
+      HAFLO_LAUNCH(k_xw_lists, sh, st, d_X, rows, cols, lists, cnt, (const u32*)ws);
     }
     {
       const LaunchShape sh = launch_shape(ctx, rows, m.t, 8);
-#define CALL(LPT, T) \
-  HAFLO_LAUNCH((k_xw_main<LPT, T>), sh, st, m.ref(), rows, cols, (const int*)nz, (const u32*)cnt, (const u32*)tables, (u32*)d_out, (const u32*)ws)
+#define CALL(LPT, T)                                                                                          \
+  HAFLO_LAUNCH((k_xw_main<LPT, T>), sh, st, m.ref(), rows, cols * (size_t)kMaxPos, (const u32*)lists,         \
+               (const u32*)cnt, (const u32*)tables, (u32*)d_out)
       HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
     }
