@@ -278,14 +278,15 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_xtd_main(ModRef M, const i
   __shared__ u32 lds[(kBlockThreads / 2) * LPT];
   Grp<T> g;
   Batch<T> bt;
-  // Blocks are handed to the 8 XCDs round-robin; the blocks of all columns j of one (s, rs)
-  // slice read the same table entries, so renumber them to put a slice's column blocks on one
-  // XCD and let its L2 serve the re-reads (identity when the grid is not a multiple of 8).
-  size_t b = blockIdx.x;
-  if (gridDim.x % 8u == 0u) b = (size_t)(blockIdx.x % 8u) * (gridDim.x / 8u) + blockIdx.x / 8u;
-  const size_t j = b % cols;
-  const int rs = (int)((b / cols) % (size_t)rsplit);
-  const int s = (int)(b / (cols * (size_t)rsplit));
+  // Blocks are handed to the 8 XCDs round-robin. The `cols` blocks of one (s, rs) slice read
+  // the same table entries, so a slice is kept on one XCD (whose L2 then serves the re-reads)
+  // and consecutive slices go to consecutive XCDs. The grid holds a multiple of 8 slices.
+  const size_t xcd = blockIdx.x % 8u, local = blockIdx.x / 8u;
+  const size_t slice = xcd + 8u * (local / cols);
+  const size_t j = local % cols;
+  const int rs = (int)(slice % (size_t)rsplit);
+  const int s = (int)(slice / (size_t)rsplit);
+  if (s >= kSMaxPos) return;  // padding slices
   const int npos = signed_digit_positions(*maxmag);
   if (s >= npos) return;  // no digit at this position anywhere
   const u64 offset = signed_digit_offset(npos);
@@ -641,7 +642,7 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
       LaunchShape mainsh;
       mainsh.threads = kBlockThreads;
       mainsh.gpb = kBlockThreads / m.t;
-      mainsh.blocks = (int)(cols * (size_t)p.rsplit * kSMaxPos);
+      mainsh.blocks = (int)(cols * ((((size_t)p.rsplit * kSMaxPos) + 7) / 8 * 8));
 #define CALL(LPT, T) \
   HAFLO_LAUNCH((k_xtd_main<LPT, T>), mainsh, st, m.ref(), d_X, rows, cols, (const u32*)tables, p.rsplit, partials, (const u32*)ws)
       HAFLO_DISPATCH_GEOMETRY(m, CALL);

@@ -205,6 +205,45 @@ def test_matvec_signed_digit_boundaries(env, top):
     assert export(lib, ctx, d_o, 2) == O.matvec(pk, 0, cs, X.tolist())
 
 
+@pytest.mark.parametrize("bits", [1024, 2048, 4096])
+def test_wider_lane_groups(emu, bits):
+    """The 4-, 8- and 16-lane geometries (1024/2048/4096-bit keys) on a few elements: Montgomery
+    form, addition, inverse and a short power, i.e. every cross-lane primitive."""
+    lib = emu
+    p, q = oracle_key(bits)
+    sk = O.PrivateKey(p, q)
+    pk = sk.public
+    nsq = pk.nsq
+    ctx = C.c_void_p()
+    buf = (C.c_uint8 * (bits // 8)).from_buffer_copy(pk.n.to_bytes(bits // 8, "little"))
+    assert lib.haflo_ctx_create_public(buf, bits, C.byref(ctx)) == 0
+    cb = C.c_size_t()
+    lib.haflo_ctx_info(ctx, None, None, None, C.byref(cb), None)
+    nlw = cb.value // 4
+    assert nlw == bits * 9 // 128
+    rng = random.Random(bits)
+    cs = [rng.randrange(1, nsq) for _ in range(2)] + [nsq - 1]
+    lc = bits // 16
+
+    def exp_(d, count):
+        out = zeros(lib, (count, lc))
+        assert lib.haflo_export_cipher(ctx, d.p, out.p, count, None) == 0
+        return synth.words_to_ints(out.get())
+
+    d_c = zeros(lib, (len(cs), nlw))
+    assert lib.haflo_import_cipher(ctx, words(lib, cs, lc).p, d_c.p, None, len(cs), None) == 0
+    R = 1 << (29 * nlw)
+    assert [sum(int(v) << (29 * i) for i, v in enumerate(row)) for row in d_c.get()] == [c * R % nsq for c in cs]
+    assert exp_(d_c, len(cs)) == cs
+    d_o = zeros(lib, (len(cs), nlw))
+    assert lib.haflo_add(ctx, d_c.p, d_c.p, d_o.p, len(cs), None) == 0
+    assert exp_(d_o, len(cs)) == [c * c % nsq for c in cs]
+    w, nb = ws(lib, ctx, _cabi.OP_SCALAR_MUL, len(cs))
+    assert lib.haflo_scalar_mul_i64_bcast(ctx, d_c.p, -3, d_o.p, len(cs), w.p, nb, None) == 0
+    assert exp_(d_o, len(cs)) == [pow(pow(c, -1, nsq), 3, nsq) for c in cs]
+    lib.haflo_ctx_destroy(ctx)
+
+
 def test_encode_decode(env):
     lib, ctx, sk, nlw = env
     pk = sk.public
