@@ -81,6 +81,9 @@ __device__ __forceinline__ u32 opaque_eight() {
   return e;
 }
 
+// Keeps a loaded value (and so the load) alive up to this point without using it.
+__device__ __forceinline__ void keep_live(u32 v) { asm volatile("" ::"r"(v)); }
+
 // Push the upper 32 bits of every column accumulator one column up
 // (A[j+1] += 8 * hi(A[j]), radix 2^29 vs word 2^32), leaving each column below
 // 2^32 (column 0 below 2^36). The top lane's top column is bounded by the value

@@ -169,4 +169,17 @@ int power_tables(const haflo_ctx* ctx, const uint32_t* d_c, uint32_t* d_tables, 
 // out[i] = in[i]^-1 mod n^2 on internal ciphertexts; out may alias in (kernels_matvec.hip)
 int invert_batch(const haflo_ctx* ctx, const uint32_t* in, uint32_t* out, size_t count, hipStream_t st);
 
+// X^T [[d]] by the bucket method (kernels_buckets.hip). Workspace layout in 32-bit words.
+struct XtdBucketPlan {
+  int rounds;
+  size_t keys, scan_blocks;
+  size_t off_cnt, off_totals, off_offs, off_sorted, off_arena[2], off_G, off_AT, off_R, total;
+};
+bool xtd_buckets_fit(size_t rows, size_t cols);
+XtdBucketPlan xtd_bucket_plan(const haflo_ctx* ctx, size_t rows, size_t cols);
+// d_P[j][sign] = product of c_i^|x_ij| over the entries of column j with that sign (lazy Montgomery form);
+// d_maxmag: the largest |x|. ws: xtd_bucket_plan(...).total words.
+int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, size_t rows, size_t cols,
+                uint32_t* ws, const uint32_t* d_maxmag, uint32_t* d_P, hipStream_t st);
+
 }  // namespace haflo

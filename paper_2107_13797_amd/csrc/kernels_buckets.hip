@@ -1,0 +1,478 @@
+// X^T [[d]] for tall matrices by the bucket method: no per-base tables, one
+// Montgomery product per non-zero exponent digit.
+//
+// Every |x_ij| is read in signed base-1024 digits (|x| = sum_s d_s 1024^s,
+// d_s in [-512, 511]). For output column j, digit position s and effective sign
+// (sign of x_ij times sign of d_s), the rows whose digit has magnitude m form
+// the bucket (j, s, sign, m); with B = product of c_i over a bucket,
+//   out_j = P_j[+] / P_j[-],  P_j[sg] = prod_s ( prod_m B(j,s,sg,m)^m )^(1024^s).
+// Steps:
+//   1. count the bucket sizes, prefix-sum them, scatter the row indices into
+//      one array sorted by bucket (atomics; the order inside a bucket is
+//      arbitrary and does not change the canonical result);
+//   2. reduce every bucket to its product in rounds: a round cuts each bucket's
+//      items into chunks of at most kChunk, one lane group multiplies one chunk,
+//      the chunk products are the next round's items. A bucket of any size (a
+//      column of equal entries puts all its rows into one) is spread over the
+//      whole chip, and the number of rounds is fixed by the row count;
+//   3. prod_m B_m^m with m = 32 h + (l + 1): 16 + 32 sub-products over h and l,
+//      two running products, five squarings;
+//   4. Horner over the digit positions, and P[+] * P[-]^-1 by the caller.
+#include "kernels_common.hpp"
+
+using namespace haflo;
+using namespace haflo::dev;
+
+namespace {
+
+constexpr int kDigitBits = 10;
+constexpr int kMags = 512;     // digit magnitudes 1..512
+constexpr int kMaxPos = 4;     // 1024^4 - offset(4) > 2^31
+constexpr int kChunkBits = 4, kChunk = 1 << kChunkBits;  // items per lane group and round
+constexpr int kLoCount = 32, kHiCount = 16, kSubProducts = kLoCount + kHiCount;  // m = 32 h + l + 1
+
+__host__ __device__ inline unsigned long long digit_offset(int npos) {
+  unsigned long long c = 0;
+  for (int s = 0; s < npos; ++s) c = c * 1024ull + 512ull;
+  return c;
+}
+// positions needed so that maxmag + offset(S) < 1024^S (0 for an all-zero matrix)
+__host__ __device__ inline int digit_positions(unsigned maxmag) {
+  if (maxmag == 0) return 0;
+  for (int s = 1; s < kMaxPos; ++s)
+    if ((unsigned long long)maxmag + digit_offset(s) < (1ull << (kDigitBits * s))) return s;
+  return kMaxPos;
+}
+__device__ __forceinline__ size_t bucket_key(size_t cols, size_t j, int s, bool negative, u32 mag) {
+  return ((((size_t)s * cols + j) * 2 + (negative ? 1 : 0)) * (size_t)kMags) + (mag - 1u);
+}
+
+__global__ __launch_bounds__(kBlockThreads) void k_bk_zero(u32* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+// SCATTER = false: cnt[key] = bucket sizes.  SCATTER = true: sorted[off[key] + n] = row, n from cnt (zeroed again).
+template <bool SCATTER>
+__global__ __launch_bounds__(kBlockThreads) void k_bk_terms(const int* __restrict__ X, size_t rows, size_t cols,
+                                                            u32* __restrict__ cnt, const u32* __restrict__ off,
+                                                            u32* __restrict__ sorted,
+                                                            const u32* __restrict__ maxmag) {
+  const int npos = digit_positions(*maxmag);
+  const unsigned long long offset = digit_offset(npos);
+  const size_t total = rows * cols;
+  for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+    const int x = X[e];
+    if (x == 0) continue;
+    const size_t i = e / cols, j = e - i * cols;
+    const u32 mag = x < 0 ? 0u - (u32)x : (u32)x;
+    for (int s = 0; s < npos; ++s) {
+      const int d = (int)((((unsigned long long)mag + offset) >> (s * kDigitBits)) & 1023ull) - 512;
+      if (d == 0) continue;
+      const size_t key = bucket_key(cols, j, s, (x < 0) != (d < 0), (u32)(d < 0 ? -d : d));
+      const u32 n = atomicAdd(&cnt[key], 1u);
+      if (SCATTER) sorted[(size_t)off[key] + n] = (u32)i;
+    }
+  }
+}
+
+// Items of a key with `c` rows at the start of round r: ceil(c / kChunk^r).
+__host__ __device__ inline u32 items_at(u32 c, int r) {
+  const int sh = kChunkBits * r;
+  return sh >= 32 ? (c != 0u) : (u32)(((u64)c + ((1ull << sh) - 1ull)) >> sh);
+}
+
+// Exclusive prefix sums over the keys, for all rounds at once: component 0 of key k is its row count
+// (offsets into the sorted row array), component r + 1 its number of chunks in round r
+// (= its items at round r + 1). Two kernels: per-block totals, then every block adds up the totals
+// before it and scans its own kScanKeys keys. offs: (rounds + 1) arrays of K + 1 words.
+constexpr int kScanThreads = 256, kScanPer = 8, kScanKeys = kScanThreads * kScanPer;
+constexpr int kMaxComp = 9;  // kChunk^8 = 2^32 bounds the rounds
+
+// sum over the block of v, returned to every thread (red: kScanThreads words)
+__device__ __forceinline__ u32 block_sum(u32 v, u32* red) {
+  __syncthreads();
+  red[threadIdx.x] = v;
+  __syncthreads();
+  for (int step = kScanThreads >> 1; step >= 1; step >>= 1) {
+    if ((int)threadIdx.x < step) red[threadIdx.x] += red[threadIdx.x + step];
+    __syncthreads();
+  }
+  return red[0];
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_bk_scan_totals(const u32* __restrict__ cnt, size_t K, int ncomp,
+                                                                u32* __restrict__ totals) {
+  __shared__ u32 red[kScanThreads];
+  u32 mine[kMaxComp];
+  for (int c = 0; c < kMaxComp; ++c) mine[c] = 0u;
+  const size_t k0 = ((size_t)blockIdx.x * kScanThreads + threadIdx.x) * kScanPer;
+  for (int i = 0; i < kScanPer; ++i) {
+    const u32 n = (k0 + i < K) ? cnt[k0 + i] : 0u;
+    for (int c = 0; c < ncomp; ++c) mine[c] += items_at(n, c);
+  }
+  for (int c = 0; c < ncomp; ++c) {
+    u32 t = block_sum(mine[c], red);
+    if (threadIdx.x == 0) totals[(size_t)c * gridDim.x + blockIdx.x] = t;
+  }
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_bk_scan_final(const u32* __restrict__ cnt, size_t K, int ncomp,
+                                                               const u32* __restrict__ totals,
+                                                               u32* __restrict__ offs) {
+  __shared__ u32 red[kScanThreads];
+  __shared__ u32 scan[kScanThreads];
+  const size_t k0 = ((size_t)blockIdx.x * kScanThreads + threadIdx.x) * kScanPer;
+  u32 n[kScanPer];
+  for (int i = 0; i < kScanPer; ++i) n[i] = (k0 + i < K) ? cnt[k0 + i] : 0u;
+  for (int c = 0; c < ncomp; ++c) {
+    u32 before = 0;
+    for (unsigned b = threadIdx.x; b < blockIdx.x; b += kScanThreads) before += totals[(size_t)c * gridDim.x + b];
+    before = block_sum(before, red);
+    u32 mine = 0;
+    for (int i = 0; i < kScanPer; ++i) mine += items_at(n[i], c);
+    // Hillis-Steele inclusive scan of the per-thread sums
+    scan[threadIdx.x] = mine;
+    __syncthreads();
+    for (int step = 1; step < kScanThreads; step <<= 1) {
+      u32 add = ((int)threadIdx.x >= step) ? scan[threadIdx.x - step] : 0u;
+      __syncthreads();
+      scan[threadIdx.x] += add;
+      __syncthreads();
+    }
+    u32 run = before + scan[threadIdx.x] - mine;
+    u32* dst = offs + (size_t)c * (K + 1);
+    for (int i = 0; i < kScanPer; ++i) {
+      if (k0 + i < K) dst[k0 + i] = run;
+      run += items_at(n[i], c);
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == kScanThreads - 1) dst[K] = run;
+    __syncthreads();
+  }
+}
+
+// Reduction round `round`. Key k owns items [off[k], off[k] + items_at(cnt[k], round)) and is cut into
+// choff[k+1] - choff[k] chunks of near-equal size; chunk q's product goes to out[q]. FIRST: item t is the
+// ciphertext of row sorted[t]; otherwise item t is in[t].
+template <int LPT, int T, bool FIRST>
+__global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u32* __restrict__ in,
+                                                            const u32* __restrict__ sorted,
+                                                            const u32* __restrict__ cnt,
+                                                            const u32* __restrict__ off,
+                                                            const u32* __restrict__ choff, size_t K,
+                                                            int round, u32* __restrict__ out) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  const size_t total = choff[K];
+  for (size_t base = bt.first(); base < total; base += bt.stride()) {
+    const size_t q = base + bt.gib;
+    const bool active = q < total;
+    const u32 qq = active ? (u32)q : 0u;
+    // the key with choff[key] <= q < choff[key + 1]
+    size_t lo = 0, hi = K;
+    while (hi - lo > 1) {
+      size_t mid = (lo + hi) >> 1;
+      if (choff[mid] <= qq) lo = mid;
+      else hi = mid;
+    }
+    const u32 first_chunk = choff[lo], nc = choff[lo + 1] - first_chunk, n = items_at(cnt[lo], round);
+    const u32 cc = qq - first_chunk;
+    u32 begin = 0, len = 0;
+    if (active && nc != 0u) {
+      begin = (u32)(((u64)n * cc) / nc);
+      len = (u32)(((u64)n * (cc + 1u)) / nc) - begin;
+    }
+    const size_t start = (size_t)off[lo] + begin;
+    auto item = [&](u32 e) -> const u32* {
+      if (e >= len) return M.r1;
+      return in + (FIRST ? (size_t)sorted[start + e] : start + e) * (size_t)NL;
+    };
+    u32 acc[LPT];
+    load_limbs<LPT, T>(acc, item(0), g);
+#pragma unroll 1
+    for (u32 e = 1; wave_any(e < len); ++e) {
+      // Touch the next item while this one is multiplied: the lanes of the group read words 72 bytes
+      // apart, which covers every cache line of the item; the value only has to stay live.
+      const u32 touch = item(e + 1)[g.k * LPT];
+      // a group that has run out of items multiplies by one and stays in step with its wave
+      montmul_mem<LPT, T>(acc, acc, item(e), mod.n, mod.n0inv, g);
+      keep_live(touch);
+    }
+    if (active) store_limbs<LPT, T>(out + q * (size_t)NL, acc, g);
+  }
+}
+
+// Sub-products of one (position, column, sign): item g < 16: prod_l B[32 g + l]; item 16 + l: prod_h B[32 h + l].
+// B[k] is the single item left of key k after the last round, at index off[k] (one when the bucket is empty:
+// cnt[k] = 0).
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* __restrict__ B,
+                                                          const u32* __restrict__ cnt, const u32* __restrict__ off,
+                                                          size_t combos, u32* __restrict__ G) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  const size_t count = combos * kSubProducts;
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    const size_t it = base + bt.gib;
+    const bool active = it < count;
+    const size_t combo = active ? it / kSubProducts : 0;
+    const int sub = active ? (int)(it - combo * kSubProducts) : 0;
+    const bool is_hi = sub < kHiCount;
+    const size_t key0 = combo * kMags + (is_hi ? (size_t)sub * kLoCount : (size_t)(sub - kHiCount));
+    const size_t stride = is_hi ? 1 : kLoCount;
+    const int n = active ? (is_hi ? kLoCount : kHiCount) : 0;
+    u32 acc[LPT];
+    load_limbs<LPT, T>(acc, M.r1, g);
+#pragma unroll 1
+    for (int e = 0; e < kLoCount; ++e) {
+      const size_t key = key0 + (size_t)e * stride;
+      const bool have = e < n && cnt[key] != 0u;
+      if (!wave_any(have)) continue;
+      const u32* src = have ? B + (size_t)off[key] * NL : M.r1;
+      montmul_mem<LPT, T>(acc, acc, src, mod.n, mod.n0inv, g);
+    }
+    if (active) store_limbs<LPT, T>(G + it * (size_t)NL, acc, g);
+  }
+}
+
+// Weighted products prod_e G[e]^(e+1) in two stages. The low part has the 32 entries Glo[0..31]; the high part
+// prod_h Ghi[h]^h is the same form over the 15 entries Ghi[1..15]. Stage 1, per segment of 8 entries
+// (4 low segments, 2 high ones): A = prod_u G[8q+u]^(u+1) and T = prod_u G[8q+u] by a running product from
+// the top (run *= G; acc *= run). Stage 2: prod_q A_q * (prod_q T_q^q)^8.
+constexpr int kSegLen = 8, kLoSegs = kLoCount / kSegLen, kHiSegs = kHiCount / kSegLen, kSegs = kLoSegs + kHiSegs;
+
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_bk_fold1(ModRef M, const u32* __restrict__ G, size_t combos,
+                                                            u32* __restrict__ AT) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  const size_t count = combos * kSegs;
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    const size_t it = base + bt.gib;
+    const bool active = it < count;
+    const size_t combo = active ? it / kSegs : 0;
+    const int seg = active ? (int)(it - combo * kSegs) : 0;
+    const bool is_hi = seg >= kLoSegs;
+    // entry e of the segment's sequence: Glo[e], or Ghi[e + 1] (absent for e = 15)
+    const int e0 = (is_hi ? seg - kLoSegs : seg) * kSegLen;
+    const u32* seq = G + (combo * kSubProducts + (is_hi ? 1 : kHiCount)) * (size_t)NL;
+    const int limit = active ? (is_hi ? kHiCount - 1 : kLoCount) : 0;
+    auto entry = [&](int u) -> const u32* { return (e0 + u < limit) ? seq + (size_t)(e0 + u) * NL : M.r1; };
+    u32 run[LPT], acc[LPT];
+    load_limbs<LPT, T>(run, entry(kSegLen - 1), g);
+#pragma unroll
+    for (int jj = 0; jj < LPT; ++jj) acc[jj] = run[jj];
+#pragma unroll 1
+    for (int u = kSegLen - 2; u >= 0; --u) {
+      montmul_mem<LPT, T>(run, run, entry(u), mod.n, mod.n0inv, g);
+      montmul<LPT, T>(acc, acc, run, mod.n, mod.n0inv, g);
+    }
+    if (active) {
+      store_limbs<LPT, T>(AT + (it * 2) * (size_t)NL, acc, g);
+      store_limbs<LPT, T>(AT + (it * 2 + 1) * (size_t)NL, run, g);
+    }
+  }
+}
+
+// R[combo][0] = low part, R[combo][1] = high part
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_bk_fold2(ModRef M, const u32* __restrict__ AT, size_t combos,
+                                                            u32* __restrict__ R) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  const size_t count = combos * 2;
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    const size_t it = base + bt.gib;
+    const bool active = it < count;
+    const size_t combo = active ? it >> 1 : 0;
+    const bool is_hi = (it & 1) != 0;
+    const int nseg = active ? (is_hi ? kHiSegs : kLoSegs) : 0;
+    const u32* mine = AT + ((combo * kSegs + (is_hi ? kLoSegs : 0)) * 2) * (size_t)NL;
+    auto a_of = [&](int q) -> const u32* { return q < nseg ? mine + (size_t)(2 * q) * NL : M.r1; };
+    auto t_of = [&](int q) -> const u32* { return q < nseg ? mine + (size_t)(2 * q + 1) * NL : M.r1; };
+    u32 run[LPT], acc[LPT];
+    load_limbs<LPT, T>(run, t_of(kLoSegs - 1), g);
+#pragma unroll
+    for (int jj = 0; jj < LPT; ++jj) acc[jj] = run[jj];
+#pragma unroll 1
+    for (int q = kLoSegs - 2; q >= 1; --q) {
+      montmul_mem<LPT, T>(run, run, t_of(q), mod.n, mod.n0inv, g);
+      montmul<LPT, T>(acc, acc, run, mod.n, mod.n0inv, g);
+    }
+#pragma unroll 1
+    for (int i = 0; i < 3; ++i) montmul<LPT, T>(acc, acc, acc, mod.n, mod.n0inv, g);  // ^8 = ^kSegLen
+#pragma unroll 1
+    for (int q = 0; q < kLoSegs; ++q) montmul_mem<LPT, T>(acc, acc, a_of(q), mod.n, mod.n0inv, g);
+    if (active) store_limbs<LPT, T>(R + it * (size_t)NL, acc, g);
+  }
+}
+
+// P[j][sign] = prod_s (R_hi[s]^32 R_lo[s])^(1024^s), top position first.
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_bk_horner(ModRef M, const u32* __restrict__ R, size_t cols,
+                                                             u32* __restrict__ P, const u32* __restrict__ maxmag) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  const int npos = digit_positions(*maxmag);
+  const size_t count = cols * 2;
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    const size_t it = base + bt.gib;
+    const bool active = it < count;
+    const size_t js = active ? it : 0;  // j * 2 + sign
+    u32 acc[LPT];
+    load_limbs<LPT, T>(acc, M.r1, g);
+#pragma unroll 1
+    for (int s = npos - 1; s >= 0; --s) {
+      const u32* r = R + (((size_t)s * cols * 2 + js) * 2) * (size_t)NL;  // [0] low part, [1] high part
+#pragma unroll 1
+      for (int half = 1; half >= 0; --half) {
+        if (s != npos - 1 || half != 1) {
+#pragma unroll 1
+          for (int i = 0; i < 5; ++i) montmul<LPT, T>(acc, acc, acc, mod.n, mod.n0inv, g);
+        }
+        montmul_mem<LPT, T>(acc, acc, r + (size_t)half * NL, mod.n, mod.n0inv, g);
+      }
+    }
+    if (active) store_limbs<LPT, T>(P + it * (size_t)NL, acc, g);
+  }
+}
+
+int rounds_for(size_t rows) {
+  int r = 0;
+  for (size_t reach = 1; reach < rows; reach *= kChunk) ++r;
+  return r < 1 ? 1 : r;
+}
+
+}  // namespace
+
+namespace haflo {
+
+bool xtd_buckets_fit(size_t rows, size_t cols) {
+  // row indices, chunk counts and item offsets are 32-bit
+  return rows < (1ull << 32) && cols != 0 && rows * kMaxPos <= 0xFFFFFFFFull / cols;
+}
+
+XtdBucketPlan xtd_bucket_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
+  XtdBucketPlan p;
+  const size_t nl = (size_t)ctx->N.nl;
+  p.rounds = rounds_for(rows);
+  p.keys = cols * kMaxPos * 2 * kMags;
+  p.scan_blocks = (p.keys + kScanKeys - 1) / kScanKeys;
+  const size_t terms = rows * cols * kMaxPos;
+  size_t p1 = terms / kChunk + p.keys;
+  if (p1 > terms) p1 = terms;
+  size_t p2 = p1 / kChunk + p.keys;
+  if (p2 > p1) p2 = p1;
+  const size_t combos = cols * kMaxPos * 2;
+  size_t w = 0;
+  p.off_cnt = w;     w += 2 * p.keys;  // row counts, scatter cursors
+  p.off_totals = w;  w += (size_t)(p.rounds + 1) * p.scan_blocks;
+  p.off_offs = w;    w += (size_t)(p.rounds + 1) * (p.keys + 1);
+  p.off_sorted = w;  w += terms;
+  w = (w + 63) & ~(size_t)63;
+  p.off_arena[0] = w; w += p1 * nl;
+  p.off_arena[1] = w; w += p2 * nl;
+  p.off_G = w;       w += combos * kSubProducts * nl;
+  p.off_AT = w;      w += combos * kSegs * 2 * nl;
+  p.off_R = w;       w += combos * 2 * nl;
+  p.total = w;
+  return p;
+}
+
+int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, size_t rows, size_t cols,
+                uint32_t* ws, const uint32_t* d_maxmag, uint32_t* d_P, hipStream_t st) {
+  const ModHost& m = ctx->N;
+  const XtdBucketPlan p = xtd_bucket_plan(ctx, rows, cols);
+  if (p.rounds + 1 > kMaxComp) return HAFLO_EINVAL;
+  const size_t K = p.keys;
+  u32* cnt = ws + p.off_cnt;
+  u32* cursor = cnt + K;
+  u32* totals = ws + p.off_totals;
+  // offs(0) = positions in the sorted row array; offs(r + 1) = chunk offsets of round r = item offsets of round r + 1
+  auto offs = [&](int idx) { return ws + p.off_offs + (size_t)idx * (K + 1); };
+  u32* sorted = ws + p.off_sorted;
+  const LaunchShape flat = launch_shape(ctx, rows * cols, 1, 8);
+  const LaunchShape fill = launch_shape(ctx, 2 * K, 1, 8);
+  LaunchShape scan;
+  scan.blocks = (int)p.scan_blocks;
+  scan.threads = kScanThreads;
+  scan.gpb = kScanThreads;
+  HAFLO_LAUNCH(k_bk_zero, fill, st, cnt, 2 * K);
+  HAFLO_LAUNCH((k_bk_terms<false>), flat, st, d_X, rows, cols, cnt, (const u32*)nullptr, (u32*)nullptr, d_maxmag);
+  HAFLO_LAUNCH(k_bk_scan_totals, scan, st, (const u32*)cnt, K, p.rounds + 1, totals);
+  HAFLO_LAUNCH(k_bk_scan_final, scan, st, (const u32*)cnt, K, p.rounds + 1, (const u32*)totals, offs(0));
+  HAFLO_LAUNCH((k_bk_terms<true>), flat, st, d_X, rows, cols, cursor, (const u32*)offs(0), sorted, d_maxmag);
+  const u32* items = d_c;
+  for (int r = 0; r < p.rounds; ++r) {
+    // upper bound of the chunks of this round: one lane group each, capped by the grid-stride loop
+    size_t bound = rows * cols * kMaxPos;
+    for (int i = 0; i <= r; ++i) bound = bound / kChunk + K;
+    const LaunchShape sh = launch_shape(ctx, bound, m.t, 3);
+    u32* out = ws + p.off_arena[r & 1];
+    if (r == 0) {
+#define CALL(LPT, T)                                                                                       \
+  HAFLO_LAUNCH((k_bk_round<LPT, T, true>), sh, st, m.ref(), items, (const u32*)sorted, (const u32*)cnt,  \
+               (const u32*)offs(0), (const u32*)offs(1), K, 0, out)
+      HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+    } else {
+#define CALL(LPT, T)                                                                                        \
+  HAFLO_LAUNCH((k_bk_round<LPT, T, false>), sh, st, m.ref(), items, (const u32*)nullptr, (const u32*)cnt, \
+               (const u32*)offs(r), (const u32*)offs(r + 1), K, r, out)
+      HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+    }
+    items = out;
+  }
+  const size_t combos = cols * kMaxPos * 2;
+  u32* G = ws + p.off_G;
+  u32* AT = ws + p.off_AT;
+  u32* R = ws + p.off_R;
+  {
+    // half of the items belong to unused digit positions and leave at once
+    const bool wide = haflo::few_groups(ctx, combos * kSubProducts, 64);
+    const LaunchShape sh = launch_shape(ctx, combos * kSubProducts, wide ? haflo_wide_lanes(m) : m.t, 8);
+#define CALL(LPT, T) \
+  HAFLO_LAUNCH((k_bk_sub<LPT, T>), sh, st, m.ref(), items, (const u32*)cnt, (const u32*)offs(p.rounds), combos, G)
+    if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
+#undef CALL
+  }
+  {
+    const bool wide = haflo::few_groups(ctx, combos * kSegs);
+    const LaunchShape sh = launch_shape(ctx, combos * kSegs, wide ? haflo_wide_lanes(m) : m.t, 8);
+#define CALL(LPT, T) HAFLO_LAUNCH((k_bk_fold1<LPT, T>), sh, st, m.ref(), (const u32*)G, combos, AT)
+    if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
+#undef CALL
+  }
+  {
+    const bool wide = haflo::few_groups(ctx, combos * 2);
+    const LaunchShape sh = launch_shape(ctx, combos * 2, wide ? haflo_wide_lanes(m) : m.t, 8);
+#define CALL(LPT, T) HAFLO_LAUNCH((k_bk_fold2<LPT, T>), sh, st, m.ref(), (const u32*)AT, combos, R)
+    if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
+#undef CALL
+  }
+  {
+    const bool wide = haflo::few_groups(ctx, cols * 2);
+    const LaunchShape sh = launch_shape(ctx, cols * 2, wide ? haflo_wide_lanes(m) : m.t, 8);
+#define CALL(LPT, T) HAFLO_LAUNCH((k_bk_horner<LPT, T>), sh, st, m.ref(), (const u32*)R, cols, d_P, d_maxmag)
+    if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
+#undef CALL
+  }
+  return hip_status(hipGetLastError());
+}
+
+}  // namespace haflo

@@ -188,3 +188,25 @@ __global__ __launch_bounds__(kBlockThreads, 4) void k_engine_pair(EngineJob j0, 
     else if ((m).lpt == 9 && (m).t == 1) { CALL(9, 1); }          \
     else return HAFLO_EINVAL;                                     \
   } while (0)
+
+// The same dispatch for the short, latency-bound kernels at the end of a reduction, where only a
+// few big integers are left: spread each over twice the lanes (9 limbs per lane) so that a single
+// product finishes sooner. The limb arrays in memory are the same for both geometries.
+#define HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL)                     \
+  do {                                                            \
+    if ((m).lpt == 18 && (m).t == 1) { CALL(9, 2); }              \
+    else if ((m).lpt == 18 && (m).t == 2) { CALL(9, 4); }         \
+    else if ((m).lpt == 18 && (m).t == 4) { CALL(9, 8); }         \
+    else if ((m).lpt == 18 && (m).t == 8) { CALL(9, 16); }        \
+    else if ((m).lpt == 18 && (m).t == 16) { CALL(18, 16); }      \
+    else if ((m).lpt == 9 && (m).t == 1) { CALL(9, 1); }          \
+    else return HAFLO_EINVAL;                                     \
+  } while (0)
+// true when so few big integers are in flight that the chip is mostly idle anyway
+namespace haflo {
+inline bool few_groups(const haflo_ctx* ctx, size_t groups, int per_cu = 8) {
+  return groups <= (size_t)ctx->num_cu * (size_t)per_cu;
+}
+}
+// lanes per big integer under HAFLO_DISPATCH_GEOMETRY_WIDE
+inline int haflo_wide_lanes(const haflo::ModHost& m) { return (m.lpt == 18 && m.t < 16) ? 2 * m.t : m.t; }

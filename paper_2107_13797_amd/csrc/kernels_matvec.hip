@@ -11,6 +11,8 @@
 //   which are compacted per row first.
 #include "kernels_common.hpp"
 
+#include <stdlib.h>
+
 using namespace haflo;
 using namespace haflo::dev;
 
@@ -551,6 +553,26 @@ XtdPlan xtd_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
   return p;
 }
 
+// Tall matrices go through the bucket method (one product per exponent digit instead of four or
+// five, no tables); below the row threshold its fixed cost per column (1024 buckets per digit
+// position) outweighs that. HAFLO_XTD_BUCKET_MIN_ROWS overrides the threshold.
+constexpr size_t kBucketMinRows = 4096;
+bool use_buckets(size_t rows, size_t cols) {
+  size_t min_rows = kBucketMinRows;
+  if (const char* e = getenv("HAFLO_XTD_BUCKET_MIN_ROWS")) min_rows = (size_t)strtoull(e, nullptr, 10);
+  return rows >= min_rows && rows > 0 && xtd_buckets_fit(rows, cols);
+}
+struct XtdBucketLayout {
+  size_t off_P, off_ws, total;  // in u32 words; word 0 holds the largest |x|
+};
+XtdBucketLayout xtd_bucket_layout(const haflo_ctx* ctx, size_t rows, size_t cols) {
+  XtdBucketLayout l;
+  l.off_P = 64;
+  l.off_ws = (l.off_P + cols * 2 * (size_t)ctx->N.nl + 63) & ~(size_t)63;
+  l.total = l.off_ws + xtd_bucket_plan(ctx, rows, cols).total;
+  return l;
+}
+
 struct XwPlan {
   size_t off_inv, off_tables, off_nz, off_cnt, total;  // in u32 words; word 0 holds the largest |x|
 };
@@ -592,10 +614,11 @@ namespace haflo {
 
 int invert_batch(const haflo_ctx* ctx, const uint32_t* in, uint32_t* out, size_t count, hipStream_t st) {
   const ModHost& m = ctx->N;
-  const LaunchShape sh = launch_shape(ctx, count, m.t, 8);
+  const bool wide = haflo::few_groups(ctx, count);
+  const LaunchShape sh = launch_shape(ctx, count, wide ? haflo_wide_lanes(m) : m.t, 8);
   const int nbatch = inverse_batches(ctx);
 #define CALL(LPT, T) HAFLO_LAUNCH((k_invert<LPT, T>), sh, st, m.ref(), in, out, count, nbatch)
-  HAFLO_DISPATCH_GEOMETRY(m, CALL);
+  if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
   return hip_status(hipGetLastError());
 }
@@ -610,7 +633,9 @@ size_t haflo_workspace_bytes(const haflo_ctx* ctx, int op, size_t rows, size_t c
     case HAFLO_OP_ENCRYPT: return ws_encrypt(ctx, rows);
     case HAFLO_OP_DECRYPT: return ctx->has_priv ? ws_decrypt(ctx, rows) : (size_t)-1;
     case HAFLO_OP_SCALAR_MUL: return ws_scalar_mul(ctx, rows);
-    case HAFLO_OP_MATVEC_XT_D: return cols ? xtd_plan(ctx, rows, cols).total * 4 : 0;
+    case HAFLO_OP_MATVEC_XT_D:
+      if (!cols) return 0;
+      return (use_buckets(rows, cols) ? xtd_bucket_layout(ctx, rows, cols).total : xtd_plan(ctx, rows, cols).total) * 4;
     case HAFLO_OP_MATVEC_X_W: return xw_plan(ctx, rows, cols).total * 4;
     default: return (size_t)-1;
   }
@@ -631,7 +656,17 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
   int rc = launch_maxmag(ctx, d_X, rows * cols, ws, st);
   if (rc != HAFLO_OK) return rc;
   const int nbatch = inverse_batches(ctx);
-  if (orientation == 0) {
+  if (orientation == 0 && use_buckets(rows, cols)) {
+    const XtdBucketLayout l = xtd_bucket_layout(ctx, rows, cols);
+    u32* P = ws + l.off_P;
+    rc = xtd_buckets(ctx, (const u32*)d_c, d_X, rows, cols, ws + l.off_ws, ws, P, st);
+    if (rc != HAFLO_OK) return rc;
+    const bool wide = haflo::few_groups(ctx, cols);
+    const LaunchShape sh = launch_shape(ctx, cols, wide ? haflo_wide_lanes(m) : m.t, 8);
+#define CALL(LPT, T) HAFLO_LAUNCH((k_xtd_finish<LPT, T>), sh, st, m.ref(), cols, (const u32*)P, (u32*)d_out, nbatch)
+    if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
+#undef CALL
+  } else if (orientation == 0) {
     const XtdPlan p = xtd_plan(ctx, rows, cols);
     u32* tables = ws + p.off_tables;
     u32* partials = ws + p.off_partials;
@@ -649,16 +684,18 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
 #undef CALL
     }
     {
-      const LaunchShape sh = launch_shape(ctx, cols * 2, m.t, 8);
+      const bool wide = haflo::few_groups(ctx, cols * 2);
+      const LaunchShape sh = launch_shape(ctx, cols * 2, wide ? haflo_wide_lanes(m) : m.t, 8);
 #define CALL(LPT, T) \
   HAFLO_LAUNCH((k_xtd_horner<LPT, T>), sh, st, m.ref(), cols, p.rsplit, (const u32*)partials, P, (const u32*)ws)
-      HAFLO_DISPATCH_GEOMETRY(m, CALL);
+      if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
     }
     {
-      const LaunchShape sh = launch_shape(ctx, cols, m.t, 8);
+      const bool wide = haflo::few_groups(ctx, cols);
+      const LaunchShape sh = launch_shape(ctx, cols, wide ? haflo_wide_lanes(m) : m.t, 8);
 #define CALL(LPT, T) HAFLO_LAUNCH((k_xtd_finish<LPT, T>), sh, st, m.ref(), cols, (const u32*)P, (u32*)d_out, nbatch)
-      HAFLO_DISPATCH_GEOMETRY(m, CALL);
+      if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
     }
   } else {

@@ -205,6 +205,52 @@ def test_matvec_signed_digit_boundaries(env, top):
     assert export(lib, ctx, d_o, 2) == O.matvec(pk, 0, cs, X.tolist())
 
 
+@pytest.fixture
+def force_buckets(monkeypatch):
+    monkeypatch.setenv("HAFLO_XTD_BUCKET_MIN_ROWS", "1")
+
+
+def _xtd_case(env, X, seed):
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    rows, cols = X.shape
+    rng = random.Random(seed)
+    cs = [O.encrypt(pk, rng.randrange(pk.n), rng.randrange(1, pk.n)) for _ in range(rows)]
+    d_c = zeros(lib, (rows, nlw))
+    assert lib.haflo_import_cipher(ctx, words(lib, cs, BITS // 16).p, d_c.p, None, rows, None) == 0
+    w, nb = ws(lib, ctx, _cabi.OP_MATVEC_XT_D, rows, cols)
+    d_o = zeros(lib, (cols, nlw))
+    assert lib.haflo_cipher_matvec(ctx, 0, d_c.p, Dev(lib, X).p, rows, cols, d_o.p, w.p, nb, None) == 0
+    assert export(lib, ctx, d_o, cols) == O.matvec(pk, 0, cs, X.tolist())
+
+
+def test_bucket_matvec_random(env, force_buckets):
+    """Bucket method on a small matrix: mixed signs, zeros, the most negative exponent."""
+    npr = np.random.default_rng(11)
+    X = npr.integers(-(1 << 19), 1 << 19, size=(37, 3)).astype(np.int32)
+    X[npr.random(X.shape) < 0.2] = 0
+    X[1, 1], X[2, 2], X[3, 0] = -1, -2 ** 31, 2 ** 31 - 1
+    _xtd_case(env, X, 21)
+
+
+def test_bucket_matvec_heavy_buckets(env, force_buckets):
+    """Columns of equal entries put every row into one bucket, which then takes several
+    reduction rounds (37 rows > 16 items per chunk); a zero column gives the encryption-free one."""
+    X = np.zeros((37, 4), dtype=np.int32)
+    X[:, 0] = 1 << 16
+    X[:, 1] = -3
+    X[::2, 3] = 1023
+    X[1::2, 3] = -1025
+    _xtd_case(env, X, 22)
+
+
+@pytest.mark.parametrize("top", [511, 512, 513, 523775, 523776, 535821823, 535821824])
+def test_bucket_matvec_digit_boundaries(env, force_buckets, top):
+    """Magnitudes around the points where the signed base-1024 recoding needs one more position."""
+    X = np.array([[top, -top], [top - 1, 1], [-(top // 2), top // 3], [512, -513]], dtype=np.int64).astype(np.int32)
+    _xtd_case(env, X, top)
+
+
 @pytest.mark.parametrize("bits", [1024, 2048, 4096])
 def test_wider_lane_groups(emu, bits):
     """The 4-, 8- and 16-lane geometries (1024/2048/4096-bit keys) on a few elements: Montgomery
@@ -241,6 +287,33 @@ def test_wider_lane_groups(emu, bits):
     w, nb = ws(lib, ctx, _cabi.OP_SCALAR_MUL, len(cs))
     assert lib.haflo_scalar_mul_i64_bcast(ctx, d_c.p, -3, d_o.p, len(cs), w.p, nb, None) == 0
     assert exp_(d_o, len(cs)) == [pow(pow(c, -1, nsq), 3, nsq) for c in cs]
+    lib.haflo_ctx_destroy(ctx)
+
+
+def test_bucket_matvec_four_lane_groups(emu, force_buckets):
+    """The bucket method with 4 lanes per integer (1024-bit key), where several groups share a
+    wave and chunks of different length keep them in lock step."""
+    lib, bits = emu, 1024
+    p, q = oracle_key(bits)
+    pk = O.PrivateKey(p, q).public
+    ctx = C.c_void_p()
+    buf = (C.c_uint8 * (bits // 8)).from_buffer_copy(pk.n.to_bytes(bits // 8, "little"))
+    assert lib.haflo_ctx_create_public(buf, bits, C.byref(ctx)) == 0
+    nlw, lc = bits * 9 // 128, bits // 16
+    rows, cols = 21, 2
+    rng = random.Random(77)
+    cs = [rng.randrange(1, pk.nsq) for _ in range(rows)]
+    npr = np.random.default_rng(78)
+    X = npr.integers(-(1 << 18), 1 << 18, size=(rows, cols)).astype(np.int32)
+    X[:, 1] = np.where(np.arange(rows) % 3 == 0, 0, 5)
+    d_c = zeros(lib, (rows, nlw))
+    assert lib.haflo_import_cipher(ctx, words(lib, cs, lc).p, d_c.p, None, rows, None) == 0
+    w, nb = ws(lib, ctx, _cabi.OP_MATVEC_XT_D, rows, cols)
+    d_o = zeros(lib, (cols, nlw))
+    assert lib.haflo_cipher_matvec(ctx, 0, d_c.p, Dev(lib, X).p, rows, cols, d_o.p, w.p, nb, None) == 0
+    out = zeros(lib, (cols, lc))
+    assert lib.haflo_export_cipher(ctx, d_o.p, out.p, cols, None) == 0
+    assert synth.words_to_ints(out.get()) == O.matvec(pk, 0, cs, X.tolist())
     lib.haflo_ctx_destroy(ctx)
 
 

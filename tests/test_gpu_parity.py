@@ -53,6 +53,11 @@ def context(api, bits):
 
 from helpers import dev_to_ints, ints_to_dev, random_units_words, to_dev  # noqa: E402
 
+# X^T [[d]] has two implementations chosen by the row count (power tables below the threshold,
+# buckets above); this environment variable moves the threshold so that either can be forced.
+XTD_THRESHOLD = "HAFLO_XTD_BUCKET_MIN_ROWS"
+XTD_METHODS = {"tables": "1000000000000", "buckets": "1"}
+
 
 def sample_indices(count, k, seed):
     """k seeded indices that always include the ends and the neighbours of
@@ -104,7 +109,7 @@ def test_cfg1_operator_mix_full_parity(api):
 # ---------------------------------------------------------------------------
 # configuration 2: hetero-LR encrypted gradient at a 1024-bit key, everything compared
 # ---------------------------------------------------------------------------
-def test_cfg2_encrypted_gradient_full_parity(api):
+def test_cfg2_encrypted_gradient_full_parity(api, monkeypatch):
     cfg = synth.CONFIGS[2]
     bits, rows, cols = cfg["n_bits"], cfg["rows"], cfg["cols"]
     ctx, sk = context(api, bits)
@@ -129,8 +134,13 @@ def test_cfg2_encrypted_gradient_full_parity(api):
     want_c = OP.encrypt_many(n, md, rs)
     assert dev_to_ints(api.haflo_export_cipher(ctx, c)) == want_c
     say("cfg2: matvec")
-    out = api.haflo_cipher_matvec(ctx, 0, c, X)
     want_out = OP.matvec_cols(n, want_c, [[row[j] for row in Xo] for j in range(cols)])
+    for method, threshold in XTD_METHODS.items():
+        monkeypatch.setenv(XTD_THRESHOLD, threshold)
+        forced = api.haflo_cipher_matvec(ctx, 0, c, X)
+        assert dev_to_ints(api.haflo_export_cipher(ctx, forced)) == want_out, method
+    monkeypatch.delenv(XTD_THRESHOLD)
+    out = api.haflo_cipher_matvec(ctx, 0, c, X)
     assert dev_to_ints(api.haflo_export_cipher(ctx, out)) == want_out
     say("cfg2: decrypt + decode")
     pl = api.haflo_decrypt(ctx, out)
@@ -229,7 +239,7 @@ def test_cfg4_aggregation_full_size(api):
 # ---------------------------------------------------------------------------
 # configuration 5: large-key gradient at a 4096-bit key
 # ---------------------------------------------------------------------------
-def test_cfg5_large_key_gradient(api):
+def test_cfg5_large_key_gradient(api, monkeypatch):
     cfg = synth.CONFIGS[5]
     bits, rows, cols = cfg["n_bits"], cfg["rows"], cfg["cols"]
     ctx, sk = context(api, bits)
@@ -255,13 +265,16 @@ def test_cfg5_large_key_gradient(api):
     sub_idx_t = torch.tensor(sub_idx, device="cuda")
     sub_c = c[sub_idx_t].contiguous()
     sub_X = X[sub_idx_t][:, :sub_cols].contiguous()
-    sub_out = api.haflo_cipher_matvec(ctx, 0, sub_c, sub_X)
     # the oracle needs these 2048 ciphertexts: take the 16 already checked plus GPU exports of
     # the rest, whose encryption path is the one checked on the sample above
     sub_c_int = dev_to_ints(api.haflo_export_cipher(ctx, sub_c))
     assert sub_c_int[:16] == want_c[:16]
     want_sub = OP.matvec_cols(n, sub_c_int, [Xo[sub_idx, j].tolist() for j in range(sub_cols)])
-    assert dev_to_ints(api.haflo_export_cipher(ctx, sub_out)) == want_sub
+    for method, threshold in XTD_METHODS.items():
+        monkeypatch.setenv(XTD_THRESHOLD, threshold)
+        sub_out = api.haflo_cipher_matvec(ctx, 0, sub_c, sub_X)
+        assert dev_to_ints(api.haflo_export_cipher(ctx, sub_out)) == want_sub, method
+    monkeypatch.delenv(XTD_THRESHOLD)
     say("cfg5: full matvec, plaintext identity on every output")
     out = api.haflo_cipher_matvec(ctx, 0, c, X)
     pl = api.haflo_decrypt(ctx, out)
@@ -344,8 +357,10 @@ def test_edges_scalar_mul(api):
     assert dev_to_ints(api.haflo_export_cipher(ctx, out)) == [pow(c, k, n * n) for c, k in zip(cs, ks)]
 
 
+@pytest.mark.parametrize("method", ["tables", "buckets"])
 @pytest.mark.parametrize("bits", [512, 2048])
-def test_edges_matvec(api, bits):
+def test_edges_matvec(api, bits, method, monkeypatch):
+    monkeypatch.setenv(XTD_THRESHOLD, XTD_METHODS[method])
     ctx, sk = context(api, bits)
     pk = sk.public
     n = pk.n
@@ -363,6 +378,14 @@ def test_edges_matvec(api, bits):
     cases.append((0, np.ones((nc, 1), dtype=np.int32)))          # summation
     cases.append((0, -np.ones((nc, 1), dtype=np.int32)))         # inverse of the product
     cases.append((0, np.zeros((nc, 2), dtype=np.int32)))
+    # equal entries: one bucket holds all 70 rows of a column and takes several reduction rounds
+    H = np.zeros((nc, 3), dtype=np.int32)
+    H[:, 0], H[:, 1] = 1 << 16, -3
+    H[::2, 2], H[1::2, 2] = 1023, -1025
+    cases.append((0, H))
+    # magnitudes around the points where the base-32 / base-1024 signed digits need one more position
+    for top in (16, 496, 512, 507376, 523776, 535821824):
+        cases.append((0, np.array([[top, -top], [top - 1, 1], [-(top // 2), top // 3]], dtype=np.int64).astype(np.int32)))
     Y = npr.integers(-(2 ** 16), 2 ** 16, size=(67, nc)).astype(np.int32)
     Y[npr.random(Y.shape) < 0.7] = 0
     Y[3, :] = 0                        # an empty row -> 1
@@ -370,8 +393,12 @@ def test_edges_matvec(api, bits):
     cases.append((1, Y))
     cases.append((1, np.eye(nc, dtype=np.int32)[:9]))
     for orientation, M in cases:
-        out = api.haflo_cipher_matvec(ctx, orientation, ci, to_dev(M))
-        assert dev_to_ints(api.haflo_export_cipher(ctx, out)) == O.matvec(pk, orientation, cs, M.tolist())
+        if orientation == 1 and method == "buckets":
+            continue  # orientation 1 has a single implementation
+        used = ci[:M.shape[0]].contiguous() if orientation == 0 else ci
+        out = api.haflo_cipher_matvec(ctx, orientation, used, to_dev(M))
+        assert dev_to_ints(api.haflo_export_cipher(ctx, out)) == O.matvec(pk, orientation, cs[:used.shape[0]],
+                                                                         M.tolist())
     s = api.haflo_cipher_sum(ctx, ci)
     assert dev_to_ints(api.haflo_export_cipher(ctx, s)) == [O.summation(pk, cs)]
     s1 = api.haflo_cipher_sum(ctx, ci[:1].contiguous())
