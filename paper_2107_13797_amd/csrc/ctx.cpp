@@ -294,6 +294,7 @@ static int ctx_build(haflo_ctx* ctx, const Big& n, const Big* p, const Big* q, u
   Uploader up{ctx};
   const int nl_n2 = (int)(n_bits * 9 / 128);
   build_modulus(ctx->N, ctx->nsq, nl_n2, up);
+  build_modulus(ctx->Nw, n, nl_n2, up);
   if (!up.ok) return HAFLO_ENOMEM;
   build_prog_encrypt(ctx->prog_enc, n, up);
   {

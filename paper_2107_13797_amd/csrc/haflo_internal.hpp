@@ -106,6 +106,7 @@ struct haflo_ctx {
   int num_cu = 0;
   haflo::Big n, nsq, p, q;
   haflo::ModHost N;            // n^2
+  haflo::ModHost Nw;           // n, at the limb count (and Montgomery radix) of n^2
   haflo::ModHost P2, Q2;       // p^2, q^2 (private)
   haflo::ModHost P, Q;         // p, q (private)
   haflo::DevProg prog_enc;     // encryption: r^n modulo n^2 and the (1 + m n) factor

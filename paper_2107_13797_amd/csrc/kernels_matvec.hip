@@ -190,8 +190,45 @@ __device__ __forceinline__ void invert_mont(u32 (&out)[LPT], const u32 (&a)[LPT]
   for (int j = 0; j < LPT; ++j) out[j] = x[j];
 }
 
+// The same inverse modulo n^2, through n: y = x^-1 mod n costs half the division steps (the modulus
+// has half the bits), and one Newton step lifts it, x^-1 = y (2 - x y) mod n^2.
+//   a: Montgomery form x R mod n^2 (lazy), M2/mod2: n^2, Mn: the modulus n with the same R and limb
+//   count, nbatch_n: batches for the bit length of n. Returns x^-1 R mod n^2, canonical.
 template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_invert(ModRef M, const u32* in, u32* out, size_t count, int nbatch) {
+__device__ __forceinline__ void invert_lifted(u32 (&out)[LPT], const u32 (&a)[LPT], const ModRegs<LPT>& mod2,
+                                              const ModRef& M2, const ModRef& Mn, int nbatch_n, const Grp<T>& g) {
+  ModRegs<LPT> mn;
+  load_mod<LPT, T>(mn, Mn, g);
+  u32 y[LPT], t[LPT];
+  load_limbs<LPT, T>(t, Mn.r1, g);
+  montmul<LPT, T>(y, a, t, mn.n, mn.n0inv, g);  // a (R mod n) / R = a mod n, which is x R mod n
+  canonicalise<LPT, T>(y, mn.n, g);
+  invert_mont<LPT, T>(y, y, mn, Mn.r3, nbatch_n, g);  // (x^-1 mod n) R mod n
+  load_limbs<LPT, T>(t, Mn.one, g);
+  montmul<LPT, T>(y, y, t, mn.n, mn.n0inv, g);  // x^-1 mod n, as a plain integer
+  canonicalise<LPT, T>(y, mn.n, g);
+  load_limbs<LPT, T>(t, M2.r2, g);
+  montmul<LPT, T>(y, y, t, mod2.n, mod2.n0inv, g);  // Y = y R mod n^2
+  montmul<LPT, T>(t, a, y, mod2.n, mod2.n0inv, g);  // x y R mod n^2
+  canonicalise<LPT, T>(t, mod2.n, g);
+  // u = (2 - x y) R + n^2 > 0, below 3 n^2
+  u32 r1[LPT];
+  load_limbs<LPT, T>(r1, M2.r1, g);
+  s32 u[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) u[j] = (s32)(2u * r1[j] + mod2.n[j]) - (s32)t[j];
+  resolve<LPT, T>(u, g);
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) t[j] = (u32)u[j];
+  montmul<LPT, T>(y, y, t, mod2.n, mod2.n0inv, g);
+  canonicalise<LPT, T>(y, mod2.n, g);
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) out[j] = y[j];
+}
+
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_invert(ModRef M, ModRef Mn, const u32* in, u32* out, size_t count,
+                                                          int nbatch_n) {
   constexpr int NL = LPT * T;
   Grp<T> g;
   Batch<T> bt;
@@ -203,7 +240,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_invert(ModRef M, const u32* i
     u32 x[LPT];
     if (active) load_limbs<LPT, T>(x, in + item * (size_t)NL, g);
     else zero_limbs<LPT>(x);
-    invert_mont<LPT, T>(x, x, mod, M.r3, nbatch, g);
+    invert_lifted<LPT, T>(x, x, mod, M, Mn, nbatch_n, g);
     if (active) store_limbs<LPT, T>(out + item * (size_t)NL, x, g);
   }
 }
@@ -365,8 +402,9 @@ __global__ __launch_bounds__(kBlockThreads) void k_xtd_horner(ModRef M, size_t c
 
 // out[j] = P[j][+] * (P[j][-])^-1
 template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_xtd_finish(ModRef M, size_t cols, const u32* __restrict__ P,
-                                                              u32* __restrict__ out, int nbatch) {
+__global__ __launch_bounds__(kBlockThreads) void k_xtd_finish(ModRef M, ModRef Mn, size_t cols,
+                                                              const u32* __restrict__ P, u32* __restrict__ out,
+                                                              int nbatch_n) {
   constexpr int NL = LPT * T;
   Grp<T> g;
   Batch<T> bt;
@@ -383,8 +421,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_xtd_finish(ModRef M, size_t c
       load_limbs<LPT, T>(pos, M.r1, g);
       load_limbs<LPT, T>(neg, M.r1, g);
     }
-    canonicalise<LPT, T>(neg, mod.n, g);
-    invert_mont<LPT, T>(neg, neg, mod, M.r3, nbatch, g);
+    invert_lifted<LPT, T>(neg, neg, mod, M, Mn, nbatch_n, g);
     montmul<LPT, T>(pos, pos, neg, mod.n, mod.n0inv, g);
     canonicalise<LPT, T>(pos, mod.n, g);
     if (active) store_limbs<LPT, T>(out + j * (size_t)NL, pos, g);
@@ -525,8 +562,9 @@ __global__ __launch_bounds__(kBlockThreads) void k_sum(ModRef M, const u32* __re
   if (bt.gib == 0) store_limbs<LPT, T>(out + (size_t)blockIdx.x * NL, acc, g);
 }
 
+// batches of 29 division steps that always suffice for the modulus n
 int inverse_batches(const haflo_ctx* ctx) {
-  size_t bits = ctx->N.mod.bits();
+  size_t bits = ctx->Nw.mod.bits();
   size_t steps = (49 * bits + 57) / 17;
   return (int)((steps + LIMB_BITS - 1) / LIMB_BITS);
 }
@@ -617,7 +655,7 @@ int invert_batch(const haflo_ctx* ctx, const uint32_t* in, uint32_t* out, size_t
   const bool wide = haflo::few_groups(ctx, count);
   const LaunchShape sh = launch_shape(ctx, count, wide ? haflo_wide_lanes(m) : m.t, 8);
   const int nbatch = inverse_batches(ctx);
-#define CALL(LPT, T) HAFLO_LAUNCH((k_invert<LPT, T>), sh, st, m.ref(), in, out, count, nbatch)
+#define CALL(LPT, T) HAFLO_LAUNCH((k_invert<LPT, T>), sh, st, m.ref(), ctx->Nw.ref(), in, out, count, nbatch)
   if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
   return hip_status(hipGetLastError());
@@ -663,7 +701,7 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
     if (rc != HAFLO_OK) return rc;
     const bool wide = haflo::few_groups(ctx, cols);
     const LaunchShape sh = launch_shape(ctx, cols, wide ? haflo_wide_lanes(m) : m.t, 8);
-#define CALL(LPT, T) HAFLO_LAUNCH((k_xtd_finish<LPT, T>), sh, st, m.ref(), cols, (const u32*)P, (u32*)d_out, nbatch)
+#define CALL(LPT, T) HAFLO_LAUNCH((k_xtd_finish<LPT, T>), sh, st, m.ref(), ctx->Nw.ref(), cols, (const u32*)P, (u32*)d_out, nbatch)
     if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
   } else if (orientation == 0) {
@@ -694,7 +732,7 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
     {
       const bool wide = haflo::few_groups(ctx, cols);
       const LaunchShape sh = launch_shape(ctx, cols, wide ? haflo_wide_lanes(m) : m.t, 8);
-#define CALL(LPT, T) HAFLO_LAUNCH((k_xtd_finish<LPT, T>), sh, st, m.ref(), cols, (const u32*)P, (u32*)d_out, nbatch)
+#define CALL(LPT, T) HAFLO_LAUNCH((k_xtd_finish<LPT, T>), sh, st, m.ref(), ctx->Nw.ref(), cols, (const u32*)P, (u32*)d_out, nbatch)
       if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
     }
