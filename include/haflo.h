@@ -67,7 +67,8 @@ enum haflo_op {
   HAFLO_OP_DECRYPT = 2,
   HAFLO_OP_SCALAR_MUL = 3,
   HAFLO_OP_MATVEC_XT_D = 4, /* orientation 0 */
-  HAFLO_OP_MATVEC_X_W = 5   /* orientation 1 */
+  HAFLO_OP_MATVEC_X_W = 5,  /* orientation 1 */
+  HAFLO_OP_FORE_GRADIENT = 6
 };
 
 /* Text for an error code; never NULL. */
@@ -209,6 +210,27 @@ int haflo_scalar_mul_i64_bcast(const haflo_ctx* ctx, const void* d_c, int64_t k,
  */
 int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, const int32_t* d_X, size_t rows,
                         size_t cols, void* d_out, void* d_workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The guest's fore gradient of heterogeneous logistic regression as one call
+ * (paper section 3.4 and the workflow figure there: [[0.25 (logits_host +
+ * logits_guest) - 0.5 label]], eight operator calls in the framework the paper
+ * accelerates), with every intermediate kept on the device:
+ *   out[i] = c_host[i] * E(q(logits_guest[i]) - 2 q(label[i]) mod n; r[i]) mod n^2,
+ * q(v) = rint(v * 2^scale_bits) as in haflo_encode_f32. With c_host[i] an
+ * encryption of q(logits_host[i]) at the same scale, out[i] encrypts
+ * q_host + q_guest - 2 q_label, which is the fore gradient at scale
+ * 2^(scale_bits + 2): the factor 0.25 is a change of scale, not a ciphertext
+ * operation. d_c_host, d_out: count internal elements (d_out may alias
+ * d_c_host); d_logits_guest, d_label: device float[count]; d_r: device
+ * count*Lp uint32 as for haflo_encrypt; d_status: device uint32[count] or
+ * NULL, HAFLO_ST_RANGE (and plaintext part 0) when an input is not finite or
+ * a quantised input reaches 2^61 in magnitude. scale_bits <= 60.
+ * Workspace: HAFLO_OP_FORE_GRADIENT with rows = count.
+ */
+int haflo_fore_gradient(const haflo_ctx* ctx, const void* d_c_host, const float* d_logits_guest,
+                        const float* d_label, const uint32_t* d_r, uint32_t scale_bits, void* d_out,
+                        uint32_t* d_status, size_t count, void* d_workspace, size_t workspace_bytes, void* stream);
 
 /* "Homomorphic Summation" (paper Table 1): out[0] = prod_i c[i] mod n^2 over
  * count internal elements (1 for count = 0). Workspace: the same as

@@ -252,6 +252,24 @@ def matvec(pk: PublicKey, orientation: int, cs: Sequence[int], X: Sequence[Seque
     raise ValueError("orientation must be 0 or 1")
 
 
+def fore_gradient(pk: PublicKey, c_host: int, logit_guest: float, label: float, r: int,
+                  scale_bits: int) -> Tuple[int, int]:
+    """Guest's fore gradient of heterogeneous logistic regression, section 3.4 (workflow figure):
+    [[0.25 * (logits_host + logits_guest) - 0.5 * label]].
+
+    Fixed-point reading: c_host encrypts q(logits_host) at scale 2^scale_bits; the guest adds an
+    encryption of q(logits_guest) - 2 q(label). The sum q_host + q_guest - 2 q_label is
+    4 * 2^scale_bits times the fore gradient, so the result is read at scale 2^(scale_bits + 2)
+    and the factor 0.25 needs no ciphertext operation.
+
+    Returns (ciphertext, status): status 1 and a guest part of 0 when an input is not finite or a
+    quantised input reaches 2^61 in magnitude, else status 0."""
+    qg, ql = quantise(logit_guest, scale_bits), quantise(label, scale_bits)
+    ok = qg is not None and ql is not None and abs(qg) < (1 << 61) and abs(ql) < (1 << 61)
+    q = qg - 2 * ql if ok else 0
+    return add(pk, c_host, encrypt(pk, q % pk.n, r)), (0 if ok else 1)
+
+
 # --------------------------------------------------------------------------
 # signed fixed point
 # --------------------------------------------------------------------------

@@ -173,6 +173,17 @@ def haflo_encrypt(ctx, plain, r, out=None):
     return out
 
 
+def haflo_fore_gradient(ctx, c_host, logits_guest, label, r, scale_bits, out=None, status=None):
+    count = c_host.shape[0]
+    if out is None:
+        out = _new_cipher(ctx, count)
+    ws = ctx.workspace(haflo_workspace_bytes(ctx, _cabi.OP_FORE_GRADIENT, count))
+    _check(lib().haflo_fore_gradient(ctx.handle, _ptr(c_host), _ptr(logits_guest), _ptr(label), _ptr(r), scale_bits,
+                                     _ptr(out), _ptr(status) if status is not None else None, count, _ptr(ws),
+                                     ws.numel(), _stream()))
+    return out
+
+
 def haflo_decrypt(ctx, cipher, out=None):
     count = cipher.shape[0]
     if out is None:

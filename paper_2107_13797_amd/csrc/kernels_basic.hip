@@ -111,8 +111,10 @@ __device__ __forceinline__ bool quantise(float v, int scale_bits, long long& q) 
 // quad of an element's Lp words, so stores are fully coalesced. A negative q
 // is n - |q|: |q| < 2^64 only touches the two lowest words, above them the
 // borrow runs through zero words of n up to its first non-zero word `z`.
-__global__ __launch_bounds__(kBlockThreads) void k_encode(const float* __restrict__ v, int scale_bits,
-                                                          const u32* __restrict__ nw, int lp, int z,
+// With a second input v2 the encoded integer is q(v) - 2 q(v2) (the plaintext part of the fore
+// gradient); both must then stay below 2^61 in magnitude.
+__global__ __launch_bounds__(kBlockThreads) void k_encode(const float* __restrict__ v, const float* __restrict__ v2,
+                                                          int scale_bits, const u32* __restrict__ nw, int lp, int z,
                                                           u32* __restrict__ plain, u32* __restrict__ status,
                                                           size_t count) {
   const int qpi = lp >> 2;  // quads per item
@@ -123,6 +125,12 @@ __global__ __launch_bounds__(kBlockThreads) void k_encode(const float* __restric
     int quad = (int)(idx - item * (size_t)qpi);
     long long q;
     bool ok = quantise(v[item], scale_bits, q);
+    if (v2) {
+      long long q2;
+      const long long lim = 1ll << 61;
+      ok = quantise(v2[item], scale_bits, q2) && ok && q > -lim && q < lim && q2 > -lim && q2 < lim;
+      q = ok ? q - 2 * q2 : 0;
+    }
     u32 w[4] = {0u, 0u, 0u, 0u};
     if (q >= 0) {
       if (quad == 0) {
@@ -287,9 +295,32 @@ int haflo_encode_f32(const haflo_ctx* ctx, const float* d_v, uint32_t scale_bits
   while (z < ctx->lp && ctx->n.word(z) == 0) ++z;
   size_t total = count * (size_t)(ctx->lp / 4);
   const LaunchShape sh = launch_shape(ctx, total, 1, 16);
-  HAFLO_LAUNCH(k_encode, sh, (hipStream_t)stream, d_v, (int)scale_bits, ctx->d_n_words, ctx->lp, z, d_plain,
-               d_status, count);
+  HAFLO_LAUNCH(k_encode, sh, (hipStream_t)stream, d_v, (const float*)nullptr, (int)scale_bits, ctx->d_n_words,
+               ctx->lp, z, d_plain, d_status, count);
   return hip_status(hipGetLastError());
+}
+
+int haflo_fore_gradient(const haflo_ctx* ctx, const void* d_c_host, const float* d_logits_guest,
+                        const float* d_label, const uint32_t* d_r, uint32_t scale_bits, void* d_out,
+                        uint32_t* d_status, size_t count, void* d_workspace, size_t workspace_bytes, void* stream) {
+  if (!ctx || scale_bits > 60 || (count && (!d_c_host || !d_logits_guest || !d_label || !d_r || !d_out)))
+    return HAFLO_EINVAL;
+  if (count == 0) return HAFLO_OK;
+  // workspace: [guest plaintexts][their encryptions][encryption workspace]
+  const size_t plain_bytes = (count * (size_t)ctx->lp * 4 + 255) & ~(size_t)255;
+  const size_t cipher_bytes = (count * (size_t)ctx->N.nl * 4 + 255) & ~(size_t)255;
+  const size_t enc_bytes = haflo_workspace_bytes(ctx, HAFLO_OP_ENCRYPT, count, 0);
+  if (!d_workspace || workspace_bytes < plain_bytes + cipher_bytes + enc_bytes) return HAFLO_EINVAL;
+  uint32_t* plain = (uint32_t*)d_workspace;
+  char* guest = (char*)d_workspace + plain_bytes;
+  int z = 2;
+  while (z < ctx->lp && ctx->n.word(z) == 0) ++z;
+  const LaunchShape sh = launch_shape(ctx, count * (size_t)(ctx->lp / 4), 1, 16);
+  HAFLO_LAUNCH(k_encode, sh, (hipStream_t)stream, d_logits_guest, d_label, (int)scale_bits, ctx->d_n_words, ctx->lp,
+               z, plain, d_status, count);
+  int rc = haflo_encrypt(ctx, plain, d_r, guest, count, guest + cipher_bytes, enc_bytes, stream);
+  if (rc != HAFLO_OK) return rc;
+  return haflo_add(ctx, d_c_host, guest, d_out, count, stream);
 }
 
 int haflo_encode_exponents_f32(const float* d_x, uint32_t scale_bits, int32_t* d_e, uint32_t* d_status, size_t count,

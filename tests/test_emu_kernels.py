@@ -317,6 +317,30 @@ def test_bucket_matvec_four_lane_groups(emu, force_buckets):
     lib.haflo_ctx_destroy(ctx)
 
 
+def test_fore_gradient(env):
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    lp = BITS // 32
+    rng = random.Random(31)
+    ug = np.concatenate([synth.normal_f32(9, 2.0, 32), np.array([np.nan, 1.0, -3.5], dtype=np.float32)])
+    y = np.concatenate([np.array([1, -1, 0, 1, 1, -1, 0, 1, -1, 1], dtype=np.float32),
+                        np.array([2.0 ** 38, -(2.0 ** 37)], dtype=np.float32)])
+    count = len(ug)
+    c_host = [O.encrypt(pk, rng.randrange(pk.n), rng.randrange(1, pk.n)) for _ in range(count)]
+    rs = [rng.randrange(1, pk.n) for _ in range(count)]
+    d_c = zeros(lib, (count, nlw))
+    assert lib.haflo_import_cipher(ctx, words(lib, c_host, BITS // 16).p, d_c.p, None, count, None) == 0
+    w, nb = ws(lib, ctx, _cabi.OP_FORE_GRADIENT, count)
+    d_o, d_st = zeros(lib, (count, nlw)), zeros(lib, (count,))
+    assert lib.haflo_fore_gradient(ctx, d_c.p, Dev(lib, ug).p, Dev(lib, y).p, words(lib, rs, lp).p, 24, d_o.p, d_st.p,
+                                   count, w.p, nb, None) == 0
+    want = [O.fore_gradient(pk, c_host[i], float(ug[i]), float(y[i]), rs[i], 24) for i in range(count)]
+    assert export(lib, ctx, d_o, count) == [c for c, _ in want]
+    assert d_st.get().tolist() == [st for _, st in want] and sum(st for _, st in want) == 3
+    assert lib.haflo_fore_gradient(ctx, d_c.p, Dev(lib, ug).p, Dev(lib, y).p, words(lib, rs, lp).p, 24, d_o.p, None,
+                                   count, w.p, nb - 1, None) == -1
+
+
 def test_encode_decode(env):
     lib, ctx, sk, nlw = env
     pk = sk.public

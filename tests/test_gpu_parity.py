@@ -405,6 +405,42 @@ def test_edges_matvec(api, bits, method, monkeypatch):
     assert dev_to_ints(api.haflo_export_cipher(ctx, s1)) == cs[:1]
 
 
+def test_fore_gradient_chain(api):
+    """The fused fore-gradient call against the oracle (sampled ciphertexts at a 2048-bit key,
+    every element through decryption and the closed form on the quantised inputs)."""
+    bits, count, s = 2048, 3000, 24
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n = pk.n
+    uh = synth.normal_f32(count, 2.0, 71)
+    ug = synth.normal_f32(count, 2.0, 72)
+    y = np.where(np.random.default_rng(73).random(count) < 0.5, -1.0, 1.0).astype(np.float32)
+    ug[5], y[6] = np.inf, np.nan
+    r1 = random_units_words(count, bits, 74)
+    r2 = random_units_words(count, bits, 75)
+    c_host = api.haflo_encrypt(ctx, api.haflo_encode_f32(ctx, to_dev(uh), s), to_dev(r1))
+    st = torch.zeros(count, dtype=torch.int32, device="cuda")
+    out = api.haflo_fore_gradient(ctx, c_host, to_dev(ug), to_dev(y), to_dev(r2), s, status=st)
+    idx = sample_indices(count, 48, 76) + [5, 6]
+    idx_t = torch.tensor(idx, device="cuda")
+    host_int = dev_to_ints(api.haflo_export_cipher(ctx, c_host[idx_t].contiguous()))
+    r2_int = synth.words_to_ints(r2[idx])
+    want = [O.fore_gradient(pk, host_int[k], float(ug[i]), float(y[i]), r2_int[k], s) for k, i in enumerate(idx)]
+    assert dev_to_ints(api.haflo_export_cipher(ctx, out[idx_t].contiguous())) == [c for c, _ in want]
+    assert st.cpu().numpy()[idx].tolist() == [f for _, f in want]
+    flags = st.cpu().numpy()
+    assert flags.sum() == 2 and flags[5] == 1 and flags[6] == 1
+    q, _ = api.haflo_decode(ctx, api.haflo_decrypt(ctx, out), s + 2)
+    qh = np.rint(uh.astype(np.float64) * 2.0 ** s).astype(np.int64)
+    with np.errstate(invalid="ignore", over="ignore"):
+        qg = np.rint(np.where(flags == 0, ug, 0).astype(np.float64) * 2.0 ** s).astype(np.int64)
+        ql = np.rint(np.where(flags == 0, y, 0).astype(np.float64) * 2.0 ** s).astype(np.int64)
+    assert q.cpu().numpy().tolist() == (qh + qg - 2 * ql).tolist()
+    aliased = c_host.clone()
+    api.haflo_fore_gradient(ctx, aliased, to_dev(ug), to_dev(y), to_dev(r2), s, out=aliased)
+    assert torch.equal(aliased, out)
+
+
 def test_edges_encode_decode(api):
     bits = 1024
     ctx, sk = context(api, bits)

@@ -276,3 +276,32 @@ def test_limb_helpers_roundtrip():
         limbs = O.to_limbs(x, bits // 32)
         assert all(0 <= w < 2 ** 32 for w in limbs) and O.from_limbs(limbs) == x
     assert O.to_limbs(1 + (2 << 32), 3) == [1, 2, 0]
+
+
+def test_fore_gradient_plaintext_closed_form():
+    """Section 3.4's fore gradient 0.25 (logits_host + logits_guest) - 0.5 label: the decrypted,
+    decoded result equals the exact integer combination of the three quantised inputs at scale
+    2^(s+2), and lies within the quantisation bound of the real-valued formula. A wrong sign, a
+    missing factor 2 on the label or a wrong output scale breaks one of the two."""
+    sk = _real_key(512)
+    pk = sk.public
+    rng = random.Random(99)
+    s = 24
+    for _ in range(40):
+        uh, ug = rng.gauss(0, 2.0), rng.gauss(0, 2.0)
+        y = rng.choice([-1.0, 1.0, 0.0])
+        uh32, ug32 = float(np.float32(uh)), float(np.float32(ug))
+        qh = O.quantise(uh32, s)
+        c_host = O.encrypt(pk, qh % pk.n, rng.randrange(1, pk.n))
+        c, st = O.fore_gradient(pk, c_host, ug32, y, rng.randrange(1, pk.n), s)
+        assert st == 0
+        m = O.decrypt(sk, c)
+        qd, val, dst = O.decode(pk, m, s + 2)
+        assert dst == 0
+        assert qd == qh + O.quantise(ug32, s) - 2 * O.quantise(y, s)
+        want = 0.25 * (uh32 + ug32) - 0.5 * y
+        assert abs(val - want) <= 2.0 ** -(s + 1)
+    c, st = O.fore_gradient(pk, 1, float("nan"), 1.0, 5, s)
+    assert st == 1 and c == O.encrypt(pk, 0, 5)
+    c, st = O.fore_gradient(pk, 1, 1.0, 2.0 ** 38, 5, s)       # 2^62 after scaling
+    assert st == 1 and c == O.encrypt(pk, 0, 5)
