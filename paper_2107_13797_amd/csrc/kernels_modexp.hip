@@ -153,8 +153,14 @@ __global__ __launch_bounds__(kBlockThreads) void k_enc_crt(ModRef MP2, ModRef MQ
   }
 }
 
-LaunchShape modexp_shape(const haflo_ctx* ctx, size_t count, int t) {
-  return launch_shape(ctx, count, t, kModexpBlocksPerCu);
+// A batch that leaves most of the chip idle is latency-bound: its integers are spread over twice
+// the lanes (9 limbs each), which shortens every product of the chain at 1.2 times the
+// instructions. Taken while the doubled batch still is at most two wavefronts per SIMD.
+bool engine_wide(const haflo_ctx* ctx, size_t count, const ModHost& m) {
+  return m.lpt == 18 && m.t < 16 && count * (size_t)m.t <= (size_t)ctx->num_cu * 256;
+}
+LaunchShape modexp_shape(const haflo_ctx* ctx, size_t count, const ModHost& m) {
+  return launch_shape(ctx, count, engine_wide(ctx, count, m) ? 2 * m.t : m.t, kModexpBlocksPerCu);
 }
 
 EngineIO engine_io(const ModHost& m) {
@@ -178,8 +184,9 @@ bool to_inline(ProgInline& pi, const std::vector<uint32_t>& prog) {
 template <class Prog>
 int launch_engine(const ModHost& m, const LaunchShape& sh, hipStream_t st, const Prog& prog, const EngineIO& io,
                   size_t count) {
+  const bool wide = sh.gpb * m.t != sh.threads;  // the shape was made for twice the lanes per integer
 #define CALL(LPT, T) HAFLO_LAUNCH((k_engine<LPT, T, Prog>), sh, st, m.ref(), prog, io, count)
-  HAFLO_DISPATCH_GEOMETRY(m, CALL);
+  if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
   return hip_status(hipGetLastError());
 }
@@ -190,24 +197,24 @@ namespace haflo {
 // table slots: one set per resident lane group
 size_t ws_encrypt(const haflo_ctx* ctx, size_t count) {
   if (!ctx->has_priv)
-    return modexp_shape(ctx, count, ctx->N.t).slots() * (size_t)ctx->prog_enc.table_entries * ctx->N.nl * 4;
+    return modexp_shape(ctx, count, ctx->N).slots() * (size_t)ctx->prog_enc.table_entries * ctx->N.nl * 4;
   // key owner: [y_p, y_q: count*P2.nl each][r^n: count*N.nl][branch tables, both halves of the grid]
   // and, for the last stage, one table slot of N.nl limbs per lane group (placed over the branch tables)
   size_t tl = (size_t)std::max(ctx->prog_enc_p.table_entries, ctx->prog_enc_q.table_entries);
-  size_t branch = 2 * modexp_shape(ctx, count, ctx->P2.t).slots() * tl * ctx->P2.nl;
-  size_t last = modexp_shape(ctx, count, ctx->N.t).slots() * (size_t)ctx->N.nl;
+  size_t branch = 2 * modexp_shape(ctx, count, ctx->P2).slots() * tl * ctx->P2.nl;
+  size_t last = modexp_shape(ctx, count, ctx->N).slots() * (size_t)ctx->N.nl;
   return (2 * count * (size_t)ctx->P2.nl + count * (size_t)ctx->N.nl + std::max(branch, last)) * 4;
 }
 // sized for the per-element variant (16 entries); the broadcast variant never needs more
 size_t ws_scalar_mul(const haflo_ctx* ctx, size_t count) {
-  return modexp_shape(ctx, count, ctx->N.t).slots() * (size_t)16 * ctx->N.nl * 4;
+  return modexp_shape(ctx, count, ctx->N).slots() * (size_t)16 * ctx->N.nl * 4;
 }
 // layout: [canon29: count*N.nl][yp: count*P2.nl][yq: count*Q2.nl][tables]
 size_t ws_decrypt(const haflo_ctx* ctx, size_t count) {
   if (!ctx->has_priv) return 0;
   size_t tl = (size_t)std::max(ctx->prog_dec_p.table_entries, ctx->prog_dec_q.table_entries);
   return (count * (size_t)ctx->N.nl + 2 * count * (size_t)ctx->P2.nl +
-          2 * modexp_shape(ctx, count, ctx->P2.t).slots() * tl * ctx->P2.nl) * 4;
+          2 * modexp_shape(ctx, count, ctx->P2).slots() * tl * ctx->P2.nl) * 4;
 }
 
 // tables[i][d] = c_i^d, d < entries, for `count` internal ciphertexts (used by the matvec)
@@ -249,7 +256,7 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
     io.tables = (u32*)d_workspace;
     io.table_entries = ctx->prog_enc.table_entries;
     ProgPtr prog = {ctx->prog_enc.d_ins, (int)ctx->prog_enc.host.size()};
-    return launch_engine(m, modexp_shape(ctx, count, m.t), st, prog, io, count);
+    return launch_engine(m, modexp_shape(ctx, count, m), st, prog, io, count);
   }
   // key owner: r^n through p^2 and q^2 (half-size moduli: a quarter of the multiplications per
   // branch), Chinese remainder, then the (1 + m n) factor and the Montgomery form modulo n^2.
@@ -261,7 +268,7 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
   u32* tables = rn + count * (size_t)m.nl;
   {
     const int tl = std::max(ctx->prog_enc_p.table_entries, ctx->prog_enc_q.table_entries);
-    LaunchShape sh = modexp_shape(ctx, count, h.t);
+    LaunchShape sh = modexp_shape(ctx, count, h);
     EngineJob job[2];
     for (int side = 0; side < 2; ++side) {
       const ModHost& ms = side ? ctx->Q2 : ctx->P2;
@@ -278,7 +285,7 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
     const unsigned split = (unsigned)sh.blocks;
     sh.blocks *= 2;
 #define CALL(LPT, T) HAFLO_LAUNCH((k_engine_pair<LPT, T>), sh, st, job[0], job[1], split, count)
-    HAFLO_DISPATCH_GEOMETRY(h, CALL);
+    if (engine_wide(ctx, count, h)) { HAFLO_DISPATCH_GEOMETRY_WIDE(h, CALL); } else { HAFLO_DISPATCH_GEOMETRY(h, CALL); }
 #undef CALL
   }
   {
@@ -309,7 +316,7 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
   io.out = (u32*)d_cipher;
   io.tables = tables;
   io.table_entries = 1;
-  return launch_engine(m, modexp_shape(ctx, count, m.t), st, pi, io, count);
+  return launch_engine(m, modexp_shape(ctx, count, m), st, pi, io, count);
 }
 
 int haflo_scalar_mul_u64(const haflo_ctx* ctx, const void* d_c, const uint64_t* d_k, void* d_out, size_t count,
@@ -337,7 +344,7 @@ int haflo_scalar_mul_u64(const haflo_ctx* ctx, const void* d_c, const uint64_t* 
   io.out = (u32*)d_out;
   io.tables = (u32*)d_workspace;
   io.table_entries = 16;
-  return launch_engine(m, modexp_shape(ctx, count, m.t), (hipStream_t)stream, pi, io, count);
+  return launch_engine(m, modexp_shape(ctx, count, m), (hipStream_t)stream, pi, io, count);
 }
 
 int haflo_scalar_mul_i64_bcast(const haflo_ctx* ctx, const void* d_c, int64_t k, void* d_out, size_t count,
@@ -367,7 +374,7 @@ int haflo_scalar_mul_i64_bcast(const haflo_ctx* ctx, const void* d_c, int64_t k,
   io.out = (u32*)d_out;
   io.tables = (u32*)d_workspace;
   io.table_entries = plan.table_len + 1;
-  return launch_engine(m, modexp_shape(ctx, count, m.t), st, pi, io, count);
+  return launch_engine(m, modexp_shape(ctx, count, m), st, pi, io, count);
 }
 
 int haflo_decrypt(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain, size_t count, void* d_workspace,
@@ -393,7 +400,7 @@ int haflo_decrypt(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain,
     // both prime-power branches in one launch: the first half of the grid works modulo p^2,
     // the second half modulo q^2, each half with its own table slots
     const ModHost& m = ctx->P2;
-    LaunchShape sh = modexp_shape(ctx, count, m.t);
+    LaunchShape sh = modexp_shape(ctx, count, m);
     EngineJob job[2];
     for (int side = 0; side < 2; ++side) {
       const ModHost& ms = side ? ctx->Q2 : ctx->P2;
@@ -410,7 +417,7 @@ int haflo_decrypt(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain,
     const unsigned split = (unsigned)sh.blocks;
     sh.blocks *= 2;
 #define CALL(LPT, T) HAFLO_LAUNCH((k_engine_pair<LPT, T>), sh, st, job[0], job[1], split, count)
-    HAFLO_DISPATCH_GEOMETRY(m, CALL);
+    if (engine_wide(ctx, count, m)) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
   }
   {

@@ -131,6 +131,38 @@ def test_encrypt_decrypt_scalar_mul(env):
         assert export(lib, ctx, d_o, len(ms)) == [O.scalar_mul(pk, c, k) for c in want], k
 
 
+def test_batch_above_the_wide_lane_threshold(env):
+    """Small batches run the exponentiation engine with twice the lanes per integer; 20 elements
+    exceed that threshold on the one-unit emulated chip, so this is the regular geometry (both
+    encryption paths, decryption, scalar multiplication)."""
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    n = pk.n
+    lp = BITS // 32
+    rng = random.Random(23)
+    count = 20
+    ms = [rng.randrange(n) for _ in range(count)]
+    rs = [rng.randrange(1, n) for _ in range(count)]
+    want = [O.encrypt(pk, m, r) for m, r in zip(ms, rs)]
+    pub = C.c_void_p()
+    buf = (C.c_uint8 * (BITS // 8)).from_buffer_copy(n.to_bytes(BITS // 8, "little"))
+    assert lib.haflo_ctx_create_public(buf, BITS, C.byref(pub)) == 0
+    for handle in (pub, ctx):
+        d_c = zeros(lib, (count, nlw))
+        w, nb = ws(lib, handle, _cabi.OP_ENCRYPT, count)
+        assert lib.haflo_encrypt(handle, words(lib, ms, lp).p, words(lib, rs, lp).p, d_c.p, count, w.p, nb, None) == 0
+        assert export(lib, handle, d_c, count) == want
+    lib.haflo_ctx_destroy(pub)
+    d_pl = zeros(lib, (count, lp))
+    w, nb = ws(lib, ctx, _cabi.OP_DECRYPT, count)
+    assert lib.haflo_decrypt(ctx, d_c.p, d_pl.p, count, w.p, nb, None) == 0
+    assert synth.words_to_ints(d_pl.get()) == ms
+    d_o = zeros(lib, (count, nlw))
+    w, nb = ws(lib, ctx, _cabi.OP_SCALAR_MUL, count)
+    assert lib.haflo_scalar_mul_i64_bcast(ctx, d_c.p, -5, d_o.p, count, w.p, nb, None) == 0
+    assert export(lib, ctx, d_o, count) == [O.scalar_mul(pk, c, -5) for c in want]
+
+
 def test_public_context_encrypts_identically(env):
     """The public-key path (full exponent modulo n^2) and the key owner's path (through p^2 and
     q^2) must produce the same ciphertext bits; a public context cannot decrypt."""
