@@ -178,9 +178,9 @@ struct XtdBucketPlan {
 };
 bool xtd_buckets_fit(size_t rows, size_t cols);
 XtdBucketPlan xtd_bucket_plan(const haflo_ctx* ctx, size_t rows, size_t cols);
-// d_P[j][sign] = product of c_i^|x_ij| over the entries of column j with that sign (lazy Montgomery form);
-// d_maxmag: the largest |x|. ws: xtd_bucket_plan(...).total words.
+// d_P[j][sign] = product of c_i^|x_ij| over the entries of column j with that sign (lazy Montgomery form).
+// ws: xtd_bucket_plan(...).total words.
 int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, size_t rows, size_t cols,
-                uint32_t* ws, const uint32_t* d_maxmag, uint32_t* d_P, hipStream_t st);
+                uint32_t* ws, uint32_t* d_P, hipStream_t st);
 
 }  // namespace haflo

@@ -51,21 +51,41 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_zero(u32* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
 
-// SCATTER = false: cnt[key] = bucket sizes.  SCATTER = true: sorted[off[key] + n] = row, n from cnt (zeroed again).
+// Words of the statistics block at the start of the workspace (zeroed with the counters).
+enum { kStatMaxMag = 0, kStatMaxCount = 1, kStatNextChunk = 2, kStatWords = 16 };
+
+// largest value of `m` over the wavefront, bit by bit from the top: keep the lanes that still can hold it
+__device__ __forceinline__ u32 wave_max(u32 m) {
+  u32 best = 0;
+  bool cand = true;
+#pragma unroll 1
+  for (int b = 31; b >= 0; --b) {
+    bool has = cand && ((m >> b) & 1u);
+    if (__builtin_amdgcn_ballot_w64(has) != 0ull) {
+      best |= 1u << b;
+      cand = has;
+    }
+  }
+  return best;
+}
+
+// Every non-zero digit of every entry, always over kMaxPos positions (positions above the largest
+// magnitude only hold zero digits). SCATTER = false: cnt[key] = bucket sizes, stats[kStatMaxMag] = largest
+// |x|. SCATTER = true: sorted[off[key] + n] = row, with n counted in cnt (zero at launch).
 template <bool SCATTER>
 __global__ __launch_bounds__(kBlockThreads) void k_bk_terms(const int* __restrict__ X, size_t rows, size_t cols,
                                                             u32* __restrict__ cnt, const u32* __restrict__ off,
-                                                            u32* __restrict__ sorted,
-                                                            const u32* __restrict__ maxmag) {
-  const int npos = digit_positions(*maxmag);
-  const unsigned long long offset = digit_offset(npos);
+                                                            u32* __restrict__ sorted, u32* __restrict__ stats) {
+  const unsigned long long offset = digit_offset(kMaxPos);
   const size_t total = rows * cols;
+  u32 largest = 0;
   for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
     const int x = X[e];
     if (x == 0) continue;
     const size_t i = e / cols, j = e - i * cols;
     const u32 mag = x < 0 ? 0u - (u32)x : (u32)x;
-    for (int s = 0; s < npos; ++s) {
+    largest = mag > largest ? mag : largest;
+    for (int s = 0; s < kMaxPos; ++s) {
       const int d = (int)((((unsigned long long)mag + offset) >> (s * kDigitBits)) & 1023ull) - 512;
       if (d == 0) continue;
       const size_t key = bucket_key(cols, j, s, (x < 0) != (d < 0), (u32)(d < 0 ? -d : d));
@@ -73,12 +93,24 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_terms(const int* __restric
       if (SCATTER) sorted[(size_t)off[key] + n] = (u32)i;
     }
   }
+  if (!SCATTER) {
+    largest = wave_max(largest);
+    if ((threadIdx.x & (WAVE - 1)) == 0 && largest) atomicMax(&stats[kStatMaxMag], largest);
+  }
 }
 
 // Items of a key with `c` rows at the start of round r: ceil(c / kChunk^r).
 __host__ __device__ inline u32 items_at(u32 c, int r) {
   const int sh = kChunkBits * r;
   return sh >= 32 ? (c != 0u) : (u32)(((u64)c + ((1ull << sh) - 1ull)) >> sh);
+}
+
+// Rounds that have work when the largest bucket holds `largest` rows: round 0, then every round that
+// still finds a key with more than one item.
+__host__ __device__ inline int rounds_run(u32 largest) {
+  int r = 1;
+  while (items_at(largest, r) > 1u) ++r;
+  return r;
 }
 
 // Exclusive prefix sums over the keys, for all rounds at once: component 0 of key k is its row count
@@ -101,15 +133,19 @@ __device__ __forceinline__ u32 block_sum(u32 v, u32* red) {
 }
 
 __global__ __launch_bounds__(kScanThreads) void k_bk_scan_totals(const u32* __restrict__ cnt, size_t K, int ncomp,
-                                                                u32* __restrict__ totals) {
+                                                                u32* __restrict__ totals, u32* __restrict__ stats) {
   __shared__ u32 red[kScanThreads];
   u32 mine[kMaxComp];
   for (int c = 0; c < kMaxComp; ++c) mine[c] = 0u;
   const size_t k0 = ((size_t)blockIdx.x * kScanThreads + threadIdx.x) * kScanPer;
+  u32 largest = 0;
   for (int i = 0; i < kScanPer; ++i) {
     const u32 n = (k0 + i < K) ? cnt[k0 + i] : 0u;
+    largest = n > largest ? n : largest;
     for (int c = 0; c < ncomp; ++c) mine[c] += items_at(n, c);
   }
+  largest = wave_max(largest);
+  if ((threadIdx.x & (WAVE - 1)) == 0 && largest) atomicMax(&stats[kStatMaxCount], largest);
   for (int c = 0; c < ncomp; ++c) {
     u32 t = block_sum(mine[c], red);
     if (threadIdx.x == 0) totals[(size_t)c * gridDim.x + blockIdx.x] = t;
@@ -159,17 +195,27 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u
                                                             const u32* __restrict__ cnt,
                                                             const u32* __restrict__ off,
                                                             const u32* __restrict__ choff, size_t K,
-                                                            int round, u32* __restrict__ out) {
+                                                            int round, u32* __restrict__ stats,
+                                                            u32* __restrict__ out) {
   constexpr int NL = LPT * T;
+  constexpr int GW = WAVE / T;                 // lane groups per wavefront
+  constexpr int IDX = (kChunk + T - 1) / T;    // row indices each lane keeps for its group's chunk
   Grp<T> g;
-  Batch<T> bt;
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
-  const size_t total = choff[K];
-  for (size_t base = bt.first(); base < total; base += bt.stride()) {
-    const size_t q = base + bt.gib;
+  const int lane = (int)(threadIdx.x & (WAVE - 1));
+  if (round >= rounds_run(stats[kStatMaxCount])) return;  // every bucket already is a single item
+  u32* next_chunk = stats + kStatNextChunk + round;
+  const u32 total = choff[K];
+  // A wavefront takes GW consecutive chunks at a time: first the run of its own index, then runs drawn
+  // from a counter (zero at launch) behind those, until the end is passed.
+  const u32 nwaves = (u32)((gridDim.x * blockDim.x) / WAVE);
+  u32 q0 = (u32)((blockIdx.x * blockDim.x + threadIdx.x) / WAVE) * (u32)GW;
+  for (;; ) {
+    if (q0 >= total) break;
+    const u32 q = q0 + (u32)(lane / T);
     const bool active = q < total;
-    const u32 qq = active ? (u32)q : 0u;
+    const u32 qq = active ? q : 0u;
     // the key with choff[key] <= q < choff[key + 1]
     size_t lo = 0, hi = K;
     while (hi - lo > 1) {
@@ -182,12 +228,27 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u
     u32 begin = 0, len = 0;
     if (active && nc != 0u) {
       begin = (u32)(((u64)n * cc) / nc);
-      len = (u32)(((u64)n * (cc + 1u)) / nc) - begin;
+      len = (u32)(((u64)n * (cc + 1u)) / nc) - begin;  // at most kChunk
     }
     const size_t start = (size_t)off[lo] + begin;
+    // first round: the chunk's row indices, spread over the lanes of the group
+    u32 idx[IDX];
+    if (FIRST) {
+#pragma unroll
+      for (int r = 0; r < IDX; ++r) {
+        const u32 e = (u32)(r * T + g.k);
+        idx[r] = e < len ? sorted[start + e] : 0u;
+      }
+    }
     auto item = [&](u32 e) -> const u32* {
-      if (e >= len) return M.r1;
-      return in + (FIRST ? (size_t)sorted[start + e] : start + e) * (size_t)NL;
+      size_t at = start + e;
+      if (FIRST) {
+        u32 v = idx[0];
+#pragma unroll
+        for (int r = 1; r < IDX; ++r) v = ((int)(e / T) == r) ? idx[r] : v;
+        at = g.bcast(v, (int)(e % T));
+      }
+      return e < len ? in + at * (size_t)NL : M.r1;
     };
     u32 acc[LPT];
     load_limbs<LPT, T>(acc, item(0), g);
@@ -200,22 +261,30 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u
       montmul_mem<LPT, T>(acc, acc, item(e), mod.n, mod.n0inv, g);
       keep_live(touch);
     }
-    if (active) store_limbs<LPT, T>(out + q * (size_t)NL, acc, g);
+    if (active) store_limbs<LPT, T>(out + (size_t)q * NL, acc, g);
+    u32 drawn = 0;
+    if (lane == 0) drawn = atomicAdd(next_chunk, (u32)GW);
+    q0 = nwaves * (u32)GW + (u32)__builtin_amdgcn_ds_bpermute(0, (int)drawn);
   }
 }
 
 // Sub-products of one (position, column, sign): item g < 16: prod_l B[32 g + l]; item 16 + l: prod_h B[32 h + l].
-// B[k] is the single item left of key k after the last round, at index off[k] (one when the bucket is empty:
-// cnt[k] = 0).
+// B[k] is the single item left of key k after the last round that ran (one when the bucket is empty,
+// cnt[k] = 0): item offs_r[k] of that round's output arena, offs_r the offsets of the round after it.
 template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* __restrict__ B,
-                                                          const u32* __restrict__ cnt, const u32* __restrict__ off,
-                                                          size_t combos, u32* __restrict__ G) {
+__global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* __restrict__ arena0,
+                                                          const u32* __restrict__ arena1,
+                                                          const u32* __restrict__ cnt, const u32* __restrict__ offs,
+                                                          size_t K, const u32* __restrict__ stats, size_t combos,
+                                                          u32* __restrict__ G) {
   constexpr int NL = LPT * T;
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
+  const int ran = rounds_run(stats[kStatMaxCount]);
+  const u32* B = ((ran - 1) & 1) ? arena1 : arena0;
+  const u32* off = offs + (size_t)ran * (K + 1);
   const size_t count = combos * kSubProducts;
   for (size_t base = bt.first(); base < count; base += bt.stride()) {
     const size_t it = base + bt.gib;
@@ -226,15 +295,22 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* _
     const size_t key0 = combo * kMags + (is_hi ? (size_t)sub * kLoCount : (size_t)(sub - kHiCount));
     const size_t stride = is_hi ? 1 : kLoCount;
     const int n = active ? (is_hi ? kLoCount : kHiCount) : 0;
+    // factor e of this item, or null when its bucket is empty or the item is shorter
+    auto locate = [&](int e) -> const u32* {
+      const size_t key = key0 + (size_t)e * stride;
+      return (e < n && cnt[key] != 0u) ? B + (size_t)off[key] * NL : nullptr;
+    };
     u32 acc[LPT];
     load_limbs<LPT, T>(acc, M.r1, g);
+    const u32* next = locate(0);
 #pragma unroll 1
     for (int e = 0; e < kLoCount; ++e) {
-      const size_t key = key0 + (size_t)e * stride;
-      const bool have = e < n && cnt[key] != 0u;
-      if (!wave_any(have)) continue;
-      const u32* src = have ? B + (size_t)off[key] * NL : M.r1;
-      montmul_mem<LPT, T>(acc, acc, src, mod.n, mod.n0inv, g);
+      // the next factor is located and touched while this one is multiplied
+      const u32* cur = next;
+      next = (e + 1 < kLoCount) ? locate(e + 1) : nullptr;
+      const u32 touch = (next ? next : M.r1)[g.k * LPT];
+      if (wave_any(cur != nullptr)) montmul_mem<LPT, T>(acc, acc, cur ? cur : M.r1, mod.n, mod.n0inv, g);
+      keep_live(touch);
     }
     if (active) store_limbs<LPT, T>(G + it * (size_t)NL, acc, g);
   }
@@ -321,13 +397,13 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_fold2(ModRef M, const u32*
 // P[j][sign] = prod_s (R_hi[s]^32 R_lo[s])^(1024^s), top position first.
 template <int LPT, int T>
 __global__ __launch_bounds__(kBlockThreads) void k_bk_horner(ModRef M, const u32* __restrict__ R, size_t cols,
-                                                             u32* __restrict__ P, const u32* __restrict__ maxmag) {
+                                                             u32* __restrict__ P, const u32* __restrict__ stats) {
   constexpr int NL = LPT * T;
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
-  const int npos = digit_positions(*maxmag);
+  const int npos = digit_positions(stats[kStatMaxMag]);
   const size_t count = cols * 2;
   for (size_t base = bt.first(); base < count; base += bt.stride()) {
     const size_t it = base + bt.gib;
@@ -379,7 +455,7 @@ XtdBucketPlan xtd_bucket_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
   if (p2 > p1) p2 = p1;
   const size_t combos = cols * kMaxPos * 2;
   size_t w = 0;
-  p.off_cnt = w;     w += 2 * p.keys;  // row counts, scatter cursors
+  p.off_cnt = w;     w += kStatWords + 2 * p.keys;  // statistics and chunk counters, row counts, scatter cursors
   p.off_totals = w;  w += (size_t)(p.rounds + 1) * p.scan_blocks;
   p.off_offs = w;    w += (size_t)(p.rounds + 1) * (p.keys + 1);
   p.off_sorted = w;  w += terms;
@@ -394,28 +470,29 @@ XtdBucketPlan xtd_bucket_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
 }
 
 int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, size_t rows, size_t cols,
-                uint32_t* ws, const uint32_t* d_maxmag, uint32_t* d_P, hipStream_t st) {
+                uint32_t* ws, uint32_t* d_P, hipStream_t st) {
   const ModHost& m = ctx->N;
   const XtdBucketPlan p = xtd_bucket_plan(ctx, rows, cols);
-  if (p.rounds + 1 > kMaxComp) return HAFLO_EINVAL;
+  if (p.rounds + 1 > kMaxComp || kStatNextChunk + p.rounds > kStatWords) return HAFLO_EINVAL;
   const size_t K = p.keys;
-  u32* cnt = ws + p.off_cnt;
+  u32* stats = ws + p.off_cnt;
+  u32* cnt = stats + kStatWords;
   u32* cursor = cnt + K;
   u32* totals = ws + p.off_totals;
   // offs(0) = positions in the sorted row array; offs(r + 1) = chunk offsets of round r = item offsets of round r + 1
   auto offs = [&](int idx) { return ws + p.off_offs + (size_t)idx * (K + 1); };
   u32* sorted = ws + p.off_sorted;
   const LaunchShape flat = launch_shape(ctx, rows * cols, 1, 8);
-  const LaunchShape fill = launch_shape(ctx, 2 * K, 1, 8);
+  const LaunchShape fill = launch_shape(ctx, kStatWords + 2 * K, 1, 8);
   LaunchShape scan;
   scan.blocks = (int)p.scan_blocks;
   scan.threads = kScanThreads;
   scan.gpb = kScanThreads;
-  HAFLO_LAUNCH(k_bk_zero, fill, st, cnt, 2 * K);
-  HAFLO_LAUNCH((k_bk_terms<false>), flat, st, d_X, rows, cols, cnt, (const u32*)nullptr, (u32*)nullptr, d_maxmag);
-  HAFLO_LAUNCH(k_bk_scan_totals, scan, st, (const u32*)cnt, K, p.rounds + 1, totals);
+  HAFLO_LAUNCH(k_bk_zero, fill, st, stats, kStatWords + 2 * K);
+  HAFLO_LAUNCH((k_bk_terms<false>), flat, st, d_X, rows, cols, cnt, (const u32*)nullptr, (u32*)nullptr, stats);
+  HAFLO_LAUNCH(k_bk_scan_totals, scan, st, (const u32*)cnt, K, p.rounds + 1, totals, stats);
   HAFLO_LAUNCH(k_bk_scan_final, scan, st, (const u32*)cnt, K, p.rounds + 1, (const u32*)totals, offs(0));
-  HAFLO_LAUNCH((k_bk_terms<true>), flat, st, d_X, rows, cols, cursor, (const u32*)offs(0), sorted, d_maxmag);
+  HAFLO_LAUNCH((k_bk_terms<true>), flat, st, d_X, rows, cols, cursor, (const u32*)offs(0), sorted, stats);
   const u32* items = d_c;
   for (int r = 0; r < p.rounds; ++r) {
     // upper bound of the chunks of this round: one lane group each, capped by the grid-stride loop
@@ -426,13 +503,13 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
     if (r == 0) {
 #define CALL(LPT, T)                                                                                       \
   HAFLO_LAUNCH((k_bk_round<LPT, T, true>), sh, st, m.ref(), items, (const u32*)sorted, (const u32*)cnt,  \
-               (const u32*)offs(0), (const u32*)offs(1), K, 0, out)
+               (const u32*)offs(0), (const u32*)offs(1), K, 0, stats, out)
       HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
     } else {
 #define CALL(LPT, T)                                                                                        \
   HAFLO_LAUNCH((k_bk_round<LPT, T, false>), sh, st, m.ref(), items, (const u32*)nullptr, (const u32*)cnt, \
-               (const u32*)offs(r), (const u32*)offs(r + 1), K, r, out)
+               (const u32*)offs(r), (const u32*)offs(r + 1), K, r, stats, out)
       HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
     }
@@ -446,8 +523,9 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
     // half of the items belong to unused digit positions and leave at once
     const bool wide = haflo::few_groups(ctx, combos * kSubProducts, 64);
     const LaunchShape sh = launch_shape(ctx, combos * kSubProducts, wide ? haflo_wide_lanes(m) : m.t, 8);
-#define CALL(LPT, T) \
-  HAFLO_LAUNCH((k_bk_sub<LPT, T>), sh, st, m.ref(), items, (const u32*)cnt, (const u32*)offs(p.rounds), combos, G)
+#define CALL(LPT, T)                                                                                    \
+  HAFLO_LAUNCH((k_bk_sub<LPT, T>), sh, st, m.ref(), (const u32*)(ws + p.off_arena[0]),                 \
+               (const u32*)(ws + p.off_arena[1]), (const u32*)cnt, (const u32*)offs(0), K, (const u32*)stats, combos, G)
     if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
   }
@@ -468,7 +546,7 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
   {
     const bool wide = haflo::few_groups(ctx, cols * 2);
     const LaunchShape sh = launch_shape(ctx, cols * 2, wide ? haflo_wide_lanes(m) : m.t, 8);
-#define CALL(LPT, T) HAFLO_LAUNCH((k_bk_horner<LPT, T>), sh, st, m.ref(), (const u32*)R, cols, d_P, d_maxmag)
+#define CALL(LPT, T) HAFLO_LAUNCH((k_bk_horner<LPT, T>), sh, st, m.ref(), (const u32*)R, cols, d_P, (const u32*)stats)
     if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
   }

@@ -694,13 +694,14 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
   const size_t need = haflo_workspace_bytes(ctx, orientation == 0 ? HAFLO_OP_MATVEC_XT_D : HAFLO_OP_MATVEC_X_W, rows, cols);
   if (!d_workspace || workspace_bytes < need) return HAFLO_EINVAL;
   u32* ws = (u32*)d_workspace;
-  int rc = launch_maxmag(ctx, d_X, rows * cols, ws, st);
+  const bool buckets = orientation == 0 && use_buckets(rows, cols);
+  int rc = buckets ? HAFLO_OK : launch_maxmag(ctx, d_X, rows * cols, ws, st);
   if (rc != HAFLO_OK) return rc;
   const int nbatch = inverse_batches(ctx);
-  if (orientation == 0 && use_buckets(rows, cols)) {
+  if (buckets) {
     const XtdBucketLayout l = xtd_bucket_layout(ctx, rows, cols);
     u32* P = ws + l.off_P;
-    rc = xtd_buckets(ctx, (const u32*)d_c, d_X, rows, cols, ws + l.off_ws, ws, P, st);
+    rc = xtd_buckets(ctx, (const u32*)d_c, d_X, rows, cols, ws + l.off_ws, P, st);
     if (rc != HAFLO_OK) return rc;
     const bool wide = haflo::few_groups(ctx, cols);
     const LaunchShape sh = launch_shape(ctx, cols, wide ? haflo_wide_lanes(m) : m.t, 8);
