@@ -18,10 +18,11 @@ using namespace haflo::dev;
 
 namespace {
 
-// Orientation 1: unsigned 4-bit digits of |x|, positional tables.
-constexpr int kWin = 4;                    // window width of the exponent digits
-constexpr int kWinEntries = 1 << kWin;     // table entries per base (entry 0 = 1)
+// Orientation 1: unsigned 8-bit digits of |x|, positional tables.
+constexpr int kWin = 8;                    // window width of the exponent digits
+constexpr int kWinEntries = 1 << kWin;     // table entries per base and position (entry 0 unused)
 constexpr int kMaxPos = (32 + kWin - 1) / kWin;  // digit positions of a 32-bit magnitude
+constexpr int kWinLow = 16;                // digit = kWinLow * hi + lo in the table construction
 
 // Orientation 0: signed 5-bit digits. |x| + c, c = 16 (32^S - 1) / 31, is read in base 32 and
 // each digit e is taken as d = e - 16 in [-16, 15], so |x| = sum d_s 32^s: the table holds only
@@ -251,7 +252,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_invert(ModRef M, ModRef Mn, c
 
 // largest |x| in the matrix (atomicMax into a zeroed word)
 __global__ __launch_bounds__(kBlockThreads) void k_zero_word(u32* p) {
-  if (blockIdx.x == 0 && threadIdx.x == 0) *p = 0u;
+  if (blockIdx.x == 0 && threadIdx.x < 2) p[threadIdx.x] = 0u;  // the largest |x| and a work counter
 }
 __global__ __launch_bounds__(kBlockThreads) void k_maxmag(const int* __restrict__ X, size_t total, u32* maxmag) {
   u32 m = 0;
@@ -432,7 +433,9 @@ __global__ __launch_bounds__(kBlockThreads) void k_xtd_finish(ModRef M, ModRef M
 // orientation 1: out[i] = prod_j c_j^X[i][j]
 // ---------------------------------------------------------------------------
 
-// positional tables: group (j, sign): T[j][sign][s][d] = b^(d 2^(w s)), b = c_j or its inverse
+// Positional tables T[j][sign][s][d] = b^(d 256^s), b = c_j or its inverse, d = 1..255, in two steps.
+// Step 1, one group per (j, sign, s): b^(256^s) by 8 s squarings, then the chains d = 1..16 and
+// d = 32, 48, .., 240. Step 2, one group per remaining entry: T[16 hi + lo] = T[16 hi] * T[lo].
 template <int LPT, int T>
 __global__ __launch_bounds__(kBlockThreads) void k_xw_tables(ModRef M, const u32* __restrict__ bases,
                                                              const u32* __restrict__ invbases, size_t cols,
@@ -444,40 +447,73 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_tables(ModRef M, const u32
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
   const int npos = (bit_length(*maxmag) + kWin - 1) / kWin;
-  const size_t count = cols * 2;
+  const size_t count = cols * 2 * (size_t)npos;
   for (size_t base = bt.first(); base < count; base += bt.stride()) {
-    size_t item = base + bt.gib;
-    bool active = item < count;
-    size_t j = active ? item >> 1 : 0;
+    const size_t it = base + bt.gib;
+    const bool active = it < count;
+    const size_t item = active ? it / (size_t)npos : 0;  // j * 2 + sign
+    const int s = active ? (int)(it - item * (size_t)npos) : 0;
     const u32* src = (item & 1) ? invbases : bases;
-    u32 b[LPT], cur[LPT], one[LPT], half[LPT];
-    load_limbs<LPT, T>(b, src + j * (size_t)NL, g);
-    load_limbs<LPT, T>(one, M.r1, g);
+    u32 b[LPT], cur[LPT], step[LPT];
+    load_limbs<LPT, T>(b, src + (item >> 1) * (size_t)NL, g);
 #pragma unroll 1
-    for (int s = 0; s < npos; ++s) {
-      u32* tb = tables + ((item * (size_t)kMaxPos + (size_t)s) * (size_t)kWinEntries) * NL;
-      if (active) {
-        store_limbs<LPT, T>(tb, one, g);
-        store_limbs<LPT, T>(tb + NL, b, g);
-      }
+    for (int i = 0; wave_any(i < kWin * s); ++i) {
+      u32 t[LPT];
+      montmul<LPT, T>(t, b, b, mod.n, mod.n0inv, g);
+      if (i < kWin * s) {
 #pragma unroll
-      for (int jj = 0; jj < LPT; ++jj) cur[jj] = b[jj];
+        for (int jj = 0; jj < LPT; ++jj) b[jj] = t[jj];
+      }
+    }
+    u32* tb = tables + ((item * (size_t)kMaxPos + (size_t)s) * (size_t)kWinEntries) * NL;
+    if (active) store_limbs<LPT, T>(tb + NL, b, g);
+#pragma unroll
+    for (int jj = 0; jj < LPT; ++jj) cur[jj] = b[jj];
 #pragma unroll 1
-      for (int dgt = 2; dgt < kWinEntries; ++dgt) {
-        montmul<LPT, T>(cur, cur, b, mod.n, mod.n0inv, g);
-        if (active) store_limbs<LPT, T>(tb + (size_t)dgt * NL, cur, g);
-        if (dgt == kWinEntries / 2) {
+    for (int dgt = 2; dgt <= kWinLow; ++dgt) {
+      montmul<LPT, T>(cur, cur, b, mod.n, mod.n0inv, g);
+      if (active) store_limbs<LPT, T>(tb + (size_t)dgt * NL, cur, g);
+    }
 #pragma unroll
-          for (int jj = 0; jj < LPT; ++jj) half[jj] = cur[jj];
-        }
-      }
-      montmul<LPT, T>(b, half, half, mod.n, mod.n0inv, g);  // b^(2^w) for the next position
+    for (int jj = 0; jj < LPT; ++jj) step[jj] = cur[jj];  // b^16
+#pragma unroll 1
+    for (int dgt = 2 * kWinLow; dgt < kWinEntries; dgt += kWinLow) {
+      montmul<LPT, T>(cur, cur, step, mod.n, mod.n0inv, g);
+      if (active) store_limbs<LPT, T>(tb + (size_t)dgt * NL, cur, g);
     }
   }
 }
 
-// Per row: the list of table entries its product consists of, one per non-zero 4-bit digit
-// of every non-zero |X[row][c]|: entry index ((c*2 + sign)*kMaxPos + s)*16 + digit, in units of
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_xw_tables_fill(ModRef M, size_t cols, u32* __restrict__ tables,
+                                                                  const u32* __restrict__ maxmag) {
+  constexpr int NL = LPT * T;
+  constexpr int kHi = kWinEntries / kWinLow - 1, kLo = kWinLow - 1;  // 15 x 15 entries per table
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  const int npos = (bit_length(*maxmag) + kWin - 1) / kWin;
+  const size_t count = cols * 2 * (size_t)npos * (size_t)(kHi * kLo);
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    const size_t it = base + bt.gib;
+    const bool active = it < count;
+    const size_t tab = active ? it / (size_t)(kHi * kLo) : 0;  // (j * 2 + sign) * npos + s
+    const int e = active ? (int)(it - tab * (size_t)(kHi * kLo)) : 0;
+    const int hi = e / kLo + 1, lo = e % kLo + 1;
+    const size_t item = tab / (size_t)(npos ? npos : 1);
+    const int s = (int)(tab - item * (size_t)(npos ? npos : 1));
+    u32* tb = tables + ((item * (size_t)kMaxPos + (size_t)s) * (size_t)kWinEntries) * NL;
+    u32 a[LPT];
+    if (active) load_limbs<LPT, T>(a, tb + (size_t)(hi * kWinLow) * NL, g);
+    else zero_limbs<LPT>(a);
+    montmul_mem<LPT, T>(a, a, active ? tb + (size_t)lo * NL : M.r1, mod.n, mod.n0inv, g);
+    if (active) store_limbs<LPT, T>(tb + (size_t)(hi * kWinLow + lo) * NL, a, g);
+  }
+}
+
+// Per row: the list of table entries its product consists of, one per non-zero 8-bit digit
+// of every non-zero |X[row][c]|: entry index ((c*2 + sign)*kMaxPos + s)*256 + digit, in units of
 // one table entry. One wave per row; lists: rows * cols * kMaxPos words, counts: rows.
 __global__ __launch_bounds__(kBlockThreads) void k_xw_lists(const int* __restrict__ X, size_t rows, size_t cols,
                                                             u32* __restrict__ lists, u32* __restrict__ counts,
@@ -508,32 +544,44 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_lists(const int* __restric
   }
 }
 
-// one group per output row: the product of the listed table entries
+// one group per output row: the product of the listed table entries. A wavefront takes the rows of its
+// own index first, then runs of rows drawn from a counter (zero at launch), so that rows with long
+// lists do not leave the rest of the chip waiting.
 template <int LPT, int T>
 __global__ __launch_bounds__(kBlockThreads, 3) void k_xw_main(ModRef M, size_t rows, size_t list_stride,
                                                            const u32* __restrict__ lists,
                                                            const u32* __restrict__ counts,
-                                                           const u32* __restrict__ tables, u32* __restrict__ out) {
+                                                           const u32* __restrict__ tables, u32* __restrict__ next_row,
+                                                           u32* __restrict__ out) {
   constexpr int NL = LPT * T;
+  constexpr int GW = WAVE / T;
   Grp<T> g;
-  Batch<T> bt;
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
-  for (size_t base = bt.first(); base < rows; base += bt.stride()) {
-    size_t row = base + bt.gib;
-    bool active = row < rows;
-    u32 cnt = active ? counts[row] : 0u;
+  const int lane = (int)(threadIdx.x & (WAVE - 1));
+  const size_t nwaves = ((size_t)gridDim.x * blockDim.x) / WAVE;
+  size_t r0 = (((size_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE) * GW;
+  while (r0 < rows) {
+    const size_t row = r0 + (size_t)(lane / T);
+    const bool active = row < rows;
+    const u32 cnt = active ? counts[row] : 0u;
     const u32* mine = lists + (active ? row : 0) * list_stride;
+    auto entry = [&](u32 e) -> const u32* { return (e < cnt) ? tables + (size_t)mine[e] * NL : M.r1; };
     u32 acc[LPT];
-    load_limbs<LPT, T>(acc, M.r1, g);
+    load_limbs<LPT, T>(acc, entry(0), g);
 #pragma unroll 1
-    for (u32 e = 0; wave_any(e < cnt); ++e) {
-      // a group that has run out of entries multiplies by one and stays in step with its wave
-      const u32* entry = (e < cnt) ? tables + (size_t)mine[e] * NL : M.r1;
-      montmul_mem<LPT, T>(acc, acc, entry, mod.n, mod.n0inv, g);
+    for (u32 e = 1; wave_any(e < cnt); ++e) {
+      // the next entry is looked up and touched while this one is multiplied; a group that has run out
+      // of entries multiplies by one and stays in step with its wave
+      const u32 touch = entry(e + 1)[g.k * LPT];
+      montmul_mem<LPT, T>(acc, acc, entry(e), mod.n, mod.n0inv, g);
+      keep_live(touch);
     }
     canonicalise<LPT, T>(acc, mod.n, g);
     if (active) store_limbs<LPT, T>(out + row * (size_t)NL, acc, g);
+    u32 drawn = 0;
+    if (lane == 0) drawn = atomicAdd(next_row, (u32)GW);
+    r0 = nwaves * GW + (size_t)(u32)__builtin_amdgcn_ds_bpermute(0, (int)drawn);
   }
 }
 
@@ -749,21 +797,31 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
     if (cols) {
       rc = invert_batch(ctx, (const u32*)d_c, inv, cols, st);
       if (rc != HAFLO_OK) return rc;
-      const LaunchShape sh = launch_shape(ctx, cols * 2, m.t, 8);
+      {
+        const size_t groups = cols * 2 * kMaxPos;
+        const bool wide = haflo::few_groups(ctx, groups, 32);
+        const LaunchShape sh = launch_shape(ctx, groups, wide ? haflo_wide_lanes(m) : m.t, 8);
 #define CALL(LPT, T) \
   HAFLO_LAUNCH((k_xw_tables<LPT, T>), sh, st, m.ref(), (const u32*)d_c, (const u32*)inv, cols, tables, (const u32*)ws)
-      HAFLO_DISPATCH_GEOMETRY(m, CALL);
+        if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
+      }
+      {
+        const LaunchShape sh = launch_shape(ctx, cols * 2 * kMaxPos * 225, m.t, 8);
+#define CALL(LPT, T) HAFLO_LAUNCH((k_xw_tables_fill<LPT, T>), sh, st, m.ref(), cols, tables, (const u32*)ws)
+        HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+      }
     }
     {
       const LaunchShape sh = launch_shape(ctx, rows, 64, 8);
       HAFLO_LAUNCH(k_xw_lists, sh, st, d_X, rows, cols, lists, cnt, (const u32*)ws);
     }
     {
-      const LaunchShape sh = launch_shape(ctx, rows, m.t, 8);
+      const LaunchShape sh = launch_shape(ctx, rows, m.t, 3);
 #define CALL(LPT, T)                                                                                          \
   HAFLO_LAUNCH((k_xw_main<LPT, T>), sh, st, m.ref(), rows, cols * (size_t)kMaxPos, (const u32*)lists,         \
-               (const u32*)cnt, (const u32*)tables, (u32*)d_out)
+               (const u32*)cnt, (const u32*)tables, ws + 1, (u32*)d_out)
       HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
     }
