@@ -51,6 +51,17 @@ struct Grp {
     if (T == 1) return v;
     return (u32)__builtin_amdgcn_ds_bpermute(base_addr + (src_k << 2), (int)v);
   }
+  // value of `v` held by lane 0 of this group, through DPP moves (quad broadcast, then row shifts by
+  // 4 and 8 lanes into the upper banks): a few VALU cycles instead of a round trip through the LDS
+  // crossbar, which matters where the result is needed at once.
+  __device__ __forceinline__ u32 bcast0(u32 v) const {
+    if (T == 1) return v;
+    int x = (int)v;
+    x = __builtin_amdgcn_update_dpp(x, x, T == 2 ? 0xA0 /* quad_perm:[0,0,2,2] */ : 0x00 /* [0,0,0,0] */, 0xf, 0xf, false);
+    if (T >= 8) x = __builtin_amdgcn_update_dpp(x, x, 0x114 /* row_shr:4 */, 0xf, 0xA, false);
+    if (T >= 16) x = __builtin_amdgcn_update_dpp(x, x, 0x118 /* row_shr:8 */, 0xf, 0xC, false);
+    return (u32)x;
+  }
   // v of the next-higher lane; 0 past the end of the 16-lane row. The top lane
   // of a group that is not at a row end sees lane 0 of the next group.
   __device__ __forceinline__ u32 from_upper_raw(u32 v) const {
@@ -107,20 +118,25 @@ __device__ __forceinline__ void hi_normalise(u64 (&A)[LPT], const Grp<T>& g, u32
 // Where the word-serial operand b of a product comes from: the lanes' own
 // registers (limb i sits on lane i / LPT and is broadcast with ds_bpermute), or
 // an NL-limb array in memory that every lane of the group reads directly.
+// limb (o, rr): limb rr of lane o. kAhead = how many steps before its use a limb is requested, so that
+// the exchange is complete by then (rr then runs on into lane o + 1); 0 = fetched in its own step.
 template <int LPT, int T>
 struct BRegs {
   const u32 (&b)[LPT];
-  __device__ __forceinline__ u32 limb(int o, int r, int src_addr) const {
-    (void)o;
-    return (T == 1) ? b[r] : (u32)__builtin_amdgcn_ds_bpermute(src_addr, (int)b[r]);
+  static constexpr int kAhead = 1;
+  __device__ __forceinline__ u32 limb(int o, int rr, const Grp<T>& g) const {
+    if (T == 1) return b[rr % LPT];
+    // past the last limb this reads a lane of the next group (or wraps); that value is never used
+    return (u32)__builtin_amdgcn_ds_bpermute(g.base_addr + ((o + rr / LPT) << 2), (int)b[rr % LPT]);
   }
 };
 template <int LPT, int T>
 struct BMem {
   const u32* p;
-  __device__ __forceinline__ u32 limb(int o, int r, int src_addr) const {
-    (void)src_addr;
-    return p[o * LPT + r];
+  static constexpr int kAhead = 0;  // plain loads, which the compiler batches per lane by itself
+  __device__ __forceinline__ u32 limb(int o, int rr, const Grp<T>& g) const {
+    (void)g;
+    return p[o * LPT + rr];
   }
 };
 
@@ -141,15 +157,28 @@ __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT
   u64 A[LPT];
 #pragma unroll
   for (int j = 0; j < LPT; ++j) A[j] = 0;
+  // Nothing a step waits long for: the limbs b_i were asked for kAhead steps earlier, and the quotient
+  // digit q is broadcast with DPP moves.
+  constexpr int D = BSrc::kAhead;
+  constexpr int RING = D > 0 ? D : 1;
+  static_assert(LPT % RING == 0, "ring size");
+  u32 ring[RING];
+#pragma unroll
+  for (int d = 0; d < D; ++d) ring[d] = bsrc.limb(0, d, g);
 #pragma unroll 1
   for (int o = 0; o < T; ++o) {
-    const int src = g.base_addr + (o << 2);
 #pragma unroll
     for (int r = 0; r < LPT; ++r) {
-      u32 bi = bsrc.limb(o, r, src);
+      u32 bi;
+      if (D > 0) {
+        bi = ring[r % RING];
+        ring[r % RING] = bsrc.limb(o, r + D, g);
+      } else {
+        bi = bsrc.limb(o, r, g);
+      }
       A[0] = mad64(a[0], bi, A[0]);
       u32 qv = ((u32)A[0] * n0inv) & LIMB_MASK;
-      u32 q = g.bcast(qv, 0);
+      u32 q = g.bcast0(qv);
 #pragma unroll
       for (int j = 1; j < LPT; ++j) A[j] = mad64(a[j], bi, A[j]);
       u64 t0 = mad64(q, n[0], A[0]);

@@ -79,10 +79,12 @@ uint32_t bpermute(int byte_addr, uint32_t v) {
   return t[((unsigned)byte_addr >> 2) & (kWave - 1)];
 }
 
-uint32_t dpp(uint32_t old, uint32_t src, int ctrl, bool bound_ctrl) {
+uint32_t dpp(uint32_t old, uint32_t src, int ctrl, int row_mask, int bank_mask, bool bound_ctrl) {
   int lane = cur->lane;
   const uint32_t* t = exchange(src);
   int row = lane & ~15, pos = lane & 15;
+  // lanes outside the enabled rows and banks keep `old`
+  if (!((row_mask >> (lane >> 4)) & 1) || !((bank_mask >> (pos >> 2)) & 1)) return old;
   int from = -1;
   if (ctrl >= 0x101 && ctrl <= 0x10f) {  // row_shl:n - lane i reads lane i+n
     int s = pos + (ctrl - 0x100);

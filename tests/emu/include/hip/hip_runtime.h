@@ -57,7 +57,7 @@ struct LaneState {
 LaneState* current();
 void launch(dim3 grid, dim3 block, const std::function<void()>& body);
 uint32_t bpermute(int byte_addr, uint32_t v);
-uint32_t dpp(uint32_t old, uint32_t src, int ctrl, bool bound_ctrl);
+uint32_t dpp(uint32_t old, uint32_t src, int ctrl, int row_mask, int bank_mask, bool bound_ctrl);
 uint64_t ballot(bool p);
 void barrier();
 void* dev_alloc(size_t bytes);
@@ -75,10 +75,11 @@ void dev_free(void* p);
 static inline int __builtin_amdgcn_ds_bpermute(int addr, int v) { return (int)hipemu::bpermute(addr, (uint32_t)v); }
 static inline int __builtin_amdgcn_update_dpp(int old, int src, int ctrl, int row_mask, int bank_mask,
                                               bool bound_ctrl) {
-  if (row_mask != 0xf || bank_mask != 0xf) abort();
-  return (int)hipemu::dpp((uint32_t)old, (uint32_t)src, ctrl, bound_ctrl);
+  return (int)hipemu::dpp((uint32_t)old, (uint32_t)src, ctrl, row_mask, bank_mask, bound_ctrl);
 }
 static inline uint64_t __builtin_amdgcn_ballot_w64(bool p) { return hipemu::ballot(p); }
+static inline void __builtin_amdgcn_sched_barrier(int) {}
+static inline void __builtin_amdgcn_sched_group_barrier(int, int, int) {}
 static inline void __syncthreads() { hipemu::barrier(); }
 static inline uint32_t atomicOr(uint32_t* p, uint32_t v) {
   uint32_t o = *p;
