@@ -33,6 +33,7 @@ def main():
     ap.add_argument("--instances", type=int, default=100000)
     ap.add_argument("--features", type=int, default=32)
     ap.add_argument("--reps", type=int, default=3)
+    ap.add_argument("--tall", action="store_true", help="also time X^T[[d]] on an instances x features matrix")
     ap.add_argument("--json", default=None)
     args = ap.parse_args()
 
@@ -94,6 +95,14 @@ def main():
     res["addition"] = N / t
     t, _ = timed(lambda: api.haflo_cipher_matvec(pub, 0, c[:rows].contiguous(), X))
     res["matrix multiplication"] = rows * F / t
+    if args.tall:
+        # a tall matrix (the shape of the encrypted gradient of a large mini-batch): the bucket method
+        tall = api.haflo_encode_exponents_f32(dev(synth.normal_f32((N, F), 1.0, seed + 3)), 16)
+        t, _ = timed(lambda: api.haflo_cipher_matvec(pub, 0, c, tall))
+        res["matrix multiplication (%d x %d)" % (N, F)] = N * F / t
+    label = dev(np.where(rng.random(N) < 0.5, -1.0, 1.0).astype(np.float32))
+    t, _ = timed(lambda: api.haflo_fore_gradient(pub, c, v, label, r, 24))
+    res["fore gradient (fused)"] = N / t
     t, _ = timed(lambda: api.haflo_cipher_sum(pub, c))
     res["summation"] = N / t
 
