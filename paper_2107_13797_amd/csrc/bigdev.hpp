@@ -147,12 +147,10 @@ struct BMem {
 // with q chosen so the lowest column vanishes mod 2^29, then drops that column;
 // every lane hands the low 29 bits of its lowest column to the lane below and
 // keeps the rest as a carry, so no lane is special-cased.
-// NORM = number of steps between hi_normalise passes (<= 31).
 template <int LPT, int T, class BSrc>
 __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT], const BSrc& bsrc,
                                              const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
-  constexpr int NORM = (LPT <= 31) ? LPT : (LPT / 2);
-  static_assert(NORM <= 31 && LPT % NORM == 0, "normalisation interval");
+  static_assert(LPT <= 18, "a column must not collect more than 36 products");
   const u32 eight = opaque_eight();
   u64 A[LPT];
 #pragma unroll
@@ -193,9 +191,13 @@ __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT
       } else {
         A[0] = (u64)recv + carry;
       }
-      if ((r + 1) % NORM == 0) hi_normalise<LPT, T>(A, g, eight);
     }
   }
+  // A column register lives LPT steps in a lane (it enters at the top as the 29 bits handed over by
+  // the lane above and leaves at the bottom) and takes two products per step: at most 2 * 18 products
+  // below 2^58.01 plus one carry below 2^36, which fits 64 bits without intermediate carry handling.
+  // One pass before the compression keeps the limbs and the carry to the next lane small.
+  hi_normalise<LPT, T>(A, g, eight);
   // Compress the columns to 32-bit limbs: ripple inside the lane, then hand the
   // lane's carry to the lane above (which absorbs it lazily in its limb 0).
   u64 c = 0;
@@ -332,9 +334,13 @@ __device__ __forceinline__ void mul_plain(u32 (&lo)[LPT], u32 (&hi)[LPT], const 
       } else {
         A[0] = (u64)recv + carry;
       }
-      if ((r + 1) % NORM == 0) hi_normalise<LPT, T>(A, g, eight);
     }
   }
+  // A column register lives LPT steps in a lane (it enters at the top as the 29 bits handed over by
+  // the lane above and leaves at the bottom) and takes two products per step: at most 2 * 18 products
+  // below 2^58.01 plus one carry below 2^36, which fits 64 bits without intermediate carry handling.
+  // One pass before the compression keeps the limbs and the carry to the next lane small.
+  hi_normalise<LPT, T>(A, g, eight);
   if (WANT_HI) {
     u64 c = 0;
 #pragma unroll
