@@ -68,7 +68,8 @@ enum haflo_op {
   HAFLO_OP_SCALAR_MUL = 3,
   HAFLO_OP_MATVEC_XT_D = 4, /* orientation 0 */
   HAFLO_OP_MATVEC_X_W = 5,  /* orientation 1 */
-  HAFLO_OP_FORE_GRADIENT = 6
+  HAFLO_OP_FORE_GRADIENT = 6,
+  HAFLO_OP_TAYLOR_LOSS = 7
 };
 
 /* Text for an error code; never NULL. */
@@ -231,6 +232,28 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
 int haflo_fore_gradient(const haflo_ctx* ctx, const void* d_c_host, const float* d_logits_guest,
                         const float* d_label, const uint32_t* d_r, uint32_t scale_bits, void* d_out,
                         uint32_t* d_status, size_t count, void* d_workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Encrypted second-order Taylor loss (paper section 2.1, the approximated loss
+ * l_H): sum_i ( -1/2 y_i u_i + 1/8 u_i^2 ) with u_i = u_host,i + u_guest,i, as
+ * one ciphertext; the constant log 2 per instance and the factor 1/h are
+ * public and left to the caller. With q(v) = rint(v * 2^scale_bits),
+ * c_u[i] an encryption of m1_i = q(u_host,i) and c_u2[i] of m2_i = m1_i^2,
+ *   out = prod_i c_u2[i] * prod_i c_u[i]^(k_i) * E(P; r)  mod n^2,
+ *   k_i = 2 q(u_guest,i) - 4 q(y_i),
+ *   P   = sum_i q(u_guest,i) (q(u_guest,i) - 4 q(y_i))  mod n,
+ * which encrypts sum_i ( m2_i + k_i m1_i ) + P = 8 * 2^(2 scale_bits) times
+ * the sum above: the result is read at scale 2^(2 scale_bits + 3).
+ * d_c_u, d_c_u2: count internal elements; d_u_guest, d_label: device
+ * float[count]; d_r: device Lp uint32 (one r); d_out: one internal element;
+ * d_status: device uint32 (one word) or NULL, OR-ed with HAFLO_ST_RANGE when
+ * an element is not finite or too large (|q(u_guest)| >= 2^28 or
+ * |q(y)| >= 2^27; such an element contributes m2_i only). scale_bits <= 27,
+ * count < 2^32. Workspace: HAFLO_OP_TAYLOR_LOSS with rows = count.
+ */
+int haflo_taylor_loss(const haflo_ctx* ctx, const void* d_c_u, const void* d_c_u2, const float* d_u_guest,
+                      const float* d_label, const uint32_t* d_r, uint32_t scale_bits, void* d_out,
+                      uint32_t* d_status, size_t count, void* d_workspace, size_t workspace_bytes, void* stream);
 
 /* "Homomorphic Summation" (paper Table 1): out[0] = prod_i c[i] mod n^2 over
  * count internal elements (1 for count = 0). Workspace: the same as

@@ -270,6 +270,34 @@ def fore_gradient(pk: PublicKey, c_host: int, logit_guest: float, label: float, 
     return add(pk, c_host, encrypt(pk, q % pk.n, r)), (0 if ok else 1)
 
 
+def taylor_loss(pk: PublicKey, c_u: Sequence[int], c_u2: Sequence[int], u_guest: Sequence[float],
+                label: Sequence[float], r: int, scale_bits: int) -> Tuple[int, int]:
+    """Encrypted second-order Taylor loss of section 2.1 (the approximated l_H) without its public
+    parts (log 2 per instance, the factor 1/h):  sum_i ( -1/2 y_i u_i + 1/8 u_i^2 ),
+    u_i = u_host,i + u_guest,i.
+
+    c_u[i] encrypts m1_i = q(u_host,i), c_u2[i] encrypts m2_i = m1_i^2 (scale 2^s and 2^(2s)).
+    Multiplying the sum by 8 * 2^(2s) gives sum_i ( m2_i + k_i m1_i + p_i ) with
+    k_i = 2 q(u_guest,i) - 4 q(y_i) and p_i = q(u_guest,i) (q(u_guest,i) - 4 q(y_i)); on ciphertexts
+    that is the summation of c_u2, the product of c_u[i]^(k_i) and one encryption of sum p_i.
+
+    Returns (ciphertext, status): an element that is not finite or too large (|q(u_guest)| >= 2^28,
+    |q(y)| >= 2^27) counts with k_i = p_i = 0 and sets status 1."""
+    assert len(c_u) == len(c_u2) == len(u_guest) == len(label)
+    status = 0
+    ks, plain = [], 0
+    for ug, y in zip(u_guest, label):
+        qg, qy = quantise(ug, scale_bits), quantise(y, scale_bits)
+        if qg is None or qy is None or abs(qg) >= (1 << 28) or abs(qy) >= (1 << 27):
+            qg, qy, status = 0, 0, 1
+        ks.append(2 * qg - 4 * qy)
+        plain += qg * (qg - 4 * qy)
+    out = summation(pk, c_u2)
+    out = add(pk, out, summation(pk, (scalar_mul(pk, c, k) for c, k in zip(c_u, ks))))
+    out = add(pk, out, encrypt(pk, plain % pk.n, r))
+    return out, status
+
+
 # --------------------------------------------------------------------------
 # signed fixed point
 # --------------------------------------------------------------------------

@@ -37,10 +37,12 @@ PROTOTYPES = {
                                     c_size_t, c_void_p]),
     "haflo_fore_gradient": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_u32, c_void_p, c_void_p, c_size_t,
                                     c_void_p, c_size_t, c_void_p]),
+    "haflo_taylor_loss": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_u32, c_void_p, c_void_p,
+                                  c_size_t, c_void_p, c_size_t, c_void_p]),
     "haflo_cipher_sum": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_size_t, c_void_p]),
 }
 
-OP_ENCRYPT, OP_DECRYPT, OP_SCALAR_MUL, OP_MATVEC_XT_D, OP_MATVEC_X_W, OP_FORE_GRADIENT = 1, 2, 3, 4, 5, 6
+OP_ENCRYPT, OP_DECRYPT, OP_SCALAR_MUL, OP_MATVEC_XT_D, OP_MATVEC_X_W, OP_FORE_GRADIENT, OP_TAYLOR_LOSS = 1, 2, 3, 4, 5, 6, 7
 
 
 def bind(lib, names=None):

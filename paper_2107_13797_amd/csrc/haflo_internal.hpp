@@ -162,6 +162,8 @@ std::vector<uint32_t> to_limbs29(const Big& x, int nl);
 size_t ws_encrypt(const haflo_ctx* ctx, size_t count);
 size_t ws_scalar_mul(const haflo_ctx* ctx, size_t count);
 size_t ws_decrypt(const haflo_ctx* ctx, size_t count);
+// workspace of the Taylor-loss sequence in bytes (kernels_loss.hip)
+size_t ws_taylor_loss(const haflo_ctx* ctx, size_t count);
 
 // tables[i][d] = c_i^d for d < entries (kernels_modexp.hip)
 int power_tables(const haflo_ctx* ctx, const uint32_t* d_c, uint32_t* d_tables, int entries, size_t count,

@@ -373,6 +373,36 @@ def test_fore_gradient(env):
                                    count, w.p, nb - 1, None) == -1
 
 
+def test_taylor_loss(env):
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    lp = BITS // 32
+    rng = random.Random(41)
+    s = 20
+    for count, bad in ((9, False), (9, True), (0, False)):
+        ug = synth.normal_f32(count, 1.5, 42)
+        y = np.where(np.arange(count) % 2 == 0, 1.0, -1.0).astype(np.float32)
+        if bad:
+            ug[3], y[4] = np.nan, 200.0
+        m1 = [O.quantise(float(v), s) for v in synth.normal_f32(count, 1.5, 43)]
+        c_u = [O.encrypt(pk, m % pk.n, rng.randrange(1, pk.n)) for m in m1]
+        c_u2 = [O.encrypt(pk, m * m, rng.randrange(1, pk.n)) for m in m1]
+        r = rng.randrange(1, pk.n)
+        d_u, d_u2 = zeros(lib, (max(count, 1), nlw)), zeros(lib, (max(count, 1), nlw))
+        if count:
+            assert lib.haflo_import_cipher(ctx, words(lib, c_u, BITS // 16).p, d_u.p, None, count, None) == 0
+            assert lib.haflo_import_cipher(ctx, words(lib, c_u2, BITS // 16).p, d_u2.p, None, count, None) == 0
+        w, nb = ws(lib, ctx, _cabi.OP_TAYLOR_LOSS, count)
+        d_o, d_st = zeros(lib, (1, nlw)), zeros(lib, (1,))
+        assert lib.haflo_taylor_loss(ctx, d_u.p, d_u2.p, Dev(lib, ug).p, Dev(lib, y).p, words(lib, [r], lp).p, s,
+                                     d_o.p, d_st.p, count, w.p, nb, None) == 0
+        want, st = O.taylor_loss(pk, c_u, c_u2, [float(v) for v in ug], [float(v) for v in y], r, s)
+        assert export(lib, ctx, d_o, 1) == [want]
+        assert d_st.get().tolist() == [st] and st == (1 if bad else 0)
+    assert lib.haflo_taylor_loss(ctx, d_u.p, d_u2.p, None, None, words(lib, [r], lp).p, 28, d_o.p, None, 0, w.p, nb,
+                                 None) == -1
+
+
 def test_encode_decode(env):
     lib, ctx, sk, nlw = env
     pk = sk.public

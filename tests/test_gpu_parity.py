@@ -441,6 +441,49 @@ def test_fore_gradient_chain(api):
     assert torch.equal(aliased, out)
 
 
+def test_taylor_loss_sequence(api):
+    """Encrypted Taylor loss: ciphertext parity with the oracle on a size the oracle finishes
+    (the single-column matvec runs through the table method), and the plaintext closed form at
+    a size that takes the bucket method."""
+    bits, s = 1024, 20
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n = pk.n
+    for count, exact_cipher in ((600, True), (20000, False)):
+        uh = synth.normal_f32(count, 1.5, 81)
+        ug = synth.normal_f32(count, 1.5, 82)
+        y = np.where(np.random.default_rng(83).random(count) < 0.5, -1.0, 1.0).astype(np.float32)
+        if exact_cipher:
+            ug[7] = np.nan
+        m1 = np.rint(uh.astype(np.float64) * 2.0 ** s).astype(np.int64)
+        plain1 = api.haflo_encode_f32(ctx, to_dev(uh), s)
+        m2_words = synth.ints_to_words([int(v) * int(v) for v in m1], bits // 32)
+        r1 = random_units_words(count, bits, 84)
+        r2 = random_units_words(count, bits, 85)
+        r3 = random_units_words(1, bits, 86)
+        c_u = api.haflo_encrypt(ctx, plain1, to_dev(r1))
+        c_u2 = api.haflo_encrypt(ctx, to_dev(m2_words), to_dev(r2))
+        st = torch.zeros(1, dtype=torch.int32, device="cuda")
+        out = api.haflo_taylor_loss(ctx, c_u, c_u2, to_dev(ug), to_dev(y), to_dev(r3), s, status=st)
+        flagged = int(st.item())
+        assert flagged == (1 if exact_cipher else 0)
+        with np.errstate(invalid="ignore"):
+            qg = np.rint(np.nan_to_num(ug.astype(np.float64)) * 2.0 ** s).astype(np.int64)
+        qy = np.rint(y.astype(np.float64) * 2.0 ** s).astype(np.int64)
+        if exact_cipher:
+            qy[7] = 0
+        total = sum(int(a) * int(a) + (2 * int(b) - 4 * int(t)) * int(a) + int(b) * (int(b) - 4 * int(t))
+                    for a, b, t in zip(m1, qg, qy))
+        assert dev_to_ints(api.haflo_decrypt(ctx, out)) == [total % n]
+        if exact_cipher:
+            cu_int = dev_to_ints(api.haflo_export_cipher(ctx, c_u))
+            cu2_int = dev_to_ints(api.haflo_export_cipher(ctx, c_u2))
+            assert cu_int[:4] == OP.encrypt_many(n, [int(v) % n for v in m1[:4]], synth.words_to_ints(r1[:4]))
+            want, flag = O.taylor_loss(pk, cu_int, cu2_int, [float(v) for v in ug], [float(v) for v in y],
+                                       synth.words_to_ints(r3)[0], s)
+            assert flag == 1 and dev_to_ints(api.haflo_export_cipher(ctx, out)) == [want]
+
+
 def test_edges_encode_decode(api):
     bits = 1024
     ctx, sk = context(api, bits)

@@ -305,3 +305,32 @@ def test_fore_gradient_plaintext_closed_form():
     assert st == 1 and c == O.encrypt(pk, 0, 5)
     c, st = O.fore_gradient(pk, 1, 1.0, 2.0 ** 38, 5, s)       # 2^62 after scaling
     assert st == 1 and c == O.encrypt(pk, 0, 5)
+
+
+def test_taylor_loss_plaintext_closed_form():
+    """Section 2.1's approximated loss: decrypting the oracle's loss ciphertext and decoding at
+    scale 2^(2s+3) gives the exact integer combination and lies within the quantisation bound of
+    sum(-y u / 2 + u^2 / 8) evaluated in floating point. A wrong coefficient or sign breaks it."""
+    sk = _real_key(512)
+    pk = sk.public
+    rng = random.Random(5)
+    s, count = 20, 24
+    uh = [float(np.float32(rng.gauss(0, 1.5))) for _ in range(count)]
+    ug = [float(np.float32(rng.gauss(0, 1.5))) for _ in range(count)]
+    y = [rng.choice([-1.0, 1.0]) for _ in range(count)]
+    m1 = [O.quantise(v, s) for v in uh]
+    c_u = [O.encrypt(pk, m % pk.n, rng.randrange(1, pk.n)) for m in m1]
+    c_u2 = [O.encrypt(pk, m * m, rng.randrange(1, pk.n)) for m in m1]
+    c, st = O.taylor_loss(pk, c_u, c_u2, ug, y, rng.randrange(1, pk.n), s)
+    assert st == 0
+    q, val, dst = O.decode(pk, O.decrypt(sk, c), 2 * s + 3)
+    assert dst == 0
+    qg = [O.quantise(v, s) for v in ug]
+    qy = [O.quantise(v, s) for v in y]
+    assert q == sum((a + b) ** 2 - 4 * t * (a + b) for a, b, t in zip(m1, qg, qy))
+    want = sum(-0.5 * t * (a + b) + 0.125 * (a + b) ** 2 for a, b, t in zip(uh, ug, y))
+    # each u is off by at most 2^-s (two roundings); d/du of the term is |u/4 - y/2| <= 2 here
+    assert abs(val - want) <= count * 2.0 * 2.0 ** -s + count * 2.0 ** (-2 * s)
+    c, st = O.taylor_loss(pk, c_u[:2], c_u2[:2], [float("inf"), 0.0], [1.0, 1.0], 7, s)
+    assert st == 1
+    assert O.decrypt(sk, c) == (m1[0] ** 2 + m1[1] ** 2 - 4 * (1 << s) * m1[1]) % pk.n
