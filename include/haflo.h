@@ -208,6 +208,11 @@ int haflo_scalar_mul_i64_bcast(const haflo_ctx* ctx, const void* d_c, int64_t k,
  *     out[i] = prod_j c[j]^X[i][j] mod n^2.
  * An empty or all-zero product is an encryption-free 1. d_out may not alias
  * d_c. Workspace: HAFLO_OP_MATVEC_XT_D / HAFLO_OP_MATVEC_X_W with the shape.
+ * Orientation 0 has two implementations with identical results: per-base
+ * power tables for matrices of fewer than 4096 rows (or more than 1024
+ * columns), the bucket method above that. The environment variable
+ * HAFLO_XTD_BUCKET_MIN_ROWS, read at every call and at every workspace query,
+ * replaces the 4096 (a tuning and testing aid).
  */
 int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, const int32_t* d_X, size_t rows,
                         size_t cols, void* d_out, void* d_workspace, size_t workspace_bytes, void* stream);

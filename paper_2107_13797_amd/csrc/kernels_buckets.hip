@@ -438,8 +438,9 @@ int rounds_for(size_t rows) {
 namespace haflo {
 
 bool xtd_buckets_fit(size_t rows, size_t cols) {
-  // row indices, chunk counts and item offsets are 32-bit
-  return rows < (1ull << 32) && cols != 0 && rows * kMaxPos <= 0xFFFFFFFFull / cols;
+  // row indices, chunk counts and item offsets are 32-bit; the prefix sum over the 4096 keys per column
+  // adds up the totals of all earlier blocks in every block, which is meant for at most a few thousand blocks
+  return rows < (1ull << 32) && cols != 0 && cols <= 1024 && rows * kMaxPos <= 0xFFFFFFFFull / cols;
 }
 
 XtdBucketPlan xtd_bucket_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {

@@ -484,6 +484,39 @@ def test_taylor_loss_sequence(api):
             assert flag == 1 and dev_to_ints(api.haflo_export_cipher(ctx, out)) == [want]
 
 
+@pytest.mark.parametrize("kind", ["int32_range", "one_hot", "sparse_small"])
+def test_xtd_methods_agree_at_scale(api, kind, monkeypatch):
+    """Tall matrices beyond what the oracle can multiply: both X^T [[d]] methods must give the same
+    canonical ciphertexts, and every output must decrypt to sum_i x_ij m_i mod n. The shapes put
+    up to 70000 rows into one bucket (five reduction rounds) and use all four digit positions."""
+    bits = 1024
+    ctx, sk = context(api, bits)
+    n = sk.public.n
+    rows, cols = 70001, 3
+    rng = np.random.default_rng(91)
+    if kind == "int32_range":
+        X = rng.integers(-2 ** 31, 2 ** 31, size=(rows, cols), dtype=np.int64).astype(np.int32)
+        X[0, 0], X[1, 0] = -2 ** 31, 2 ** 31 - 1
+    elif kind == "one_hot":
+        X = np.zeros((rows, cols), dtype=np.int32)
+        X[:, 0] = 1 << 16
+        X[:, 1] = np.where(rng.random(rows) < 0.5, 0, -(1 << 16))
+        X[::7, 2] = 5
+    else:
+        X = rng.integers(-300, 300, size=(rows, cols)).astype(np.int32)
+        X[rng.random(X.shape) < 0.9] = 0
+    m = rng.integers(0, 2 ** 62, size=rows, dtype=np.int64)
+    plain = to_dev(synth.ints_to_words([int(v) for v in m], bits // 32))
+    c = api.haflo_encrypt(ctx, plain, to_dev(random_units_words(rows, bits, 92)))
+    outs = {}
+    for method, threshold in XTD_METHODS.items():
+        monkeypatch.setenv(XTD_THRESHOLD, threshold)
+        outs[method] = api.haflo_cipher_matvec(ctx, 0, c, to_dev(X)).clone()
+    assert torch.equal(outs["tables"], outs["buckets"])
+    exact = [int(np.dot(X[:, j].astype(object), m.astype(object))) % n for j in range(cols)]
+    assert dev_to_ints(api.haflo_decrypt(ctx, outs["buckets"])) == exact
+
+
 def test_edges_encode_decode(api):
     bits = 1024
     ctx, sk = context(api, bits)
