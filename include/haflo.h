@@ -266,6 +266,36 @@ int haflo_taylor_loss(const haflo_ctx* ctx, const void* d_c_u, const void* d_c_u
 int haflo_cipher_sum(const haflo_ctx* ctx, const void* d_c, size_t count, void* d_out, void* d_workspace,
                      size_t workspace_bytes, void* stream);
 
+/*
+ * Host staging (paper section 3.2, "Operator-level Storage Optimizer": page-locked
+ * buffers reused by size, serialised arrays moved in bulk, transfers overlapped
+ * with computation). A stager moves arrays in the interchange format between
+ * ordinary host memory and device arrays in chunks of `chunk_elems` elements:
+ * while one chunk is converted by the import / export kernel on the caller's
+ * stream, the next is copied through a page-locked buffer on the stager's own
+ * copy stream. The page-locked buffers come from a pool keyed by size; idle
+ * buffers beyond `pool_cap_bytes` are released, least recently used first.
+ * A stager belongs to one context and one host thread at a time; it owns two
+ * device staging buffers of chunk_elems canonical ciphertexts.
+ * The calls return when the host buffer may be reused (in) or is filled (out);
+ * device-side work of the "in" calls is ordered on `stream`.
+ */
+typedef struct haflo_stager haflo_stager;
+int haflo_stager_create(const haflo_ctx* ctx, size_t chunk_elems, size_t pool_cap_bytes, haflo_stager** out);
+int haflo_stager_destroy(haflo_stager* s);
+/* Page-locked bytes currently held, buffers allocated so far, requests served from the pool. */
+int haflo_stager_stats(const haflo_stager* s, size_t* pinned_bytes, size_t* pinned_allocs, size_t* pinned_reuses);
+/* h_canon: host, count*Lc uint32 canonical ciphertexts -> d_cipher: count internal elements
+ * (d_status as for haflo_import_cipher). */
+int haflo_stage_in_cipher(haflo_stager* s, const uint32_t* h_canon, void* d_cipher, uint32_t* d_status, size_t count,
+                          void* stream);
+/* h_plain: host, count*Lp uint32 -> d_plain: device, the same words. */
+int haflo_stage_in_plain(haflo_stager* s, const uint32_t* h_plain, uint32_t* d_plain, size_t count, void* stream);
+/* d_cipher: count internal elements (produced on `stream`) -> h_canon: host, count*Lc uint32. */
+int haflo_stage_out_cipher(haflo_stager* s, const void* d_cipher, uint32_t* h_canon, size_t count, void* stream);
+/* d_plain: device, count*Lp uint32 (produced on `stream`) -> h_plain: host. */
+int haflo_stage_out_plain(haflo_stager* s, const uint32_t* d_plain, uint32_t* h_plain, size_t count, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -39,6 +39,14 @@ PROTOTYPES = {
                                     c_void_p, c_size_t, c_void_p]),
     "haflo_taylor_loss": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_u32, c_void_p, c_void_p,
                                   c_size_t, c_void_p, c_size_t, c_void_p]),
+    "haflo_stager_create": (c_int, [c_void_p, c_size_t, c_size_t, C.POINTER(c_void_p)]),
+    "haflo_stager_destroy": (c_int, [c_void_p]),
+    "haflo_stager_stats": (c_int, [c_void_p, C.POINTER(c_size_t), C.POINTER(c_size_t),
+                                   C.POINTER(c_size_t)]),
+    "haflo_stage_in_cipher": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "haflo_stage_in_plain": (c_int, [c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "haflo_stage_out_cipher": (c_int, [c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "haflo_stage_out_plain": (c_int, [c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "haflo_cipher_sum": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_size_t, c_void_p]),
 }
 

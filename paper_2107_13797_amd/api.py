@@ -249,3 +249,67 @@ def haflo_cipher_sum(ctx, c):
     ws = ctx.workspace(haflo_workspace_bytes(ctx, _cabi.OP_MATVEC_XT_D, count, 1))
     _check(lib().haflo_cipher_sum(ctx.handle, _ptr(c), count, _ptr(out), _ptr(ws), ws.numel(), _stream()))
     return out
+
+
+class Stager:
+    """Owner of a haflo_stager: host numpy arrays in the interchange format <-> device arrays."""
+
+    def __init__(self, ctx, chunk_elems=8192, pool_cap_bytes=256 << 20):
+        self.ctx = ctx
+        h = C.c_void_p()
+        _check(lib().haflo_stager_create(ctx.handle, chunk_elems, pool_cap_bytes, C.byref(h)))
+        self.handle = h
+
+    def stats(self):
+        a, b, c = C.c_size_t(), C.c_size_t(), C.c_size_t()
+        _check(lib().haflo_stager_stats(self.handle, C.byref(a), C.byref(b), C.byref(c)))
+        return {"pinned_bytes": a.value, "pinned_allocs": b.value, "pinned_reuses": c.value}
+
+    def close(self):
+        if self.handle is not None:
+            torch.cuda.synchronize()
+            lib().haflo_stager_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _host_words(arr, words):
+    import numpy as np
+    arr = np.ascontiguousarray(arr, dtype=np.uint32)
+    if arr.ndim != 2 or arr.shape[1] != words:
+        raise HafloError("expected a [count, %d] uint32 array" % words)
+    return arr
+
+
+def haflo_stage_in_cipher(stager, h_canon, status=None):
+    h = _host_words(h_canon, stager.ctx.cipher_limbs)
+    out = _new_cipher(stager.ctx, h.shape[0])
+    _check(lib().haflo_stage_in_cipher(stager.handle, h.ctypes.data, _ptr(out),
+                                       _ptr(status) if status is not None else None, h.shape[0], _stream()))
+    return out
+
+
+def haflo_stage_in_plain(stager, h_plain):
+    h = _host_words(h_plain, stager.ctx.plain_limbs)
+    out = torch.empty((h.shape[0], stager.ctx.plain_limbs), dtype=torch.int32, device="cuda")
+    _check(lib().haflo_stage_in_plain(stager.handle, h.ctypes.data, _ptr(out), h.shape[0], _stream()))
+    return out
+
+
+def haflo_stage_out_cipher(stager, cipher):
+    import numpy as np
+    h = np.empty((cipher.shape[0], stager.ctx.cipher_limbs), dtype=np.uint32)
+    _check(lib().haflo_stage_out_cipher(stager.handle, _ptr(cipher), h.ctypes.data, cipher.shape[0], _stream()))
+    return h
+
+
+def haflo_stage_out_plain(stager, plain):
+    import numpy as np
+    h = np.empty((plain.shape[0], stager.ctx.plain_limbs), dtype=np.uint32)
+    _check(lib().haflo_stage_out_plain(stager.handle, _ptr(plain), h.ctypes.data, plain.shape[0], _stream()))
+    return h

@@ -403,6 +403,46 @@ def test_taylor_loss(env):
                                  None) == -1
 
 
+def test_host_staging_roundtrip(env):
+    """Chunked staging between host arrays and device arrays: chunk boundaries (count not a multiple
+    of the chunk, count below one chunk, zero), reuse of page-locked buffers, the range flag."""
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    lc, lp = BITS // 16, BITS // 32
+    st = C.c_void_p()
+    assert lib.haflo_stager_create(ctx, 4, 1 << 20, C.byref(st)) == 0
+    rng = random.Random(51)
+    for count in (11, 3, 0, 8):
+        cs = [rng.randrange(pk.nsq) for _ in range(count)]
+        h_in = np.ascontiguousarray(synth.ints_to_words(cs, lc)) if count else np.zeros((0, lc), np.uint32)
+        d_c = zeros(lib, (max(count, 1), nlw))
+        d_st = zeros(lib, (1,))
+        assert lib.haflo_stage_in_cipher(st, h_in.ctypes.data, d_c.p, d_st.p, count, None) == 0
+        assert d_st.get().tolist() == [0]
+        if count:
+            assert export(lib, ctx, d_c, count) == cs
+        h_out = np.zeros((max(count, 1), lc), np.uint32)
+        assert lib.haflo_stage_out_cipher(st, d_c.p, h_out.ctypes.data, count, None) == 0
+        assert synth.words_to_ints(h_out[:count]) == cs
+        ms = [rng.randrange(pk.n) for _ in range(count)]
+        h_pl = np.ascontiguousarray(synth.ints_to_words(ms, lp)) if count else np.zeros((0, lp), np.uint32)
+        d_pl = zeros(lib, (max(count, 1), lp))
+        assert lib.haflo_stage_in_plain(st, h_pl.ctypes.data, d_pl.p, count, None) == 0
+        h_back = np.zeros((max(count, 1), lp), np.uint32)
+        assert lib.haflo_stage_out_plain(st, d_pl.p, h_back.ctypes.data, count, None) == 0
+        assert synth.words_to_ints(h_back[:count]) == ms
+    bad = np.ascontiguousarray(synth.ints_to_words([5, pk.nsq, 7, 8, 9], lc))
+    d_c, d_st = zeros(lib, (5, nlw)), zeros(lib, (1,))
+    assert lib.haflo_stage_in_cipher(st, bad.ctypes.data, d_c.p, d_st.p, 5, None) == 0
+    assert d_st.get().tolist() == [1] and export(lib, ctx, d_c, 5) == [5, 0, 7, 8, 9]
+    pb, pa, pr = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    assert lib.haflo_stager_stats(st, C.byref(pb), C.byref(pa), C.byref(pr)) == 0
+    assert pa.value <= 4 and pr.value > pa.value and pb.value <= 1 << 20
+    assert lib.haflo_stage_in_cipher(st, None, d_c.p, None, 5, None) == -1
+    assert lib.haflo_stager_destroy(st) == 0
+    assert lib.haflo_stager_create(ctx, 0, 0, C.byref(st)) == -1
+
+
 def test_encode_decode(env):
     lib, ctx, sk, nlw = env
     pk = sk.public

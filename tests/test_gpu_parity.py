@@ -517,6 +517,37 @@ def test_xtd_methods_agree_at_scale(api, kind, monkeypatch):
     assert dev_to_ints(api.haflo_decrypt(ctx, outs["buckets"])) == exact
 
 
+def test_host_staging_pipeline(api):
+    """Host arrays through the staging path: canonical ciphertexts in and out (chunked, overlapped
+    copies), plaintexts in and out, and an encrypt -> stage out -> oracle check from host data."""
+    bits = 1024
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n = pk.n
+    stager = api.Stager(ctx, chunk_elems=1000)
+    rng = random.Random(61)
+    count = 4321
+    cs = [rng.randrange(pk.nsq) for _ in range(count)]
+    h = np.ascontiguousarray(synth.ints_to_words(cs, bits // 16))
+    st = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d = api.haflo_stage_in_cipher(stager, h, status=st)
+    assert int(st.item()) == 0
+    assert torch.equal(d, api.haflo_import_cipher(ctx, to_dev(h)))
+    assert np.array_equal(api.haflo_stage_out_cipher(stager, d), h)
+    ms = [rng.randrange(n) for _ in range(count)]
+    rs = synth.units_below(n, count, 62)
+    d_m = api.haflo_stage_in_plain(stager, np.ascontiguousarray(synth.ints_to_words(ms, bits // 32)))
+    d_r = api.haflo_stage_in_plain(stager, np.ascontiguousarray(synth.ints_to_words(rs, bits // 32)))
+    c = api.haflo_encrypt(ctx, d_m, d_r)
+    got = synth.words_to_ints(api.haflo_stage_out_cipher(stager, c))
+    idx = sample_indices(count, 64, 63)
+    assert [got[i] for i in idx] == OP.encrypt_many(n, [ms[i] for i in idx], [rs[i] for i in idx])
+    assert synth.words_to_ints(api.haflo_stage_out_plain(stager, api.haflo_decrypt(ctx, c))) == ms
+    stats = stager.stats()
+    assert stats["pinned_reuses"] > stats["pinned_allocs"]
+    stager.close()
+
+
 def test_edges_encode_decode(api):
     bits = 1024
     ctx, sk = context(api, bits)
