@@ -548,6 +548,23 @@ def test_host_staging_pipeline(api):
     stager.close()
 
 
+def test_hetero_lr_iteration_end_to_end(api):
+    """One two-party training iteration composed from the operators (fore gradient, both gradient
+    matvecs, Taylor loss, decryption, decoding): what the arbiter decodes must equal the exact
+    integer evaluation of the Taylor-approximated formulas of section 2.1 on the quantised inputs,
+    and stay close to their float64 evaluation."""
+    from paper_2107_13797_amd.examples import hetero_lr
+    bits = 1024
+    ctx, sk = context(api, bits)
+    pub = api.haflo_ctx_create_public(sk.public.n, bits)
+    res = hetero_lr.run_iteration(api, pub, ctx, instances=6000, features=5, seed=3)
+    pub.close()
+    assert res["gradient_q"] == res["want_gradient_q"]
+    assert res["loss_q"] == res["want_loss_q"]
+    for got, want in zip(res["gradient"], res["float_gradient"]):
+        assert abs(got - want) < 6000 * 5.0 * 2.0 ** -16  # entries of X are quantised to 2^-16
+
+
 def test_edges_encode_decode(api):
     bits = 1024
     ctx, sk = context(api, bits)
