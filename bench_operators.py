@@ -85,6 +85,8 @@ def main():
     res["encryption"] = N / t
     t, _ = timed(lambda: api.haflo_encrypt(own, plain, r))
     res["encryption (key owner)"] = N / t
+    t, _ = timed(lambda: api.haflo_encrypt_with_obfuscator(pub, plain, c))
+    res["encryption (precomputed r^n)"] = N / t
     t, pl = timed(lambda: api.haflo_decrypt(own, c))
     res["decryption"] = N / t
     t, _ = timed(lambda: api.haflo_decode(own, pl, 24))

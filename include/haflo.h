@@ -69,7 +69,8 @@ enum haflo_op {
   HAFLO_OP_MATVEC_XT_D = 4, /* orientation 0 */
   HAFLO_OP_MATVEC_X_W = 5,  /* orientation 1 */
   HAFLO_OP_FORE_GRADIENT = 6,
-  HAFLO_OP_TAYLOR_LOSS = 7
+  HAFLO_OP_TAYLOR_LOSS = 7,
+  HAFLO_OP_ENCRYPT_OBFUSCATOR = 8
 };
 
 /* Text for an error code; never NULL. */
@@ -170,6 +171,19 @@ int haflo_decode(const haflo_ctx* ctx, const uint32_t* d_plain, uint32_t scale_b
  */
 int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t* d_r, void* d_cipher, size_t count,
                   void* d_workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Encryption with a precomputed obfuscator (the usual split of Paillier
+ * encryption into an offline and an online part; paper Table 1, "Homomorphic
+ * Encryption": E(m) = g^m r^n mod n^2): d_obfuscator holds count internal
+ * elements r_i^n mod n^2, i.e. encryptions of zero made ahead of time with
+ * haflo_encrypt (plaintext 0); out[i] = (1 + m_i n) * obfuscator[i] mod n^2,
+ * two products per element. Each obfuscator may be used once. d_cipher may
+ * alias d_obfuscator. Workspace: HAFLO_OP_ENCRYPT_OBFUSCATOR.
+ */
+int haflo_encrypt_with_obfuscator(const haflo_ctx* ctx, const uint32_t* d_plain, const void* d_obfuscator,
+                                  void* d_cipher, size_t count, void* d_workspace, size_t workspace_bytes,
+                                  void* stream);
 
 /*
  * "Homomorphic Decryption" (paper Table 2; the scheme of the paper's reference

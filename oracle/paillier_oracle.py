@@ -252,6 +252,12 @@ def matvec(pk: PublicKey, orientation: int, cs: Sequence[int], X: Sequence[Seque
     raise ValueError("orientation must be 0 or 1")
 
 
+def encrypt_with_obfuscator(pk: PublicKey, m: int, obfuscator: int) -> int:
+    """Table 1's encryption g^m * r^n mod n^2 with the factor r^n supplied ready-made."""
+    assert 0 <= m < pk.n and 0 <= obfuscator < pk.nsq
+    return pow(pk.g, m, pk.nsq) * obfuscator % pk.nsq
+
+
 def fore_gradient(pk: PublicKey, c_host: int, logit_guest: float, label: float, r: int,
                   scale_bits: int) -> Tuple[int, int]:
     """Guest's fore gradient of heterogeneous logistic regression, section 3.4 (workflow figure):

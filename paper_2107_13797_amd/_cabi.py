@@ -47,10 +47,12 @@ PROTOTYPES = {
     "haflo_stage_in_plain": (c_int, [c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "haflo_stage_out_cipher": (c_int, [c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "haflo_stage_out_plain": (c_int, [c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "haflo_encrypt_with_obfuscator": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p, c_size_t,
+                                              c_void_p]),
     "haflo_cipher_sum": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_size_t, c_void_p]),
 }
 
-OP_ENCRYPT, OP_DECRYPT, OP_SCALAR_MUL, OP_MATVEC_XT_D, OP_MATVEC_X_W, OP_FORE_GRADIENT, OP_TAYLOR_LOSS = 1, 2, 3, 4, 5, 6, 7
+OP_ENCRYPT, OP_DECRYPT, OP_SCALAR_MUL, OP_MATVEC_XT_D, OP_MATVEC_X_W, OP_FORE_GRADIENT, OP_TAYLOR_LOSS, OP_ENCRYPT_OBFUSCATOR = 1, 2, 3, 4, 5, 6, 7, 8
 
 
 def bind(lib, names=None):

@@ -184,6 +184,16 @@ def haflo_fore_gradient(ctx, c_host, logits_guest, label, r, scale_bits, out=Non
     return out
 
 
+def haflo_encrypt_with_obfuscator(ctx, plain, obfuscator, out=None):
+    count = plain.shape[0]
+    if out is None:
+        out = _new_cipher(ctx, count)
+    ws = ctx.workspace(haflo_workspace_bytes(ctx, _cabi.OP_ENCRYPT_OBFUSCATOR, count))
+    _check(lib().haflo_encrypt_with_obfuscator(ctx.handle, _ptr(plain), _ptr(obfuscator), _ptr(out), count, _ptr(ws),
+                                               ws.numel(), _stream()))
+    return out
+
+
 def haflo_taylor_loss(ctx, c_u, c_u2, u_guest, label, r, scale_bits, status=None):
     count = c_u.shape[0]
     out = _new_cipher(ctx, 1)

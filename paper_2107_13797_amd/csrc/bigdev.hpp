@@ -14,9 +14,9 @@
 // the modulus without a final subtraction. Only values that are stored or
 // compared are brought to canonical form (limbs < 2^29, value < modulus).
 //
-// Cross-lane traffic: ds_bpermute for broadcasts inside a group, DPP row
-// shifts by one lane for neighbour exchange (groups never straddle a 16-lane
-// DPP row, so T <= 16).
+// Cross-lane traffic: ds_bpermute for broadcasts from a lane chosen at run time,
+// DPP moves for broadcasts from lane 0 of a group and for the exchange with the
+// neighbouring lane (groups never straddle a 16-lane DPP row, so T <= 16).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>

@@ -161,6 +161,7 @@ std::vector<uint32_t> to_limbs29(const Big& x, int nl);
 // workspace sizes in bytes (kernels_modexp.hip)
 size_t ws_encrypt(const haflo_ctx* ctx, size_t count);
 size_t ws_scalar_mul(const haflo_ctx* ctx, size_t count);
+size_t ws_encrypt_obf(const haflo_ctx* ctx, size_t count);
 size_t ws_decrypt(const haflo_ctx* ctx, size_t count);
 // workspace of the Taylor-loss sequence in bytes (kernels_loss.hip)
 size_t ws_taylor_loss(const haflo_ctx* ctx, size_t count);

@@ -720,6 +720,7 @@ size_t haflo_workspace_bytes(const haflo_ctx* ctx, int op, size_t rows, size_t c
     case HAFLO_OP_DECRYPT: return ctx->has_priv ? ws_decrypt(ctx, rows) : (size_t)-1;
     case HAFLO_OP_SCALAR_MUL: return ws_scalar_mul(ctx, rows);
     case HAFLO_OP_TAYLOR_LOSS: return ws_taylor_loss(ctx, rows);
+    case HAFLO_OP_ENCRYPT_OBFUSCATOR: return ws_encrypt_obf(ctx, rows);
     case HAFLO_OP_FORE_GRADIENT:
       return ((rows * (size_t)ctx->lp * 4 + 255) & ~(size_t)255) + ((rows * (size_t)ctx->N.nl * 4 + 255) & ~(size_t)255) +
              ws_encrypt(ctx, rows);

@@ -205,6 +205,10 @@ size_t ws_encrypt(const haflo_ctx* ctx, size_t count) {
   size_t last = modexp_shape(ctx, count, ctx->N).slots() * (size_t)ctx->N.nl;
   return (2 * count * (size_t)ctx->P2.nl + count * (size_t)ctx->N.nl + std::max(branch, last)) * 4;
 }
+// one table slot per resident lane group
+size_t ws_encrypt_obf(const haflo_ctx* ctx, size_t count) {
+  return launch_shape(ctx, count, ctx->N.t, 8).slots() * (size_t)ctx->N.nl * 4;
+}
 // sized for the per-element variant (16 entries); the broadcast variant never needs more
 size_t ws_scalar_mul(const haflo_ctx* ctx, size_t count) {
   return modexp_shape(ctx, count, ctx->N).slots() * (size_t)16 * ctx->N.nl * 4;
@@ -317,6 +321,35 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
   io.tables = tables;
   io.table_entries = 1;
   return launch_engine(m, modexp_shape(ctx, count, m), st, pi, io, count);
+}
+
+int haflo_encrypt_with_obfuscator(const haflo_ctx* ctx, const uint32_t* d_plain, const void* d_obfuscator,
+                                  void* d_cipher, size_t count, void* d_workspace, size_t workspace_bytes,
+                                  void* stream) {
+  if (!ctx || (count && (!d_plain || !d_obfuscator || !d_cipher))) return HAFLO_EINVAL;
+  if (count == 0) return HAFLO_OK;
+  if (!d_workspace || workspace_bytes < ws_encrypt_obf(ctx, count)) return HAFLO_EINVAL;
+  const ModHost& m = ctx->N;
+  // table[0] = r^n (Montgomery form); acc = m -> (m n) R + R = (1 + m n) R -> times table[0]
+  std::vector<uint32_t> prog;
+  prog.push_back(eng_ins(ENG_LOAD_L, 0));
+  prog.push_back(eng_ins(ENG_STORE_T, 0));
+  prog.push_back(eng_ins(ENG_LOAD_W, 0));
+  prog.push_back(eng_ins(ENG_MUL_C, kConstExtra));
+  prog.push_back(eng_ins(ENG_ADD_C, kConstR1));
+  prog.push_back(eng_ins(ENG_MUL_T, 0));
+  ProgInline pi;
+  if (!to_inline(pi, prog)) return HAFLO_EINVAL;
+  EngineIO io = engine_io(m);
+  io.constant[kConstExtra] = ctx->d_k1;
+  io.in_words[0] = d_plain;
+  io.in_nwords = ctx->lp;
+  io.in_limbs = (const u32*)d_obfuscator;
+  io.in_limbs_stride = m.nl;
+  io.out = (u32*)d_cipher;
+  io.tables = (u32*)d_workspace;
+  io.table_entries = 1;
+  return launch_engine(m, launch_shape(ctx, count, m.t, 8), (hipStream_t)stream, pi, io, count);
 }
 
 int haflo_scalar_mul_u64(const haflo_ctx* ctx, const void* d_c, const uint64_t* d_k, void* d_out, size_t count,

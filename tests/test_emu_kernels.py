@@ -163,6 +163,25 @@ def test_batch_above_the_wide_lane_threshold(env):
     assert export(lib, ctx, d_o, count) == [O.scalar_mul(pk, c, -5) for c in want]
 
 
+def test_encrypt_with_obfuscator(env):
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    lp = BITS // 32
+    rng = random.Random(27)
+    ms = [rng.randrange(pk.n) for _ in range(5)] + [0, pk.n - 1]
+    rs = [rng.randrange(1, pk.n) for _ in range(len(ms))]
+    d_obf = zeros(lib, (len(ms), nlw))
+    w, nb = ws(lib, ctx, _cabi.OP_ENCRYPT, len(ms))
+    zero = zeros(lib, (len(ms), lp))
+    assert lib.haflo_encrypt(ctx, zero.p, words(lib, rs, lp).p, d_obf.p, len(ms), w.p, nb, None) == 0
+    obf = export(lib, ctx, d_obf, len(ms))
+    assert obf == [pow(r, pk.n, pk.nsq) for r in rs]
+    w, nb = ws(lib, ctx, _cabi.OP_ENCRYPT_OBFUSCATOR, len(ms))
+    assert lib.haflo_encrypt_with_obfuscator(ctx, words(lib, ms, lp).p, d_obf.p, d_obf.p, len(ms), w.p, nb, None) == 0
+    assert export(lib, ctx, d_obf, len(ms)) == [O.encrypt_with_obfuscator(pk, m, o) for m, o in zip(ms, obf)]
+    assert export(lib, ctx, d_obf, len(ms)) == [O.encrypt(pk, m, r) for m, r in zip(ms, rs)]
+
+
 def test_public_context_encrypts_identically(env):
     """The public-key path (full exponent modulo n^2) and the key owner's path (through p^2 and
     q^2) must produce the same ciphertext bits; a public context cannot decrypt."""

@@ -565,6 +565,27 @@ def test_hetero_lr_iteration_end_to_end(api):
         assert abs(got - want) < 6000 * 5.0 * 2.0 ** -16  # entries of X are quantised to 2^-16
 
 
+def test_encrypt_with_obfuscator_matches_encrypt(api):
+    """Offline/online split of the encryption: obfuscators r^n made ahead of time, then two
+    products per element; the ciphertexts must be the ordinary ones (oracle on a sample)."""
+    bits, count = 2048, 5000
+    ctx, sk = context(api, bits)
+    n = sk.public.n
+    rng = random.Random(95)
+    ms = [rng.randrange(n) for _ in range(count)]
+    r_words = random_units_words(count, bits, 96)
+    zero = torch.zeros((count, bits // 32), dtype=torch.int32, device="cuda")
+    obf = api.haflo_encrypt(ctx, zero, to_dev(r_words))
+    plain = ints_to_dev(ms, bits // 32)
+    direct = api.haflo_encrypt(ctx, plain, to_dev(r_words))
+    split = api.haflo_encrypt_with_obfuscator(ctx, plain, obf)
+    assert torch.equal(direct, split)
+    idx = sample_indices(count, 24, 97)
+    idx_t = torch.tensor(idx, device="cuda")
+    assert dev_to_ints(api.haflo_export_cipher(ctx, split[idx_t].contiguous())) == OP.encrypt_many(
+        n, [ms[i] for i in idx], synth.words_to_ints(r_words[idx]))
+
+
 def test_edges_encode_decode(api):
     bits = 1024
     ctx, sk = context(api, bits)

@@ -334,3 +334,21 @@ def test_taylor_loss_plaintext_closed_form():
     c, st = O.taylor_loss(pk, c_u[:2], c_u2[:2], [float("inf"), 0.0], [1.0, 1.0], 7, s)
     assert st == 1
     assert O.decrypt(sk, c) == (m1[0] ** 2 + m1[1] ** 2 - 4 * (1 << s) * m1[1]) % pk.n
+
+
+def test_obfuscator_encryption_is_the_same_encryption():
+    """E(m; r) = g^m * (r^n): with the obfuscator r^n = E(0; r) the split form must reproduce the
+    ordinary encryption on every plaintext and unit of a tiny key, and on a real key."""
+    for sk in tiny_keys():
+        pk = sk.public
+        for r in range(1, pk.n):
+            if math.gcd(r, pk.n) != 1:
+                continue
+            obf = O.encrypt(pk, 0, r)
+            assert obf == pow(r, pk.n, pk.nsq)
+            for m in range(pk.n):
+                assert O.encrypt_with_obfuscator(pk, m, obf) == O.encrypt(pk, m, r)
+    pk = _real_key(512).public
+    rng = random.Random(8)
+    m, r = rng.randrange(pk.n), rng.randrange(1, pk.n)
+    assert O.encrypt_with_obfuscator(pk, m, O.encrypt(pk, 0, r)) == O.encrypt(pk, m, r)
