@@ -264,7 +264,10 @@ int haflo_fore_gradient(const haflo_ctx* ctx, const void* d_c_host, const float*
  * which encrypts sum_i ( m2_i + k_i m1_i ) + P = 8 * 2^(2 scale_bits) times
  * the sum above: the result is read at scale 2^(2 scale_bits + 3).
  * d_c_u, d_c_u2: count internal elements; d_u_guest, d_label: device
- * float[count]; d_r: device Lp uint32 (one r); d_out: one internal element;
+ * float[count]; d_r: device Lp uint32 (one r), or NULL for r = 1 without the
+ * exponentiation (the result is then randomised by the host's ciphertexts
+ * only, which suffices when it goes straight to the key owner);
+ * d_out: one internal element;
  * d_status: device uint32 (one word) or NULL, OR-ed with HAFLO_ST_RANGE when
  * an element is not finite or too large (|q(u_guest)| >= 2^28 or
  * |q(y)| >= 2^27; such an element contributes m2_i only). scale_bits <= 27,

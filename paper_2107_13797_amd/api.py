@@ -198,7 +198,8 @@ def haflo_taylor_loss(ctx, c_u, c_u2, u_guest, label, r, scale_bits, status=None
     count = c_u.shape[0]
     out = _new_cipher(ctx, 1)
     ws = ctx.workspace(haflo_workspace_bytes(ctx, _cabi.OP_TAYLOR_LOSS, count))
-    _check(lib().haflo_taylor_loss(ctx.handle, _ptr(c_u), _ptr(c_u2), _ptr(u_guest), _ptr(label), _ptr(r), scale_bits,
+    _check(lib().haflo_taylor_loss(ctx.handle, _ptr(c_u), _ptr(c_u2), _ptr(u_guest), _ptr(label),
+                                   _ptr(r) if r is not None else None, scale_bits,
                                    _ptr(out), _ptr(status) if status is not None else None, count, _ptr(ws),
                                    ws.numel(), _stream()))
     return out

@@ -119,7 +119,9 @@ LossPlan loss_plan(const haflo_ctx* ctx, size_t count) {
   p.off_t3 = b;       b += cipher;
   p.off_ws = b;
   size_t w = haflo_workspace_bytes(ctx, HAFLO_OP_MATVEC_XT_D, count, 1);
-  const size_t e = haflo_workspace_bytes(ctx, HAFLO_OP_ENCRYPT, 1, 0);
+  size_t e = haflo_workspace_bytes(ctx, HAFLO_OP_ENCRYPT, 1, 0);
+  if (e > w) w = e;
+  e = haflo_workspace_bytes(ctx, HAFLO_OP_ENCRYPT_OBFUSCATOR, 1, 0);
   if (e > w) w = e;
   p.ws_bytes = w;
   p.total = b + w;
@@ -137,7 +139,7 @@ extern "C" {
 int haflo_taylor_loss(const haflo_ctx* ctx, const void* d_c_u, const void* d_c_u2, const float* d_u_guest,
                       const float* d_label, const uint32_t* d_r, uint32_t scale_bits, void* d_out,
                       uint32_t* d_status, size_t count, void* d_workspace, size_t workspace_bytes, void* stream) {
-  if (!ctx || scale_bits > 27 || !d_out || !d_r || (count && (!d_c_u || !d_c_u2 || !d_u_guest || !d_label)))
+  if (!ctx || scale_bits > 27 || !d_out || (count && (!d_c_u || !d_c_u2 || !d_u_guest || !d_label)))
     return HAFLO_EINVAL;
   if (count > 0xFFFFFFFFull) return HAFLO_EINVAL;
   const LossPlan p = loss_plan(ctx, count);
@@ -166,7 +168,10 @@ int haflo_taylor_loss(const haflo_ctx* ctx, const void* d_c_u, const void* d_c_u
   if (rc != HAFLO_OK) return rc;
   rc = haflo_cipher_sum(ctx, d_c_u2, count, t2, ws, p.ws_bytes, stream);
   if (rc != HAFLO_OK) return rc;
-  rc = haflo_encrypt(ctx, plain, d_r, t3, 1, ws, p.ws_bytes, stream);
+  // without an r the plaintext part enters as g^P = 1 + P n (obfuscator 1): two products instead of a
+  // full exponentiation; the result is still randomised by the host's ciphertexts
+  rc = d_r ? haflo_encrypt(ctx, plain, d_r, t3, 1, ws, p.ws_bytes, stream)
+           : haflo_encrypt_with_obfuscator(ctx, plain, ctx->N.ref().r1, t3, 1, ws, p.ws_bytes, stream);
   if (rc != HAFLO_OK) return rc;
   rc = haflo_add(ctx, t1, t2, t1, 1, stream);
   if (rc != HAFLO_OK) return rc;

@@ -82,7 +82,7 @@ def run_iteration(api, pub, own, instances, features, seed=0, timings=None):
     g_g = timed("guest: X_g^T [[d]]", lambda: api.haflo_cipher_matvec(pub, 0, d, E_g))
     g_h = timed("host: X_h^T [[d]]", lambda: api.haflo_cipher_matvec(pub, 0, d, E_h))
     loss = timed("guest: Taylor loss", lambda: api.haflo_taylor_loss(
-        pub, c_u, c_u2, _dev(u_g), _dev(y), rand_r(1), SCALE_U))
+        pub, c_u, c_u2, _dev(u_g), _dev(y), None, SCALE_U))  # goes to the arbiter only: no fresh r needed
 
     # arbiter
     both = torch.cat([g_g, g_h, loss], dim=0)

@@ -418,6 +418,11 @@ def test_taylor_loss(env):
         want, st = O.taylor_loss(pk, c_u, c_u2, [float(v) for v in ug], [float(v) for v in y], r, s)
         assert export(lib, ctx, d_o, 1) == [want]
         assert d_st.get().tolist() == [st] and st == (1 if bad else 0)
+        # no r: the plaintext part enters as g^P, which is the encryption with r = 1
+        assert lib.haflo_taylor_loss(ctx, d_u.p, d_u2.p, Dev(lib, ug).p, Dev(lib, y).p, None, s, d_o.p, None, count,
+                                     w.p, nb, None) == 0
+        assert export(lib, ctx, d_o, 1) == [O.taylor_loss(pk, c_u, c_u2, [float(v) for v in ug],
+                                                          [float(v) for v in y], 1, s)[0]]
     assert lib.haflo_taylor_loss(ctx, d_u.p, d_u2.p, None, None, words(lib, [r], lp).p, 28, d_o.p, None, 0, w.p, nb,
                                  None) == -1
 
