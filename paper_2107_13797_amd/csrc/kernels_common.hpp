@@ -79,6 +79,7 @@ struct EngineIO {
   u32* tables;                     // table_entries * NL limbs per slot
   int table_entries;
   int table_per_item;              // 1: slot = element index (tables are an output), 0: slot = lane group
+  size_t first;                    // index of the launch's first element in the per-element arrays
 };
 
 // The exponentiation engine: every lane group runs the batch-uniform program
@@ -94,8 +95,8 @@ __device__ __forceinline__ void engine_run(const ModRef& M, const Prog& P, const
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
   for (size_t base = bt.first(); base < count; base += bt.stride()) {
-    const size_t item = base + bt.gib;
-    const bool active = item < count;
+    const bool active = base + bt.gib < count;
+    const size_t item = io.first + base + bt.gib;
     const bool tab_ok = active || !io.table_per_item;
     u32* table = io.tables + (io.table_per_item ? (active ? item : 0) : bt.slot()) * (size_t)io.table_entries * NL;
     const u64 k = (io.k64 && active) ? io.k64[item] : 0ull;

@@ -191,6 +191,42 @@ int launch_engine(const ModHost& m, const LaunchShape& sh, hipStream_t st, const
   return hip_status(hipGetLastError());
 }
 
+// One element is one sequential chain, so a batch that does not fill its last pass over the resident
+// lane groups would still pay for it in full. Such a batch is cut in two launches: the full passes, and
+// the remainder in single-wavefront blocks that spread over all SIMDs (and over twice the lanes per
+// integer when it is small), which runs the fewer wavefronts per SIMD correspondingly faster.
+struct BatchSplit {
+  size_t full;       // elements of the full passes (0: one launch of `shape` for everything)
+  LaunchShape shape; // of the full passes, or of the only launch
+  LaunchShape tail;  // of the remainder
+};
+BatchSplit split_batch(const haflo_ctx* ctx, size_t count, const ModHost& m) {
+  BatchSplit b;
+  b.shape = modexp_shape(ctx, count, m);
+  b.full = 0;
+  b.tail = b.shape;
+  const size_t slots = b.shape.slots();
+  if (engine_wide(ctx, count, m) || count <= slots || count % slots == 0) return b;
+  b.full = count / slots * slots;
+  const size_t rest = count - b.full;
+  const int t = engine_wide(ctx, rest, m) ? 2 * m.t : m.t;
+  b.tail.threads = 64;
+  b.tail.gpb = 64 / t;
+  b.tail.blocks = (int)((rest + b.tail.gpb - 1) / b.tail.gpb);
+  return b;
+}
+
+template <class Prog>
+int launch_engine_batch(const haflo_ctx* ctx, const ModHost& m, hipStream_t st, const Prog& prog, EngineIO io,
+                        size_t count) {
+  const BatchSplit b = split_batch(ctx, count, m);
+  if (b.full == 0) return launch_engine(m, b.shape, st, prog, io, count);
+  int rc = launch_engine(m, b.shape, st, prog, io, b.full);
+  if (rc != HAFLO_OK) return rc;
+  io.first = b.full;  // the table slots are free again once the first launch has finished (stream order)
+  return launch_engine(m, b.tail, st, prog, io, count - b.full);
+}
+
 }  // namespace
 
 namespace haflo {
@@ -260,7 +296,7 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
     io.tables = (u32*)d_workspace;
     io.table_entries = ctx->prog_enc.table_entries;
     ProgPtr prog = {ctx->prog_enc.d_ins, (int)ctx->prog_enc.host.size()};
-    return launch_engine(m, modexp_shape(ctx, count, m), st, prog, io, count);
+    return launch_engine_batch(ctx, m, st, prog, io, count);
   }
   // key owner: r^n through p^2 and q^2 (half-size moduli: a quarter of the multiplications per
   // branch), Chinese remainder, then the (1 + m n) factor and the Montgomery form modulo n^2.
@@ -320,7 +356,7 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
   io.out = (u32*)d_cipher;
   io.tables = tables;
   io.table_entries = 1;
-  return launch_engine(m, modexp_shape(ctx, count, m), st, pi, io, count);
+  return launch_engine_batch(ctx, m, st, pi, io, count);
 }
 
 int haflo_encrypt_with_obfuscator(const haflo_ctx* ctx, const uint32_t* d_plain, const void* d_obfuscator,
@@ -377,7 +413,7 @@ int haflo_scalar_mul_u64(const haflo_ctx* ctx, const void* d_c, const uint64_t* 
   io.out = (u32*)d_out;
   io.tables = (u32*)d_workspace;
   io.table_entries = 16;
-  return launch_engine(m, modexp_shape(ctx, count, m), (hipStream_t)stream, pi, io, count);
+  return launch_engine_batch(ctx, m, (hipStream_t)stream, pi, io, count);
 }
 
 int haflo_scalar_mul_i64_bcast(const haflo_ctx* ctx, const void* d_c, int64_t k, void* d_out, size_t count,
@@ -407,7 +443,7 @@ int haflo_scalar_mul_i64_bcast(const haflo_ctx* ctx, const void* d_c, int64_t k,
   io.out = (u32*)d_out;
   io.tables = (u32*)d_workspace;
   io.table_entries = plan.table_len + 1;
-  return launch_engine(m, modexp_shape(ctx, count, m), st, pi, io, count);
+  return launch_engine_batch(ctx, m, st, pi, io, count);
 }
 
 int haflo_decrypt(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain, size_t count, void* d_workspace,

@@ -586,6 +586,33 @@ def test_encrypt_with_obfuscator_matches_encrypt(api):
         n, [ms[i] for i in idx], synth.words_to_ints(r_words[idx]))
 
 
+def test_batch_with_partial_last_pass(api):
+    """A batch a little larger than the resident lane groups is run as full passes plus a
+    remainder launch; elements on both sides of the cut and at the very end must be right."""
+    bits = 1024
+    ctx, sk = context(api, bits)
+    n = sk.public.n
+    lp = bits // 32
+    props = torch.cuda.get_device_properties(0)
+    slots = props.multi_processor_count * 4 * (256 // 4)  # blocks per chip x lane groups per block
+    count = slots + 137
+    rng = np.random.default_rng(98)
+    m_words = rng.integers(0, 2 ** 32, size=(count, lp), dtype=np.uint32)
+    m_words[:, -1] &= 0x3FFFFFFF
+    r_words = random_units_words(count, bits, 99)
+    pub = api.haflo_ctx_create_public(n, bits)
+    c = api.haflo_encrypt(pub, to_dev(m_words), to_dev(r_words))
+    idx = sorted(set(sample_indices(count, 24, 100) + [slots - 1, slots, slots + 1, count - 1]))
+    idx_t = torch.tensor(idx, device="cuda")
+    want = OP.encrypt_many(n, synth.words_to_ints(m_words[idx]), synth.words_to_ints(r_words[idx]))
+    assert dev_to_ints(api.haflo_export_cipher(pub, c[idx_t].contiguous())) == want
+    k = rng.integers(0, 2 ** 63, size=count, dtype=np.int64)
+    p = api.haflo_scalar_mul_u64(pub, c, torch.from_numpy(k).cuda())
+    got = dev_to_ints(api.haflo_export_cipher(pub, p[idx_t].contiguous()))
+    assert got == OP.pow_many(n, want, [int(k[i]) for i in idx])
+    pub.close()
+
+
 def test_edges_encode_decode(api):
     bits = 1024
     ctx, sk = context(api, bits)
