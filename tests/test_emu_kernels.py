@@ -295,6 +295,33 @@ def test_bucket_matvec_heavy_buckets(env, force_buckets):
     _xtd_case(env, X, 22)
 
 
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("method", ["1", "1000000000000"])
+def test_gradient_matvec_random_shapes(env, monkeypatch, seed, method):
+    """Random shapes and exponent distributions through both gradient-matvec methods (the
+    environment variable moves the row threshold): sparse, dense, one magnitude only, full int32
+    range, powers of 1024 and their neighbours."""
+    monkeypatch.setenv("HAFLO_XTD_BUCKET_MIN_ROWS", method)
+    rng = np.random.default_rng(1000 + seed)
+    rows, cols = int(rng.integers(1, 45)), int(rng.integers(1, 4))
+    kind = seed % 6
+    if kind == 0:
+        X = rng.integers(-2 ** 31, 2 ** 31, size=(rows, cols), dtype=np.int64)
+    elif kind == 1:
+        X = rng.integers(-3, 4, size=(rows, cols), dtype=np.int64)
+    elif kind == 2:
+        X = np.full((rows, cols), -(1 << 20), dtype=np.int64)
+    elif kind == 3:
+        X = rng.choice(np.array([0, 1, -1, 1023, 1024, 1025, -1024 ** 2, 1024 ** 2 + 511, 1024 ** 3 - 512, -1024 ** 3]),
+                       size=(rows, cols))
+    elif kind == 4:
+        X = rng.integers(-(1 << 19), 1 << 19, size=(rows, cols), dtype=np.int64)
+        X[rng.random(X.shape) < 0.8] = 0
+    else:
+        X = (rng.normal(0, 1, (rows, cols)) * 65536).round().astype(np.int64)
+    _xtd_case(env, X.astype(np.int32), 2000 + seed)
+
+
 @pytest.mark.parametrize("top", [511, 512, 513, 523775, 523776, 535821823, 535821824])
 def test_bucket_matvec_digit_boundaries(env, force_buckets, top):
     """Magnitudes around the points where the signed base-1024 recoding needs one more position."""
