@@ -837,18 +837,42 @@ int haflo_cipher_sum(const haflo_ctx* ctx, const void* d_c, size_t count, void* 
   const ModHost& m = ctx->N;
   hipStream_t st = (hipStream_t)stream;
   const int nb = sum_blocks(ctx, count);
-  if (!d_workspace || workspace_bytes < (size_t)nb * m.nl * 4) return HAFLO_EINVAL;
+  // partial products of the first level, then of every further level, ping-pong in the workspace
+  const int gpw = kBlockThreads / haflo_wide_lanes(m);  // groups per block of the later levels
+  const size_t second = (size_t)(nb + gpw - 1) / gpw;
+  if (!d_workspace || workspace_bytes < ((size_t)nb + second) * m.nl * 4) return HAFLO_EINVAL;
+  u32* buf[2] = {(u32*)d_workspace, (u32*)d_workspace + (size_t)nb * m.nl};
   LaunchShape sh;
   sh.threads = kBlockThreads;
   sh.gpb = kBlockThreads / m.t;
   sh.blocks = nb;
-  LaunchShape fin = sh;
-  fin.blocks = 1;
-#define CALL(LPT, T)                                                                                   \
-  HAFLO_LAUNCH((k_sum<LPT, T>), sh, st, m.ref(), (const u32*)d_c, count, (u32*)d_workspace, 0);        \
-  HAFLO_LAUNCH((k_sum<LPT, T>), fin, st, m.ref(), (const u32*)d_workspace, (size_t)nb, (u32*)d_out, 1)
+  if (nb == 1) {
+#define CALL(LPT, T) HAFLO_LAUNCH((k_sum<LPT, T>), sh, st, m.ref(), (const u32*)d_c, count, (u32*)d_out, 1)
+    HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+    return hip_status(hipGetLastError());
+  }
+#define CALL(LPT, T) HAFLO_LAUNCH((k_sum<LPT, T>), sh, st, m.ref(), (const u32*)d_c, count, buf[0], 0)
   HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
+  // Further levels: one partial per lane group and a tree inside the block, in the wide geometry
+  // (few integers are left and every level is a chain of only log2(groups) + 1 products).
+  size_t n = (size_t)nb;
+  int from = 0;
+  while (n > 1) {
+    LaunchShape lv;
+    lv.threads = kBlockThreads;
+    lv.gpb = gpw;
+    lv.blocks = (int)((n + gpw - 1) / gpw);
+    const bool last = lv.blocks == 1;
+    u32* dst = last ? (u32*)d_out : buf[from ^ 1];
+    const u32* src = buf[from];
+#define CALL(LPT, T) HAFLO_LAUNCH((k_sum<LPT, T>), lv, st, m.ref(), src, n, dst, last ? 1 : 0)
+    HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL);
+#undef CALL
+    n = (size_t)lv.blocks;
+    from ^= 1;
+  }
   return hip_status(hipGetLastError());
 }
 

@@ -494,6 +494,23 @@ def test_host_staging_roundtrip(env):
     assert lib.haflo_stager_create(ctx, 0, 0, C.byref(st)) == -1
 
 
+def test_summation_levels(env):
+    """Enough elements for two first-level blocks on the one-unit emulated chip, so that the
+    second (wide-geometry) level runs."""
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    rng = random.Random(71)
+    count = 600
+    cs = [rng.randrange(1, pk.nsq) for _ in range(count)]
+    d_c = zeros(lib, (count, nlw))
+    assert lib.haflo_import_cipher(ctx, words(lib, cs, BITS // 16).p, d_c.p, None, count, None) == 0
+    w, nb = ws(lib, ctx, _cabi.OP_MATVEC_XT_D, count, 1)
+    d_s = zeros(lib, (1, nlw))
+    assert lib.haflo_cipher_sum(ctx, d_c.p, count, d_s.p, w.p, nb, None) == 0
+    assert export(lib, ctx, d_s, 1) == [O.summation(pk, cs)]
+    assert lib.haflo_cipher_sum(ctx, d_c.p, count, d_s.p, w.p, 64, None) == -1
+
+
 def test_encode_decode(env):
     lib, ctx, sk, nlw = env
     pk = sk.public
