@@ -43,10 +43,6 @@ __host__ __device__ inline int digit_positions(unsigned maxmag) {
     if ((unsigned long long)maxmag + digit_offset(s) < (1ull << (kDigitBits * s))) return s;
   return kMaxPos;
 }
-__device__ __forceinline__ size_t bucket_key(size_t cols, size_t j, int s, bool negative, u32 mag) {
-  return ((((size_t)s * cols + j) * 2 + (negative ? 1 : 0)) * (size_t)kMags) + (mag - 1u);
-}
-
 __global__ __launch_bounds__(kBlockThreads) void k_bk_zero(u32* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
@@ -70,32 +66,73 @@ __device__ __forceinline__ u32 wave_max(u32 m) {
 }
 
 // Every non-zero digit of every entry, always over kMaxPos positions (positions above the largest
-// magnitude only hold zero digits). SCATTER = false: cnt[key] = bucket sizes, stats[kStatMaxMag] = largest
-// |x|. SCATTER = true: sorted[off[key] + n] = row, with n counted in cnt (zero at launch).
+// magnitude only hold zero digits). A block takes kTermRows rows of one column and counts its digits in
+// LDS first, so that global memory sees one atomic per bucket and block instead of one per digit.
+// SCATTER = false: cnt[key] += bucket sizes, stats[kStatMaxMag] = largest |x|.
+// SCATTER = true: cnt[] are running cursors (zero at launch); the block reserves its share of every
+// bucket with one atomic, then writes sorted[off[key] + reserved + rank inside the block] = row.
+constexpr int kTermRows = 8192;
+constexpr int kLocalKeys = kMaxPos * 2 * kMags;  // buckets of one column
 template <bool SCATTER>
 __global__ __launch_bounds__(kBlockThreads) void k_bk_terms(const int* __restrict__ X, size_t rows, size_t cols,
                                                             u32* __restrict__ cnt, const u32* __restrict__ off,
                                                             u32* __restrict__ sorted, u32* __restrict__ stats) {
+  __shared__ u32 hist[kLocalKeys];
+  __shared__ u32 reserved[SCATTER ? kLocalKeys : 1];
   const unsigned long long offset = digit_offset(kMaxPos);
-  const size_t total = rows * cols;
+  const size_t j = (size_t)blockIdx.x % cols;
+  const size_t r0 = ((size_t)blockIdx.x / cols) * kTermRows;
+  const size_t r1 = r0 + kTermRows < rows ? r0 + kTermRows : rows;
+  for (int l = (int)threadIdx.x; l < kLocalKeys; l += kBlockThreads) hist[l] = 0u;
+  __syncthreads();
+  // local bucket index (position * 2 + sign) * 512 + magnitude - 1 of digit s of entry x, or -1
+  auto local_key = [&](int x, int s) -> int {
+    const u32 mag = x < 0 ? 0u - (u32)x : (u32)x;
+    const int d = (int)((((unsigned long long)mag + offset) >> (s * kDigitBits)) & 1023ull) - 512;
+    if (d == 0) return -1;
+    const int negative = ((x < 0) != (d < 0)) ? 1 : 0;
+    return (s * 2 + negative) * kMags + (d < 0 ? -d : d) - 1;
+  };
+  auto global_key = [&](int l) -> size_t {
+    const int s = l / (2 * kMags), rest = l - s * 2 * kMags;
+    return (((size_t)s * cols + j) * 2) * (size_t)kMags + (size_t)rest;
+  };
   u32 largest = 0;
-  for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
-    const int x = X[e];
+  for (size_t i = r0 + threadIdx.x; i < r1; i += kBlockThreads) {
+    const int x = X[i * cols + j];
     if (x == 0) continue;
-    const size_t i = e / cols, j = e - i * cols;
     const u32 mag = x < 0 ? 0u - (u32)x : (u32)x;
     largest = mag > largest ? mag : largest;
     for (int s = 0; s < kMaxPos; ++s) {
-      const int d = (int)((((unsigned long long)mag + offset) >> (s * kDigitBits)) & 1023ull) - 512;
-      if (d == 0) continue;
-      const size_t key = bucket_key(cols, j, s, (x < 0) != (d < 0), (u32)(d < 0 ? -d : d));
-      const u32 n = atomicAdd(&cnt[key], 1u);
-      if (SCATTER) sorted[(size_t)off[key] + n] = (u32)i;
+      const int l = local_key(x, s);
+      if (l >= 0) atomicAdd(&hist[l], 1u);
+    }
+  }
+  __syncthreads();
+  for (int l = (int)threadIdx.x; l < kLocalKeys; l += kBlockThreads) {
+    const u32 c = hist[l];
+    if (c == 0u) continue;
+    const u32 before = atomicAdd(&cnt[global_key(l)], c);
+    if (SCATTER) {
+      reserved[l] = before;
+      hist[l] = 0u;  // from here on the rank inside the block
     }
   }
   if (!SCATTER) {
     largest = wave_max(largest);
     if ((threadIdx.x & (WAVE - 1)) == 0 && largest) atomicMax(&stats[kStatMaxMag], largest);
+    return;
+  }
+  __syncthreads();
+  for (size_t i = r0 + threadIdx.x; i < r1; i += kBlockThreads) {
+    const int x = X[i * cols + j];
+    if (x == 0) continue;
+    for (int s = 0; s < kMaxPos; ++s) {
+      const int l = local_key(x, s);
+      if (l < 0) continue;
+      const u32 rank = atomicAdd(&hist[l], 1u);
+      sorted[(size_t)off[global_key(l)] + reserved[l] + rank] = (u32)i;
+    }
   }
 }
 
@@ -483,7 +520,10 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
   // offs(0) = positions in the sorted row array; offs(r + 1) = chunk offsets of round r = item offsets of round r + 1
   auto offs = [&](int idx) { return ws + p.off_offs + (size_t)idx * (K + 1); };
   u32* sorted = ws + p.off_sorted;
-  const LaunchShape flat = launch_shape(ctx, rows * cols, 1, 8);
+  LaunchShape flat;  // one block per column and kTermRows rows
+  flat.threads = kBlockThreads;
+  flat.gpb = kBlockThreads;
+  flat.blocks = (int)(cols * ((rows + kTermRows - 1) / kTermRows));
   const LaunchShape fill = launch_shape(ctx, kStatWords + 2 * K, 1, 8);
   LaunchShape scan;
   scan.blocks = (int)p.scan_blocks;
