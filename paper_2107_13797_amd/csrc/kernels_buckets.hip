@@ -50,21 +50,6 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_zero(u32* p, size_t n) {
 // Words of the statistics block at the start of the workspace (zeroed with the counters).
 enum { kStatMaxMag = 0, kStatMaxCount = 1, kStatNextChunk = 2, kStatWords = 16 };
 
-// largest value of `m` over the wavefront, bit by bit from the top: keep the lanes that still can hold it
-__device__ __forceinline__ u32 wave_max(u32 m) {
-  u32 best = 0;
-  bool cand = true;
-#pragma unroll 1
-  for (int b = 31; b >= 0; --b) {
-    bool has = cand && ((m >> b) & 1u);
-    if (__builtin_amdgcn_ballot_w64(has) != 0ull) {
-      best |= 1u << b;
-      cand = has;
-    }
-  }
-  return best;
-}
-
 // Every non-zero digit of every entry, always over kMaxPos positions (positions above the largest
 // magnitude only hold zero digits). A block takes kTermRows rows of one column and counts its digits in
 // LDS first, so that global memory sees one atomic per bucket and block instead of one per digit.

@@ -51,6 +51,21 @@ __device__ __forceinline__ void partial_norm(u32 (&x)[LPT], const Grp<T>& g) {
   if (T > 1) x[0] += g.from_lower(c);
 }
 
+// largest value of `m` over the wavefront, bit by bit from the top: keep the lanes that still can hold it
+__device__ __forceinline__ u32 wave_max(u32 m) {
+  u32 best = 0;
+  bool cand = true;
+#pragma unroll 1
+  for (int b = 31; b >= 0; --b) {
+    bool has = cand && ((m >> b) & 1u);
+    if (__builtin_amdgcn_ballot_w64(has) != 0ull) {
+      best |= 1u << b;
+      cand = has;
+    }
+  }
+  return best;
+}
+
 // Program storage for the exponentiation engine: a device array for long
 // programs (key-length exponents), an array inside the kernel arguments for
 // short ones (64-bit exponents), so that no device memory has to be allocated

@@ -261,17 +261,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_maxmag(const int* __restrict_
     u32 mag = x < 0 ? 0u - (u32)x : (u32)x;
     m = mag > m ? mag : m;
   }
-  // wave maximum, bit by bit from the top: keep the lanes that still can hold it
-  u32 best = 0;
-  bool cand = true;
-#pragma unroll 1
-  for (int b = 31; b >= 0; --b) {
-    bool has = cand && ((m >> b) & 1u);
-    if (__builtin_amdgcn_ballot_w64(has) != 0ull) {
-      best |= 1u << b;
-      cand = has;
-    }
-  }
+  const u32 best = wave_max(m);
   if ((threadIdx.x & (WAVE - 1)) == 0 && best) atomicMax(maxmag, best);
 }
 __device__ __forceinline__ int bit_length(u32 v) { return v ? 32 - __builtin_clz(v) : 0; }
