@@ -7,7 +7,8 @@
  * encryption, decryption, ciphertext addition, ciphertext-by-plaintext
  * multiplication, summation and matrix multiplication), over arrays that stay
  * resident in GPU memory between calls (the paper's "cached results" workflow,
- * Section 3.3, reduced to "the caller keeps the device pointer").
+ * Section 3.3): the caller keeps the device pointers, or lets a haflo_store
+ * manage them behind handles (end of this file).
  *
  * Conventions shared by every entry point
  * ---------------------------------------
@@ -53,7 +54,7 @@ extern "C" {
 #define HAFLO_EKEY (-2)    /* unusable key material */
 #define HAFLO_ENOPRIV (-3) /* private-key operation on a public-only context */
 #define HAFLO_EHIP (-4)    /* the HIP runtime reported an error */
-#define HAFLO_ENOMEM (-5)  /* host or device allocation for the context failed */
+#define HAFLO_ENOMEM (-5)  /* host or device allocation failed, or a store's arena is exhausted */
 
 /* Per-element status bits written by encode / decode / import. */
 #define HAFLO_ST_OK 0u
@@ -312,6 +313,92 @@ int haflo_stage_in_plain(haflo_stager* s, const uint32_t* h_plain, uint32_t* d_p
 int haflo_stage_out_cipher(haflo_stager* s, const void* d_cipher, uint32_t* h_canon, size_t count, void* stream);
 /* d_plain: device, count*Lp uint32 (produced on `stream`) -> h_plain: host. */
 int haflo_stage_out_plain(haflo_stager* s, const uint32_t* d_plain, uint32_t* h_plain, size_t count, void* stream);
+
+/*
+ * Managed device-resident operands (paper section 3.3, "Operator-level
+ * Computation Optimizer": results stay in GPU memory, the framework holds a
+ * handle for each and passes handles back as operands; the workflow figure of
+ * that section chains eight operators this way, and an allocator of the
+ * library's own serves the cached results).
+ * A store sub-allocates one device arena supplied by the caller (d_arena:
+ * device, 256-byte aligned, arena_bytes long; it stays the caller's and must
+ * outlive the store). Objects are typed arrays (enum haflo_kind) named by a
+ * haflo_handle; 0 is never a valid handle and a handle dies with its object.
+ * `uses` is the number of operator calls that will consume the object: the
+ * call that consumes it last frees it (haflo_h_add and the scalar
+ * multiplications then write their result into its block instead of a new
+ * one); uses = 0 keeps the object until haflo_store_release. A call that fails
+ * consumes nothing and leaves no new object. An operand that appears twice in
+ * one call gives up two uses. When the arena cannot hold a result or the
+ * call's temporary workspace the call fails with HAFLO_ENOMEM (nothing is
+ * moved to the host).
+ * All device work of a store is enqueued on the stream given at creation, and
+ * calls return without synchronising (haflo_h_download to host memory
+ * excepted). A store belongs to one host thread at a time.
+ * haflo_store_info gives the device address of an object, so that any
+ * pointer-based entry point above can read or fill it on the same stream.
+ */
+typedef struct haflo_store haflo_store;
+typedef uint64_t haflo_handle;
+enum haflo_kind {
+  HAFLO_KIND_CIPHER = 1, /* internal ciphertext elements */
+  HAFLO_KIND_PLAIN = 2,  /* plaintext residues, Lp uint32 each (also the random r of encryption) */
+  HAFLO_KIND_F32 = 3,
+  HAFLO_KIND_F64 = 4,
+  HAFLO_KIND_I32 = 5, /* matrix exponents */
+  HAFLO_KIND_U32 = 6, /* status words */
+  HAFLO_KIND_I64 = 7,
+  HAFLO_KIND_U64 = 8 /* per-element scalars */
+};
+int haflo_store_create(const haflo_ctx* ctx, void* d_arena, size_t arena_bytes, void* stream, haflo_store** out);
+/* Forgets every object; the arena is untouched and remains the caller's. */
+int haflo_store_destroy(haflo_store* s);
+/* Bytes in use now (objects, 256-byte granules), the highest value that figure has
+ * reached (temporaries included), live objects, the largest free block. Outputs may be NULL. */
+int haflo_store_stats(const haflo_store* s, size_t* live_bytes, size_t* peak_bytes, size_t* live_objects,
+                      size_t* largest_free);
+/* An uninitialised object of `count` elements. */
+int haflo_store_new(haflo_store* s, int kind, size_t count, uint32_t uses, haflo_handle* out);
+/* Kind, element count, device address and uses left of an object; outputs may be NULL.
+ * HAFLO_EINVAL for a handle that is not (or no longer) valid. */
+int haflo_store_info(const haflo_store* s, haflo_handle h, int* kind, size_t* count, void** d_ptr,
+                     uint32_t* uses_left);
+/* Frees an object whatever uses it has left. */
+int haflo_store_release(haflo_store* s, haflo_handle h);
+/* A new object filled with `count` elements from src (host memory when src_on_host is
+ * non-zero, else device memory). Pageable host memory is copied before the call returns. */
+int haflo_h_upload(haflo_store* s, int kind, const void* src, int src_on_host, size_t count, uint32_t uses,
+                   haflo_handle* out);
+/* Copies an object out (one use); to host memory the call waits for the stream. */
+int haflo_h_download(haflo_store* s, haflo_handle h, void* dst, int dst_on_host);
+/* The operators of the paper's Table 2 over handles; semantics, value ranges and status bits
+ * are those of the pointer-based entry point each one wraps. `status`, where present, may be
+ * NULL; otherwise it receives a HAFLO_KIND_U32 object (one word per element) with one use. */
+/* haflo_encode_f32: F32 -> PLAIN */
+int haflo_h_encode(haflo_store* s, haflo_handle values, uint32_t scale_bits, uint32_t uses, haflo_handle* plain,
+                   haflo_handle* status);
+/* haflo_encode_exponents_f32: F32 -> I32 */
+int haflo_h_encode_exponents(haflo_store* s, haflo_handle values, uint32_t scale_bits, uint32_t uses,
+                             haflo_handle* exponents, haflo_handle* status);
+/* haflo_decode: PLAIN -> F64 */
+int haflo_h_decode(haflo_store* s, haflo_handle plain, uint32_t scale_bits, uint32_t uses, haflo_handle* values,
+                   haflo_handle* status);
+/* haflo_encrypt: PLAIN, PLAIN (r) -> CIPHER */
+int haflo_h_encrypt(haflo_store* s, haflo_handle plain, haflo_handle r, uint32_t uses, haflo_handle* cipher);
+/* haflo_decrypt: CIPHER -> PLAIN */
+int haflo_h_decrypt(haflo_store* s, haflo_handle cipher, uint32_t uses, haflo_handle* plain);
+/* haflo_add: CIPHER, CIPHER -> CIPHER */
+int haflo_h_add(haflo_store* s, haflo_handle a, haflo_handle b, uint32_t uses, haflo_handle* out);
+/* haflo_scalar_mul_i64_bcast: CIPHER -> CIPHER */
+int haflo_h_scalar_mul(haflo_store* s, haflo_handle cipher, int64_t k, uint32_t uses, haflo_handle* out);
+/* haflo_scalar_mul_u64: CIPHER, U64 -> CIPHER */
+int haflo_h_scalar_mul_each(haflo_store* s, haflo_handle cipher, haflo_handle scalars, uint32_t uses,
+                            haflo_handle* out);
+/* haflo_cipher_matvec: CIPHER, I32 (rows*cols, row-major) -> CIPHER */
+int haflo_h_matvec(haflo_store* s, int orientation, haflo_handle cipher, haflo_handle exponents, size_t rows,
+                   size_t cols, uint32_t uses, haflo_handle* out);
+/* haflo_cipher_sum: CIPHER -> CIPHER (one element) */
+int haflo_h_sum(haflo_store* s, haflo_handle cipher, uint32_t uses, haflo_handle* out);
 
 #ifdef __cplusplus
 }

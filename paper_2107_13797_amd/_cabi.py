@@ -50,7 +50,29 @@ PROTOTYPES = {
     "haflo_encrypt_with_obfuscator": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p, c_size_t,
                                               c_void_p]),
     "haflo_cipher_sum": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "haflo_store_create": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p, C.POINTER(c_void_p)]),
+    "haflo_store_destroy": (c_int, [c_void_p]),
+    "haflo_store_stats": (c_int, [c_void_p, C.POINTER(c_size_t), C.POINTER(c_size_t), C.POINTER(c_size_t),
+                                  C.POINTER(c_size_t)]),
+    "haflo_store_new": (c_int, [c_void_p, c_int, c_size_t, c_u32, C.POINTER(c_u64)]),
+    "haflo_store_info": (c_int, [c_void_p, c_u64, C.POINTER(c_int), C.POINTER(c_size_t), C.POINTER(c_void_p),
+                                 C.POINTER(c_u32)]),
+    "haflo_store_release": (c_int, [c_void_p, c_u64]),
+    "haflo_h_upload": (c_int, [c_void_p, c_int, c_void_p, c_int, c_size_t, c_u32, C.POINTER(c_u64)]),
+    "haflo_h_download": (c_int, [c_void_p, c_u64, c_void_p, c_int]),
+    "haflo_h_encode": (c_int, [c_void_p, c_u64, c_u32, c_u32, C.POINTER(c_u64), C.POINTER(c_u64)]),
+    "haflo_h_encode_exponents": (c_int, [c_void_p, c_u64, c_u32, c_u32, C.POINTER(c_u64), C.POINTER(c_u64)]),
+    "haflo_h_decode": (c_int, [c_void_p, c_u64, c_u32, c_u32, C.POINTER(c_u64), C.POINTER(c_u64)]),
+    "haflo_h_encrypt": (c_int, [c_void_p, c_u64, c_u64, c_u32, C.POINTER(c_u64)]),
+    "haflo_h_decrypt": (c_int, [c_void_p, c_u64, c_u32, C.POINTER(c_u64)]),
+    "haflo_h_add": (c_int, [c_void_p, c_u64, c_u64, c_u32, C.POINTER(c_u64)]),
+    "haflo_h_scalar_mul": (c_int, [c_void_p, c_u64, c_i64, c_u32, C.POINTER(c_u64)]),
+    "haflo_h_scalar_mul_each": (c_int, [c_void_p, c_u64, c_u64, c_u32, C.POINTER(c_u64)]),
+    "haflo_h_matvec": (c_int, [c_void_p, c_int, c_u64, c_u64, c_size_t, c_size_t, c_u32, C.POINTER(c_u64)]),
+    "haflo_h_sum": (c_int, [c_void_p, c_u64, c_u32, C.POINTER(c_u64)]),
 }
+
+KIND_CIPHER, KIND_PLAIN, KIND_F32, KIND_F64, KIND_I32, KIND_U32, KIND_I64, KIND_U64 = 1, 2, 3, 4, 5, 6, 7, 8
 
 OP_ENCRYPT, OP_DECRYPT, OP_SCALAR_MUL, OP_MATVEC_XT_D, OP_MATVEC_X_W, OP_FORE_GRADIENT, OP_TAYLOR_LOSS, OP_ENCRYPT_OBFUSCATOR = 1, 2, 3, 4, 5, 6, 7, 8
 

@@ -324,3 +324,104 @@ def haflo_stage_out_plain(stager, plain):
     h = np.empty((plain.shape[0], stager.ctx.plain_limbs), dtype=np.uint32)
     _check(lib().haflo_stage_out_plain(stager.handle, _ptr(plain), h.ctypes.data, plain.shape[0], _stream()))
     return h
+
+
+class Store:
+    """Owner of a haflo_store over an arena tensor: operands and results named by integer handles.
+
+    Methods mirror the haflo_h_* entry points; `uses` is the number of operator calls that will
+    consume the result (0 = until release()).
+    """
+
+    def __init__(self, ctx, arena_bytes):
+        self.ctx = ctx
+        self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
+        h = C.c_void_p()
+        _check(lib().haflo_store_create(ctx.handle, _ptr(self.arena), arena_bytes, _stream(), C.byref(h)))
+        self.handle = h
+
+    def stats(self):
+        a, b, c, d = C.c_size_t(), C.c_size_t(), C.c_size_t(), C.c_size_t()
+        _check(lib().haflo_store_stats(self.handle, C.byref(a), C.byref(b), C.byref(c), C.byref(d)))
+        return {"live_bytes": a.value, "peak_bytes": b.value, "live_objects": c.value, "largest_free": d.value}
+
+    def info(self, h):
+        kind, count, ptr, uses = C.c_int(), C.c_size_t(), C.c_void_p(), C.c_uint32()
+        _check(lib().haflo_store_info(self.handle, h, C.byref(kind), C.byref(count), C.byref(ptr), C.byref(uses)))
+        return {"kind": kind.value, "count": count.value, "ptr": ptr.value, "uses": uses.value}
+
+    def release(self, h):
+        _check(lib().haflo_store_release(self.handle, h))
+
+    def upload(self, kind, tensor, uses=1):
+        """A device tensor's elements as a new object; `kind` says how its words are read."""
+        t = tensor.contiguous()
+        words = {_cabi.KIND_CIPHER: self.ctx.cipher_words, _cabi.KIND_PLAIN: self.ctx.plain_limbs}.get(kind)
+        count = t.numel() // words if words else t.numel()
+        h = C.c_uint64()
+        _check(lib().haflo_h_upload(self.handle, kind, _ptr(t), 0, count, uses, C.byref(h)))
+        return h.value
+
+    def download(self, h):
+        """The object's contents as a new device tensor (consumes one use)."""
+        i = self.info(h)
+        shapes = {_cabi.KIND_CIPHER: ((i["count"], self.ctx.cipher_words), torch.int32),
+                  _cabi.KIND_PLAIN: ((i["count"], self.ctx.plain_limbs), torch.int32),
+                  _cabi.KIND_F32: ((i["count"],), torch.float32), _cabi.KIND_F64: ((i["count"],), torch.float64),
+                  _cabi.KIND_I32: ((i["count"],), torch.int32), _cabi.KIND_U32: ((i["count"],), torch.int32),
+                  _cabi.KIND_I64: ((i["count"],), torch.int64), _cabi.KIND_U64: ((i["count"],), torch.int64)}
+        shape, dtype = shapes[i["kind"]]
+        out = torch.empty(shape, dtype=dtype, device="cuda")
+        _check(lib().haflo_h_download(self.handle, h, _ptr(out), 0))
+        return out
+
+    def _call(self, fn, *args, status=False):
+        out, st = C.c_uint64(), C.c_uint64()
+        if status is None:
+            _check(fn(self.handle, *args, C.byref(out)))
+            return out.value
+        _check(fn(self.handle, *args, C.byref(out), C.byref(st) if status else None))
+        return (out.value, st.value) if status else out.value
+
+    def encode(self, values, scale_bits, uses=1, status=False):
+        return self._call(lib().haflo_h_encode, values, scale_bits, uses, status=status)
+
+    def encode_exponents(self, values, scale_bits, uses=1, status=False):
+        return self._call(lib().haflo_h_encode_exponents, values, scale_bits, uses, status=status)
+
+    def decode(self, plain, scale_bits, uses=1, status=False):
+        return self._call(lib().haflo_h_decode, plain, scale_bits, uses, status=status)
+
+    def encrypt(self, plain, r, uses=1):
+        return self._call(lib().haflo_h_encrypt, plain, r, uses, status=None)
+
+    def decrypt(self, cipher, uses=1):
+        return self._call(lib().haflo_h_decrypt, cipher, uses, status=None)
+
+    def add(self, a, b, uses=1):
+        return self._call(lib().haflo_h_add, a, b, uses, status=None)
+
+    def scalar_mul(self, cipher, k, uses=1):
+        return self._call(lib().haflo_h_scalar_mul, cipher, int(k), uses, status=None)
+
+    def scalar_mul_each(self, cipher, scalars, uses=1):
+        return self._call(lib().haflo_h_scalar_mul_each, cipher, scalars, uses, status=None)
+
+    def matvec(self, orientation, cipher, exponents, rows, cols, uses=1):
+        return self._call(lib().haflo_h_matvec, orientation, cipher, exponents, rows, cols, uses, status=None)
+
+    def sum(self, cipher, uses=1):
+        return self._call(lib().haflo_h_sum, cipher, uses, status=None)
+
+    def close(self):
+        if self.handle is not None:
+            torch.cuda.synchronize()
+            lib().haflo_store_destroy(self.handle)
+            self.handle = None
+            self.arena = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhaflo.so")
-SOURCES = ["ctx.cpp", "staging.cpp", "kernels_basic.hip", "kernels_modexp.hip", "kernels_matvec.hip", "kernels_buckets.hip", "kernels_loss.hip"]
+SOURCES = ["ctx.cpp", "staging.cpp", "store.cpp", "kernels_basic.hip", "kernels_modexp.hip", "kernels_matvec.hip", "kernels_buckets.hip", "kernels_loss.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-x", "hip",

@@ -11,7 +11,7 @@ OUT = os.path.join(HERE, "libhaflo_emu.so")
 
 
 def build():
-    srcs = [os.path.join(CSRC, "ctx.cpp"), os.path.join(CSRC, "staging.cpp")] + sorted(glob.glob(os.path.join(CSRC, "kernels_*.hip")))
+    srcs = [os.path.join(CSRC, "ctx.cpp"), os.path.join(CSRC, "staging.cpp"), os.path.join(CSRC, "store.cpp")] + sorted(glob.glob(os.path.join(CSRC, "kernels_*.hip")))
     srcs.append(os.path.join(HERE, "hipemu.cpp"))
     newest = max(os.path.getmtime(p) for p in srcs + glob.glob(os.path.join(CSRC, "*.hpp")) +
                  [os.path.join(HERE, "include", "hip", "hip_runtime.h")])

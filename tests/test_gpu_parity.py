@@ -565,6 +565,66 @@ def test_hetero_lr_iteration_end_to_end(api):
         assert abs(got - want) < 6000 * 5.0 * 2.0 ** -16  # entries of X are quantised to 2^-16
 
 
+def test_store_chain_over_handles(api):
+    """The fore gradient and the encrypted gradient as a chain of basic operators over handles
+    (encode, encrypt, add, scalar_mul, add, matvec, decrypt, decode) with the store freeing every
+    intermediate at its last use: ciphertexts equal the oracle's for the same chain on a sample,
+    equal the pointer-based calls everywhere, and the decoded gradient equals exact integers."""
+    from paper_2107_13797_amd import _cabi as K
+    bits, count, cols, s, sx = 1024, 5000, 6, 20, 10
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    lp = bits // 32
+    vals = [synth.normal_f32(count, 2.0, 111), synth.normal_f32(count, 2.0, 112),
+            np.where(np.random.default_rng(113).random(count) < 0.5, -1.0, 1.0).astype(np.float32)]
+    rs = [random_units_words(count, bits, 114 + k) for k in range(3)]
+    Xf = synth.normal_f32((count, cols), 1.0, 117)
+    store = api.Store(ctx, 256 << 20)
+    enc = []
+    for v, r in zip(vals, rs):
+        hp, hs = store.encode(store.upload(K.KIND_F32, to_dev(v)), s, status=True)
+        assert int(store.download(hs).abs().sum()) == 0
+        enc.append(store.encrypt(hp, store.upload(K.KIND_PLAIN, to_dev(r))))
+    host_ptr = store.info(enc[0])["ptr"]
+    t = store.add(enc[0], enc[1])
+    d = store.add(t, store.scalar_mul(enc[2], -2), uses=2)
+    assert store.info(d)["ptr"] == host_ptr and store.stats()["live_objects"] == 1
+    hx = store.encode_exponents(store.upload(K.KIND_F32, to_dev(Xf)), sx)
+    d_copy = store.download(d)
+    g = store.matvec(0, d, hx, count, cols, uses=2)
+    assert store.stats()["live_objects"] == 1
+    g_copy = store.download(g)
+    q = store.download(store.decode(store.decrypt(g), s + sx + 2))
+    stats = store.stats()
+    assert stats["live_objects"] == 0 and stats["live_bytes"] == 0
+    say("store chain: peak bytes", stats["peak_bytes"])
+    # the pointer-based calls on the same inputs give the same words
+    c = [api.haflo_encrypt(ctx, api.haflo_encode_f32(ctx, to_dev(v), s), to_dev(r)) for v, r in zip(vals, rs)]
+    d_ref = api.haflo_add(ctx, api.haflo_add(ctx, c[0], c[1]), api.haflo_scalar_mul_i64_bcast(ctx, c[2], -2))
+    X = api.haflo_encode_exponents_f32(to_dev(Xf), sx)
+    assert torch.equal(d_copy, d_ref) and torch.equal(g_copy, api.haflo_cipher_matvec(ctx, 0, d_ref, X))
+    # the oracle runs the same chain on a sample
+    idx = sample_indices(count, 24, 118)
+    idx_t = torch.tensor(idx, device="cuda")
+    qs = [[O.quantise(float(v[i]), s) for i in idx] for v in vals]
+    co = [OP.encrypt_many(pk.n, [m % pk.n for m in qq], synth.words_to_ints(r[idx])) for qq, r in zip(qs, rs)]
+    want = [O.add(pk, O.add(pk, a, b), O.scalar_mul(pk, l, -2)) for a, b, l in zip(*co)]
+    assert dev_to_ints(api.haflo_export_cipher(ctx, d_copy[idx_t].contiguous())) == want
+    # the decoded gradient against exact integers
+    qv = [np.rint(v.astype(np.float64) * 2.0 ** s).astype(np.int64) for v in vals]
+    Xq = np.rint(Xf.astype(np.float64) * 2.0 ** sx).astype(np.int64)
+    exact = (Xq * (qv[0] + qv[1] - 2 * qv[2])[:, None]).sum(axis=0)
+    assert (q.cpu().numpy() * 2.0 ** (s + sx + 2)).tolist() == exact.astype(np.float64).tolist()
+    # an arena too small for the call reports it and keeps the operands
+    small = api.Store(ctx, 1 << 20)
+    hp = small.upload(K.KIND_PLAIN, to_dev(rs[0][:1000]), uses=2)
+    with pytest.raises(api.HafloError):
+        small.encrypt(hp, hp)
+    assert small.info(hp)["uses"] == 2
+    small.close()
+    store.close()
+
+
 def test_encrypt_with_obfuscator_matches_encrypt(api):
     """Offline/online split of the encryption: obfuscators r^n made ahead of time, then two
     products per element; the ciphertexts must be the ordinary ones (oracle on a sample)."""
