@@ -565,6 +565,20 @@ def test_hetero_lr_iteration_end_to_end(api):
         assert abs(got - want) < 6000 * 5.0 * 2.0 ** -16  # entries of X are quantised to 2^-16
 
 
+def test_homo_lr_round_end_to_end(api):
+    """One aggregation round of homogeneous LR over handles (key owners encrypt through p^2 and
+    q^2, the coordinator scales and adds under the public key): the decoded aggregate must be
+    the exact integer sum of the quantised local models weighted by the instance counts."""
+    from paper_2107_13797_amd.examples import homo_lr
+    bits = 1024
+    ctx, sk = context(api, bits)
+    pub = api.haflo_ctx_create_public(sk.public.n, bits)
+    res = homo_lr.run_round(api, pub, ctx, parties=5, weights=3000, seed=4)
+    pub.close()
+    assert res["sum_q"] == res["want_sum_q"]
+    assert max(abs(a - b) for a, b in zip(res["model"], res["float_model"])) < 2.0 ** -24
+
+
 def test_store_chain_over_handles(api):
     """The fore gradient and the encrypted gradient as a chain of basic operators over handles
     (encode, encrypt, add, scalar_mul, add, matvec, decrypt, decode) with the store freeing every
