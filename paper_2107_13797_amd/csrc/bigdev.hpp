@@ -304,7 +304,7 @@ __device__ __forceinline__ void sub_mod(u32 (&out)[LPT], const u32 (&a)[LPT], co
 template <int LPT, int T, bool WANT_HI>
 __device__ __forceinline__ void mul_plain(u32 (&lo)[LPT], u32 (&hi)[LPT], const u32 (&a)[LPT], const u32 (&b)[LPT],
                                           const Grp<T>& g) {
-  constexpr int NORM = (LPT <= 31) ? LPT : (LPT / 2);
+  static_assert(LPT <= 18, "a column must not collect more than 36 products");
   const u32 eight = opaque_eight();
   u64 A[LPT];
   u32 res[LPT];
@@ -336,10 +336,8 @@ __device__ __forceinline__ void mul_plain(u32 (&lo)[LPT], u32 (&hi)[LPT], const 
       }
     }
   }
-  // A column register lives LPT steps in a lane (it enters at the top as the 29 bits handed over by
-  // the lane above and leaves at the bottom) and takes two products per step: at most 2 * 18 products
-  // below 2^58.01 plus one carry below 2^36, which fits 64 bits without intermediate carry handling.
-  // One pass before the compression keeps the limbs and the carry to the next lane small.
+  // One product per column and step here, so the bound of montmul_core holds with room to spare;
+  // one pass before the compression keeps the limbs and the carry to the next lane small.
   hi_normalise<LPT, T>(A, g, eight);
   if (WANT_HI) {
     u64 c = 0;

@@ -2,9 +2,12 @@
 // inverse they need for negative exponents. Kernels and C entry points.
 //
 // X^T [[d]] (orientation 0): the bases c_i are shared by every output column,
-//   so each base gets a table of its first 2^w powers; output column j then is
-//   prod_s ( prod_i table_i[digit_s(|x_ij|)] )^(2^(w s)), with positive and
-//   negative entries collected separately and one inversion per column.
+//   so each base gets a table of its powers c_i^0..c_i^16; with signed 5-bit
+//   digits d_s of |x_ij| output column j is
+//   prod_s ( prod_i table_i[|d_s|] )^(32^s), with the terms of either sign
+//   collected separately and one inversion per column. Tall matrices take the
+//   bucket method of kernels_buckets.hip instead, which ends in the same
+//   per-column pair of products.
 // X [[w]] (orientation 1): the few bases c_j are shared by every output row,
 //   so each base (and its inverse) gets positional tables c_j^(d 2^(w s)); an
 //   output row is a plain product of table entries over its non-zero entries,
