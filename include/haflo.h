@@ -20,6 +20,10 @@
  *   in device memory) and frees it in haflo_ctx_destroy.
  * Streams: `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *   Device work is enqueued on it and the call returns without synchronising.
+ *   Operator calls enqueue kernels only (no allocation, no memset, no copy,
+ *   no read-back of device data), so a sequence of them can be captured into
+ *   a HIP graph and replayed on new contents of the same buffers; the
+ *   staging calls and the store's upload / download copy and may wait.
  * Workspace: operators that need temporary device memory take a caller-supplied
  *   workspace pointer and its size; haflo_workspace_bytes says how much is
  *   needed. The library never allocates device memory inside an operator call.
