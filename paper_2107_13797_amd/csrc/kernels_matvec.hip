@@ -11,7 +11,8 @@
 // X [[w]] (orientation 1): the few bases c_j are shared by every output row,
 //   so each base (and its inverse) gets positional tables c_j^(d 2^(w s)); an
 //   output row is a plain product of table entries over its non-zero entries,
-//   which are compacted per row first.
+//   which are compacted per row first; rows are processed in the order of
+//   their list lengths.
 #include "kernels_common.hpp"
 
 #include <stdlib.h>
@@ -254,8 +255,10 @@ __global__ __launch_bounds__(kBlockThreads) void k_invert(ModRef M, ModRef Mn, c
 // ---------------------------------------------------------------------------
 
 // largest |x| in the matrix (atomicMax into a zeroed word)
-__global__ __launch_bounds__(kBlockThreads) void k_zero_word(u32* p) {
-  if (blockIdx.x == 0 && threadIdx.x < 2) p[threadIdx.x] = 0u;  // the largest |x| and a work counter
+__global__ __launch_bounds__(kBlockThreads) void k_zero_word(u32* p, int n) {
+  // the largest |x|, a work counter and, for orientation 1, the histogram of list lengths
+  if (blockIdx.x == 0)
+    for (int i = (int)threadIdx.x; i < n; i += (int)blockDim.x) p[i] = 0u;
 }
 __global__ __launch_bounds__(kBlockThreads) void k_maxmag(const int* __restrict__ X, size_t total, u32* maxmag) {
   u32 m = 0;
@@ -505,11 +508,21 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_tables_fill(ModRef M, size
   }
 }
 
+// Rows are handed to the wavefronts of k_xw_main in the order of their list lengths, longest
+// first, so that the rows a wavefront multiplies side by side finish together. The lengths are
+// sorted by counting in kLenBins classes.
+constexpr int kLenBins = 1024;
+__device__ __forceinline__ u32 length_bin(u32 len, size_t longest) {
+  return (u32)(((u64)len * (u64)(kLenBins - 1)) / (u64)(longest ? longest : 1));
+}
+
 // Per row: the list of table entries its product consists of, one per non-zero 8-bit digit
 // of every non-zero |X[row][c]|: entry index ((c*2 + sign)*kMaxPos + s)*256 + digit, in units of
-// one table entry. One wave per row; lists: rows * cols * kMaxPos words, counts: rows.
+// one table entry. One wave per row; lists: rows * cols * kMaxPos words, counts: rows;
+// bins[b] += rows whose list length falls into class b.
 __global__ __launch_bounds__(kBlockThreads) void k_xw_lists(const int* __restrict__ X, size_t rows, size_t cols,
                                                             u32* __restrict__ lists, u32* __restrict__ counts,
+                                                            u32* __restrict__ bins,
                                                             const u32* __restrict__ maxmag) {
   const int lane = (int)(threadIdx.x & (WAVE - 1));
   const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
@@ -533,17 +546,60 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_lists(const int* __restric
         written += (u32)__builtin_popcountll(mask);
       }
     }
-    if (lane == 0) counts[row] = written;
+    if (lane == 0) {
+      counts[row] = written;
+      atomicAdd(&bins[length_bin(written, cols * (size_t)npos)], 1u);
+    }
   }
 }
 
-// one group per output row: the product of the listed table entries. A wavefront takes the rows of its
-// own index first, then runs of rows drawn from a counter (zero at launch), so that rows with long
-// lists do not leave the rest of the chip waiting.
+// bins[b] = number of rows in longer classes than b: where class b starts in the sorted order.
+// One block.
+__global__ __launch_bounds__(kBlockThreads) void k_xw_order_scan(u32* __restrict__ bins) {
+  constexpr int PER = kLenBins / kBlockThreads;
+  __shared__ u32 part[kBlockThreads];
+  const int t = (int)threadIdx.x;
+  // thread t owns the classes kLenBins-1 - (t*PER + i), i = 0..PER-1, i.e. the order longest first
+  u32 own[PER], sum = 0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    own[i] = bins[kLenBins - 1 - (t * PER + i)];
+    sum += own[i];
+  }
+  part[t] = sum;
+  __syncthreads();
+  for (int d = 1; d < kBlockThreads; d <<= 1) {
+    u32 add = t >= d ? part[t - d] : 0u;
+    __syncthreads();
+    part[t] += add;
+    __syncthreads();
+  }
+  u32 run = part[t] - sum;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    bins[kLenBins - 1 - (t * PER + i)] = run;
+    run += own[i];
+  }
+}
+
+// order[position] = row, positions handed out per class from the cursors in bins[]
+__global__ __launch_bounds__(kBlockThreads) void k_xw_order_scatter(const u32* __restrict__ counts, size_t rows,
+                                                                    size_t cols, u32* __restrict__ bins,
+                                                                    u32* __restrict__ order,
+                                                                    const u32* __restrict__ maxmag) {
+  const int npos = (bit_length(*maxmag) + kWin - 1) / kWin;
+  for (size_t row = (size_t)blockIdx.x * blockDim.x + threadIdx.x; row < rows; row += (size_t)gridDim.x * blockDim.x)
+    order[atomicAdd(&bins[length_bin(counts[row], cols * (size_t)npos)], 1u)] = (u32)row;
+}
+
+// one group per output row: the product of the listed table entries. Rows are taken in the order
+// `order` (longest lists first): a wavefront takes the run of its own index first, then runs drawn from
+// a counter (zero at launch), so that rows with long lists do not leave the rest of the chip waiting.
 template <int LPT, int T>
 __global__ __launch_bounds__(kBlockThreads, 3) void k_xw_main(ModRef M, size_t rows, size_t list_stride,
                                                            const u32* __restrict__ lists,
                                                            const u32* __restrict__ counts,
+                                                           const u32* __restrict__ order,
                                                            const u32* __restrict__ tables, u32* __restrict__ next_row,
                                                            u32* __restrict__ out) {
   constexpr int NL = LPT * T;
@@ -555,8 +611,9 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_xw_main(ModRef M, size_t r
   const size_t nwaves = ((size_t)gridDim.x * blockDim.x) / WAVE;
   size_t r0 = (((size_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE) * GW;
   while (r0 < rows) {
-    const size_t row = r0 + (size_t)(lane / T);
-    const bool active = row < rows;
+    const size_t ridx = r0 + (size_t)(lane / T);
+    const bool active = ridx < rows;
+    const size_t row = active ? (size_t)order[ridx] : 0;
     const u32 cnt = active ? counts[row] : 0u;
     const u32* mine = lists + (active ? row : 0) * list_stride;
     auto entry = [&](u32 e) -> const u32* { return (e < cnt) ? tables + (size_t)mine[e] * NL : M.r1; };
@@ -653,16 +710,20 @@ XtdBucketLayout xtd_bucket_layout(const haflo_ctx* ctx, size_t rows, size_t cols
 }
 
 struct XwPlan {
-  size_t off_inv, off_tables, off_nz, off_cnt, total;  // in u32 words; word 0 holds the largest |x|
+  // in u32 words; word 0 holds the largest |x|, word 1 the row counter of k_xw_main, words
+  // [kXwBinsAt, kXwBinsAt + kLenBins) the length classes
+  size_t off_inv, off_tables, off_nz, off_cnt, off_order, total;
 };
+constexpr size_t kXwBinsAt = 64;
 XwPlan xw_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
   XwPlan p;
   const size_t nl = (size_t)ctx->N.nl;
-  p.off_inv = 64;
+  p.off_inv = kXwBinsAt + kLenBins;
   p.off_tables = p.off_inv + cols * nl;
   p.off_nz = p.off_tables + cols * 2 * kMaxPos * kWinEntries * nl;
   p.off_cnt = p.off_nz + rows * cols * kMaxPos;
-  p.total = p.off_cnt + rows;
+  p.off_order = p.off_cnt + rows;
+  p.total = p.off_order + rows;
   return p;
 }
 
@@ -674,12 +735,12 @@ int sum_blocks(const haflo_ctx* ctx, size_t count) {
   return (int)(need < cap ? need : cap);
 }
 
-int launch_maxmag(const haflo_ctx* ctx, const int32_t* X, size_t total, u32* word, hipStream_t st) {
+int launch_maxmag(const haflo_ctx* ctx, const int32_t* X, size_t total, u32* word, int zero_words, hipStream_t st) {
   LaunchShape one;
   one.blocks = 1;
-  one.threads = 64;
-  one.gpb = 64;
-  HAFLO_LAUNCH(k_zero_word, one, st, word);
+  one.threads = kBlockThreads;
+  one.gpb = kBlockThreads;
+  HAFLO_LAUNCH(k_zero_word, one, st, word, zero_words);
   if (total) {
     LaunchShape sh = launch_shape(ctx, total, 1, 8);
     HAFLO_LAUNCH(k_maxmag, sh, st, X, total, word);
@@ -738,7 +799,8 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
   if (!d_workspace || workspace_bytes < need) return HAFLO_EINVAL;
   u32* ws = (u32*)d_workspace;
   const bool buckets = orientation == 0 && use_buckets(rows, cols);
-  int rc = buckets ? HAFLO_OK : launch_maxmag(ctx, d_X, rows * cols, ws, st);
+  int rc = buckets ? HAFLO_OK
+                   : launch_maxmag(ctx, d_X, rows * cols, ws, orientation == 0 ? 2 : (int)(kXwBinsAt + kLenBins), st);
   if (rc != HAFLO_OK) return rc;
   const int nbatch = inverse_batches(ctx);
   if (buckets) {
@@ -808,15 +870,24 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
 #undef CALL
       }
     }
+    u32* bins = ws + kXwBinsAt;
+    u32* order = ws + p.off_order;
     {
       const LaunchShape sh = launch_shape(ctx, rows, 64, 8);
-      HAFLO_LAUNCH(k_xw_lists, sh, st, d_X, rows, cols, lists, cnt, (const u32*)ws);
+      HAFLO_LAUNCH(k_xw_lists, sh, st, d_X, rows, cols, lists, cnt, bins, (const u32*)ws);
+      LaunchShape one;
+      one.blocks = 1;
+      one.threads = kBlockThreads;
+      one.gpb = kBlockThreads;
+      HAFLO_LAUNCH(k_xw_order_scan, one, st, bins);
+      const LaunchShape per_row = launch_shape(ctx, rows, 1, 8);
+      HAFLO_LAUNCH(k_xw_order_scatter, per_row, st, (const u32*)cnt, rows, cols, bins, order, (const u32*)ws);
     }
     {
       const LaunchShape sh = launch_shape(ctx, rows, m.t, 3);
 #define CALL(LPT, T)                                                                                          \
   HAFLO_LAUNCH((k_xw_main<LPT, T>), sh, st, m.ref(), rows, cols * (size_t)kMaxPos, (const u32*)lists,         \
-               (const u32*)cnt, (const u32*)tables, ws + 1, (u32*)d_out)
+               (const u32*)cnt, (const u32*)order, (const u32*)tables, ws + 1, (u32*)d_out)
       HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
     }
