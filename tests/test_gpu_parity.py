@@ -392,13 +392,19 @@ def test_edges_matvec(api, bits, method, monkeypatch):
     Y[4, :] = 1
     cases.append((1, Y))
     cases.append((1, np.eye(nc, dtype=np.int32)[:9]))
+    Z = np.zeros((4, nc), dtype=np.int32)   # all four digit positions of the positional tables
+    Z[0, 0], Z[0, 1], Z[1, 2], Z[2, 3] = -2 ** 31, 2 ** 31 - 1, 1 << 24, -((1 << 24) + 255)
+    cases.append((1, Z))
+    cases.append((1, np.zeros((5, 0), dtype=np.int32)))          # no columns: five empty products
+    cases.append((0, np.zeros((0, 3), dtype=np.int32)))          # no rows: three empty products
     for orientation, M in cases:
         if orientation == 1 and method == "buckets":
             continue  # orientation 1 has a single implementation
-        used = ci[:M.shape[0]].contiguous() if orientation == 0 else ci
+        used = ci[:M.shape[0]].contiguous() if orientation == 0 else ci[:M.shape[1]].contiguous()
         out = api.haflo_cipher_matvec(ctx, orientation, used, to_dev(M))
-        assert dev_to_ints(api.haflo_export_cipher(ctx, out)) == O.matvec(pk, orientation, cs[:used.shape[0]],
-                                                                         M.tolist())
+        # (a list of no rows carries no column count for the oracle: the empty products are written out)
+        want = O.matvec(pk, orientation, cs[:used.shape[0]], M.tolist()) if M.shape[0] else [1] * M.shape[1]
+        assert dev_to_ints(api.haflo_export_cipher(ctx, out)) == want
     s = api.haflo_cipher_sum(ctx, ci)
     assert dev_to_ints(api.haflo_export_cipher(ctx, s)) == [O.summation(pk, cs)]
     s1 = api.haflo_cipher_sum(ctx, ci[:1].contiguous())
