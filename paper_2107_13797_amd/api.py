@@ -330,7 +330,9 @@ class Store:
     """Owner of a haflo_store over an arena tensor: operands and results named by integer handles.
 
     Methods mirror the haflo_h_* entry points; `uses` is the number of operator calls that will
-    consume the result (0 = until release()).
+    consume the result (0 = until release()). The store enqueues everything on the torch stream
+    that is current when it is created: call it with that stream current, so that tensors handed
+    to upload() and returned by download() are ordered with its work.
     """
 
     def __init__(self, ctx, arena_bytes):

@@ -592,15 +592,19 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_order_scatter(const u32* _
     order[atomicAdd(&bins[length_bin(counts[row], cols * (size_t)npos)], 1u)] = (u32)row;
 }
 
-// one group per output row: the product of the listed table entries. Rows are taken in the order
-// `order` (longest lists first): a wavefront takes the run of its own index first, then runs drawn from
-// a counter (zero at launch), so that rows with long lists do not leave the rest of the chip waiting.
+// The product of the listed table entries of every row. A row's list is cut into 2^seg_shift segments of
+// near-equal length and one lane group multiplies one segment (few rows with long lists would otherwise
+// leave most of the chip idle); with one segment the group writes the canonical result to out[row], else
+// its lazy partial product to partial[row][segment] for k_xw_combine. Work items are taken in the order
+// `order` (rows with the longest lists first): a wavefront takes the run of its own index first, then
+// runs drawn from a counter (zero at launch), so that long lists do not leave the rest of the chip waiting.
 template <int LPT, int T>
 __global__ __launch_bounds__(kBlockThreads, 3) void k_xw_main(ModRef M, size_t rows, size_t list_stride,
                                                            const u32* __restrict__ lists,
                                                            const u32* __restrict__ counts,
                                                            const u32* __restrict__ order,
-                                                           const u32* __restrict__ tables, u32* __restrict__ next_row,
+                                                           const u32* __restrict__ tables, u32* __restrict__ next_item,
+                                                           int seg_shift, u32* __restrict__ partial,
                                                            u32* __restrict__ out) {
   constexpr int NL = LPT * T;
   constexpr int GW = WAVE / T;
@@ -609,29 +613,60 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_xw_main(ModRef M, size_t r
   load_mod<LPT, T>(mod, M, g);
   const int lane = (int)(threadIdx.x & (WAVE - 1));
   const size_t nwaves = ((size_t)gridDim.x * blockDim.x) / WAVE;
-  size_t r0 = (((size_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE) * GW;
-  while (r0 < rows) {
-    const size_t ridx = r0 + (size_t)(lane / T);
-    const bool active = ridx < rows;
-    const size_t row = active ? (size_t)order[ridx] : 0;
+  const size_t items = rows << seg_shift;
+  const u32 nseg = 1u << seg_shift;
+  size_t w0 = (((size_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE) * GW;
+  while (w0 < items) {
+    const size_t item = w0 + (size_t)(lane / T);
+    const bool active = item < items;
+    const size_t row = active ? (size_t)order[item >> seg_shift] : 0;
+    const u32 seg = (u32)item & (nseg - 1u);
     const u32 cnt = active ? counts[row] : 0u;
-    const u32* mine = lists + (active ? row : 0) * list_stride;
-    auto entry = [&](u32 e) -> const u32* { return (e < cnt) ? tables + (size_t)mine[e] * NL : M.r1; };
+    const u32 e0 = (u32)(((u64)cnt * seg) >> seg_shift), e1 = (u32)(((u64)cnt * (seg + 1u)) >> seg_shift);
+    const u32* mine = lists + row * list_stride;
+    auto entry = [&](u32 e) -> const u32* { return (e < e1) ? tables + (size_t)mine[e] * NL : M.r1; };
     u32 acc[LPT];
-    load_limbs<LPT, T>(acc, entry(0), g);
+    load_limbs<LPT, T>(acc, entry(e0), g);
 #pragma unroll 1
-    for (u32 e = 1; wave_any(e < cnt); ++e) {
+    for (u32 e = e0 + 1; wave_any(e < e1); ++e) {
       // the next entry is looked up and touched while this one is multiplied; a group that has run out
       // of entries multiplies by one and stays in step with its wave
       const u32 touch = entry(e + 1)[g.k * LPT];
       montmul_mem<LPT, T>(acc, acc, entry(e), mod.n, mod.n0inv, g);
       keep_live(touch);
     }
+    if (seg_shift == 0) {
+      canonicalise<LPT, T>(acc, mod.n, g);
+      if (active) store_limbs<LPT, T>(out + row * (size_t)NL, acc, g);
+    } else if (active) {
+      store_limbs<LPT, T>(partial + ((row << seg_shift) + seg) * (size_t)NL, acc, g);
+    }
+    u32 drawn = 0;
+    if (lane == 0) drawn = atomicAdd(next_item, (u32)GW);
+    w0 = nwaves * GW + (size_t)(u32)__builtin_amdgcn_ds_bpermute(0, (int)drawn);
+  }
+}
+
+// out[row] = product of the row's 2^seg_shift partial products, canonical
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_xw_combine(ModRef M, size_t rows, int seg_shift,
+                                                              const u32* __restrict__ partial, u32* __restrict__ out) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  for (size_t base = bt.first(); base < rows; base += bt.stride()) {
+    const size_t row = base + bt.gib;
+    const bool active = row < rows;
+    const u32* mine = partial + ((active ? row : 0) << seg_shift) * (size_t)NL;
+    u32 acc[LPT];
+    load_limbs<LPT, T>(acc, mine, g);
+#pragma unroll 1
+    for (int sgm = 1; sgm < (1 << seg_shift); ++sgm)
+      montmul_mem<LPT, T>(acc, acc, mine + (size_t)sgm * NL, mod.n, mod.n0inv, g);
     canonicalise<LPT, T>(acc, mod.n, g);
     if (active) store_limbs<LPT, T>(out + row * (size_t)NL, acc, g);
-    u32 drawn = 0;
-    if (lane == 0) drawn = atomicAdd(next_row, (u32)GW);
-    r0 = nwaves * GW + (size_t)(u32)__builtin_amdgcn_ds_bpermute(0, (int)drawn);
   }
 }
 
@@ -712,9 +747,18 @@ XtdBucketLayout xtd_bucket_layout(const haflo_ctx* ctx, size_t rows, size_t cols
 struct XwPlan {
   // in u32 words; word 0 holds the largest |x|, word 1 the row counter of k_xw_main, words
   // [kXwBinsAt, kXwBinsAt + kLenBins) the length classes
-  size_t off_inv, off_tables, off_nz, off_cnt, off_order, total;
+  size_t off_inv, off_tables, off_nz, off_cnt, off_order, off_partial, total;
+  int seg_shift;  // every row's list is multiplied in 2^seg_shift segments
 };
 constexpr size_t kXwBinsAt = 64;
+// Segments per row: doubled while the chip would hold fewer than four wavefronts per SIMD, up to 8
+// and while a full row still gives every segment a few entries.
+int xw_seg_shift(const haflo_ctx* ctx, size_t rows, size_t cols) {
+  const size_t per_wave = (size_t)(64 / ctx->N.t), want_waves = (size_t)ctx->num_cu * 16;
+  int sh = 0;
+  while (sh < 3 && (rows << sh) < want_waves * per_wave && cols >= ((size_t)4 << sh)) ++sh;
+  return sh;
+}
 XwPlan xw_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
   XwPlan p;
   const size_t nl = (size_t)ctx->N.nl;
@@ -723,7 +767,9 @@ XwPlan xw_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
   p.off_nz = p.off_tables + cols * 2 * kMaxPos * kWinEntries * nl;
   p.off_cnt = p.off_nz + rows * cols * kMaxPos;
   p.off_order = p.off_cnt + rows;
-  p.total = p.off_order + rows;
+  p.off_partial = p.off_order + rows;
+  p.seg_shift = xw_seg_shift(ctx, rows, cols);
+  p.total = p.off_partial + (p.seg_shift ? (rows << p.seg_shift) * nl : 0);
   return p;
 }
 
@@ -883,11 +929,20 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
       const LaunchShape per_row = launch_shape(ctx, rows, 1, 8);
       HAFLO_LAUNCH(k_xw_order_scatter, per_row, st, (const u32*)cnt, rows, cols, bins, order, (const u32*)ws);
     }
+    u32* partial = ws + p.off_partial;
     {
-      const LaunchShape sh = launch_shape(ctx, rows, m.t, 3);
+      const LaunchShape sh = launch_shape(ctx, rows << p.seg_shift, m.t, 3);
 #define CALL(LPT, T)                                                                                          \
   HAFLO_LAUNCH((k_xw_main<LPT, T>), sh, st, m.ref(), rows, cols * (size_t)kMaxPos, (const u32*)lists,         \
-               (const u32*)cnt, (const u32*)order, (const u32*)tables, ws + 1, (u32*)d_out)
+               (const u32*)cnt, (const u32*)order, (const u32*)tables, ws + 1, p.seg_shift, partial,          \
+               (u32*)d_out)
+      HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+    }
+    if (p.seg_shift) {
+      const LaunchShape sh = launch_shape(ctx, rows, m.t, 8);
+#define CALL(LPT, T) \
+  HAFLO_LAUNCH((k_xw_combine<LPT, T>), sh, st, m.ref(), rows, p.seg_shift, (const u32*)partial, (u32*)d_out)
       HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
     }
