@@ -51,15 +51,16 @@ struct Grp {
     if (T == 1) return v;
     return (u32)__builtin_amdgcn_ds_bpermute(base_addr + (src_k << 2), (int)v);
   }
-  // value of `v` held by lane 0 of this group, through DPP moves (quad broadcast, then row shifts by
-  // 4 and 8 lanes into the upper banks): a few VALU cycles instead of a round trip through the LDS
-  // crossbar, which matters where the result is needed at once.
+  // value of `v` held by lane 0 of this group, through DPP moves: a few VALU cycles instead of a round
+  // trip through the LDS crossbar, which matters where the result is needed at once. A group that fills
+  // a 16-lane row takes the row broadcast; smaller groups a quad broadcast, then a row shift by 4 lanes
+  // into the odd banks.
   __device__ __forceinline__ u32 bcast0(u32 v) const {
     if (T == 1) return v;
     int x = (int)v;
+    if (T == 16) return (u32)__builtin_amdgcn_update_dpp(x, x, 0x150 /* row_newbcast:0 */, 0xf, 0xf, false);
     x = __builtin_amdgcn_update_dpp(x, x, T == 2 ? 0xA0 /* quad_perm:[0,0,2,2] */ : 0x00 /* [0,0,0,0] */, 0xf, 0xf, false);
-    if (T >= 8) x = __builtin_amdgcn_update_dpp(x, x, 0x114 /* row_shr:4 */, 0xf, 0xA, false);
-    if (T >= 16) x = __builtin_amdgcn_update_dpp(x, x, 0x118 /* row_shr:8 */, 0xf, 0xC, false);
+    if (T == 8) x = __builtin_amdgcn_update_dpp(x, x, 0x114 /* row_shr:4 */, 0xf, 0xA, false);
     return (u32)x;
   }
   // v of the next-higher lane; 0 past the end of the 16-lane row. The top lane

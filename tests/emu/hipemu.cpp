@@ -92,6 +92,8 @@ uint32_t dpp(uint32_t old, uint32_t src, int ctrl, int row_mask, int bank_mask, 
   } else if (ctrl >= 0x111 && ctrl <= 0x11f) {  // row_shr:n - lane i reads lane i-n
     int s = pos - (ctrl - 0x110);
     if (s >= 0) from = row + s;
+  } else if (ctrl >= 0x150 && ctrl <= 0x15f) {  // row_newbcast:n - every lane of a row reads its lane n
+    from = row + (ctrl - 0x150);
   } else if (ctrl >= 0 && ctrl <= 0xff) {  // quad_perm
     from = (lane & ~3) + ((ctrl >> (2 * (lane & 3))) & 3);
   } else {
