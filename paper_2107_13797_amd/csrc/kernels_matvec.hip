@@ -17,6 +17,8 @@
 
 #include <stdlib.h>
 
+#include <algorithm>
+
 using namespace haflo;
 using namespace haflo::dev;
 
@@ -518,11 +520,9 @@ __device__ __forceinline__ u32 length_bin(u32 len, size_t longest) {
 
 // Per row: the list of table entries its product consists of, one per non-zero 8-bit digit
 // of every non-zero |X[row][c]|: entry index ((c*2 + sign)*kMaxPos + s)*256 + digit, in units of
-// one table entry. One wave per row; lists: rows * cols * kMaxPos words, counts: rows;
-// bins[b] += rows whose list length falls into class b.
+// one table entry. One wave per row; lists: rows * cols * kMaxPos words, counts: rows.
 __global__ __launch_bounds__(kBlockThreads) void k_xw_lists(const int* __restrict__ X, size_t rows, size_t cols,
                                                             u32* __restrict__ lists, u32* __restrict__ counts,
-                                                            u32* __restrict__ bins,
                                                             const u32* __restrict__ maxmag) {
   const int lane = (int)(threadIdx.x & (WAVE - 1));
   const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
@@ -546,10 +546,41 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_lists(const int* __restric
         written += (u32)__builtin_popcountll(mask);
       }
     }
-    if (lane == 0) {
-      counts[row] = written;
-      atomicAdd(&bins[length_bin(written, cols * (size_t)npos)], 1u);
+    if (lane == 0) counts[row] = written;
+  }
+}
+
+// Counting sort of the rows by length class, in two passes around k_xw_order_scan. A block takes 256
+// rows at a time and counts them in LDS first, so that global memory sees one atomic per class and
+// block. SCATTER = false: bins[b] += rows of class b. SCATTER = true: bins[] are the cursors left by the
+// scan; the block reserves its share of every class and writes order[cursor + rank in the block] = row.
+template <bool SCATTER>
+__global__ __launch_bounds__(kBlockThreads) void k_xw_order(const u32* __restrict__ counts, size_t rows, size_t cols,
+                                                            u32* __restrict__ bins, u32* __restrict__ order,
+                                                            const u32* __restrict__ maxmag) {
+  __shared__ u32 hist[kLenBins];
+  __shared__ u32 start[SCATTER ? kLenBins : 1];
+  const int npos = (bit_length(*maxmag) + kWin - 1) / kWin;
+  const size_t longest = cols * (size_t)npos;
+  for (size_t r0 = (size_t)blockIdx.x * kBlockThreads; r0 < rows; r0 += (size_t)gridDim.x * kBlockThreads) {
+    for (int l = (int)threadIdx.x; l < kLenBins; l += kBlockThreads) hist[l] = 0u;
+    __syncthreads();
+    const size_t row = r0 + threadIdx.x;
+    const bool active = row < rows;
+    const u32 bin = active ? length_bin(counts[row], longest) : 0u;
+    const u32 rank = active ? atomicAdd(&hist[bin], 1u) : 0u;
+    __syncthreads();
+    for (int l = (int)threadIdx.x; l < kLenBins; l += kBlockThreads) {
+      const u32 c = hist[l];
+      if (c == 0u) continue;
+      const u32 before = atomicAdd(&bins[l], c);
+      if (SCATTER) start[l] = before;
     }
+    if (SCATTER) {
+      __syncthreads();
+      if (active) order[start[bin] + rank] = (u32)row;
+    }
+    __syncthreads();
   }
 }
 
@@ -580,16 +611,6 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_order_scan(u32* __restrict
     bins[kLenBins - 1 - (t * PER + i)] = run;
     run += own[i];
   }
-}
-
-// order[position] = row, positions handed out per class from the cursors in bins[]
-__global__ __launch_bounds__(kBlockThreads) void k_xw_order_scatter(const u32* __restrict__ counts, size_t rows,
-                                                                    size_t cols, u32* __restrict__ bins,
-                                                                    u32* __restrict__ order,
-                                                                    const u32* __restrict__ maxmag) {
-  const int npos = (bit_length(*maxmag) + kWin - 1) / kWin;
-  for (size_t row = (size_t)blockIdx.x * blockDim.x + threadIdx.x; row < rows; row += (size_t)gridDim.x * blockDim.x)
-    order[atomicAdd(&bins[length_bin(counts[row], cols * (size_t)npos)], 1u)] = (u32)row;
 }
 
 // The product of the listed table entries of every row. A row's list is cut into 2^seg_shift segments of
@@ -920,14 +941,15 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
     u32* order = ws + p.off_order;
     {
       const LaunchShape sh = launch_shape(ctx, rows, 64, 8);
-      HAFLO_LAUNCH(k_xw_lists, sh, st, d_X, rows, cols, lists, cnt, bins, (const u32*)ws);
-      LaunchShape one;
+      HAFLO_LAUNCH(k_xw_lists, sh, st, d_X, rows, cols, lists, cnt, (const u32*)ws);
+      LaunchShape per_row, one;
+      per_row.threads = one.threads = kBlockThreads;
+      per_row.gpb = one.gpb = kBlockThreads;
+      per_row.blocks = (int)std::min((rows + kBlockThreads - 1) / kBlockThreads, (size_t)ctx->num_cu * 8);
       one.blocks = 1;
-      one.threads = kBlockThreads;
-      one.gpb = kBlockThreads;
+      HAFLO_LAUNCH(k_xw_order<false>, per_row, st, (const u32*)cnt, rows, cols, bins, order, (const u32*)ws);
       HAFLO_LAUNCH(k_xw_order_scan, one, st, bins);
-      const LaunchShape per_row = launch_shape(ctx, rows, 1, 8);
-      HAFLO_LAUNCH(k_xw_order_scatter, per_row, st, (const u32*)cnt, rows, cols, bins, order, (const u32*)ws);
+      HAFLO_LAUNCH(k_xw_order<true>, per_row, st, (const u32*)cnt, rows, cols, bins, order, (const u32*)ws);
     }
     u32* partial = ws + p.off_partial;
     {
