@@ -392,13 +392,21 @@ __device__ __forceinline__ void zero_limbs(u32 (&x)[LPT]) {
   for (int j = 0; j < LPT; ++j) x[j] = 0;
 }
 
-// This lane's 29-bit limbs cut out of an array of `nwords` little-endian 32-bit
-// words (bits past the array read as zero).
+// limbs [k*LPT, (k+1)*LPT) of an array that holds only `valid` limbs (zero above them)
 template <int LPT, int T>
-__device__ __forceinline__ void load_words_as_limbs(u32 (&x)[LPT], const u32* wp, int nwords, const Grp<T>& g) {
+__device__ __forceinline__ void load_limbs_below(u32 (&x)[LPT], const u32* p, int valid, const Grp<T>& g) {
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) x[j] = (g.k * LPT + j < valid) ? p[g.k * LPT + j] : 0u;
+}
+
+// This lane's 29-bit limbs, counted from limb `first_limb` of the integer, cut out of an array
+// of `nwords` little-endian 32-bit words (bits past the array read as zero).
+template <int LPT, int T>
+__device__ __forceinline__ void load_words_as_limbs(u32 (&x)[LPT], const u32* wp, int nwords, const Grp<T>& g,
+                                                    int first_limb = 0) {
 #pragma unroll
   for (int j = 0; j < LPT; ++j) {
-    int bitpos = (g.k * LPT + j) * LIMB_BITS;
+    int bitpos = (first_limb + g.k * LPT + j) * LIMB_BITS;
     int wi = bitpos >> 5;
     int sh = bitpos & 31;
     u32 lo = (wi < nwords) ? wp[wi] : 0u;

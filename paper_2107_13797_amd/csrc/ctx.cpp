@@ -242,13 +242,35 @@ static void build_prog_encrypt(DevProg& p, const Big& n, Uploader& up) {
   p.d_ins = up.put(p.host);
 }
 
-// Key owner's encryption, one prime-power branch: r^n mod s^2 with the exponent reduced modulo
-// the group order s (s - 1). r (word input 1, below n < 2 s^2) needs no reduction first: the
-// Montgomery product accepts it as it is. The result leaves the Montgomery domain.
-static void build_prog_encrypt_branch(DevProg& p, const Big& e, Uploader& up) {
+// Key owner's encryption, one prime-power branch in two stages. With n = s t (s, t the primes,
+// gcd(t, s - 1) = 1) the n-th powers modulo s^2 are the subgroup of order s - 1, whose elements are
+// determined by their residues modulo s: the one that is a modulo s is a^s mod s^2. Hence
+//   r^n mod s^2 = (r^(n mod (s-1)) mod s)^s mod s^2:
+// a half-length exponent on the quarter-size modulus s, then a half-length exponent on s^2, instead
+// of a full-length exponent on s^2.
+// Stage 1: r (word input 1, below n) = r_hi R + r_lo goes to Montgomery form modulo s as
+// montmul(r_lo, R^2) + montmul(r_hi, R^3), is raised to e = n mod (s - 1) and leaves the Montgomery
+// domain.
+static void build_prog_encrypt_low(DevProg& p, const Big& e, Uploader& up) {
   p.sched = make_schedule(e, 0);
   p.host.clear();
+  p.host.push_back(eng_ins(ENG_LOAD_WH, 1));
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstR3));
+  p.host.push_back(eng_ins(ENG_STORE_T, 0));
   p.host.push_back(eng_ins(ENG_LOAD_W, 1));
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstR2));
+  p.host.push_back(eng_ins(ENG_ADD_T, 0));
+  append_modexp(p.host, p.sched);
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstOne));
+  p.table_entries = p.sched.table_len + 1;
+  p.d_ins = up.put(p.host);
+}
+// Stage 2: y (limb input, the canonical result of stage 1, zero-extended) to the power s modulo s^2;
+// the result leaves the Montgomery domain.
+static void build_prog_encrypt_lift(DevProg& p, const Big& s, Uploader& up) {
+  p.sched = make_schedule(s, 0);
+  p.host.clear();
+  p.host.push_back(eng_ins(ENG_LOAD_L, 0));
   p.host.push_back(eng_ins(ENG_MUL_C, kConstR2));
   append_modexp(p.host, p.sched);
   p.host.push_back(eng_ins(ENG_MUL_C, kConstOne));
@@ -320,10 +342,12 @@ static int ctx_build(haflo_ctx* ctx, const Big& n, const Big* p, const Big* q, u
     build_prog_decrypt(ctx->prog_dec_p, Big::sub(*p, Big(1)), up);
     build_prog_decrypt(ctx->prog_dec_q, Big::sub(*q, Big(1)), up);
     {
-      // r^n mod s^2 only depends on n modulo |(Z/s^2)*| = s (s - 1)
-      Big ordp = Big::mul(*p, Big::sub(*p, Big(1))), ordq = Big::mul(*q, Big::sub(*q, Big(1)));
-      build_prog_encrypt_branch(ctx->prog_enc_p, Big::mod(n, ordp), up);
-      build_prog_encrypt_branch(ctx->prog_enc_q, Big::mod(n, ordq), up);
+      Big pm1 = Big::sub(*p, Big(1)), qm1 = Big::sub(*q, Big(1));
+      Big ordq = Big::mul(*q, qm1);  // |(Z/q^2)*|
+      build_prog_encrypt_low(ctx->prog_enc_p, Big::mod(n, pm1), up);
+      build_prog_encrypt_low(ctx->prog_enc_q, Big::mod(n, qm1), up);
+      build_prog_encrypt_lift(ctx->prog_lift_p, *p, up);
+      build_prog_encrypt_lift(ctx->prog_lift_q, *q, up);
       // (p^2)^-1 mod q^2 = (p^2)^(q(q-1)-1) mod q^2 (p is a unit there), kept in Montgomery form
       const Big& q2 = ctx->Q2.mod;
       MontHost mq2(q2);
@@ -473,11 +497,18 @@ int haflo_op_cost(const haflo_ctx* ctx, int op, uint64_t* montmuls, uint32_t* mo
   uint32_t limbs = 0;
   if (op == HAFLO_OP_ENCRYPT) {
     if (ctx->has_priv) {
-      // through p^2 and q^2: per branch into Montgomery form, the power, out of it; then one
-      // half-size product and one plain product to recombine and three full-size products
-      // (= 12 half-size ones) for the (1 + m n) factor and the Montgomery form of the result
-      mm = ctx->prog_enc_p.sched.nsquare + ctx->prog_enc_p.sched.nmul + ctx->prog_enc_q.sched.nsquare +
-           ctx->prog_enc_q.sched.nmul + 4 + 2 + 12;
+      // through p^2 and q^2, counted in products of the half-size moduli: per branch the second
+      // stage (into Montgomery form, the power, out of it) and the first stage on the quarter-size
+      // modulus (three products into Montgomery form, the power, one out), a quarter-size product
+      // being (2 L^2 + L) / (2 (2L)^2 + 2L) of a half-size one; then one half-size product and one
+      // plain product to recombine and three full-size products (= 12 half-size ones) for the
+      // (1 + m n) factor and the Montgomery form of the result
+      const uint64_t lift = ctx->prog_lift_p.sched.nsquare + ctx->prog_lift_p.sched.nmul +
+                            ctx->prog_lift_q.sched.nsquare + ctx->prog_lift_q.sched.nmul + 4;
+      const uint64_t low = ctx->prog_enc_p.sched.nsquare + ctx->prog_enc_p.sched.nmul +
+                           ctx->prog_enc_q.sched.nsquare + ctx->prog_enc_q.sched.nmul + 8;
+      const uint64_t lq = (uint64_t)ctx->lc / 4, lh = (uint64_t)ctx->lc / 2;
+      mm = lift + (low * (2 * lq * lq + lq) + (2 * lh * lh + lh) - 1) / (2 * lh * lh + lh) + 2 + 12;
       limbs = (uint32_t)ctx->lc / 2;
     } else {
       // into Montgomery form, the power r^n, (1 + m n) R, the final product

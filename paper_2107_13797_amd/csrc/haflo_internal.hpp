@@ -60,7 +60,8 @@ enum EngOp : uint32_t {
   ENG_ADD_T = 12,    // acc += table[a]
   ENG_LOAD_W = 13,   // acc = the element's 32-bit-word input a (0 or 1), cut into limbs
   ENG_LOAD_L = 14,   // acc = limbs [a*NL, (a+1)*NL) of the element's limb input
-  ENG_LOAD_TD = 15   // acc = table[(k >> a) & 15]
+  ENG_LOAD_TD = 15,  // acc = table[(k >> a) & 15]
+  ENG_LOAD_WH = 16   // acc = limbs [NL, 2 NL) of the element's 32-bit-word input a: the part above ENG_LOAD_W's
 };
 enum { kConstR1 = 0, kConstR2 = 1, kConstR3 = 2, kConstOne = 3, kConstExtra = 4, kNumConst = 5 };
 inline uint32_t eng_ins(uint32_t op, uint32_t a = 0, uint32_t b = 0) { return op | (a << 8) | (b << 20); }
@@ -112,8 +113,10 @@ struct haflo_ctx {
   haflo::DevProg prog_enc;     // encryption: r^n modulo n^2 and the (1 + m n) factor
   haflo::DevProg prog_dec_p;   // decryption branch: c^(p-1) modulo p^2
   haflo::DevProg prog_dec_q;   // decryption branch: c^(q-1) modulo q^2
-  haflo::DevProg prog_enc_p;   // key owner's encryption: r^(n mod p(p-1)) modulo p^2
-  haflo::DevProg prog_enc_q;   // key owner's encryption: r^(n mod q(q-1)) modulo q^2
+  haflo::DevProg prog_enc_p;   // key owner's encryption, first stage: r^(n mod (p-1)) modulo p
+  haflo::DevProg prog_enc_q;   //   and r^(n mod (q-1)) modulo q
+  haflo::DevProg prog_lift_p;  // second stage: y^p modulo p^2
+  haflo::DevProg prog_lift_q;  //   and y^q modulo q^2
   uint32_t* d_p2inv = nullptr; // ((p^2)^-1 mod q^2) * R mod q^2 (P2.nl limbs)
   // device constants
   uint32_t* d_k1 = nullptr;      // n * R^2 mod n^2 (N.nl limbs): montmul(m, k1) = m*n*R

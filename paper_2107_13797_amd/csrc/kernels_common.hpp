@@ -89,6 +89,7 @@ struct EngineIO {
   int in_nwords;
   const u32* in_limbs;             // per-element limb arrays, in_limbs_stride limbs apart
   int in_limbs_stride;
+  int in_limbs_valid;              // limbs an element's array holds (read as zero above); 0 = as many as asked for
   const unsigned long long* k64;   // per-element exponent for the *_TD instructions
   u32* out;                        // NL limbs per element (canonical) or null
   u32* tables;                     // table_entries * NL limbs per slot
@@ -124,12 +125,16 @@ __device__ __forceinline__ void engine_run(const ModRef& M, const Prog& P, const
       if (op >= ENG_LOAD_T) {
         if (op == ENG_STORE_T) {
           if (tab_ok) store_limbs<LPT, T>(table + (size_t)a * NL, acc, g);
-        } else if (op == ENG_LOAD_W) {
-          if (active) load_words_as_limbs<LPT, T>(acc, io.in_words[a] + item * (size_t)io.in_nwords, io.in_nwords, g);
+        } else if (op == ENG_LOAD_W || op == ENG_LOAD_WH) {
+          if (active)
+            load_words_as_limbs<LPT, T>(acc, io.in_words[a] + item * (size_t)io.in_nwords, io.in_nwords, g,
+                                        op == ENG_LOAD_WH ? NL : 0);
           else zero_limbs<LPT>(acc);
         } else if (op == ENG_LOAD_L) {
-          if (active) load_limbs<LPT, T>(acc, io.in_limbs + item * (size_t)io.in_limbs_stride + (size_t)a * NL, g);
-          else zero_limbs<LPT>(acc);
+          const u32* src = io.in_limbs + item * (size_t)io.in_limbs_stride + (size_t)a * NL;
+          if (!active) zero_limbs<LPT>(acc);
+          else if (io.in_limbs_valid) load_limbs_below<LPT, T>(acc, src, io.in_limbs_valid - (int)a * NL, g);
+          else load_limbs<LPT, T>(acc, src, g);
         } else {
           const u32* src;
           if (op == ENG_LOAD_C || op == ENG_ADD_C) src = io.constant[a];

@@ -234,12 +234,15 @@ namespace haflo {
 size_t ws_encrypt(const haflo_ctx* ctx, size_t count) {
   if (!ctx->has_priv)
     return modexp_shape(ctx, count, ctx->N).slots() * (size_t)ctx->prog_enc.table_entries * ctx->N.nl * 4;
-  // key owner: [y_p, y_q: count*P2.nl each][r^n: count*N.nl][branch tables, both halves of the grid]
-  // and, for the last stage, one table slot of N.nl limbs per lane group (placed over the branch tables)
-  size_t tl = (size_t)std::max(ctx->prog_enc_p.table_entries, ctx->prog_enc_q.table_entries);
-  size_t branch = 2 * modexp_shape(ctx, count, ctx->P2).slots() * tl * ctx->P2.nl;
+  // key owner: [y_p, y_q: count*P2.nl each][r^n: count*N.nl; before it is written, the first
+  // stage's results: count*P.nl for each prime][tables of whichever stage runs, both halves of the
+  // grid; for the last stage one table slot of N.nl limbs per lane group]
+  size_t tl1 = (size_t)std::max(ctx->prog_enc_p.table_entries, ctx->prog_enc_q.table_entries);
+  size_t tl2 = (size_t)std::max(ctx->prog_lift_p.table_entries, ctx->prog_lift_q.table_entries);
+  size_t low = 2 * modexp_shape(ctx, count, ctx->P).slots() * tl1 * ctx->P.nl;
+  size_t lift = 2 * modexp_shape(ctx, count, ctx->P2).slots() * tl2 * ctx->P2.nl;
   size_t last = modexp_shape(ctx, count, ctx->N).slots() * (size_t)ctx->N.nl;
-  return (2 * count * (size_t)ctx->P2.nl + count * (size_t)ctx->N.nl + std::max(branch, last)) * 4;
+  return (2 * count * (size_t)ctx->P2.nl + count * (size_t)ctx->N.nl + std::max(std::max(low, lift), last)) * 4;
 }
 // one table slot per resident lane group
 size_t ws_encrypt_obf(const haflo_ctx* ctx, size_t count) {
@@ -298,34 +301,46 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
     ProgPtr prog = {ctx->prog_enc.d_ins, (int)ctx->prog_enc.host.size()};
     return launch_engine_batch(ctx, m, st, prog, io, count);
   }
-  // key owner: r^n through p^2 and q^2 (half-size moduli: a quarter of the multiplications per
-  // branch), Chinese remainder, then the (1 + m n) factor and the Montgomery form modulo n^2.
+  // key owner: r^n modulo p^2 and q^2, each as (r^(n mod (s-1)) mod s)^s mod s^2 (a half-length
+  // exponent on the quarter-size modulus, then a half-length exponent on the half-size one),
+  // Chinese remainder, then the (1 + m n) factor and the Montgomery form modulo n^2.
   // Bit-identical to the public path: the residue r^n mod n^2 is unique.
   const ModHost& h = ctx->P2;
+  const ModHost& l = ctx->P;
   u32* yp = (u32*)d_workspace;
   u32* yq = yp + count * (size_t)h.nl;
   u32* rn = yq + count * (size_t)h.nl;
   u32* tables = rn + count * (size_t)m.nl;
-  {
-    const int tl = std::max(ctx->prog_enc_p.table_entries, ctx->prog_enc_q.table_entries);
-    LaunchShape sh = modexp_shape(ctx, count, h);
+  u32* y0p = rn;  // the first stage's results live where r^n goes later
+  u32* y0q = y0p + count * (size_t)l.nl;
+  for (int stage = 0; stage < 2; ++stage) {
+    const ModHost& geo = stage ? h : l;
+    const DevProg* progs[2] = {stage ? &ctx->prog_lift_p : &ctx->prog_enc_p, stage ? &ctx->prog_lift_q : &ctx->prog_enc_q};
+    const int tl = std::max(progs[0]->table_entries, progs[1]->table_entries);
+    LaunchShape sh = modexp_shape(ctx, count, geo);
     EngineJob job[2];
     for (int side = 0; side < 2; ++side) {
-      const ModHost& ms = side ? ctx->Q2 : ctx->P2;
-      const DevProg& dp = side ? ctx->prog_enc_q : ctx->prog_enc_p;
+      const ModHost& ms = stage ? (side ? ctx->Q2 : ctx->P2) : (side ? ctx->Q : ctx->P);
       job[side].M = ms.ref();
-      job[side].P = ProgPtr{dp.d_ins, (int)dp.host.size()};
+      job[side].P = ProgPtr{progs[side]->d_ins, (int)progs[side]->host.size()};
       job[side].io = engine_io(ms);
-      job[side].io.in_words[1] = d_r;
-      job[side].io.in_nwords = ctx->lp;
-      job[side].io.out = side ? yq : yp;
+      if (stage == 0) {
+        job[side].io.in_words[1] = d_r;
+        job[side].io.in_nwords = ctx->lp;
+        job[side].io.out = side ? y0q : y0p;
+      } else {
+        job[side].io.in_limbs = side ? y0q : y0p;
+        job[side].io.in_limbs_stride = l.nl;
+        job[side].io.in_limbs_valid = l.nl;
+        job[side].io.out = side ? yq : yp;
+      }
       job[side].io.tables = tables + (side ? sh.slots() * (size_t)tl * ms.nl : 0);
       job[side].io.table_entries = tl;
     }
     const unsigned split = (unsigned)sh.blocks;
     sh.blocks *= 2;
 #define CALL(LPT, T) HAFLO_LAUNCH((k_engine_pair<LPT, T>), sh, st, job[0], job[1], split, count)
-    if (engine_wide(ctx, count, h)) { HAFLO_DISPATCH_GEOMETRY_WIDE(h, CALL); } else { HAFLO_DISPATCH_GEOMETRY(h, CALL); }
+    if (engine_wide(ctx, count, geo)) { HAFLO_DISPATCH_GEOMETRY_WIDE(geo, CALL); } else { HAFLO_DISPATCH_GEOMETRY(geo, CALL); }
 #undef CALL
   }
   {

@@ -539,9 +539,10 @@ def test_op_cost_and_workspace_queries(env):
     lib, ctx, sk, nlw = env
     mm, limbs = C.c_uint64(), C.c_uint32()
     assert lib.haflo_op_cost(ctx, _cabi.OP_ENCRYPT, C.byref(mm), C.byref(limbs)) == 0
-    # key owner: two branches with ~512-bit exponents on half-size moduli; each needs at least
-    # one squaring per bit and fewer than 1.5 products per bit
-    assert 2 * 500 < mm.value < 2 * 768 + 18 and limbs.value == BITS // 32
+    # key owner: per branch a ~256-bit exponent on the half-size modulus and one on the quarter-size
+    # modulus (a product there counts (2*8^2+8)/(2*16^2+16) = 0.258 of a half-size one); each
+    # exponent needs at least one squaring per bit and fewer than 1.5 products per bit
+    assert 2 * 250 * 1.258 < mm.value < 2 * 384 * 1.258 + 30 and limbs.value == BITS // 32
     assert lib.haflo_op_cost(ctx, 99, None, None) == -1
     assert lib.haflo_workspace_bytes(ctx, 99, 1, 1) == 2 ** 64 - 1
     assert lib.haflo_encrypt(ctx, None, None, None, 4, None, 0, None) == -1
