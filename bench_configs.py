@@ -122,6 +122,10 @@ def main():
             # seven encryptions would take the same time each
             ms, c = timed(lambda: api.haflo_encrypt(pub, api.haflo_encode_f32(pub, vec, cfg["scale_w"]), r))
             add("encode + encrypt, one party's vector", n, ms, "encryptions")
+            ms, c_own = timed(lambda: api.haflo_encrypt(own, api.haflo_encode_f32(own, vec, cfg["scale_w"]), r))
+            add("the same by a key owner", n, ms, "encryptions")
+            assert torch.equal(c, c_own)
+            del c_own
             acc = c.clone()
 
             def fold():
