@@ -118,8 +118,11 @@ int haflo_ctx_info(const haflo_ctx* ctx, uint32_t* n_bits, uint32_t* cipher_limb
  * the number of Montgomery products the library's schedule executes per
  * element (exponentiation windows and table building included) and the size,
  * in 32-bit limbs, of the modulus they run on. Defined for HAFLO_OP_ENCRYPT
- * (modulus n^2) and HAFLO_OP_DECRYPT (the sum over both prime-power branches,
- * modulus size of p^2). Either output may be NULL. */
+ * (modulus n^2 on a public context; on a private one the key owner's route
+ * through p^2 and q^2, with its products on smaller and larger moduli
+ * converted to products of the size of p^2 by their multiplication counts)
+ * and HAFLO_OP_DECRYPT (the sum over both prime-power branches, modulus size
+ * of p^2). Either output may be NULL. */
 int haflo_op_cost(const haflo_ctx* ctx, int op, uint64_t* montmuls, uint32_t* modulus_limbs);
 
 /* Workspace needed by an operator call of the given shape. For element-wise
@@ -173,6 +176,8 @@ int haflo_decode(const haflo_ctx* ctx, const uint32_t* d_plain, uint32_t scale_b
  * uint32, the caller's random units in [1, n) (the library draws no random
  * numbers). d_cipher: device, count internal elements (may not alias inputs).
  * Workspace: haflo_workspace_bytes(ctx, HAFLO_OP_ENCRYPT, count, 0).
+ * A private context computes r^n through p^2 and q^2 (about three times the
+ * rate of a public one); the ciphertexts are the same bit for bit.
  */
 int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t* d_r, void* d_cipher, size_t count,
                   void* d_workspace, size_t workspace_bytes, void* stream);
