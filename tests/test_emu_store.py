@@ -226,3 +226,42 @@ def test_store_matvec_sum_and_scalars_match_oracle(env):
     # temporaries are gone: what is live is hc, hx, f, t, e
     assert st.stats()["live_objects"] == 5 and st.stats()["peak_bytes"] > st.stats()["live_bytes"]
     st.close()
+
+
+def test_store_allocator_random_sequences(env):
+    """Random allocate / release traffic against a model: blocks never overlap, stay inside the
+    arena, the accounting matches, and everything merges back into one free block."""
+    lib, ctx, sk, nlw = env
+    arena_bytes = 64 * 1024
+    sizes = {K.KIND_F32: 4, K.KIND_F64: 8, K.KIND_CIPHER: nlw * 4, K.KIND_PLAIN: BITS // 8}
+    for seed in range(4):
+        rng = random.Random(seed)
+        st = EmuStore(lib, ctx, arena_bytes)
+        base, live = None, {}
+        for _ in range(400):
+            if live and (rng.random() < 0.45 or len(live) > 40):
+                h = rng.choice(sorted(live))
+                assert lib.haflo_store_release(st.h, h) == 0
+                del live[h]
+            else:
+                kind = rng.choice(sorted(sizes))
+                count = rng.choice((0, 1, 3, 17, 64, 200, 1000))
+                rc, h = st.new(kind, count, rng.choice((0, 1, 2)))
+                need = max(1, -(-sizes[kind] * count // 256)) * 256
+                if rc == ENOMEM:
+                    assert st.stats()["largest_free"] < need
+                    continue
+                assert rc == 0 and h not in live
+                ptr = st.info(h)[2]
+                base = ptr if base is None else min(base, ptr)
+                live[h] = (ptr, need)
+            spans = sorted(live.values())
+            assert all(a + n <= b for (a, n), (b, _) in zip(spans, spans[1:]))
+            s = st.stats()
+            assert s["live_bytes"] == sum(n for _, n in spans) and s["live_objects"] == len(live)
+            assert all(st.arena.p <= a and a + n <= st.arena.p + arena_bytes for a, n in spans)
+        for h in sorted(live):
+            assert lib.haflo_store_release(st.h, h) == 0
+        s = st.stats()
+        assert s["live_bytes"] == 0 and s["largest_free"] == arena_bytes
+        st.close()
