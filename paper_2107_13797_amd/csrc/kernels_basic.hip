@@ -113,55 +113,73 @@ __device__ __forceinline__ bool quantise(float v, int scale_bits, long long& q) 
 // borrow runs through zero words of n up to its first non-zero word `z`.
 // With a second input v2 the encoded integer is q(v) - 2 q(v2) (the plaintext part of the fore
 // gradient); both must then stay below 2^61 in magnitude.
+// The grid stride is a multiple of the quads per element (a power of two that divides the block
+// size), so a lane keeps its quad index, and with it its words of n, for the whole loop; the
+// inputs of kEncodeAhead elements are requested before the first is used.
+constexpr int kEncodeAhead = 4;
 __global__ __launch_bounds__(kBlockThreads) void k_encode(const float* __restrict__ v, const float* __restrict__ v2,
                                                           int scale_bits, const u32* __restrict__ nw, int lp, int z,
                                                           u32* __restrict__ plain, u32* __restrict__ status,
                                                           size_t count) {
   const int qpi = lp >> 2;  // quads per item
+  const int qshift = 31 - __builtin_clz((unsigned)qpi);
   const size_t total = count * (size_t)qpi;
-  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-       idx += (size_t)gridDim.x * blockDim.x) {
-    size_t item = idx / (size_t)qpi;
-    int quad = (int)(idx - item * (size_t)qpi);
-    long long q;
-    bool ok = quantise(v[item], scale_bits, q);
-    if (v2) {
-      long long q2;
-      const long long lim = 1ll << 61;
-      ok = quantise(v2[item], scale_bits, q2) && ok && q > -lim && q < lim && q2 > -lim && q2 < lim;
-      q = ok ? q - 2 * q2 : 0;
-    }
-    u32 w[4] = {0u, 0u, 0u, 0u};
-    if (q >= 0) {
-      if (quad == 0) {
-        w[0] = (u32)(u64)q;
-        w[1] = (u32)((u64)q >> 32);
-      }
-    } else {
-      u64 a = 0ull - (u64)q;  // |q| <= 2^63
-      u64 nlo = (u64)nw[0] | ((u64)nw[1] << 32);
-      u32 borrow = nlo < a ? 1u : 0u;
-      if (quad == 0) {
-        u64 d = nlo - a;
-        w[0] = (u32)d;
-        w[1] = (u32)(d >> 32);
-      }
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const size_t first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int quad = (int)(first & (size_t)(qpi - 1));
+  const u64 nlo = (u64)nw[0] | ((u64)nw[1] << 32);
+  u32 nq[4];  // this quad's words of n
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        int j = quad * 4 + i;
-        if (j >= 2) {
-          u32 nj = nw[j];
-          w[i] = (j < z) ? (0u - borrow) : (j == z ? nj - borrow : nj);
+  for (int i = 0; i < 4; ++i) nq[i] = nw[quad * 4 + i];
+  for (size_t idx0 = first; idx0 < total; idx0 += stride * kEncodeAhead) {
+    float in[kEncodeAhead], in2[kEncodeAhead];
+#pragma unroll
+    for (int u = 0; u < kEncodeAhead; ++u) {
+      const size_t idx = idx0 + (size_t)u * stride;
+      in[u] = idx < total ? v[idx >> qshift] : 0.0f;
+      in2[u] = (v2 && idx < total) ? v2[idx >> qshift] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < kEncodeAhead; ++u) {
+      const size_t idx = idx0 + (size_t)u * stride;
+      if (idx >= total) break;
+      const size_t item = idx >> qshift;
+      long long q;
+      bool ok = quantise(in[u], scale_bits, q);
+      if (v2) {
+        long long q2;
+        const long long lim = 1ll << 61;
+        ok = quantise(in2[u], scale_bits, q2) && ok && q > -lim && q < lim && q2 > -lim && q2 < lim;
+        q = ok ? q - 2 * q2 : 0;
+      }
+      u32 w[4] = {0u, 0u, 0u, 0u};
+      if (q >= 0) {
+        if (quad == 0) {
+          w[0] = (u32)(u64)q;
+          w[1] = (u32)((u64)q >> 32);
+        }
+      } else {
+        const u64 a = 0ull - (u64)q;  // |q| <= 2^63
+        const u32 borrow = nlo < a ? 1u : 0u;
+        if (quad == 0) {
+          const u64 d = nlo - a;
+          w[0] = (u32)d;
+          w[1] = (u32)(d >> 32);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int j = quad * 4 + i;
+          if (j >= 2) w[i] = (j < z) ? (0u - borrow) : (j == z ? nq[i] - borrow : nq[i]);
         }
       }
+      uint4 o;
+      o.x = w[0];
+      o.y = w[1];
+      o.z = w[2];
+      o.w = w[3];
+      reinterpret_cast<uint4*>(plain)[idx] = o;
+      if (quad == 0 && status) status[item] = ok ? HAFLO_ST_OK : HAFLO_ST_RANGE;
     }
-    uint4 o;
-    o.x = w[0];
-    o.y = w[1];
-    o.z = w[2];
-    o.w = w[3];
-    reinterpret_cast<uint4*>(plain)[idx] = o;
-    if (quad == 0 && status) status[item] = ok ? HAFLO_ST_OK : HAFLO_ST_RANGE;
   }
 }
 
