@@ -103,6 +103,9 @@ int haflo_keygen(uint32_t n_bits, uint64_t seed, uint8_t* p_le, uint8_t* q_le);
  * product has exactly n_bits bits and is coprime to (p-1)(q-1); primality is
  * the caller's responsibility. n_bits in {512, 1024, 2048, 4096}.
  * Context creation synchronises with the device (it uploads constant tables).
+ * A context belongs to the device that is current when it is created and is
+ * read-only afterwards: operator calls on one context may run from several
+ * host threads as long as each uses its own workspace and stream.
  */
 int haflo_ctx_create_private(const uint8_t* p_le, const uint8_t* q_le, uint32_t n_bits, haflo_ctx** out);
 int haflo_ctx_create_public(const uint8_t* n_le, uint32_t n_bits, haflo_ctx** out);
