@@ -107,59 +107,61 @@ __device__ __forceinline__ bool quantise(float v, int scale_bits, long long& q) 
   return true;
 }
 
-// Signed fixed-point encoding to residues mod n. One lane writes one 16-byte
-// quad of an element's Lp words, so stores are fully coalesced. A negative q
-// is n - |q|: |q| < 2^64 only touches the two lowest words, above them the
-// borrow runs through zero words of n up to its first non-zero word `z`.
+// Signed fixed-point encoding to residues mod n. A wavefront takes 64 elements at a time: every
+// lane quantises one of them (one coalesced read of the inputs), then the wavefront writes the
+// 64 * Lp words in Lp/4 fully coalesced stores of one 16-byte quad per lane, each lane fetching
+// the quantised integer of the element its quad belongs to from the lane that holds it. 64 is a
+// multiple of the quads per element, so a lane keeps its quad index, and with it its words of n.
+// A negative q is n - |q|: |q| < 2^64 only touches the two lowest words, above them the borrow
+// runs through zero words of n up to its first non-zero word `z`.
 // With a second input v2 the encoded integer is q(v) - 2 q(v2) (the plaintext part of the fore
 // gradient); both must then stay below 2^61 in magnitude.
-// The grid stride is a multiple of the quads per element (a power of two that divides the block
-// size), so a lane keeps its quad index, and with it its words of n, for the whole loop; the
-// inputs of kEncodeAhead elements are requested before the first is used.
-constexpr int kEncodeAhead = 4;
 __global__ __launch_bounds__(kBlockThreads) void k_encode(const float* __restrict__ v, const float* __restrict__ v2,
                                                           int scale_bits, const u32* __restrict__ nw, int lp, int z,
                                                           u32* __restrict__ plain, u32* __restrict__ status,
                                                           size_t count) {
-  const int qpi = lp >> 2;  // quads per item
+  const int qpi = lp >> 2;  // quads per element: 4, 8, 16 or 32
   const int qshift = 31 - __builtin_clz((unsigned)qpi);
-  const size_t total = count * (size_t)qpi;
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  const size_t first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int quad = (int)(first & (size_t)(qpi - 1));
+  const int lane = (int)(threadIdx.x & (WAVE - 1));
+  const int quad = lane & (qpi - 1);
+  const int per_store = WAVE >> qshift;  // elements one store of the wavefront covers
+  const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+  const size_t nwaves = ((size_t)gridDim.x * blockDim.x) / WAVE;
   const u64 nlo = (u64)nw[0] | ((u64)nw[1] << 32);
   u32 nq[4];  // this quad's words of n
 #pragma unroll
   for (int i = 0; i < 4; ++i) nq[i] = nw[quad * 4 + i];
-  for (size_t idx0 = first; idx0 < total; idx0 += stride * kEncodeAhead) {
-    float in[kEncodeAhead], in2[kEncodeAhead];
-#pragma unroll
-    for (int u = 0; u < kEncodeAhead; ++u) {
-      const size_t idx = idx0 + (size_t)u * stride;
-      in[u] = idx < total ? v[idx >> qshift] : 0.0f;
-      in2[u] = (v2 && idx < total) ? v2[idx >> qshift] : 0.0f;
-    }
-#pragma unroll
-    for (int u = 0; u < kEncodeAhead; ++u) {
-      const size_t idx = idx0 + (size_t)u * stride;
-      if (idx >= total) break;
-      const size_t item = idx >> qshift;
-      long long q;
-      bool ok = quantise(in[u], scale_bits, q);
+  const size_t tiles = (count + WAVE - 1) / WAVE;
+  for (size_t tile = wave; tile < tiles; tile += nwaves) {
+    const size_t mine = tile * WAVE + (size_t)lane;
+    long long q = 0;
+    bool ok = true;
+    if (mine < count) {
+      ok = quantise(v[mine], scale_bits, q);
       if (v2) {
         long long q2;
         const long long lim = 1ll << 61;
-        ok = quantise(in2[u], scale_bits, q2) && ok && q > -lim && q < lim && q2 > -lim && q2 < lim;
+        ok = quantise(v2[mine], scale_bits, q2) && ok && q > -lim && q < lim && q2 > -lim && q2 < lim;
         q = ok ? q - 2 * q2 : 0;
       }
+      if (status) status[mine] = ok ? HAFLO_ST_OK : HAFLO_ST_RANGE;
+    }
+    const int qlo = (int)(u32)(u64)q, qhi = (int)(u32)((u64)q >> 32);
+#pragma unroll 1
+    for (int t = 0; t < qpi; ++t) {
+      const int src = t * per_store + (lane >> qshift);  // the lane that quantised this quad's element
+      const u64 sq = (u64)(u32)__builtin_amdgcn_ds_bpermute(src << 2, qlo) |
+                     ((u64)(u32)__builtin_amdgcn_ds_bpermute(src << 2, qhi) << 32);
+      const size_t item = tile * WAVE + (size_t)src;
+      if (item >= count) continue;
       u32 w[4] = {0u, 0u, 0u, 0u};
-      if (q >= 0) {
+      if ((long long)sq >= 0) {
         if (quad == 0) {
-          w[0] = (u32)(u64)q;
-          w[1] = (u32)((u64)q >> 32);
+          w[0] = (u32)sq;
+          w[1] = (u32)(sq >> 32);
         }
       } else {
-        const u64 a = 0ull - (u64)q;  // |q| <= 2^63
+        const u64 a = 0ull - sq;  // |q| <= 2^63
         const u32 borrow = nlo < a ? 1u : 0u;
         if (quad == 0) {
           const u64 d = nlo - a;
@@ -177,8 +179,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_encode(const float* __restric
       o.y = w[1];
       o.z = w[2];
       o.w = w[3];
-      reinterpret_cast<uint4*>(plain)[idx] = o;
-      if (quad == 0 && status) status[item] = ok ? HAFLO_ST_OK : HAFLO_ST_RANGE;
+      reinterpret_cast<uint4*>(plain)[item * (size_t)qpi + (size_t)quad] = o;
     }
   }
 }
@@ -311,8 +312,7 @@ int haflo_encode_f32(const haflo_ctx* ctx, const float* d_v, uint32_t scale_bits
   if (count == 0) return HAFLO_OK;
   int z = 2;
   while (z < ctx->lp && ctx->n.word(z) == 0) ++z;
-  size_t total = count * (size_t)(ctx->lp / 4);
-  const LaunchShape sh = launch_shape(ctx, total, 1, 16);
+  const LaunchShape sh = launch_shape(ctx, count, 1, 8);
   HAFLO_LAUNCH(k_encode, sh, (hipStream_t)stream, d_v, (const float*)nullptr, (int)scale_bits, ctx->d_n_words,
                ctx->lp, z, d_plain, d_status, count);
   return hip_status(hipGetLastError());
@@ -333,7 +333,7 @@ int haflo_fore_gradient(const haflo_ctx* ctx, const void* d_c_host, const float*
   char* guest = (char*)d_workspace + plain_bytes;
   int z = 2;
   while (z < ctx->lp && ctx->n.word(z) == 0) ++z;
-  const LaunchShape sh = launch_shape(ctx, count * (size_t)(ctx->lp / 4), 1, 16);
+  const LaunchShape sh = launch_shape(ctx, count, 1, 8);
   HAFLO_LAUNCH(k_encode, sh, (hipStream_t)stream, d_logits_guest, d_label, (int)scale_bits, ctx->d_n_words, ctx->lp,
                z, plain, d_status, count);
   int rc = haflo_encrypt(ctx, plain, d_r, guest, count, guest + cipher_bytes, enc_bytes, stream);
