@@ -56,7 +56,12 @@ def _le(x, nbytes):
 
 
 class Context:
-    """Owner of a haflo_ctx plus a growable workspace tensor."""
+    """Owner of a haflo_ctx plus a growable workspace tensor.
+
+    Every wrapper below that needs temporaries uses this one workspace, so calls through one
+    Context must be ordered on one stream (torch's current stream); use a second Context, or the
+    C entry points with workspaces of your own, to run operators concurrently.
+    """
 
     def __init__(self, handle):
         self.handle = handle
