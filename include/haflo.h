@@ -193,6 +193,9 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
  * haflo_encrypt (plaintext 0); out[i] = (1 + m_i n) * obfuscator[i] mod n^2,
  * two products per element. Each obfuscator may be used once. d_cipher may
  * alias d_obfuscator. Workspace: HAFLO_OP_ENCRYPT_OBFUSCATOR.
+ * With any ciphertext array in place of the obfuscators the same call adds the
+ * plaintexts to it without an exponentiation: out[i] = c[i] * g^(m_i) mod n^2
+ * encrypts D(c[i]) + m_i (and is as randomised as c[i] was, no more).
  */
 int haflo_encrypt_with_obfuscator(const haflo_ctx* ctx, const uint32_t* d_plain, const void* d_obfuscator,
                                   void* d_cipher, size_t count, void* d_workspace, size_t workspace_bytes,

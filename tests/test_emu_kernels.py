@@ -180,6 +180,13 @@ def test_encrypt_with_obfuscator(env):
     assert lib.haflo_encrypt_with_obfuscator(ctx, words(lib, ms, lp).p, d_obf.p, d_obf.p, len(ms), w.p, nb, None) == 0
     assert export(lib, ctx, d_obf, len(ms)) == [O.encrypt_with_obfuscator(pk, m, o) for m, o in zip(ms, obf)]
     assert export(lib, ctx, d_obf, len(ms)) == [O.encrypt(pk, m, r) for m, r in zip(ms, rs)]
+    # with ciphertexts in place of the obfuscators the call adds plaintexts: D(out) = m + b mod n
+    bs = [rng.randrange(pk.n) for _ in ms]
+    d_sum = zeros(lib, (len(ms), nlw))
+    assert lib.haflo_encrypt_with_obfuscator(ctx, words(lib, bs, lp).p, d_obf.p, d_sum.p, len(ms), w.p, nb, None) == 0
+    got = export(lib, ctx, d_sum, len(ms))
+    assert got == [O.add(pk, O.encrypt(pk, m, r), O.encrypt(pk, b, 1)) for m, r, b in zip(ms, rs, bs)]
+    assert [O.decrypt(sk, c) for c in got] == [(m + b) % pk.n for m, b in zip(ms, bs)]
 
 
 def test_public_context_encrypts_identically(env):
