@@ -68,7 +68,7 @@ struct haflo_stager {
         if (lru == pool.end() || it->last_use < lru->last_use) lru = it;
       }
       if (idle <= pool_cap || lru == pool.end()) break;
-      hipHostFree(lru->p);
+      (void)hipHostFree(lru->p);
       pool.erase(lru);
     }
   }
@@ -139,14 +139,13 @@ int stage_out(haflo_stager* s, const void* d_src, size_t src_stride_bytes, size_
     return HAFLO_ENOMEM;
   }
   int rc = HAFLO_OK;
-  size_t issued = 0, drained = 0;
+  size_t issued = 0;
   size_t len[2] = {0, 0}, at[2] = {0, 0};
   bool busy[2] = {false, false};
   auto drain = [&](int slot) {
     if (!busy[slot]) return;
     if (hipEventSynchronize(s->copied[slot]) != hipSuccess) rc = HAFLO_EHIP;
     memcpy(h_dst + at[slot] * words, pin[slot]->p, len[slot] * words * 4);
-    drained += len[slot];
     busy[slot] = false;
   };
   for (int slot = 0; issued < count && rc == HAFLO_OK; slot ^= 1) {
@@ -177,10 +176,9 @@ int stage_out(haflo_stager* s, const void* d_src, size_t src_stride_bytes, size_
   drain(first);
   drain(first ^ 1);
   for (int slot = 0; slot < 2; ++slot) {
-    if (busy[slot]) hipEventSynchronize(s->copied[slot]);  // error path: the copy must not outlive the buffer
+    if (busy[slot]) (void)hipEventSynchronize(s->copied[slot]);  // error path: the copy must not outlive the buffer
     s->release(pin[slot]);
   }
-  (void)drained;
   return rc;
 }
 
@@ -210,14 +208,15 @@ int haflo_stager_create(const haflo_ctx* ctx, size_t chunk_elems, size_t pool_ca
 
 int haflo_stager_destroy(haflo_stager* s) {
   if (!s) return HAFLO_OK;
-  if (s->copy) hipStreamSynchronize(s->copy);
-  for (PinnedBuf& b : s->pool) hipHostFree(b.p);
+  // best effort: nothing useful can be done about a failing release
+  if (s->copy) (void)hipStreamSynchronize(s->copy);
+  for (PinnedBuf& b : s->pool) (void)hipHostFree(b.p);
   for (int i = 0; i < 2; ++i) {
-    if (s->d_stage[i]) hipFree(s->d_stage[i]);
-    if (s->copied[i]) hipEventDestroy(s->copied[i]);
-    if (s->consumed[i]) hipEventDestroy(s->consumed[i]);
+    if (s->d_stage[i]) (void)hipFree(s->d_stage[i]);
+    if (s->copied[i]) (void)hipEventDestroy(s->copied[i]);
+    if (s->consumed[i]) (void)hipEventDestroy(s->consumed[i]);
   }
-  if (s->copy) hipStreamDestroy(s->copy);
+  if (s->copy) (void)hipStreamDestroy(s->copy);
   delete s;
   return HAFLO_OK;
 }
