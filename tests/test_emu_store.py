@@ -5,7 +5,6 @@ import ctypes as C
 import random
 
 import numpy as np
-import pytest
 
 from oracle import paillier_oracle as O
 from paper_2107_13797_amd import _cabi, synth

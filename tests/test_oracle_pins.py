@@ -5,7 +5,6 @@ closed forms on plaintexts, hand-worked golden values, independent primality
 checks and fixed-point round trips. A dropped term, a wrong sign, modulus or
 index anywhere in oracle/paillier_oracle.py fails at least one of these.
 """
-import itertools
 import math
 import os
 import random
