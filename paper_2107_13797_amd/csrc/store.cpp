@@ -390,11 +390,13 @@ int haflo_h_decrypt(haflo_store* s, haflo_handle cipher, uint32_t uses, haflo_ha
   const int kinds[1] = {HAFLO_KIND_CIPHER};
   if (!s->operands_ok(&cipher, kinds, 1)) return HAFLO_EINVAL;
   size_t count = s->get(cipher)->count;
+  const size_t want = haflo_workspace_bytes(s->ctx, HAFLO_OP_DECRYPT, count, 0);
+  if (want == (size_t)-1) return HAFLO_ENOPRIV;  // a public-only context has no decryption workspace
   haflo_handle hp;
   int rc = s->create(HAFLO_KIND_PLAIN, count, uses, &hp);
   if (rc != HAFLO_OK) return rc;
   Scratch ws(s);
-  if (!ws.take(haflo_workspace_bytes(s->ctx, HAFLO_OP_DECRYPT, count, 0))) {
+  if (!ws.take(want)) {
     s->drop(hp);
     return HAFLO_ENOMEM;
   }

@@ -187,6 +187,15 @@ def test_store_fore_gradient_chain_matches_oracle(env):
     assert vals.tolist() == [(a + b - 2 * l) / 2.0 ** (s + 2) for a, b, l in zip(*q)]
     assert lib.haflo_store_release(st.h, d) == 0 and st.stats()["live_bytes"] == 0
     st.close()
+    # a store over a public-only context refuses to decrypt and keeps the operand
+    pub = C.c_void_p()
+    nb = pk.n.to_bytes(BITS // 8, "little")
+    assert lib.haflo_ctx_create_public((C.c_uint8 * len(nb)).from_buffer_copy(nb), BITS, C.byref(pub)) == 0
+    ps = EmuStore(lib, pub, 1 << 20)
+    rc, hc = ps.new(K.KIND_CIPHER, 2, 1)
+    assert rc == 0 and ps.op("haflo_h_decrypt", hc, 1)[0] == -3 and ps.info(hc)[3] == 1
+    ps.close()
+    assert lib.haflo_ctx_destroy(pub) == 0
 
 
 def test_store_matvec_sum_and_scalars_match_oracle(env):
