@@ -33,8 +33,8 @@ PEAK_MAD32_PER_S = 256 * 64 * 2.4e9
 
 # HBM bytes per 2048-bit encryption measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this
 # launch shape, each scaled by what the counter reads for a 1 GiB device copy
-# (profiles/k_engine_encrypt_2048bit_b65536_pmc.md): (11787397 + 3465925) KiB per 65536 encryptions.
-TRAFFIC_BYTES_PER_ENCRYPT_2048 = (11787397 + 3465925) * 1024 / 65536
+# (profiles/k_engine_encrypt_2048bit_b65536_pmc.md): (11430924 + 3085898) KiB per 65536 encryptions.
+TRAFFIC_BYTES_PER_ENCRYPT_2048 = (11430924 + 3085898) * 1024 / 65536
 
 
 def montmul_mul32(limbs):
