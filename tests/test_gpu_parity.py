@@ -571,6 +571,52 @@ def test_hetero_lr_iteration_end_to_end(api):
         assert abs(got - want) < 6000 * 5.0 * 2.0 ** -16  # entries of X are quantised to 2^-16
 
 
+def test_benchmark_workload_shape(api):
+    """The step the benchmark times, at its size and launch configuration (2048-bit key, 65536 x 32,
+    public-key encryption): sampled ciphertexts through encrypt -> add -> scalar_mul against the
+    oracle, and every decoded matvec output against exact integers."""
+    bits, B, F = 2048, 65536, 32
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n = pk.n
+    pub = api.haflo_ctx_create_public(n, bits)
+    seed = synth.BASE_SEED + bits
+    dv = synth.normal_f32(B, 0.25, seed + 1)
+    ov = synth.normal_f32(B, 0.25, seed + 4)
+    wv = synth.normal_f32(F, 0.1, seed + 5)
+    r_words = random_units_words(B, bits, seed)
+    Xg = api.haflo_encode_exponents_f32(to_dev(synth.normal_f32((B, F), 1.0, seed + 2)), 16)
+    Xw = api.haflo_encode_exponents_f32(to_dev(synth.sparse_uniform_f32((B, F), 0.7, seed + 3)), 16)
+    other = api.haflo_encrypt(ctx, api.haflo_encode_f32(ctx, to_dev(ov), 24), to_dev(np.roll(r_words, 1, axis=0)))
+    wc = api.haflo_encrypt(ctx, api.haflo_encode_f32(ctx, to_dev(wv), 24), to_dev(r_words[:F].copy()))
+    say("bench shape: step")
+    c = api.haflo_encrypt(pub, api.haflo_encode_f32(pub, to_dev(dv), 24), to_dev(r_words))
+    fg = api.haflo_scalar_mul_i64_bcast(pub, api.haflo_add(pub, c, other), 64)
+    grad = api.haflo_cipher_matvec(pub, 0, fg, Xg)
+    fwd = api.haflo_cipher_matvec(pub, 1, wc, Xw)
+    q_fwd, _ = api.haflo_decode(ctx, api.haflo_decrypt(ctx, fwd[:4096].contiguous()), 40)
+    q_grad, _ = api.haflo_decode(ctx, api.haflo_decrypt(ctx, grad), 48)
+    pub.close()
+    say("bench shape: oracle on a sample")
+    idx = sample_indices(B, 24, seed + 6)
+    idx_t = torch.tensor(idx, device="cuda")
+    qd = np.rint(dv.astype(np.float64) * 2.0 ** 24).astype(np.int64)
+    qo = np.rint(ov.astype(np.float64) * 2.0 ** 24).astype(np.int64)
+    qw = np.rint(wv.astype(np.float64) * 2.0 ** 24).astype(np.int64)
+    r_int = synth.words_to_ints(r_words[idx])
+    ro_int = synth.words_to_ints(np.roll(r_words, 1, axis=0)[idx])
+    want_c = OP.encrypt_many(n, [int(qd[i]) % n for i in idx], r_int)
+    assert dev_to_ints(api.haflo_export_cipher(ctx, c[idx_t].contiguous())) == want_c
+    want_o = OP.encrypt_many(n, [int(qo[i]) % n for i in idx], ro_int)
+    want_fg = OP.pow_many(n, [O.add(pk, a, b) for a, b in zip(want_c, want_o)], [64] * len(idx))
+    assert dev_to_ints(api.haflo_export_cipher(ctx, fg[idx_t].contiguous())) == want_fg
+    say("bench shape: exact plaintexts")
+    Xg_h, Xw_h = Xg.cpu().numpy().astype(object), Xw.cpu().numpy()[:4096].astype(object)
+    resid = (64 * (qd.astype(object) + qo.astype(object)))
+    assert q_grad.cpu().tolist() == [int(v) for v in resid @ Xg_h]
+    assert q_fwd.cpu().tolist() == [int(v) for v in Xw_h @ qw.astype(object)]
+
+
 def test_side_stream_and_graph_replay(api):
     """The operators only enqueue kernels on the stream they are given: a chain (fused fore
     gradient, bucket matvec, table matvec, summation) gives the same words on a side stream as
