@@ -206,7 +206,8 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u32 limbs (32x32+64 integer multiply-add)",
+        "dtype": "u32",
+        "dtype_note": "29-bit limbs in u32 words, 32x32+64-bit integer multiply-add, exact integer arithmetic",
         "data": "synthetic",
         "config": {"workload": "hetero-LR step at a %d-bit key: encode, encrypt, add, scalar_mul, X^T[[d]], "
                                "X[[w]], decrypt, decode" % bits,
@@ -216,12 +217,13 @@ def main():
         "encrypt_key_owner_per_s": B / (own_ms * 1e-3),
         "roofline_key_owner_encrypt": {"bound": "alu", "kernel": "k_engine_pair (r^n mod p^2, q^2) + recombination",
                                        "achieved": achieved_o / 1e12, "peak": PEAK_MAD32_PER_S / 1e12,
-                                       "unit": "Tmad32/s", "frac": achieved_o / PEAK_MAD32_PER_S,
+                                       "unit": "TOP/s", "op": "32x32+64-bit integer multiply-add", "frac": achieved_o / PEAK_MAD32_PER_S,
                                        "algorithmic": "%d Montgomery-product equivalents x (2*%d^2+%d) mul32 per "
                                                       "encryption" % (mm_o, limbs_o, limbs_o)},
         "stage_ms": {k: v / args.steps for k, v in stage_ms.items()},
         "roofline": {"bound": "alu", "kernel": "k_engine (encryption program, modulus n^2)", "achieved": achieved / 1e12,
-                     "peak": PEAK_MAD32_PER_S / 1e12, "unit": "Tmad32/s", "frac": achieved / PEAK_MAD32_PER_S,
+                     "peak": PEAK_MAD32_PER_S / 1e12, "unit": "TOP/s", "op": "32x32+64-bit integer multiply-add",
+                     "frac": achieved / PEAK_MAD32_PER_S,
                      "traffic": (TRAFFIC_BYTES_PER_ENCRYPT_2048 * B if bits == 2048 else None),
                      "traffic_unit": "bytes per launch (rocprofv3 counters, see profiles/)",
                      "algorithmic": "%d Montgomery products x (2*%d^2+%d) mul32 per encryption" % (mm, limbs, limbs)},
