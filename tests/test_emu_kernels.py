@@ -174,8 +174,8 @@ def test_encrypt_with_obfuscator(env):
     w, nb = ws(lib, ctx, _cabi.OP_ENCRYPT, len(ms))
     zero = zeros(lib, (len(ms), lp))
     assert lib.haflo_encrypt(ctx, zero.p, words(lib, rs, lp).p, d_obf.p, len(ms), w.p, nb, None) == 0
-    obf = export(lib, ctx, d_obf, len(ms))
-    assert obf == [pow(r, pk.n, pk.nsq) for r in rs]
+    obf = [pow(r, pk.n, pk.nsq) for r in rs]
+    assert export(lib, ctx, d_obf, len(ms)) == obf
     w, nb = ws(lib, ctx, _cabi.OP_ENCRYPT_OBFUSCATOR, len(ms))
     assert lib.haflo_encrypt_with_obfuscator(ctx, words(lib, ms, lp).p, d_obf.p, d_obf.p, len(ms), w.p, nb, None) == 0
     assert export(lib, ctx, d_obf, len(ms)) == [O.encrypt_with_obfuscator(pk, m, o) for m, o in zip(ms, obf)]
@@ -184,9 +184,9 @@ def test_encrypt_with_obfuscator(env):
     bs = [rng.randrange(pk.n) for _ in ms]
     d_sum = zeros(lib, (len(ms), nlw))
     assert lib.haflo_encrypt_with_obfuscator(ctx, words(lib, bs, lp).p, d_obf.p, d_sum.p, len(ms), w.p, nb, None) == 0
-    got = export(lib, ctx, d_sum, len(ms))
-    assert got == [O.add(pk, O.encrypt(pk, m, r), O.encrypt(pk, b, 1)) for m, r, b in zip(ms, rs, bs)]
-    assert [O.decrypt(sk, c) for c in got] == [(m + b) % pk.n for m, b in zip(ms, bs)]
+    want_sum = [O.add(pk, O.encrypt(pk, m, r), O.encrypt(pk, b, 1)) for m, r, b in zip(ms, rs, bs)]
+    assert export(lib, ctx, d_sum, len(ms)) == want_sum
+    assert [O.decrypt(sk, c) for c in want_sum] == [(m + b) % pk.n for m, b in zip(ms, bs)]
 
 
 def test_public_context_encrypts_identically(env):

@@ -263,12 +263,13 @@ def test_cfg5_large_key_gradient(api, monkeypatch):
     sub_rows, sub_cols = 2048, 8
     sub_idx = idx[:16] + list(range(300, 300 + sub_rows - 16))
     sub_idx_t = torch.tensor(sub_idx, device="cuda")
-    sub_c = c[sub_idx_t].contiguous()
     sub_X = X[sub_idx_t][:, :sub_cols].contiguous()
-    # the oracle needs these 2048 ciphertexts: take the 16 already checked plus GPU exports of
-    # the rest, whose encryption path is the one checked on the sample above
-    sub_c_int = dev_to_ints(api.haflo_export_cipher(ctx, sub_c))
-    assert sub_c_int[:16] == want_c[:16]
+    # 2048 oracle encryptions at this key size would take half an hour: the inputs of the reduced
+    # product are the 16 oracle ciphertexts of the sample plus seeded random residues modulo n^2
+    # (units, but for a negligible chance), imported like any ciphertext a framework hands over
+    unit_rng = random.Random(synth.seed_for(5, 4))
+    sub_c_int = want_c[:16] + [unit_rng.randrange(1, n * n) for _ in range(sub_rows - 16)]
+    sub_c = api.haflo_import_cipher(ctx, ints_to_dev(sub_c_int, bits // 16))
     want_sub = OP.matvec_cols(n, sub_c_int, [Xo[sub_idx, j].tolist() for j in range(sub_cols)])
     for method, threshold in XTD_METHODS.items():
         monkeypatch.setenv(XTD_THRESHOLD, threshold)
@@ -283,7 +284,6 @@ def test_cfg5_large_key_gradient(api, monkeypatch):
     assert dev_to_ints(pl) == [e % n for e in exact]
     q, _ = api.haflo_decode(ctx, pl, cfg["scale_d"] + cfg["scale_x"])
     assert q.cpu().tolist() == exact
-    assert dev_to_ints(pl) == OP.decrypt_many(sk.p, sk.q, dev_to_ints(api.haflo_export_cipher(ctx, out)))
 
 
 # ---------------------------------------------------------------------------
@@ -429,7 +429,8 @@ def test_fore_gradient_chain(api):
     out = api.haflo_fore_gradient(ctx, c_host, to_dev(ug), to_dev(y), to_dev(r2), s, status=st)
     idx = sample_indices(count, 48, 76) + [5, 6]
     idx_t = torch.tensor(idx, device="cuda")
-    host_int = dev_to_ints(api.haflo_export_cipher(ctx, c_host[idx_t].contiguous()))
+    host_int = OP.encrypt_many(n, [O.quantise(float(uh[i]), s) % n for i in idx], synth.words_to_ints(r1[idx]))
+    assert dev_to_ints(api.haflo_export_cipher(ctx, c_host[idx_t].contiguous())) == host_int
     r2_int = synth.words_to_ints(r2[idx])
     want = [O.fore_gradient(pk, host_int[k], float(ug[i]), float(y[i]), r2_int[k], s) for k, i in enumerate(idx)]
     assert dev_to_ints(api.haflo_export_cipher(ctx, out[idx_t].contiguous())) == [c for c, _ in want]
@@ -482,9 +483,10 @@ def test_taylor_loss_sequence(api):
                     for a, b, t in zip(m1, qg, qy))
         assert dev_to_ints(api.haflo_decrypt(ctx, out)) == [total % n]
         if exact_cipher:
-            cu_int = dev_to_ints(api.haflo_export_cipher(ctx, c_u))
-            cu2_int = dev_to_ints(api.haflo_export_cipher(ctx, c_u2))
-            assert cu_int[:4] == OP.encrypt_many(n, [int(v) % n for v in m1[:4]], synth.words_to_ints(r1[:4]))
+            cu_int = OP.encrypt_many(n, [int(v) % n for v in m1], synth.words_to_ints(r1))
+            cu2_int = OP.encrypt_many(n, [int(v) * int(v) for v in m1], synth.words_to_ints(r2))
+            assert dev_to_ints(api.haflo_export_cipher(ctx, c_u)) == cu_int
+            assert dev_to_ints(api.haflo_export_cipher(ctx, c_u2)) == cu2_int
             want, flag = O.taylor_loss(pk, cu_int, cu2_int, [float(v) for v in ug], [float(v) for v in y],
                                        synth.words_to_ints(r3)[0], s)
             assert flag == 1 and dev_to_ints(api.haflo_export_cipher(ctx, out)) == [want]
