@@ -573,6 +573,63 @@ def test_hetero_lr_iteration_end_to_end(api):
         assert abs(got - want) < 6000 * 5.0 * 2.0 ** -16  # entries of X are quantised to 2^-16
 
 
+def test_random_operator_mixes(api, monkeypatch):
+    """Seeded random shapes, key sizes, sparsities and exponent widths through every operator:
+    sampled ciphertexts against the oracle, every decrypted result against exact integers, the two
+    X^T [[d]] methods and the two encryption routes against each other."""
+    rng = random.Random(20210713)
+    pubs = {}
+    for it in range(36):
+        bits = rng.choice((512, 1024, 1024, 2048))
+        own, sk = context(api, bits)
+        pk = sk.public
+        n = pk.n
+        lp = bits // 32
+        if bits not in pubs:
+            pubs[bits] = api.haflo_ctx_create_public(n, bits)
+        pub = pubs[bits]
+        count = rng.choice((1, 2, 7, 63, 65, 300, 1000, 2500, 5000))
+        ms = [rng.randrange(n) if rng.random() < 0.8 else rng.choice((0, 1, n - 1)) for _ in range(count)]
+        rs = [rng.randrange(1, n) for _ in range(count)]
+        say("mix", it, bits, count)
+        c = api.haflo_encrypt(pub, ints_to_dev(ms, lp), ints_to_dev(rs, lp))
+        assert torch.equal(c, api.haflo_encrypt(own, ints_to_dev(ms, lp), ints_to_dev(rs, lp)))
+        idx = sorted({0, count - 1} | {rng.randrange(count) for _ in range(3)})
+        got = dev_to_ints(api.haflo_export_cipher(pub, c[torch.tensor(idx, device="cuda")].contiguous()))
+        assert got == [O.encrypt(pk, ms[i], rs[i]) for i in idx]
+        assert dev_to_ints(api.haflo_decrypt(own, c)) == ms
+        k = rng.choice((0, 1, -1, 3, -7, rng.randrange(-2 ** 63, 2 ** 63)))
+        sm = api.haflo_scalar_mul_i64_bcast(pub, c, k)
+        assert dev_to_ints(api.haflo_decrypt(own, sm)) == [(m * k) % n for m in ms]
+        ks = [rng.randrange(2 ** 64) for _ in range(count)]
+        sm2 = api.haflo_scalar_mul_u64(pub, c, to_dev(np.array(ks, dtype=np.uint64)))
+        assert dev_to_ints(api.haflo_decrypt(own, sm2)) == [(m * kk) % n for m, kk in zip(ms, ks)]
+        assert dev_to_ints(api.haflo_decrypt(own, api.haflo_add(pub, c, sm))) == [(m * (k + 1)) % n for m in ms]
+        cols, magbits, zero_frac = rng.choice((1, 2, 5, 33)), rng.choice((1, 8, 16, 20, 31)), rng.choice((0.0, 0.5, 0.9))
+        npr = np.random.default_rng(rng.randrange(2 ** 31))
+        X = npr.integers(-(2 ** magbits), 2 ** magbits, size=(count, cols))
+        X[npr.random(X.shape) < zero_frac] = 0
+        X = X.astype(np.int32)
+        want = [sum(int(X[i, j]) * ms[i] for i in range(count)) % n for j in range(cols)]
+        outs = []
+        for threshold in XTD_METHODS.values():
+            monkeypatch.setenv(XTD_THRESHOLD, threshold)
+            outs.append(api.haflo_cipher_matvec(pub, 0, c, to_dev(X)).clone())
+            assert dev_to_ints(api.haflo_decrypt(own, outs[-1])) == want
+        monkeypatch.delenv(XTD_THRESHOLD)
+        assert torch.equal(outs[0], outs[1])
+        rows2 = rng.choice((1, 3, 70))
+        Y = npr.integers(-(2 ** magbits), 2 ** magbits, size=(rows2, count))
+        Y[npr.random(Y.shape) < max(zero_frac, 0.5 if count > 1000 else 0.0)] = 0
+        Y = Y.astype(np.int32)
+        f = api.haflo_cipher_matvec(pub, 1, c, to_dev(Y))
+        assert dev_to_ints(api.haflo_decrypt(own, f)) == [sum(int(Y[i, j]) * ms[j] for j in range(count)) % n
+                                                       for i in range(rows2)]
+        assert dev_to_ints(api.haflo_decrypt(own, api.haflo_cipher_sum(pub, c))) == [sum(ms) % n]
+    for pub in pubs.values():
+        pub.close()
+
+
 def test_benchmark_workload_shape(api):
     """The step the benchmark times, at its size and launch configuration (2048-bit key, 65536 x 32,
     public-key encryption): sampled ciphertexts through encrypt -> add -> scalar_mul against the
