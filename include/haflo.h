@@ -117,6 +117,18 @@ int haflo_ctx_destroy(haflo_ctx* ctx);
 int haflo_ctx_info(const haflo_ctx* ctx, uint32_t* n_bits, uint32_t* cipher_limbs, uint32_t* plain_limbs,
                    size_t* cipher_bytes_internal, size_t* plain_bytes);
 
+/* Row count from which X^T [[d]] (haflo_cipher_matvec, orientation 0) takes
+ * the bucket method instead of per-base power tables; both give the same
+ * ciphertext bits. The setting belongs to the context and is read by the
+ * matvec itself and by every workspace query that contains one
+ * (haflo_workspace_bytes for the matvec and the Taylor loss, the store's
+ * calls), so change it only between a query and the call it sizes if both are
+ * repeated. min_rows = 0 restores HAFLO_XTD_BUCKET_MIN_ROWS_DEFAULT; 1 forces
+ * buckets wherever the shape allows them; SIZE_MAX forces tables. Not
+ * synchronised: do not call it while another thread uses the context. */
+#define HAFLO_XTD_BUCKET_MIN_ROWS_DEFAULT 4096
+int haflo_ctx_set_xtd_bucket_min_rows(haflo_ctx* ctx, size_t min_rows);
+
 /* Arithmetic cost of one element of an operator, for throughput accounting:
  * the number of Montgomery products the library's schedule executes per
  * element (exponentiation windows and table building included) and the size,
@@ -240,9 +252,8 @@ int haflo_scalar_mul_i64_bcast(const haflo_ctx* ctx, const void* d_c, int64_t k,
  * d_c. Workspace: HAFLO_OP_MATVEC_XT_D / HAFLO_OP_MATVEC_X_W with the shape.
  * Orientation 0 has two implementations with identical results: per-base
  * power tables for matrices of fewer than 4096 rows (or more than 1024
- * columns), the bucket method above that. The environment variable
- * HAFLO_XTD_BUCKET_MIN_ROWS, read at every call and at every workspace query,
- * replaces the 4096 (a tuning and testing aid).
+ * columns), the bucket method above that; the row threshold is a setting of
+ * the context (haflo_ctx_set_xtd_bucket_min_rows).
  */
 int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, const int32_t* d_X, size_t rows,
                         size_t cols, void* d_out, void* d_workspace, size_t workspace_bytes, void* stream);

@@ -233,6 +233,14 @@ def summation(pk: PublicKey, cs: Iterable[int]) -> int:
     return acc
 
 
+def summation_segments(pk: PublicKey, cs: Sequence[int], offsets: Sequence[int]) -> List[int]:
+    """The summation of Table 1 over consecutive slices of one array: output i
+    is the product of cs[offsets[i]:offsets[i+1]] modulo n^2 (1 for an empty
+    slice). offsets is non-decreasing and stays within the array."""
+    assert all(0 <= a <= b <= len(cs) for a, b in zip(offsets, offsets[1:]))
+    return [summation(pk, cs[a:b]) for a, b in zip(offsets, offsets[1:])]
+
+
 def matvec(pk: PublicKey, orientation: int, cs: Sequence[int], X: Sequence[Sequence[int]]) -> List[int]:
     """Ciphertext matrix-vector product with signed integer exponents.
 

@@ -21,6 +21,7 @@ PROTOTYPES = {
     "haflo_ctx_destroy": (c_int, [c_void_p]),
     "haflo_ctx_info": (c_int, [c_void_p, C.POINTER(c_u32), C.POINTER(c_u32), C.POINTER(c_u32),
                                C.POINTER(c_size_t), C.POINTER(c_size_t)]),
+    "haflo_ctx_set_xtd_bucket_min_rows": (c_int, [c_void_p, c_size_t]),
     "haflo_op_cost": (c_int, [c_void_p, c_int, C.POINTER(c_u64), C.POINTER(c_u32)]),
     "haflo_workspace_bytes": (c_size_t, [c_void_p, c_int, c_size_t, c_size_t]),
     "haflo_import_cipher": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),

@@ -118,6 +118,10 @@ def haflo_ctx_destroy(ctx):
     ctx.close()
 
 
+def haflo_ctx_set_xtd_bucket_min_rows(ctx, min_rows):
+    _check(lib().haflo_ctx_set_xtd_bucket_min_rows(ctx.handle, min_rows))
+
+
 def haflo_workspace_bytes(ctx, op, rows, cols=0):
     return lib().haflo_workspace_bytes(ctx.handle, op, rows, cols)
 

@@ -491,6 +491,12 @@ int haflo_ctx_info(const haflo_ctx* ctx, uint32_t* n_bits, uint32_t* cipher_limb
   return HAFLO_OK;
 }
 
+int haflo_ctx_set_xtd_bucket_min_rows(haflo_ctx* ctx, size_t min_rows) {
+  if (!ctx) return HAFLO_EINVAL;
+  ctx->xtd_bucket_min_rows = min_rows ? min_rows : (size_t)HAFLO_XTD_BUCKET_MIN_ROWS_DEFAULT;
+  return HAFLO_OK;
+}
+
 int haflo_op_cost(const haflo_ctx* ctx, int op, uint64_t* montmuls, uint32_t* modulus_limbs) {
   if (!ctx) return HAFLO_EINVAL;
   uint64_t mm = 0;

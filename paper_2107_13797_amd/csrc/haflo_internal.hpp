@@ -105,6 +105,7 @@ struct haflo_ctx {
   bool has_priv = false;
   int lc = 0, lp = 0;  // canonical 32-bit limbs of a ciphertext / plaintext
   int num_cu = 0;
+  size_t xtd_bucket_min_rows = HAFLO_XTD_BUCKET_MIN_ROWS_DEFAULT;  // X^T [[d]]: bucket method from this many rows on
   haflo::Big n, nsq, p, q;
   haflo::ModHost N;            // n^2
   haflo::ModHost Nw;           // n, at the limb count (and Montgomery radix) of n^2

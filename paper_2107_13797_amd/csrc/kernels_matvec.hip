@@ -747,12 +747,9 @@ XtdPlan xtd_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
 
 // Tall matrices go through the bucket method (one product per exponent digit instead of four or
 // five, no tables); below the row threshold its fixed cost per column (1024 buckets per digit
-// position) outweighs that. HAFLO_XTD_BUCKET_MIN_ROWS overrides the threshold.
-constexpr size_t kBucketMinRows = 4096;
-bool use_buckets(size_t rows, size_t cols) {
-  size_t min_rows = kBucketMinRows;
-  if (const char* e = getenv("HAFLO_XTD_BUCKET_MIN_ROWS")) min_rows = (size_t)strtoull(e, nullptr, 10);
-  return rows >= min_rows && rows > 0 && xtd_buckets_fit(rows, cols);
+// position) outweighs that. The threshold is a setting of the context (haflo_ctx_set_xtd_bucket_min_rows).
+bool use_buckets(const haflo_ctx* ctx, size_t rows, size_t cols) {
+  return rows >= ctx->xtd_bucket_min_rows && rows > 0 && xtd_buckets_fit(rows, cols);
 }
 struct XtdBucketLayout {
   size_t off_P, off_ws, total;  // in u32 words; word 0 holds the largest |x|
@@ -847,7 +844,7 @@ size_t haflo_workspace_bytes(const haflo_ctx* ctx, int op, size_t rows, size_t c
              ws_encrypt(ctx, rows);
     case HAFLO_OP_MATVEC_XT_D:
       if (!cols) return 0;
-      return (use_buckets(rows, cols) ? xtd_bucket_layout(ctx, rows, cols).total : xtd_plan(ctx, rows, cols).total) * 4;
+      return (use_buckets(ctx, rows, cols) ? xtd_bucket_layout(ctx, rows, cols).total : xtd_plan(ctx, rows, cols).total) * 4;
     case HAFLO_OP_MATVEC_X_W: return xw_plan(ctx, rows, cols).total * 4;
     default: return (size_t)-1;
   }
@@ -865,7 +862,7 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
   const size_t need = haflo_workspace_bytes(ctx, orientation == 0 ? HAFLO_OP_MATVEC_XT_D : HAFLO_OP_MATVEC_X_W, rows, cols);
   if (!d_workspace || workspace_bytes < need) return HAFLO_EINVAL;
   u32* ws = (u32*)d_workspace;
-  const bool buckets = orientation == 0 && use_buckets(rows, cols);
+  const bool buckets = orientation == 0 && use_buckets(ctx, rows, cols);
   int rc = buckets ? HAFLO_OK
                    : launch_maxmag(ctx, d_X, rows * cols, ws, orientation == 0 ? 2 : (int)(kXwBinsAt + kLenBins), st);
   if (rc != HAFLO_OK) return rc;

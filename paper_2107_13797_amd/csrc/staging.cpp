@@ -34,6 +34,10 @@ struct haflo_stager {
   hipStream_t copy = nullptr;
   hipEvent_t copied[2] = {nullptr, nullptr};    // chunk arrived in / left d_stage[s]
   hipEvent_t consumed[2] = {nullptr, nullptr};  // d_stage[s] may be overwritten
+  // consumed[s] has been recorded by some call: its kernel may still be queued on the caller's stream
+  // when the next call starts, so every later writer of d_stage[s] waits for the event first
+  bool consumed_recorded[2] = {false, false};
+  hipEvent_t entered = nullptr;  // position of the caller's stream when a transfer into device memory starts
   size_t pinned_allocs = 0, pinned_reuses = 0;
 
   // a free buffer of at least `bytes` (the smallest that fits), or a new one
@@ -92,14 +96,18 @@ int stage_in(haflo_stager* s, const uint32_t* h_src, size_t words, void* d_dst, 
   int rc = HAFLO_OK;
   bool used[2] = {false, false};
   size_t done = 0;
+  // Nothing this call copies may overtake work already queued on the caller's stream: kernels that
+  // still read the destination (a recycled block) or, for plaintexts, anything ordered before the call.
+  if (hipEventRecord(s->entered, st) != hipSuccess || hipStreamWaitEvent(s->copy, s->entered, 0) != hipSuccess)
+    rc = HAFLO_EHIP;
   for (int slot = 0; done < count && rc == HAFLO_OK; slot ^= 1) {
     const size_t n = std::min(s->chunk, count - done);
-    // the page-locked buffer and the staging buffer of this slot are free once the copy that used
-    // them has finished and (for imports) the kernel that read the staging buffer has run
-    if (used[slot]) {
-      if (hipEventSynchronize(s->copied[slot]) != hipSuccess) rc = HAFLO_EHIP;
-      if (import && hipStreamWaitEvent(s->copy, s->consumed[slot], 0) != hipSuccess) rc = HAFLO_EHIP;
-    }
+    // the page-locked buffer of this slot is free once the copy that used it has finished
+    if (used[slot] && hipEventSynchronize(s->copied[slot]) != hipSuccess) rc = HAFLO_EHIP;
+    // the staging buffer is free once the kernel that read it last has run: one of this call, or
+    // one that an earlier call left queued on its stream
+    if (import && s->consumed_recorded[slot] && hipStreamWaitEvent(s->copy, s->consumed[slot], 0) != hipSuccess)
+      rc = HAFLO_EHIP;
     if (rc != HAFLO_OK) break;
     memcpy(pin[slot]->p, h_src + done * words, n * words * 4);
     void* dst = import ? s->d_stage[slot] : (void*)((char*)d_dst + done * dst_stride_bytes);
@@ -116,7 +124,10 @@ int stage_in(haflo_stager* s, const uint32_t* h_src, size_t words, void* d_dst, 
     if (import) {
       rc = haflo_import_cipher(s->ctx, (const uint32_t*)s->d_stage[slot], (char*)d_dst + done * dst_stride_bytes,
                                d_status, n, st);
-      if (rc == HAFLO_OK && hipEventRecord(s->consumed[slot], st) != hipSuccess) rc = HAFLO_EHIP;
+      if (rc == HAFLO_OK) {
+        if (hipEventRecord(s->consumed[slot], st) != hipSuccess) rc = HAFLO_EHIP;
+        else s->consumed_recorded[slot] = true;
+      }
     }
     done += n;
   }
@@ -154,7 +165,12 @@ int stage_out(haflo_stager* s, const void* d_src, size_t src_stride_bytes, size_
     const size_t n = std::min(s->chunk, count - issued);
     const void* src = (const char*)d_src + issued * src_stride_bytes;
     if (do_export) {
-      // the staging buffer of this slot was last read by the copy that drain() waited for
+      // the staging buffer of this slot was last read by the copy that drain() waited for, or by an
+      // import kernel that an earlier call queued (on this stream or another)
+      if (s->consumed_recorded[slot] && hipStreamWaitEvent(st, s->consumed[slot], 0) != hipSuccess) {
+        rc = HAFLO_EHIP;
+        break;
+      }
       rc = haflo_export_cipher(s->ctx, src, (uint32_t*)s->d_stage[slot], n, st);
       if (rc != HAFLO_OK) break;
       src = s->d_stage[slot];
@@ -166,6 +182,7 @@ int stage_out(haflo_stager* s, const void* d_src, size_t src_stride_bytes, size_
       rc = HAFLO_EHIP;
       break;
     }
+    s->consumed_recorded[slot] = true;
     busy[slot] = true;
     len[slot] = n;
     at[slot] = issued;
@@ -192,7 +209,8 @@ int haflo_stager_create(const haflo_ctx* ctx, size_t chunk_elems, size_t pool_ca
   s->ctx = ctx;
   s->chunk = chunk_elems;
   s->pool_cap = pool_cap_bytes;
-  bool ok = hipStreamCreateWithFlags(&s->copy, hipStreamNonBlocking) == hipSuccess;
+  bool ok = hipStreamCreateWithFlags(&s->copy, hipStreamNonBlocking) == hipSuccess &&
+            hipEventCreateWithFlags(&s->entered, hipEventDisableTiming) == hipSuccess;
   for (int i = 0; i < 2 && ok; ++i) {
     ok = hipMalloc(&s->d_stage[i], chunk_elems * (size_t)ctx->lc * 4) == hipSuccess &&
          hipEventCreateWithFlags(&s->copied[i], hipEventDisableTiming) == hipSuccess &&
@@ -216,6 +234,7 @@ int haflo_stager_destroy(haflo_stager* s) {
     if (s->copied[i]) (void)hipEventDestroy(s->copied[i]);
     if (s->consumed[i]) (void)hipEventDestroy(s->consumed[i]);
   }
+  if (s->entered) (void)hipEventDestroy(s->entered);
   if (s->copy) (void)hipStreamDestroy(s->copy);
   delete s;
   return HAFLO_OK;

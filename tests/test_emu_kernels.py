@@ -264,8 +264,11 @@ def test_matvec_signed_digit_boundaries(env, top):
 
 
 @pytest.fixture
-def force_buckets(monkeypatch):
-    monkeypatch.setenv("HAFLO_XTD_BUCKET_MIN_ROWS", "1")
+def force_buckets(env):
+    lib, ctx = env[0], env[1]
+    assert lib.haflo_ctx_set_xtd_bucket_min_rows(ctx, 1) == 0
+    yield
+    assert lib.haflo_ctx_set_xtd_bucket_min_rows(ctx, 0) == 0
 
 
 def _xtd_case(env, X, seed):
@@ -303,12 +306,20 @@ def test_bucket_matvec_heavy_buckets(env, force_buckets):
 
 
 @pytest.mark.parametrize("seed", range(6))
-@pytest.mark.parametrize("method", ["1", "1000000000000"])
-def test_gradient_matvec_random_shapes(env, monkeypatch, seed, method):
+@pytest.mark.parametrize("method", [1, 2 ** 64 - 1])
+def test_gradient_matvec_random_shapes(env, seed, method):
     """Random shapes and exponent distributions through both gradient-matvec methods (the
-    environment variable moves the row threshold): sparse, dense, one magnitude only, full int32
+    context's row threshold forces either): sparse, dense, one magnitude only, full int32
     range, powers of 1024 and their neighbours."""
-    monkeypatch.setenv("HAFLO_XTD_BUCKET_MIN_ROWS", method)
+    lib, ctx = env[0], env[1]
+    assert lib.haflo_ctx_set_xtd_bucket_min_rows(ctx, method) == 0
+    try:
+        _gradient_matvec_random_shape(env, seed)
+    finally:
+        assert lib.haflo_ctx_set_xtd_bucket_min_rows(ctx, 0) == 0
+
+
+def _gradient_matvec_random_shape(env, seed):
     rng = np.random.default_rng(1000 + seed)
     rows, cols = int(rng.integers(1, 45)), int(rng.integers(1, 4))
     kind = seed % 6

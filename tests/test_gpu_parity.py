@@ -54,9 +54,22 @@ def context(api, bits):
 from helpers import dev_to_ints, ints_to_dev, random_units_words, to_dev  # noqa: E402
 
 # X^T [[d]] has two implementations chosen by the row count (power tables below the threshold,
-# buckets above); this environment variable moves the threshold so that either can be forced.
-XTD_THRESHOLD = "HAFLO_XTD_BUCKET_MIN_ROWS"
-XTD_METHODS = {"tables": "1000000000000", "buckets": "1"}
+# buckets above); the threshold is a setting of the context, so either can be forced.
+XTD_METHODS = {"tables": 2 ** 64 - 1, "buckets": 1}
+
+
+class xtd_method:
+    """with xtd_method(api, ctx, "tables"|"buckets"): ... - the default threshold is restored on exit."""
+
+    def __init__(self, api, ctx, method):
+        self.api, self.ctx, self.threshold = api, ctx, XTD_METHODS[method]
+
+    def __enter__(self):
+        self.api.haflo_ctx_set_xtd_bucket_min_rows(self.ctx, self.threshold)
+
+    def __exit__(self, *exc):
+        self.api.haflo_ctx_set_xtd_bucket_min_rows(self.ctx, 0)
+        return False
 
 
 def sample_indices(count, k, seed):
@@ -109,7 +122,7 @@ def test_cfg1_operator_mix_full_parity(api):
 # ---------------------------------------------------------------------------
 # configuration 2: hetero-LR encrypted gradient at a 1024-bit key, everything compared
 # ---------------------------------------------------------------------------
-def test_cfg2_encrypted_gradient_full_parity(api, monkeypatch):
+def test_cfg2_encrypted_gradient_full_parity(api):
     cfg = synth.CONFIGS[2]
     bits, rows, cols = cfg["n_bits"], cfg["rows"], cfg["cols"]
     ctx, sk = context(api, bits)
@@ -135,11 +148,10 @@ def test_cfg2_encrypted_gradient_full_parity(api, monkeypatch):
     assert dev_to_ints(api.haflo_export_cipher(ctx, c)) == want_c
     say("cfg2: matvec")
     want_out = OP.matvec_cols(n, want_c, [[row[j] for row in Xo] for j in range(cols)])
-    for method, threshold in XTD_METHODS.items():
-        monkeypatch.setenv(XTD_THRESHOLD, threshold)
-        forced = api.haflo_cipher_matvec(ctx, 0, c, X)
+    for method in XTD_METHODS:
+        with xtd_method(api, ctx, method):
+            forced = api.haflo_cipher_matvec(ctx, 0, c, X)
         assert dev_to_ints(api.haflo_export_cipher(ctx, forced)) == want_out, method
-    monkeypatch.delenv(XTD_THRESHOLD)
     out = api.haflo_cipher_matvec(ctx, 0, c, X)
     assert dev_to_ints(api.haflo_export_cipher(ctx, out)) == want_out
     say("cfg2: decrypt + decode")
@@ -239,7 +251,7 @@ def test_cfg4_aggregation_full_size(api):
 # ---------------------------------------------------------------------------
 # configuration 5: large-key gradient at a 4096-bit key
 # ---------------------------------------------------------------------------
-def test_cfg5_large_key_gradient(api, monkeypatch):
+def test_cfg5_large_key_gradient(api):
     cfg = synth.CONFIGS[5]
     bits, rows, cols = cfg["n_bits"], cfg["rows"], cfg["cols"]
     ctx, sk = context(api, bits)
@@ -256,6 +268,14 @@ def test_cfg5_large_key_gradient(api, monkeypatch):
     qd = np.rint(d.astype(np.float64) * 2.0 ** cfg["scale_d"]).astype(np.int64)
     want_c = OP.encrypt_many(n, [int(qd[i]) % n for i in idx], synth.words_to_ints(r_words[idx]))
     assert dev_to_ints(api.haflo_export_cipher(ctx, c[idx_t].contiguous())) == want_c
+    say("cfg5: encrypt with the public key only (full size)")
+    # the full-length exponentiation modulo n^2, the route a party without the private key takes
+    pub = api.haflo_ctx_create_public(n, bits)
+    c_pub = api.haflo_encrypt(pub, plain, to_dev(r_words))
+    assert dev_to_ints(api.haflo_export_cipher(pub, c_pub[idx_t].contiguous())) == want_c
+    assert torch.equal(c_pub, c)
+    del c_pub
+    pub.close()
     X = api.haflo_encode_exponents_f32(to_dev(Xf), cfg["scale_x"])
     Xo = np.rint(Xf.astype(np.float64) * 2.0 ** cfg["scale_x"]).astype(np.int64)
     assert np.array_equal(X.cpu().numpy().astype(np.int64), Xo)
@@ -271,11 +291,10 @@ def test_cfg5_large_key_gradient(api, monkeypatch):
     sub_c_int = want_c[:16] + [unit_rng.randrange(1, n * n) for _ in range(sub_rows - 16)]
     sub_c = api.haflo_import_cipher(ctx, ints_to_dev(sub_c_int, bits // 16))
     want_sub = OP.matvec_cols(n, sub_c_int, [Xo[sub_idx, j].tolist() for j in range(sub_cols)])
-    for method, threshold in XTD_METHODS.items():
-        monkeypatch.setenv(XTD_THRESHOLD, threshold)
-        sub_out = api.haflo_cipher_matvec(ctx, 0, sub_c, sub_X)
+    for method in XTD_METHODS:
+        with xtd_method(api, ctx, method):
+            sub_out = api.haflo_cipher_matvec(ctx, 0, sub_c, sub_X)
         assert dev_to_ints(api.haflo_export_cipher(ctx, sub_out)) == want_sub, method
-    monkeypatch.delenv(XTD_THRESHOLD)
     say("cfg5: full matvec, plaintext identity on every output")
     out = api.haflo_cipher_matvec(ctx, 0, c, X)
     pl = api.haflo_decrypt(ctx, out)
@@ -289,7 +308,7 @@ def test_cfg5_large_key_gradient(api, monkeypatch):
 # ---------------------------------------------------------------------------
 # edge cases
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("bits", [512, 1024, 2048])
+@pytest.mark.parametrize("bits", [512, 1024, 2048, 4096])
 def test_edges_import_export_add(api, bits):
     ctx, sk = context(api, bits)
     n, nsq = sk.n, sk.n ** 2
@@ -316,8 +335,8 @@ def test_edges_import_export_add(api, bits):
     assert api.haflo_export_cipher(ctx, empty).shape[0] == 0
 
 
-def test_edges_encrypt_decrypt(api):
-    bits = 1024
+@pytest.mark.parametrize("bits", [1024, 4096])
+def test_edges_encrypt_decrypt(api, bits):
     ctx, sk = context(api, bits)
     pk = sk.public
     n = pk.n
@@ -341,8 +360,8 @@ def test_edges_encrypt_decrypt(api):
     pub.close()
 
 
-def test_edges_scalar_mul(api):
-    bits = 1024
+@pytest.mark.parametrize("bits", [1024, 4096])
+def test_edges_scalar_mul(api, bits):
     ctx, sk = context(api, bits)
     pk = sk.public
     n = pk.n
@@ -359,9 +378,13 @@ def test_edges_scalar_mul(api):
 
 @pytest.mark.parametrize("method", ["tables", "buckets"])
 @pytest.mark.parametrize("bits", [512, 2048])
-def test_edges_matvec(api, bits, method, monkeypatch):
-    monkeypatch.setenv(XTD_THRESHOLD, XTD_METHODS[method])
+def test_edges_matvec(api, bits, method):
     ctx, sk = context(api, bits)
+    with xtd_method(api, ctx, method):
+        _edges_matvec(api, bits, method, ctx, sk)
+
+
+def _edges_matvec(api, bits, method, ctx, sk):
     pk = sk.public
     n = pk.n
     rng = random.Random(8)
@@ -493,7 +516,7 @@ def test_taylor_loss_sequence(api):
 
 
 @pytest.mark.parametrize("kind", ["int32_range", "one_hot", "sparse_small"])
-def test_xtd_methods_agree_at_scale(api, kind, monkeypatch):
+def test_xtd_methods_agree_at_scale(api, kind):
     """Tall matrices beyond what the oracle can multiply: both X^T [[d]] methods must give the same
     canonical ciphertexts, and every output must decrypt to sum_i x_ij m_i mod n. The shapes put
     up to 70000 rows into one bucket (five reduction rounds) and use all four digit positions."""
@@ -517,9 +540,9 @@ def test_xtd_methods_agree_at_scale(api, kind, monkeypatch):
     plain = to_dev(synth.ints_to_words([int(v) for v in m], bits // 32))
     c = api.haflo_encrypt(ctx, plain, to_dev(random_units_words(rows, bits, 92)))
     outs = {}
-    for method, threshold in XTD_METHODS.items():
-        monkeypatch.setenv(XTD_THRESHOLD, threshold)
-        outs[method] = api.haflo_cipher_matvec(ctx, 0, c, to_dev(X)).clone()
+    for method in XTD_METHODS:
+        with xtd_method(api, ctx, method):
+            outs[method] = api.haflo_cipher_matvec(ctx, 0, c, to_dev(X)).clone()
     assert torch.equal(outs["tables"], outs["buckets"])
     exact = [int(np.dot(X[:, j].astype(object), m.astype(object))) % n for j in range(cols)]
     assert dev_to_ints(api.haflo_decrypt(ctx, outs["buckets"])) == exact
@@ -556,6 +579,42 @@ def test_host_staging_pipeline(api):
     stager.close()
 
 
+def test_host_staging_back_to_back_calls_behind_queued_work(api):
+    """Two staging calls in a row while the stream is still busy: the import kernels of the first
+    call sit behind a long encryption when the second call starts to refill the two staging buffers,
+    and a plaintext transfer lands in a block that queued work still reads. Each call must see its
+    own data (the copy stream waits for what the caller's stream still has to run)."""
+    bits = 1024
+    ctx, sk = context(api, bits)
+    n = sk.public.n
+    stager = api.Stager(ctx, chunk_elems=700)
+    rng = random.Random(64)
+    count = 1400  # exactly two chunks: both staging buffers are in use when the call returns
+    h1 = np.ascontiguousarray(synth.ints_to_words([rng.randrange(n * n) for _ in range(count)], bits // 16))
+    h2 = np.ascontiguousarray(synth.ints_to_words([rng.randrange(n * n) for _ in range(count)], bits // 16))
+    busy_m = to_dev(random_units_words(60000, bits, 65))
+    busy_r = to_dev(random_units_words(60000, bits, 66))
+    p1 = np.ascontiguousarray(random_units_words(count, bits, 67))
+    p2 = np.ascontiguousarray(random_units_words(count, bits, 68))
+    torch.cuda.synchronize()
+    busy = api.haflo_encrypt(ctx, busy_m, busy_r)  # tens of milliseconds of queued work
+    d1 = api.haflo_stage_in_cipher(stager, h1)
+    d2 = api.haflo_stage_in_cipher(stager, h2)
+    # a plaintext array staged in, consumed by a queued kernel, released, and its block taken by the next transfer
+    a = api.haflo_stage_in_plain(stager, p1)
+    ca = api.haflo_encrypt(ctx, a, busy_r[:count].contiguous())
+    del a
+    b = api.haflo_stage_in_plain(stager, p2)
+    cb = api.haflo_encrypt(ctx, b, busy_r[:count].contiguous())
+    torch.cuda.synchronize()
+    assert torch.equal(d1, api.haflo_import_cipher(ctx, to_dev(h1)))
+    assert torch.equal(d2, api.haflo_import_cipher(ctx, to_dev(h2)))
+    assert torch.equal(ca, api.haflo_encrypt(ctx, to_dev(p1), busy_r[:count].contiguous()))
+    assert torch.equal(cb, api.haflo_encrypt(ctx, to_dev(p2), busy_r[:count].contiguous()))
+    assert busy.shape[0] == 60000
+    stager.close()
+
+
 def test_hetero_lr_iteration_end_to_end(api):
     """One two-party training iteration composed from the operators (fore gradient, both gradient
     matvecs, Taylor loss, decryption, decoding): what the arbiter decodes must equal the exact
@@ -573,14 +632,15 @@ def test_hetero_lr_iteration_end_to_end(api):
         assert abs(got - want) < 6000 * 5.0 * 2.0 ** -16  # entries of X are quantised to 2^-16
 
 
-def test_random_operator_mixes(api, monkeypatch):
+def test_random_operator_mixes(api):
     """Seeded random shapes, key sizes, sparsities and exponent widths through every operator:
     sampled ciphertexts against the oracle, every decrypted result against exact integers, the two
     X^T [[d]] methods and the two encryption routes against each other."""
     rng = random.Random(20210713)
     pubs = {}
-    for it in range(36):
-        bits = rng.choice((512, 1024, 1024, 2048))
+    for it in range(44):
+        # the first 36 draws are over the smaller keys; the last 8 run a 4096-bit key at small counts
+        bits = rng.choice((512, 1024, 1024, 2048)) if it < 36 else 4096
         own, sk = context(api, bits)
         pk = sk.public
         n = pk.n
@@ -588,7 +648,7 @@ def test_random_operator_mixes(api, monkeypatch):
         if bits not in pubs:
             pubs[bits] = api.haflo_ctx_create_public(n, bits)
         pub = pubs[bits]
-        count = rng.choice((1, 2, 7, 63, 65, 300, 1000, 2500, 5000))
+        count = rng.choice((1, 2, 7, 63, 65, 300, 1000, 2500, 5000)) if bits < 4096 else rng.choice((1, 3, 17, 65, 130, 400))
         ms = [rng.randrange(n) if rng.random() < 0.8 else rng.choice((0, 1, n - 1)) for _ in range(count)]
         rs = [rng.randrange(1, n) for _ in range(count)]
         say("mix", it, bits, count)
@@ -612,11 +672,10 @@ def test_random_operator_mixes(api, monkeypatch):
         X = X.astype(np.int32)
         want = [sum(int(X[i, j]) * ms[i] for i in range(count)) % n for j in range(cols)]
         outs = []
-        for threshold in XTD_METHODS.values():
-            monkeypatch.setenv(XTD_THRESHOLD, threshold)
-            outs.append(api.haflo_cipher_matvec(pub, 0, c, to_dev(X)).clone())
+        for method in XTD_METHODS:
+            with xtd_method(api, pub, method):
+                outs.append(api.haflo_cipher_matvec(pub, 0, c, to_dev(X)).clone())
             assert dev_to_ints(api.haflo_decrypt(own, outs[-1])) == want
-        monkeypatch.delenv(XTD_THRESHOLD)
         assert torch.equal(outs[0], outs[1])
         rows2 = rng.choice((1, 3, 70))
         Y = npr.integers(-(2 ** magbits), 2 ** magbits, size=(rows2, count))

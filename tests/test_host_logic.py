@@ -45,7 +45,8 @@ def test_strerror(lib):
 
 @pytest.mark.parametrize("bits,seed", [(512, 1), (512, 2), (512, 77), (512, 2 ** 63 + 5), (512, 2 ** 64 - 1),
                                        (1024, 1), (1024, 31337), (1024, 0), (1024, 12), (1024, 2 ** 40),
-                                       (2048, 5), (2048, 6), (2048, 7), (2048, 1000), (2048, 2 ** 62)])
+                                       (2048, 5), (2048, 6), (2048, 7), (2048, 1000), (2048, 2 ** 62),
+                                       (4096, 3), (4096, 4), (4096, 99), (4096, 2 ** 33 + 1), (4096, 2 ** 64 - 2)])
 def test_keygen_matches_oracle(lib, bits, seed):
     p = (C.c_uint8 * (bits // 16))()
     q = (C.c_uint8 * (bits // 16))()
@@ -69,6 +70,7 @@ def test_argument_errors_without_gpu(lib):
     assert lib.haflo_ctx_create_private(short, p, 512, C.byref(out)) == -2  # wrong bit length
     assert lib.haflo_ctx_destroy(None) == -1
     assert lib.haflo_ctx_info(None, None, None, None, None, None) == -1
+    assert lib.haflo_ctx_set_xtd_bucket_min_rows(None, 1) == -1
     assert lib.haflo_workspace_bytes(None, 1, 1, 0) == 2 ** 64 - 1
     assert lib.haflo_add(None, None, None, None, 4, None) == -1
     assert lib.haflo_encrypt(None, None, None, None, 4, None, 0, None) == -1

@@ -166,6 +166,30 @@ def test_roundtrip_and_crt_real_sizes(bits):
     assert O.summation(pk, []) == 1
 
 
+def test_summation_segments_decrypt_to_slice_sums():
+    """Every segment's product decrypts (through the brute-force-pinned decryption) to the sum of
+    its slice of plaintexts; empty segments give the encryption-free 1; one segment over the whole
+    array is the plain summation; on a tiny key the products are also checked by brute force."""
+    sk = _real_key(512)
+    pk = sk.public
+    n = pk.n
+    rng = random.Random(13)
+    ms = [rng.randrange(n) for _ in range(23)]
+    cs = [O.encrypt(pk, m, rng.randrange(1, n)) for m in ms]
+    offsets = [0, 0, 1, 1, 9, 20, 20, 23]
+    out = O.summation_segments(pk, cs, offsets)
+    assert len(out) == len(offsets) - 1
+    assert [O.decrypt_crt(sk, c) for c in out] == [sum(ms[a:b]) % n for a, b in zip(offsets, offsets[1:])]
+    assert out[0] == 1 and out[2] == 1 and out[5] == 1 and out[1] == cs[0]
+    assert O.summation_segments(pk, cs, [0, 23]) == [O.summation(pk, cs)]
+    assert O.summation_segments(pk, cs, [4, 7]) == [cs[4] * cs[5] * cs[6] % pk.nsq]
+    assert O.summation_segments(pk, cs, [5]) == [] and O.summation_segments(pk, [], [0, 0]) == [1]
+    tiny = O.PrivateKey(11, 13)
+    tcs = [O.encrypt(tiny.public, m, r) for m, r in ((3, 2), (140, 5), (0, 7), (77, 9))]
+    got = O.summation_segments(tiny.public, tcs, [1, 3, 4])
+    assert [brute_force_decrypt(tiny.public, c) for c in got] == [140 % 143, 77]
+
+
 def test_matvec_closed_form_on_plaintexts():
     """D(out) must equal the integer matrix-vector product of the plaintexts
     (exact Python integers), for both orientations, with signed entries."""
