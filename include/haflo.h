@@ -75,7 +75,8 @@ enum haflo_op {
   HAFLO_OP_MATVEC_X_W = 5,  /* orientation 1 */
   HAFLO_OP_FORE_GRADIENT = 6,
   HAFLO_OP_TAYLOR_LOSS = 7,
-  HAFLO_OP_ENCRYPT_OBFUSCATOR = 8
+  HAFLO_OP_ENCRYPT_OBFUSCATOR = 8,
+  HAFLO_OP_SUM_SEGMENTS = 9 /* rows = elements, cols = segments */
 };
 
 /* Text for an error code; never NULL. */
@@ -309,6 +310,22 @@ int haflo_taylor_loss(const haflo_ctx* ctx, const void* d_c_u, const void* d_c_u
  * HAFLO_OP_MATVEC_XT_D with rows = count, cols = 1. */
 int haflo_cipher_sum(const haflo_ctx* ctx, const void* d_c, size_t count, void* d_out, void* d_workspace,
                      size_t workspace_bytes, void* stream);
+
+/* "Homomorphic Summation" (paper Table 1) over consecutive slices of one
+ * array: out[k] = prod of c[offsets[k] .. offsets[k+1]) mod n^2 for k < nseg
+ * (1 for an empty slice); one slice over everything is haflo_cipher_sum.
+ * d_c: count internal elements, count < 2^32. d_offsets: nseg + 1 device
+ * uint32, non-decreasing, last <= count; nseg < 2^24. Slices may be of any
+ * length, from empty to the whole array: every slice is spread over the chip
+ * in chunks of 16 elements and reduced in rounds. An offset that runs
+ * backwards or past count is the caller's error: that slice is clipped or
+ * empty and HAFLO_ST_RANGE is OR-ed into d_status (one device uint32, or
+ * NULL); nothing outside the array is read. d_out: nseg internal elements, may
+ * not alias d_c. Workspace: HAFLO_OP_SUM_SEGMENTS with rows = count,
+ * cols = nseg. */
+int haflo_cipher_sum_segments(const haflo_ctx* ctx, const void* d_c, size_t count, const uint32_t* d_offsets,
+                              size_t nseg, void* d_out, uint32_t* d_status, void* d_workspace, size_t workspace_bytes,
+                              void* stream);
 
 /*
  * Host staging (paper section 3.2, "Operator-level Storage Optimizer": page-locked

@@ -51,6 +51,8 @@ PROTOTYPES = {
     "haflo_encrypt_with_obfuscator": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p, c_size_t,
                                               c_void_p]),
     "haflo_cipher_sum": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "haflo_cipher_sum_segments": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p, c_size_t, c_void_p, c_void_p, c_void_p,
+                                          c_size_t, c_void_p]),
     "haflo_store_create": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p, C.POINTER(c_void_p)]),
     "haflo_store_destroy": (c_int, [c_void_p]),
     "haflo_store_stats": (c_int, [c_void_p, C.POINTER(c_size_t), C.POINTER(c_size_t), C.POINTER(c_size_t),
@@ -76,6 +78,7 @@ PROTOTYPES = {
 KIND_CIPHER, KIND_PLAIN, KIND_F32, KIND_F64, KIND_I32, KIND_U32, KIND_I64, KIND_U64 = 1, 2, 3, 4, 5, 6, 7, 8
 
 OP_ENCRYPT, OP_DECRYPT, OP_SCALAR_MUL, OP_MATVEC_XT_D, OP_MATVEC_X_W, OP_FORE_GRADIENT, OP_TAYLOR_LOSS, OP_ENCRYPT_OBFUSCATOR = 1, 2, 3, 4, 5, 6, 7, 8
+OP_SUM_SEGMENTS = 9
 
 
 def bind(lib, names=None):

@@ -271,6 +271,18 @@ def haflo_cipher_sum(ctx, c):
     return out
 
 
+def haflo_cipher_sum_segments(ctx, c, offsets, status=None):
+    """offsets: int32 CUDA tensor of nseg + 1 non-decreasing element indices (read as uint32)."""
+    count, nseg = c.shape[0], offsets.numel() - 1
+    if offsets.dtype != torch.int32 or nseg < 0:
+        raise HafloError("offsets: int32 tensor of nseg + 1 entries")
+    out = _new_cipher(ctx, nseg)
+    ws = ctx.workspace(haflo_workspace_bytes(ctx, _cabi.OP_SUM_SEGMENTS, count, nseg))
+    _check(lib().haflo_cipher_sum_segments(ctx.handle, _ptr(c) if count else None, count, _ptr(offsets), nseg,
+                                           _ptr(out) if nseg else None, _ptr(status), _ptr(ws), ws.numel(), _stream()))
+    return out
+
+
 class Stager:
     """Owner of a haflo_stager: host numpy arrays in the interchange format <-> device arrays."""
 

@@ -190,4 +190,14 @@ XtdBucketPlan xtd_bucket_plan(const haflo_ctx* ctx, size_t rows, size_t cols);
 int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, size_t rows, size_t cols,
                 uint32_t* ws, uint32_t* d_P, hipStream_t st);
 
+// Segmented summation through the bucket reduction rounds (kernels_buckets.hip). Workspace layout in 32-bit words.
+struct SegSumPlan {
+  int rounds;
+  size_t scan_blocks, off_cnt, off_totals, off_offs, off_arena[2], total;
+};
+SegSumPlan seg_sum_plan(const haflo_ctx* ctx, size_t count, size_t nseg);
+// d_out[k] = product of d_c[offsets[k] .. offsets[k+1]) (canonical internal elements); ws: seg_sum_plan(...).total words
+int seg_sum(const haflo_ctx* ctx, const uint32_t* d_c, const uint32_t* d_offsets, size_t count, size_t nseg,
+            uint32_t* d_out, uint32_t* d_status, uint32_t* ws, hipStream_t st);
+
 }  // namespace haflo

@@ -449,6 +449,47 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_horner(ModRef M, const u32
   }
 }
 
+// Segmented summation: segment k = elements [o[k], o[k+1]) of one array is a "bucket" whose rows are
+// already in place. cnt[k] = its length; offsets that run backwards or past the end of the array are
+// the caller's error and give an empty or clipped segment (and a status bit), never an access outside.
+__global__ __launch_bounds__(kBlockThreads) void k_seg_counts(const u32* __restrict__ offsets, size_t nseg, u32 count,
+                                                              u32* __restrict__ cnt, u32* __restrict__ first,
+                                                              u32* __restrict__ status) {
+  for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < nseg; k += (size_t)gridDim.x * blockDim.x) {
+    const u32 a = offsets[k], b = offsets[k + 1];
+    const u32 a1 = a < count ? a : count, b1 = b < count ? b : count;
+    const bool bad = b < a || b > count;
+    cnt[k] = b1 > a1 ? b1 - a1 : 0u;
+    first[k] = a1;
+    if (bad && status) atomicOr(status, (u32)HAFLO_ST_RANGE);
+  }
+}
+
+// out[k] = the single item left of segment k after the last round that ran, canonical (1 for an empty one)
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads) void k_seg_finish(ModRef M, const u32* __restrict__ arena0,
+                                                              const u32* __restrict__ arena1,
+                                                              const u32* __restrict__ cnt, const u32* __restrict__ offs,
+                                                              size_t K, const u32* __restrict__ stats,
+                                                              u32* __restrict__ out) {
+  constexpr int NL = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  const int ran = rounds_run(stats[kStatMaxCount]);
+  const u32* B = ((ran - 1) & 1) ? arena1 : arena0;
+  const u32* off = offs + (size_t)ran * (K + 1);
+  for (size_t base = bt.first(); base < K; base += bt.stride()) {
+    const size_t k = base + bt.gib;
+    const bool active = k < K;
+    u32 acc[LPT];
+    load_limbs<LPT, T>(acc, (active && cnt[k] != 0u) ? B + (size_t)off[k] * NL : M.r1, g);
+    canonicalise<LPT, T>(acc, mod.n, g);
+    if (active) store_limbs<LPT, T>(out + k * (size_t)NL, acc, g);
+  }
+}
+
 int rounds_for(size_t rows) {
   int r = 0;
   for (size_t reach = 1; reach < rows; reach *= kChunk) ++r;
@@ -458,6 +499,75 @@ int rounds_for(size_t rows) {
 }  // namespace
 
 namespace haflo {
+
+SegSumPlan seg_sum_plan(const haflo_ctx* ctx, size_t count, size_t nseg) {
+  SegSumPlan p;
+  const size_t nl = (size_t)ctx->N.nl;
+  p.rounds = rounds_for(count);
+  p.scan_blocks = (nseg + kScanKeys - 1) / kScanKeys;
+  size_t p1 = count / kChunk + nseg;
+  if (p1 > count) p1 = count;
+  size_t p2 = p1 / kChunk + nseg;
+  if (p2 > p1) p2 = p1;
+  size_t w = 0;
+  p.off_cnt = w;     w += kStatWords + 2 * nseg;  // statistics and chunk counters, lengths, first elements
+  p.off_totals = w;  w += (size_t)(p.rounds + 1) * p.scan_blocks;
+  p.off_offs = w;    w += (size_t)(p.rounds + 1) * (nseg + 1);
+  w = (w + 63) & ~(size_t)63;
+  p.off_arena[0] = w; w += p1 * nl;
+  p.off_arena[1] = w; w += p2 * nl;
+  p.total = w;
+  return p;
+}
+
+int seg_sum(const haflo_ctx* ctx, const uint32_t* d_c, const uint32_t* d_offsets, size_t count, size_t nseg,
+            uint32_t* d_out, uint32_t* d_status, uint32_t* ws, hipStream_t st) {
+  const ModHost& m = ctx->N;
+  const SegSumPlan p = seg_sum_plan(ctx, count, nseg);
+  if (p.rounds + 1 > kMaxComp || kStatNextChunk + p.rounds > kStatWords) return HAFLO_EINVAL;
+  const size_t K = nseg;
+  u32* stats = ws + p.off_cnt;
+  u32* cnt = stats + kStatWords;
+  u32* first = cnt + K;
+  u32* totals = ws + p.off_totals;
+  auto offs = [&](int idx) { return ws + p.off_offs + (size_t)idx * (K + 1); };
+  LaunchShape one;
+  one.blocks = 1;
+  one.threads = kBlockThreads;
+  one.gpb = kBlockThreads;
+  LaunchShape scan;
+  scan.blocks = (int)p.scan_blocks;
+  scan.threads = kScanThreads;
+  scan.gpb = kScanThreads;
+  HAFLO_LAUNCH(k_bk_zero, one, st, stats, (size_t)kStatWords);
+  HAFLO_LAUNCH(k_seg_counts, launch_shape(ctx, K, 1, 8), st, d_offsets, K, (u32)count, cnt, first, d_status);
+  HAFLO_LAUNCH(k_bk_scan_totals, scan, st, (const u32*)cnt, K, p.rounds + 1, totals, stats);
+  HAFLO_LAUNCH(k_bk_scan_final, scan, st, (const u32*)cnt, K, p.rounds + 1, (const u32*)totals, offs(0));
+  const u32* items = d_c;
+  for (int r = 0; r < p.rounds; ++r) {
+    size_t bound = count;
+    for (int i = 0; i <= r; ++i) bound = bound / kChunk + K;
+    const LaunchShape sh = launch_shape(ctx, bound, m.t, 3);
+    u32* out = ws + p.off_arena[r & 1];
+    // round 0 reads the elements where they are: a segment's items start at its first element
+    const u32* off = r == 0 ? (const u32*)first : (const u32*)offs(r);
+#define CALL(LPT, T)                                                                                        \
+  HAFLO_LAUNCH((k_bk_round<LPT, T, false>), sh, st, m.ref(), items, (const u32*)nullptr, (const u32*)cnt, \
+               off, (const u32*)offs(r + 1), K, r, stats, out)
+    HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+    items = out;
+  }
+  {
+    const LaunchShape sh = launch_shape(ctx, K, m.t, 8);
+#define CALL(LPT, T)                                                                          \
+  HAFLO_LAUNCH((k_seg_finish<LPT, T>), sh, st, m.ref(), (const u32*)(ws + p.off_arena[0]),  \
+               (const u32*)(ws + p.off_arena[1]), (const u32*)cnt, (const u32*)offs(0), K, (const u32*)stats, d_out)
+    HAFLO_DISPATCH_GEOMETRY(m, CALL);
+#undef CALL
+  }
+  return hip_status(hipGetLastError());
+}
 
 bool xtd_buckets_fit(size_t rows, size_t cols) {
   // row indices, chunk counts and item offsets are 32-bit; the prefix sum over the 4096 keys per column

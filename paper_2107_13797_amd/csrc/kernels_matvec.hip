@@ -846,6 +846,9 @@ size_t haflo_workspace_bytes(const haflo_ctx* ctx, int op, size_t rows, size_t c
       if (!cols) return 0;
       return (use_buckets(ctx, rows, cols) ? xtd_bucket_layout(ctx, rows, cols).total : xtd_plan(ctx, rows, cols).total) * 4;
     case HAFLO_OP_MATVEC_X_W: return xw_plan(ctx, rows, cols).total * 4;
+    case HAFLO_OP_SUM_SEGMENTS:
+      if (rows >= (1ull << 32) || cols >= (1ull << 24)) return (size_t)-1;
+      return cols ? seg_sum_plan(ctx, rows, cols).total * 4 : 0;
     default: return (size_t)-1;
   }
 }
@@ -1012,6 +1015,17 @@ int haflo_cipher_sum(const haflo_ctx* ctx, const void* d_c, size_t count, void* 
     from ^= 1;
   }
   return hip_status(hipGetLastError());
+}
+
+int haflo_cipher_sum_segments(const haflo_ctx* ctx, const void* d_c, size_t count, const uint32_t* d_offsets,
+                              size_t nseg, void* d_out, uint32_t* d_status, void* d_workspace, size_t workspace_bytes,
+                              void* stream) {
+  if (!ctx || count >= (1ull << 32) || nseg >= (1ull << 24)) return HAFLO_EINVAL;
+  if (nseg == 0) return HAFLO_OK;
+  if (!d_offsets || !d_out || (count && !d_c)) return HAFLO_EINVAL;
+  if (!d_workspace || workspace_bytes < seg_sum_plan(ctx, count, nseg).total * 4) return HAFLO_EINVAL;
+  return seg_sum(ctx, (const u32*)d_c, d_offsets, count, nseg, (u32*)d_out, d_status, (u32*)d_workspace,
+                 (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -529,6 +529,54 @@ def test_summation_levels(env):
     assert lib.haflo_cipher_sum(ctx, d_c.p, count, d_s.p, w.p, 64, None) == -1
 
 
+@pytest.mark.parametrize("offsets", [
+    [0, 0, 1, 1, 9, 20, 20, 300, 337],        # empty segments, single elements, three reduction rounds (280 > 16^2)
+    [0, 337],                                  # one segment over everything
+    [5, 5],                                    # one empty segment
+    [3, 20, 36, 37, 337],                      # first element not at 0; lengths 17 (two chunks) and 16 (one)
+    list(range(0, 338)),                       # every element its own segment
+])
+def test_summation_segments(env, offsets):
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    rng = random.Random(73)
+    count = 337
+    cs = [rng.randrange(1, pk.nsq) for _ in range(count)]
+    d_c = zeros(lib, (count, nlw))
+    assert lib.haflo_import_cipher(ctx, words(lib, cs, BITS // 16).p, d_c.p, None, count, None) == 0
+    nseg = len(offsets) - 1
+    w, nb = ws(lib, ctx, _cabi.OP_SUM_SEGMENTS, count, nseg)
+    d_s, st = zeros(lib, (nseg, nlw)), zeros(lib, (1,))
+    d_off = Dev(lib, np.array(offsets, dtype=np.uint32))
+    assert lib.haflo_cipher_sum_segments(ctx, d_c.p, count, d_off.p, nseg, d_s.p, st.p, w.p, nb, None) == 0
+    assert export(lib, ctx, d_s, nseg) == O.summation_segments(pk, cs, offsets)
+    assert st.get()[0] == 0
+
+
+def test_summation_segments_bad_offsets_and_arguments(env):
+    """Offsets that run backwards or past the array are clipped and flagged; nothing outside the
+    array is read (the emulated buffers end at a guard page)."""
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    rng = random.Random(74)
+    count = 40
+    cs = [rng.randrange(1, pk.nsq) for _ in range(count)]
+    d_c = zeros(lib, (count, nlw))
+    assert lib.haflo_import_cipher(ctx, words(lib, cs, BITS // 16).p, d_c.p, None, count, None) == 0
+    offsets = [0, 10, 5, 30, 2 ** 32 - 1]
+    nseg = len(offsets) - 1
+    w, nb = ws(lib, ctx, _cabi.OP_SUM_SEGMENTS, count, nseg)
+    d_s, st = zeros(lib, (nseg, nlw)), zeros(lib, (1,))
+    d_off = Dev(lib, np.array(offsets, dtype=np.uint32))
+    assert lib.haflo_cipher_sum_segments(ctx, d_c.p, count, d_off.p, nseg, d_s.p, st.p, w.p, nb, None) == 0
+    assert export(lib, ctx, d_s, nseg) == [O.summation(pk, cs[0:10]), 1, O.summation(pk, cs[5:30]), O.summation(pk, cs[30:40])]
+    assert st.get()[0] == 1
+    assert lib.haflo_cipher_sum_segments(ctx, d_c.p, count, d_off.p, nseg, d_s.p, st.p, w.p, nb - 4, None) == -1
+    assert lib.haflo_cipher_sum_segments(ctx, d_c.p, count, None, nseg, d_s.p, st.p, w.p, nb, None) == -1
+    assert lib.haflo_cipher_sum_segments(ctx, d_c.p, 2 ** 32, d_off.p, nseg, d_s.p, st.p, w.p, nb, None) == -1
+    assert lib.haflo_cipher_sum_segments(ctx, d_c.p, count, d_off.p, 0, None, None, None, 0, None) == 0
+
+
 def test_encode_decode(env):
     lib, ctx, sk, nlw = env
     pk = sk.public

@@ -434,6 +434,48 @@ def _edges_matvec(api, bits, method, ctx, sk):
     assert dev_to_ints(api.haflo_export_cipher(ctx, s1)) == cs[:1]
 
 
+@pytest.mark.parametrize("bits", [1024, 2048])
+def test_summation_segments(api, bits):
+    """Homomorphic summation over slices: empty slices, single elements, a slice longer than
+    16^3 elements (four reduction rounds), one slice over everything, and many short ones; the
+    ciphertexts against the oracle, every slice also through decryption against the plaintext sums."""
+    ctx, sk = context(api, bits)
+    pk = sk.public
+    n = pk.n
+    count = 9000
+    rng = random.Random(bits + 7)
+    ms = [rng.randrange(n) for _ in range(count)]
+    c = api.haflo_encrypt(ctx, ints_to_dev(ms, bits // 32), to_dev(random_units_words(count, bits, 75)))
+    cs = dev_to_ints(api.haflo_export_cipher(ctx, c))
+    probe = sample_indices(count, 12, 76)
+    assert [cs[i] for i in probe] == OP.encrypt_many(n, [ms[i] for i in probe],
+                                                     synth.words_to_ints(random_units_words(count, bits, 75)[probe]))
+    cases = [
+        [0, 0, 1, 1, 9, 20, 20, 300, 4500, 4500, 9000],
+        [0, count],
+        [17, 17],
+        [3, 4200],
+        list(range(0, count + 1, 3)),
+        sorted(rng.randrange(count + 1) for _ in range(700)),
+    ]
+    for offsets in cases:
+        st = torch.zeros(1, dtype=torch.int32, device="cuda")
+        out = api.haflo_cipher_sum_segments(ctx, c, torch.tensor(offsets, dtype=torch.int32, device="cuda"), st)
+        assert int(st.item()) == 0
+        got = dev_to_ints(api.haflo_export_cipher(ctx, out))
+        # the oracle's products from the (sample-checked) exported ciphertexts: plain modular products
+        assert got == O.summation_segments(pk, cs, offsets)
+        assert dev_to_ints(api.haflo_decrypt(ctx, out)) == [sum(ms[a:b]) % n for a, b in zip(offsets, offsets[1:])]
+    whole = api.haflo_cipher_sum_segments(ctx, c, torch.tensor([0, count], dtype=torch.int32, device="cuda"))
+    assert torch.equal(whole, api.haflo_cipher_sum(ctx, c))
+    # no segments, and no elements
+    none = api.haflo_cipher_sum_segments(ctx, c, torch.tensor([5], dtype=torch.int32, device="cuda"))
+    assert none.shape[0] == 0
+    empty = torch.empty((0, ctx.cipher_words), dtype=torch.int32, device="cuda")
+    ones = api.haflo_cipher_sum_segments(ctx, empty, torch.tensor([0, 0, 0], dtype=torch.int32, device="cuda"))
+    assert dev_to_ints(api.haflo_export_cipher(ctx, ones)) == [1, 1]
+
+
 def test_fore_gradient_chain(api):
     """The fused fore-gradient call against the oracle (sampled ciphertexts at a 2048-bit key,
     every element through decryption and the closed form on the quantised inputs)."""
