@@ -21,6 +21,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace haflo {
 namespace dev {
 
@@ -34,6 +36,15 @@ constexpr u32 LIMB_MASK = (1u << LIMB_BITS) - 1u;
 constexpr int WAVE = 64;
 
 __device__ __forceinline__ u64 mad64(u32 a, u32 b, u64 c) { return (u64)a * (u64)b + c; }
+
+// f(integral_constant<int, I>) for I = BEGIN .. END - 1: a loop whose index is a compile-time constant in the body
+template <int BEGIN, int END, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (BEGIN < END) {
+    f(std::integral_constant<int, BEGIN>{});
+    static_for<BEGIN + 1, END>(f);
+  }
+}
 
 // Geometry of the lane group that owns one big integer.
 template <int T>
@@ -141,6 +152,24 @@ struct BMem {
   }
 };
 
+// Which products of a squaring a lane computes in the step that broadcasts limb r of some lane: its own
+// limb j takes part iff sq_weight(j, r) != 0, with that factor. Seen over all steps this is a round-robin
+// tournament on the limb indices of a lane: of the two steps in which the unordered pair
+// {(lane k, limb j), (lane o, limb r)} could be formed - step (o, r) on lane k, step (k, j) on lane o -
+// exactly one forms it, doubled, when the cyclic distance (j - r) mod LPT is in [1, (LPT-1)/2] or the
+// mirror of that range; for j = r, and for the distance LPT/2 that is its own mirror when LPT is even,
+// both steps form it, undoubled. Within one lane (k = o) the same rule yields every pair once and the
+// square of each limb once. Either step is at or before column j + r + LPT (k + o) becomes the lowest
+// column of lane 0, so the quotient digits see complete columns, as in a general product. All lanes use
+// the same limb indices in a step, so nothing diverges and nobody idles: 10 of 18 (5 of 9)
+// multiply-adds per step instead of 18 (9).
+__host__ __device__ constexpr int sq_weight(int lpt, int j, int r) {
+  const int d = ((j - r) % lpt + lpt) % lpt;
+  if (d == 0) return 1;
+  if (lpt % 2 == 0 && d == lpt / 2) return 1;
+  return (d <= (lpt - 1) / 2) ? 2 : 0;
+}
+
 // Montgomery product out = a * b / 2^(29*NL) mod n, lazy in and out.
 //   a, b: limbs < 2^29 + 2^8, values < 4n.  n: canonical limbs of the odd
 //   modulus.  n0inv = -n^-1 mod 2^29.  out: limbs < 2^29 + 2^5, value < 2n.
@@ -148,7 +177,10 @@ struct BMem {
 // with q chosen so the lowest column vanishes mod 2^29, then drops that column;
 // every lane hands the low 29 bits of its lowest column to the lane below and
 // keeps the rest as a carry, so no lane is special-cased.
-template <int LPT, int T, class BSrc>
+// SQ: b is a itself (bsrc hands out a's limbs) and the symmetric half of the limb products is left out,
+// see sq_weight; doubled limbs stay below 2^30 + 2^9, and a column then takes at most 8 doubled and 2
+// plain products next to the 18 of the reduction: 36 * 2^58 as before.
+template <int LPT, int T, class BSrc, bool SQ = false>
 __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT], const BSrc& bsrc,
                                              const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
   static_assert(LPT <= 18, "a column must not collect more than 36 products");
@@ -166,8 +198,8 @@ __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT
   for (int d = 0; d < D; ++d) ring[d] = bsrc.limb(0, d, g);
 #pragma unroll 1
   for (int o = 0; o < T; ++o) {
-#pragma unroll
-    for (int r = 0; r < LPT; ++r) {
+    static_for<0, LPT>([&](auto rc) {
+      constexpr int r = decltype(rc)::value;
       u32 bi;
       if (D > 0) {
         bi = ring[r % RING];
@@ -175,11 +207,18 @@ __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT
       } else {
         bi = bsrc.limb(o, r, g);
       }
-      A[0] = mad64(a[0], bi, A[0]);
+      // the limb products of this step: all of them, or for a squaring those sq_weight selects
+      [[maybe_unused]] const u32 bi2 = SQ ? bi + bi : bi;
+      auto product = [&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        constexpr int w = SQ ? sq_weight(LPT, j, r) : 1;
+        if constexpr (w == 1) A[j] = mad64(a[j], bi, A[j]);
+        else if constexpr (w == 2) A[j] = mad64(a[j], bi2, A[j]);
+      };
+      product(std::integral_constant<int, 0>{});
       u32 qv = ((u32)A[0] * n0inv) & LIMB_MASK;
       u32 q = g.bcast0(qv);
-#pragma unroll
-      for (int j = 1; j < LPT; ++j) A[j] = mad64(a[j], bi, A[j]);
+      static_for<1, LPT>(product);
       u64 t0 = mad64(q, n[0], A[0]);
       u32 low = (u32)t0 & LIMB_MASK;  // 0 on lane 0 of every group, by the choice of q
       u32 recv = g.from_upper_raw(low);
@@ -192,7 +231,7 @@ __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT
       } else {
         A[0] = (u64)recv + carry;
       }
-    }
+    });
   }
   // A column register lives LPT steps in a lane (it enters at the top as the 29 bits handed over by
   // the lane above and leaves at the bottom) and takes two products per step: at most 2 * 18 products
@@ -217,6 +256,14 @@ __device__ __forceinline__ void montmul(u32 (&out)[LPT], const u32 (&a)[LPT], co
                                         const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
   BRegs<LPT, T> src = {b};
   montmul_core<LPT, T>(out, a, src, n, n0inv, g);
+}
+
+// out = a * a / 2^(29*NL) mod n with the symmetric half of the limb products left out (out may alias a)
+template <int LPT, int T>
+__device__ __forceinline__ void montsqr(u32 (&out)[LPT], const u32 (&a)[LPT], const u32 (&n)[LPT], u32 n0inv,
+                                        const Grp<T>& g) {
+  BRegs<LPT, T> src = {a};
+  montmul_core<LPT, T, BRegs<LPT, T>, true>(out, a, src, n, n0inv, g);
 }
 
 // b = NL limbs at `bmem`, the same array for every lane of the group

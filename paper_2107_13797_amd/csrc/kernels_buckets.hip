@@ -409,7 +409,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_fold2(ModRef M, const u32*
       montmul<LPT, T>(acc, acc, run, mod.n, mod.n0inv, g);
     }
 #pragma unroll 1
-    for (int i = 0; i < 3; ++i) montmul<LPT, T>(acc, acc, acc, mod.n, mod.n0inv, g);  // ^8 = ^kSegLen
+    for (int i = 0; i < 3; ++i) montsqr<LPT, T>(acc, acc, mod.n, mod.n0inv, g);  // ^8 = ^kSegLen
 #pragma unroll 1
     for (int q = 0; q < kLoSegs; ++q) montmul_mem<LPT, T>(acc, acc, a_of(q), mod.n, mod.n0inv, g);
     if (active) store_limbs<LPT, T>(R + it * (size_t)NL, acc, g);
@@ -440,7 +440,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_horner(ModRef M, const u32
       for (int half = 1; half >= 0; --half) {
         if (s != npos - 1 || half != 1) {
 #pragma unroll 1
-          for (int i = 0; i < 5; ++i) montmul<LPT, T>(acc, acc, acc, mod.n, mod.n0inv, g);
+          for (int i = 0; i < 5; ++i) montsqr<LPT, T>(acc, acc, mod.n, mod.n0inv, g);
         }
         montmul_mem<LPT, T>(acc, acc, r + (size_t)half * NL, mod.n, mod.n0inv, g);
       }

@@ -154,7 +154,7 @@ __device__ __forceinline__ void engine_run(const ModRef& M, const Prog& P, const
         continue;
       }
       if (op == ENG_SQ) {
-        montmul<LPT, T>(acc, acc, acc, mod.n, mod.n0inv, g);
+        montsqr<LPT, T>(acc, acc, mod.n, mod.n0inv, g);
       } else {
         // the multiplier is read limb by limb straight from its table slot or constant array
         const u32* src;

@@ -386,7 +386,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_xtd_horner(ModRef M, size_t c
     for (int s = npos - 1; s >= 0; --s) {
       if (s != npos - 1) {
 #pragma unroll 1
-        for (int i = 0; i < kSWin; ++i) montmul<LPT, T>(acc, acc, acc, mod.n, mod.n0inv, g);
+        for (int i = 0; i < kSWin; ++i) montsqr<LPT, T>(acc, acc, mod.n, mod.n0inv, g);
       }
 #pragma unroll 1
       for (int rs = 0; rs < rsplit; ++rs) {
@@ -457,7 +457,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_tables(ModRef M, const u32
 #pragma unroll 1
     for (int i = 0; wave_any(i < kWin * s); ++i) {
       u32 t[LPT];
-      montmul<LPT, T>(t, b, b, mod.n, mod.n0inv, g);
+      montsqr<LPT, T>(t, b, mod.n, mod.n0inv, g);
       if (i < kWin * s) {
 #pragma unroll
         for (int jj = 0; jj < LPT; ++jj) b[jj] = t[jj];
