@@ -59,6 +59,7 @@ extern "C" {
 #define HAFLO_ENOPRIV (-3) /* private-key operation on a public-only context */
 #define HAFLO_EHIP (-4)    /* the HIP runtime reported an error */
 #define HAFLO_ENOMEM (-5)  /* host or device allocation failed, or a store's arena is exhausted */
+#define HAFLO_ETOOBIG (-6) /* haflo_decrypt_static: the batch needs more than HAFLO_STATIC_SCRATCH_BYTES */
 
 /* Per-element status bits written by encode / decode / import. */
 #define HAFLO_ST_OK 0u
@@ -226,6 +227,23 @@ int haflo_decrypt(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain,
 
 /* "Homomorphic Addition" (paper Table 1): out = c1 * c2 mod n^2, element-wise.
  * All three device arrays hold count internal elements; out may alias c1 or c2. */
+/*
+ * haflo_decrypt for callers that cannot allocate or bring a workspace: code
+ * under HIP graph capture, tight serving loops (the handful of gradient entries
+ * decrypted every iteration), harnesses that forbid hipMalloc. Same arguments
+ * and results as haflo_decrypt without the workspace pair; the temporaries live
+ * in a fixed array of HAFLO_STATIC_SCRATCH_BYTES inside the library's device
+ * image (one copy per GPU, held until the process ends; its address is
+ * resolved when a context is created). No allocation of any kind happens in
+ * the call. Limit: haflo_workspace_bytes(ctx, HAFLO_OP_DECRYPT, count, 0) <=
+ * HAFLO_STATIC_SCRATCH_BYTES (about 5000 / 1400 / 600 elements at 1024 / 2048 /
+ * 4096-bit keys), otherwise HAFLO_ETOOBIG and nothing is launched. All calls on
+ * one GPU share the array: calls that overlap (different streams, threads or
+ * contexts on the same GPU) race; order them on one stream.
+ */
+#define HAFLO_STATIC_SCRATCH_BYTES (16u << 20)
+int haflo_decrypt_static(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain, size_t count, void* stream);
+
 int haflo_add(const haflo_ctx* ctx, const void* d_c1, const void* d_c2, void* d_out, size_t count, void* stream);
 
 /*

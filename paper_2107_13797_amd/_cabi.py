@@ -31,6 +31,7 @@ PROTOTYPES = {
     "haflo_decode": (c_int, [c_void_p, c_void_p, c_u32, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "haflo_encrypt": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]),
     "haflo_decrypt": (c_int, [c_void_p, c_void_p, c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]),
+    "haflo_decrypt_static": (c_int, [c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "haflo_add": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "haflo_scalar_mul_u64": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]),
     "haflo_scalar_mul_i64_bcast": (c_int, [c_void_p, c_void_p, c_i64, c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]),

@@ -224,6 +224,15 @@ def haflo_decrypt(ctx, cipher, out=None):
     return out
 
 
+def haflo_decrypt_static(ctx, cipher, out=None):
+    """haflo_decrypt through the library's fixed scratch array: no workspace, nothing allocated by the call."""
+    count = cipher.shape[0]
+    if out is None:
+        out = torch.empty((count, ctx.plain_limbs), dtype=torch.int32, device="cuda")
+    _check(lib().haflo_decrypt_static(ctx.handle, _ptr(cipher), _ptr(out), count, _stream()))
+    return out
+
+
 def haflo_add(ctx, c1, c2, out=None):
     count = c1.shape[0]
     if out is None:

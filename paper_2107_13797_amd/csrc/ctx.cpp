@@ -312,6 +312,8 @@ static int ctx_build(haflo_ctx* ctx, const Big& n, const Big* p, const Big* q, u
   hipDeviceProp_t prop;
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return HAFLO_EHIP;
   ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+  ctx->device = dev;
+  if (int rc = static_scratch_init()) return rc;
 
   Uploader up{ctx};
   const int nl_n2 = (int)(n_bits * 9 / 128);
@@ -404,6 +406,7 @@ const char* haflo_strerror(int code) {
     case HAFLO_ENOPRIV: return "operation needs the private key";
     case HAFLO_EHIP: return "HIP runtime error";
     case HAFLO_ENOMEM: return "allocation failed";
+    case HAFLO_ETOOBIG: return "batch needs more than the fixed scratch of the allocation-free entry point";
     default: return "unknown error";
   }
 }

@@ -105,6 +105,7 @@ struct haflo_ctx {
   bool has_priv = false;
   int lc = 0, lp = 0;  // canonical 32-bit limbs of a ciphertext / plaintext
   int num_cu = 0;
+  int device = -1;  // the HIP device that was current when the context was created
   size_t xtd_bucket_min_rows = HAFLO_XTD_BUCKET_MIN_ROWS_DEFAULT;  // X^T [[d]]: bucket method from this many rows on
   haflo::Big n, nsq, p, q;
   haflo::ModHost N;            // n^2
@@ -161,6 +162,9 @@ inline int hip_status(hipError_t e) { return e == hipSuccess ? HAFLO_OK : HAFLO_
 
 // 29-bit limbs of a host integer
 std::vector<uint32_t> to_limbs29(const Big& x, int nl);
+
+// device address of the static scratch array on the current device (kernels_modexp.hip)
+int static_scratch_init();
 
 // workspace sizes in bytes (kernels_modexp.hip)
 size_t ws_encrypt(const haflo_ctx* ctx, size_t count);

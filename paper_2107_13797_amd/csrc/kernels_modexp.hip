@@ -1,11 +1,25 @@
 // Exponentiation-bound operators: encryption, decryption through p^2 and q^2,
 // ciphertext-by-scalar multiplication. Kernels and their C entry points.
+#include <mutex>
+
 #include "kernels_common.hpp"
 
 using namespace haflo;
 using namespace haflo::dev;
 
+// Scratch of the entry point that allocates nothing (haflo_decrypt_static): every GPU the library runs on
+// holds its own copy of this array, at its own address, until the process ends. In host code the name is
+// only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[HAFLO_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each device, once resolved
+
+int decrypt_launches(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain, size_t count, void* d_workspace,
+                     hipStream_t st);
 
 constexpr int kModexpBlocksPerCu = 4;  // resident blocks assumed when sizing window-table workspace
 
@@ -230,6 +244,20 @@ int launch_engine_batch(const haflo_ctx* ctx, const ModHost& m, hipStream_t st, 
 }  // namespace
 
 namespace haflo {
+// Resolves the device address of the static scratch array on the current device (once per device) and
+// keeps it. Called when a context is created, with the context's device current.
+int static_scratch_init() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return HAFLO_EHIP;
+  if (dev < 0 || dev >= kMaxDevices) return HAFLO_EINVAL;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev]) return HAFLO_OK;
+  void* ptr = nullptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return HAFLO_EHIP;
+  g_scratch_ptr[dev] = ptr;
+  return HAFLO_OK;
+}
+
 // table slots: one set per resident lane group
 size_t ws_encrypt(const haflo_ctx* ctx, size_t count) {
   if (!ctx->has_priv)
@@ -467,7 +495,31 @@ int haflo_decrypt(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain,
   if (!ctx->has_priv) return HAFLO_ENOPRIV;
   if (count == 0) return HAFLO_OK;
   if (!d_workspace || workspace_bytes < ws_decrypt(ctx, count)) return HAFLO_EINVAL;
-  hipStream_t st = (hipStream_t)stream;
+  return decrypt_launches(ctx, d_cipher, d_plain, count, d_workspace, (hipStream_t)stream);
+}
+
+int haflo_decrypt_static(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain, size_t count, void* stream) {
+  if (!ctx || (count && (!d_cipher || !d_plain))) return HAFLO_EINVAL;
+  if (!ctx->has_priv) return HAFLO_ENOPRIV;
+  if (count == 0) return HAFLO_OK;
+  if (ws_decrypt(ctx, count) > (size_t)HAFLO_STATIC_SCRATCH_BYTES) return HAFLO_ETOOBIG;
+  if (ctx->device < 0 || ctx->device >= kMaxDevices) return HAFLO_EINVAL;
+  void* ptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    ptr = g_scratch_ptr[ctx->device];
+  }
+  if (!ptr) return HAFLO_EHIP;  // the context was created on a device whose array could not be resolved
+  // every temporary of the decryption (canonical residues, both branch results, window tables) is
+  // written before it is read, so nothing of an earlier call's contents has to be cleared
+  return decrypt_launches(ctx, d_cipher, d_plain, count, ptr, (hipStream_t)stream);
+}
+
+}  // extern "C"
+
+namespace {
+int decrypt_launches(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain, size_t count, void* d_workspace,
+                     hipStream_t st) {
   u32* canon29 = (u32*)d_workspace;
   u32* yp = canon29 + count * (size_t)ctx->N.nl;
   u32* yq = yp + count * (size_t)ctx->P2.nl;
@@ -515,5 +567,4 @@ int haflo_decrypt(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain,
   }
   return hip_status(hipGetLastError());
 }
-
-}  // extern "C"
+}  // namespace

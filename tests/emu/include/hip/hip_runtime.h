@@ -25,6 +25,8 @@
 #define __forceinline__ inline
 #define __launch_bounds__(...)
 #define __shared__ static
+#define __align__(n) __attribute__((aligned(n)))
+#define HIP_SYMBOL(x) x
 
 struct dim3 {
   unsigned x, y, z;
@@ -125,6 +127,10 @@ static inline hipError_t hipMemcpyAsync(void* d, const void* s, size_t n, hipMem
 }
 static inline hipError_t hipMemsetAsync(void* d, int v, size_t n, hipStream_t) {
   memset(d, v, n);
+  return hipSuccess;
+}
+static inline hipError_t hipGetSymbolAddress(void** p, const void* symbol) {
+  *p = (void*)symbol;  // the emulated "device" array is the host array itself
   return hipSuccess;
 }
 static inline hipError_t hipDeviceSynchronize() { return hipSuccess; }

@@ -120,6 +120,12 @@ def test_encrypt_decrypt_scalar_mul(env):
     w, nb = ws(lib, ctx, _cabi.OP_DECRYPT, len(ms))
     assert lib.haflo_decrypt(ctx, d_c.p, d_pl.p, len(ms), w.p, nb, None) == 0
     assert synth.words_to_ints(d_pl.get()) == ms
+    # the same through the library's fixed scratch array, twice, the second call on fewer elements
+    for count in (len(ms), 2):
+        d_ps = zeros(lib, (count, lp))
+        assert lib.haflo_decrypt_static(ctx, d_c.p, d_ps.p, count, None) == 0
+        assert synth.words_to_ints(d_ps.get()) == ms[:count]
+    assert lib.haflo_decrypt_static(ctx, d_c.p, d_pl.p, 10 ** 7, None) == -6
     ks = [rng.getrandbits(64) for _ in range(3)] + [0, 1, 2 ** 64 - 1]
     d_o = zeros(lib, (len(ms), nlw))
     w, nb = ws(lib, ctx, _cabi.OP_SCALAR_MUL, len(ms))
