@@ -28,13 +28,15 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 # MI355X: 256 compute units x 64 lanes x one v_mad_u64_u32 per lane per clock at 2.4 GHz
-# (32x32+64 integer multiply-add issues at the full VALU rate on gfx950).
+# (32x32+64 integer multiply-add issues at the full VALU rate on gfx950: bench_peak.py measures it,
+# profiles/peak_microbench.md holds the figures).
 PEAK_MAD32_PER_S = 256 * 64 * 2.4e9
 
-# HBM bytes per 2048-bit encryption measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this
-# launch shape, each scaled by what the counter reads for a 1 GiB device copy
-# (profiles/k_engine_encrypt_2048bit_b65536_pmc.md): (11430924 + 3085898) KiB per 65536 encryptions.
-TRAFFIC_BYTES_PER_ENCRYPT_2048 = (11430924 + 3085898) * 1024 / 65536
+# HBM bytes of the encryption launch at the profiled shape (2048-bit key, 65536 elements): rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE, each scaled by what the counter reads for a 1 GiB device copy. The figure is
+# transcribed from the profile named here, not measured by this run, and is reported for that shape only.
+TRAFFIC_PROFILE = "profiles/k_engine_encrypt_2048bit_b65536_pmc.md"
+TRAFFIC_BYTES_PROFILED = {(2048, 65536): (11430924 + 3085898) * 1024}
 
 
 def montmul_mul32(limbs):
@@ -51,9 +53,46 @@ def _oracle_encrypt_chunk(args):
     return time.perf_counter() - t0, out
 
 
-def cpu_baseline(n, ms, rs, want):
-    """The oracle's encryption (the same r^n modexp the GPU headline counts) on all host cores."""
+def _oracle_operators_one_core(p, q, seed):
+    """The oracle's operators one by one on one core (the paper's Table 2 has a one-core CPU column):
+    -> {operator: {"per_s": rate, "sample": count}}; a few seconds in total."""
+    import random
+
+    from oracle import paillier_oracle as O
+    sk = O.PrivateKey(p, q)
+    pk = sk.public
+    n = pk.n
+    rng = random.Random(seed)
+    res = {}
+
+    def rate(name, count, fn):
+        t0 = time.perf_counter()
+        out = fn()
+        res[name] = {"per_s": count / (time.perf_counter() - t0), "sample": count}
+        return out
+    vals = [rng.gauss(0.0, 0.25) for _ in range(20000)]
+    enc = rate("encode", len(vals), lambda: [O.encode(pk, v, 24)[0] for v in vals])
+    rate("decode", len(enc), lambda: [O.decode(pk, m, 24) for m in enc])
+    ms = enc[:12]
+    rs = [rng.randrange(1, n) for _ in ms]
+    cs = rate("encrypt", len(ms), lambda: [O.encrypt(pk, m, r) for m, r in zip(ms, rs)])
+    rate("decrypt (lambda, mu)", 6, lambda: [O.decrypt(sk, c) for c in cs[:6]])
+    rate("decrypt (through p^2, q^2)", len(cs), lambda: [O.decrypt_crt(sk, c) for c in cs])
+    many = [cs[i % len(cs)] for i in range(4000)]
+    rate("add", len(many), lambda: [O.add(pk, a, b) for a, b in zip(many, many[1:] + many[:1])])
+    ks = [rng.getrandbits(64) for _ in range(60)]
+    rate("scalar_mul (64-bit)", len(ks), lambda: [O.scalar_mul(pk, cs[i % len(cs)], k) for i, k in enumerate(ks)])
+    X = [[rng.randrange(-(1 << 18), 1 << 18)] for _ in range(240)]
+    rate("matvec X^T[[d]] entries", len(X), lambda: O.matvec(pk, 0, [cs[i % len(cs)] for i in range(len(X))], X))
+    rate("summation", len(many), lambda: O.summation(pk, many))
+    return res
+
+
+def cpu_baseline(p, q, ms, rs, want):
+    """The oracle's encryption (the same r^n modexp the GPU headline counts) on all host cores and on
+    one core, and the other operators on one core."""
     import multiprocessing as mp
+    n = p * q
     cores = max(1, min(16, os.cpu_count() or 1))
     per = max(1, len(ms) // cores)
     chunks = [(n, ms[i * per:(i + 1) * per], rs[i * per:(i + 1) * per]) for i in range(cores)]
@@ -65,9 +104,17 @@ def cpu_baseline(n, ms, rs, want):
     done = sum(len(c[1]) for c in chunks)
     got = [c for _, part in res for c in part]
     assert got == want[:done], "GPU encryption disagrees with the oracle on the timed sample"
+    k1 = min(24, len(ms))
+    t1, one = _oracle_encrypt_chunk((n, ms[:k1], rs[:k1]))
+    assert one == want[:k1], "GPU encryption disagrees with the oracle on the one-core sample"
     return {"value": done / wall, "unit": "modexp/s", "cores": len(chunks), "kind": "oracle",
             "sample": "%d encryptions (2048-bit r^n mod n^2) of the step's first elements, python int pow, "
-                      "%.1f core-seconds" % (done, sum(t for t, _ in res))}
+                      "%.1f core-seconds" % (done, sum(t for t, _ in res)),
+            "one_core": {"value": k1 / t1, "unit": "modexp/s", "cores": 1,
+                         "sample": "the first %d of the same encryptions, %.1f s" % (k1, t1)},
+            "operators_one_core": _oracle_operators_one_core(p, q, 99),
+            "operators_note": "python int oracle at the benchmark's key size, one core, instances per second "
+                              "(the shape of the paper's one-core CPU column in its Table 2)"}
 
 
 def main():
@@ -80,6 +127,8 @@ def main():
     ap.add_argument("--bits", type=int, default=2048)
     ap.add_argument("--cpu-sample", type=int, default=192)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the per-operator timing of the five benchmark configurations (about 40 s)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy: the known-size kernel that scales "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -224,8 +273,12 @@ def main():
         "roofline": {"bound": "alu", "kernel": "k_engine (encryption program, modulus n^2)", "achieved": achieved / 1e12,
                      "peak": PEAK_MAD32_PER_S / 1e12, "unit": "TOP/s", "op": "32x32+64-bit integer multiply-add",
                      "frac": achieved / PEAK_MAD32_PER_S,
-                     "traffic": (TRAFFIC_BYTES_PER_ENCRYPT_2048 * B if bits == 2048 else None),
-                     "traffic_unit": "bytes per launch (rocprofv3 counters, see profiles/)",
+                     "traffic": TRAFFIC_BYTES_PROFILED.get((bits, B)),
+                     "traffic_unit": "bytes per launch",
+                     "traffic_source": "%s (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE on this launch shape); "
+                                       "not measured in this run" % TRAFFIC_PROFILE,
+                     "squarings": "counted as general products; the kernel's squaring forms 10 of 18 limb "
+                                  "products per step",
                      "algorithmic": "%d Montgomery products x (2*%d^2+%d) mul32 per encryption" % (mm, limbs, limbs)},
     }
     if not args.no_cpu:
@@ -234,7 +287,21 @@ def main():
         ms = _s.words_to_ints(api.haflo_encode_f32(pub, d[:k].contiguous(), 24).cpu().numpy())
         rs = _s.words_to_ints(r_words[:k])
         want = _s.words_to_ints(api.haflo_export_cipher(pub, keep["c"][:k].contiguous()).cpu().numpy())
-        out["cpu_baseline"] = cpu_baseline(n, ms, rs, want)
+        out["cpu_baseline"] = cpu_baseline(p, q, ms, rs, want)
+    if not args.no_configs:
+        # the five benchmark configurations, operator by operator (bench_configs.py), outside the timed steps
+        ctx.close()
+        pub.close()
+        del other, wc, Xg, Xw, d, r, own, keep
+        torch.cuda.empty_cache()
+        import bench_configs
+        rep = bench_configs.run_configs((1, 2, 3, 4, 5), reps=1, verbose=False)
+        out["configs"] = {"cfg%d" % k: rows for k, rows in rep.items()}
+        for k in (2, 5):
+            row = [x for x in rep[k] if x["op"].startswith("matvec")][0]
+            out["xt_d_entries_per_s_cfg%d" % k] = row["rate"]
+        out["configs_note"] = ("per operator: units, ms (one run after a warm-up, HIP events), units per second, "
+                               "fraction of the bounding roofline (alu: 39.3e12 mul32/s, hbm: 8 TB/s)")
     print(json.dumps(out))
 
 

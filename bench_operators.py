@@ -34,6 +34,9 @@ def main():
     ap.add_argument("--features", type=int, default=32)
     ap.add_argument("--reps", type=int, default=3)
     ap.add_argument("--tall", action="store_true", help="also time X^T[[d]] on an instances x features matrix")
+    ap.add_argument("--memory-side", action="store_true",
+                    help="time only the operators with little arithmetic per byte (encode, decode, import, export, "
+                         "add) and print bytes and multiply-adds per second against both rooflines")
     ap.add_argument("--json", default=None)
     args = ap.parse_args()
 
@@ -58,6 +61,8 @@ def main():
             a = a.view(np.int64)
         return torch.from_numpy(a).cuda()
 
+    if args.memory_side:
+        return memory_side(args, api, synth, torch, np, own, dev)
     rng = np.random.default_rng(seed)
     v = dev(synth.normal_f32(N, 0.25, seed + 1))
     r_words = rng.integers(0, 2 ** 32, size=(N, lp), dtype=np.uint32)
@@ -115,6 +120,61 @@ def main():
     if args.json:
         with open(args.json, "w") as fh:
             json.dump({"n_bits": bits, "instances": N, "features": F, "instances_per_s": res}, fh, indent=1)
+
+
+def memory_side(args, api, synth, torch, np, ctx, dev):
+    """encode / decode (HBM-bound) and import / export / add (one Montgomery product per element) on
+    `--instances` resident elements: milliseconds (median of --reps launches after a warm-up),
+    algorithmic bytes per second against 8 TB/s, multiply-adds per second against 39.3e12."""
+    import statistics
+    bits, N = args.bits, args.instances
+    lp, lc = bits // 32, bits // 16
+    internal = ctx.cipher_words * 4
+    seed = synth.BASE_SEED + bits
+    rng = np.random.default_rng(seed)
+    v = dev(synth.normal_f32(N, 0.25, seed + 1))
+    canon = torch.from_numpy(rng.integers(0, 2 ** 32, size=(N, lc), dtype=np.uint32).view(np.int32)).cuda()
+    canon[:, -1] &= 0x3FFFFFFF  # below 2^(2 bits - 2) < n^2
+
+    def timed(fn):
+        out = fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(max(3, args.reps)):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            out = fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return statistics.median(ts) * 1e-3, out
+
+    mad = 2 * lc * lc + lc
+    rows = []
+    st = torch.zeros(N, dtype=torch.int32, device="cuda")
+    t, plain = timed(lambda: api.haflo_encode_f32(ctx, v, 24, st))
+    rows.append(("k_encode", t, 4 + 4 * lp + 4, 0))
+    t, _ = timed(lambda: api.haflo_decode(ctx, plain, 24, st))
+    rows.append(("k_decode", t, 4 * lp + 20, 0))
+    t, c = timed(lambda: api.haflo_import_cipher(ctx, canon))
+    rows.append(("k_import", t, 4 * lc + internal, mad))
+    t, _ = timed(lambda: api.haflo_export_cipher(ctx, c))
+    rows.append(("k_export", t, 4 * lc + internal, mad))
+    dst = torch.empty_like(c)
+    t, _ = timed(lambda: api.haflo_add(ctx, c, c, out=dst))
+    rows.append(("k_add", t, 3 * internal, mad))
+    print("%d-bit key, %d elements" % (bits, N))
+    print("| kernel | ms | bytes/element | TB/s | of 8 TB/s | 10^12 mul32/s | of 39.3 |")
+    print("|---|---:|---:|---:|---:|---:|---:|")
+    for name, t, nbytes, m in rows:
+        print("| %s | %.3f | %d | %.2f | %.3f | %s | %s |" % (
+            name, t * 1e3, nbytes, N * nbytes / t / 1e12, N * nbytes / t / 8e12,
+            ("%.1f" % (N * m / t / 1e12)) if m else "-", ("%.3f" % (N * m / t / 39.3216e12)) if m else "-"))
+    if args.json:
+        with open(args.json, "w") as fh:
+            json.dump({"n_bits": bits, "elements": N,
+                       "kernels": {name: {"ms": t * 1e3, "bytes_per_element": nbytes, "mul32_per_element": m}
+                                   for name, t, nbytes, m in rows}}, fh, indent=1)
 
 
 if __name__ == "__main__":

@@ -76,16 +76,25 @@ PROTOTYPES = {
     "haflo_h_sum": (c_int, [c_void_p, c_u64, c_u32, C.POINTER(c_u64)]),
 }
 
+# include/haflo_peak.h (libhaflo_peak.so)
+PEAK_PROTOTYPES = {
+    "haflo_peak_streams": (c_int, []),
+    "haflo_peak_alu": (c_int, [c_int, c_int, c_int, c_void_p, c_void_p]),
+    "haflo_peak_hbm": (c_int, [c_int, c_int, c_void_p, c_void_p, c_size_t, c_void_p]),
+}
+PEAK_MAD_U64_U32, PEAK_MUL_LO_HI, PEAK_MUL_U24, PEAK_FMA_F64, PEAK_ADD_U32 = 0, 1, 2, 3, 4
+PEAK_FILL, PEAK_COPY, PEAK_READ = 0, 1, 2
+
 KIND_CIPHER, KIND_PLAIN, KIND_F32, KIND_F64, KIND_I32, KIND_U32, KIND_I64, KIND_U64 = 1, 2, 3, 4, 5, 6, 7, 8
 
 OP_ENCRYPT, OP_DECRYPT, OP_SCALAR_MUL, OP_MATVEC_XT_D, OP_MATVEC_X_W, OP_FORE_GRADIENT, OP_TAYLOR_LOSS, OP_ENCRYPT_OBFUSCATOR = 1, 2, 3, 4, 5, 6, 7, 8
 OP_SUM_SEGMENTS = 9
 
 
-def bind(lib, names=None):
+def bind(lib, names=None, prototypes=None):
     """Attach the prototypes to a loaded library; raises AttributeError when a
     declared symbol is missing."""
-    for name, (res, args) in PROTOTYPES.items():
+    for name, (res, args) in (PROTOTYPES if prototypes is None else prototypes).items():
         if names is not None and name not in names:
             continue
         fn = getattr(lib, name)

@@ -13,6 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhaflo.so")
+PEAK_LIB = os.path.join(HERE, "libhaflo_peak.so")  # the roofline microbenchmarks, a library of their own
 SOURCES = ["ctx.cpp", "staging.cpp", "store.cpp", "kernels_basic.hip", "kernels_modexp.hip", "kernels_matvec.hip", "kernels_buckets.hip", "kernels_loss.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -34,13 +35,14 @@ def _compile(src):
 def build_library(verbose=True):
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(4, os.cpu_count() or 1)) as pool:
-        objs = list(pool.map(_compile, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("link failed:\n%s" % res.stderr[-4000:])
-    if verbose:
-        print("built", LIB)
+        objs = list(pool.map(_compile, SOURCES + ["peak_microbench.hip"]))
+    for lib, parts in ((LIB, objs[:-1]), (PEAK_LIB, objs[-1:])):
+        cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + parts
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("link failed:\n%s" % res.stderr[-4000:])
+        if verbose:
+            print("built", lib)
     return LIB
 
 

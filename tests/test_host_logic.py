@@ -22,8 +22,8 @@ def lib():
     return _cabi.bind(C.CDLL(LIB_PATH))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "haflo.h")).read()
+def declared_symbols(header="haflo.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(haflo_[a-z0-9_]+)\s*\(", text)))
 
@@ -35,6 +35,21 @@ def test_header_and_prototypes_agree():
 def test_library_exports_every_declared_symbol(lib):
     for name in declared_symbols():
         assert hasattr(lib, name), name
+
+
+def test_peak_library_exports_every_declared_symbol(lib):
+    """The roofline microbenchmarks are a library of their own (include/haflo_peak.h)."""
+    path = os.path.join(ROOT, "paper_2107_13797_amd", "libhaflo_peak.so")
+    if not os.path.exists(path):
+        from paper_2107_13797_amd import build
+        build.build_library(verbose=False)
+    names = declared_symbols("haflo_peak.h")
+    assert set(names) == set(_cabi.PEAK_PROTOTYPES)
+    peak = _cabi.bind(C.CDLL(path), prototypes=_cabi.PEAK_PROTOTYPES)
+    for name in names:
+        assert hasattr(peak, name), name
+    assert peak.haflo_peak_streams() == 16
+    assert peak.haflo_peak_alu(0, 0, 1, None, None) == -1 and peak.haflo_peak_hbm(0, 1, None, None, 16, None) == -1
 
 
 def test_strerror(lib):

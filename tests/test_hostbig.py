@@ -15,7 +15,10 @@ OPS = {name: i for i, name in enumerate(
 @pytest.fixture(scope="module")
 def shim(tmp_path_factory):
     out = str(tmp_path_factory.mktemp("hostbig") / "libhostbig_shim.so")
-    subprocess.run(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-o", out, os.path.join(HERE, "hostbig_shim.cpp")],
+    opt = ["-O2"]
+    if os.environ.get("HAFLO_EMU_SANITIZE", "") == "1":  # see tests/test_sanitizers.py
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer"]
+    subprocess.run(["g++"] + opt + ["-std=c++17", "-shared", "-fPIC", "-o", out, os.path.join(HERE, "hostbig_shim.cpp")],
                    check=True)
     lib = C.CDLL(out)
     lib.hostbig_op.restype = C.c_long
