@@ -24,10 +24,10 @@ extern "C" {
  * haflo_peak_streams() independent dependency chains of `iters` iterations. */
 enum haflo_peak_alu_kind {
   HAFLO_PEAK_MAD_U64_U32 = 0, /* one v_mad_u64_u32 per chain and iteration (the shipped limb product) */
-  HAFLO_PEAK_MUL_LO_HI = 1,   /* one v_mul_lo_u32 and one v_mul_hi_u32 (32-bit limbs without a fused add) */
-  HAFLO_PEAK_MUL_U24 = 2,     /* one v_mul_u32_u24 and one 32-bit add (24-bit limbs) */
+  HAFLO_PEAK_MUL_LO_HI = 1,   /* one v_mul_lo_u32, one v_mul_hi_u32 and one add (32-bit limbs without a fused add) */
+  HAFLO_PEAK_MUL_U24 = 2,     /* one v_mad_u32_u24 (24-bit limbs) */
   HAFLO_PEAK_FMA_F64 = 3,     /* one FP64 fused multiply-add (limbs in doubles) */
-  HAFLO_PEAK_ADD_U32 = 4      /* one 32-bit add and one xor: plain full-rate VALU instructions, for reference */
+  HAFLO_PEAK_ADD_U32 = 4      /* one 32-bit add: a plain full-rate VALU instruction, for reference */
 };
 int haflo_peak_streams(void);
 /* blocks: 256-lane workgroups; d_out: device, blocks * 256 uint32 (written once per lane). */

@@ -329,7 +329,7 @@ static int ctx_build(haflo_ctx* ctx, const Big& n, const Big* p, const Big* q, u
     ctx->d_k1 = up.put(to_limbs29(k1, nl_n2));
   }
   ctx->d_n_words = up.put(to_words(n, ctx->lp));
-  ctx->d_halfn_words = up.put(to_words(n.shr1(), ctx->lp));
+  ctx->d_nb_words = up.put(to_words(Big::sub(n, Big::pow2(64)), ctx->lp));
 
   if (p && q) {
     ctx->has_priv = true;

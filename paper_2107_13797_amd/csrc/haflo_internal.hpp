@@ -123,7 +123,7 @@ struct haflo_ctx {
   // device constants
   uint32_t* d_k1 = nullptr;      // n * R^2 mod n^2 (N.nl limbs): montmul(m, k1) = m*n*R
   uint32_t* d_n_words = nullptr; // n as lp 32-bit words
-  uint32_t* d_halfn_words = nullptr;  // floor(n/2) as lp words
+  uint32_t* d_nb_words = nullptr;  // n - 2^64 as lp words
   uint32_t* d_priv = nullptr;    // private-key tables, see ctx.cpp
   // offsets (in limbs) into d_priv, each P.nl limbs
   const uint32_t* d_pinv = nullptr;    // p^-1 mod 2^(29*P.nl)

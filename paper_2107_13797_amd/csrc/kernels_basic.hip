@@ -2,6 +2,20 @@
 // and decoding: kernels and their C entry points.
 #include "kernels_common.hpp"
 
+// launch and access tuning of the two HBM-bound kernels
+#ifndef HAFLO_DECODE_BATCH
+#define HAFLO_DECODE_BATCH 8
+#endif
+#ifndef HAFLO_DECODE_BLOCKS_PER_CU
+#define HAFLO_DECODE_BLOCKS_PER_CU 32
+#endif
+#ifndef HAFLO_DECODE_NONTEMPORAL
+#define HAFLO_DECODE_NONTEMPORAL 1
+#endif
+#ifndef HAFLO_ENCODE_NONTEMPORAL
+#define HAFLO_ENCODE_NONTEMPORAL 1
+#endif
+
 using namespace haflo;
 using namespace haflo::dev;
 
@@ -174,12 +188,11 @@ __global__ __launch_bounds__(kBlockThreads) void k_encode(const float* __restric
           if (j >= 2) w[i] = (j < z) ? (0u - borrow) : (j == z ? nq[i] - borrow : nq[i]);
         }
       }
-      uint4 o;
-      o.x = w[0];
-      o.y = w[1];
-      o.z = w[2];
-      o.w = w[3];
-      reinterpret_cast<uint4*>(plain)[item * (size_t)qpi + (size_t)quad] = o;
+      typedef u32 quad_t __attribute__((vector_size(16)));
+      const quad_t o = {w[0], w[1], w[2], w[3]};
+      quad_t* dst = reinterpret_cast<quad_t*>(plain) + (item * (size_t)qpi + (size_t)quad);
+      if (HAFLO_ENCODE_NONTEMPORAL) __builtin_nontemporal_store(o, dst);
+      else *dst = o;
     }
   }
 }
@@ -197,68 +210,82 @@ __global__ __launch_bounds__(kBlockThreads) void k_encode_exponents(const float*
   }
 }
 
-// Decoding: LPI = Lp/4 lanes read one element's words as 16-byte quads
-// (coalesced), decide m > floor(n/2) with a ballot, form n - m with a
-// generate/propagate borrow look-ahead across the lanes, and lane 0 of the
-// element checks the int64 range and writes q and q / 2^scale.
+// Decoding: LPI = Lp/4 lanes read one element's words as 16-byte quads (coalesced). A decodable residue is
+// either below 2^63 (q = m) or within 2^63 of n (q = m - n); everything else leaves int64 and is flagged,
+// including the whole middle of [0, n) around floor(n/2), so the comparison with floor(n/2) itself never has
+// to be made: m < 2^64 iff all words above the low two are zero, and n - m < 2^64 iff the words above the
+// low two equal those of n (no borrow out of the low two words) or of n - 2^64 (borrow). A lane group takes
+// B = min(LPI, 8) consecutive elements per pass: their loads are all issued before the first is used
+// (enough bytes in flight per compute unit to cover the HBM latency), and lane u of the group ends up
+// holding the result of the group's element u, so that q, q / 2^scale and the status leave the wavefront as
+// contiguous runs instead of one word per group.
+constexpr int kDecodeBatchMax = HAFLO_DECODE_BATCH;
+constexpr int decode_batch(int lpi) { return lpi < kDecodeBatchMax ? lpi : kDecodeBatchMax; }
 template <int LPI>
 __global__ __launch_bounds__(kBlockThreads) void k_decode(const u32* __restrict__ plain, const u32* __restrict__ nw,
-                                                          const u32* __restrict__ halfw, int scale_bits,
+                                                          const u32* __restrict__ nbw, int scale_bits,
                                                           long long* __restrict__ qout, double* __restrict__ vout,
                                                           u32* __restrict__ status, size_t count) {
   static_assert(LPI >= 4 && LPI <= 32 && (LPI & (LPI - 1)) == 0, "lanes per item");
+  constexpr int B = decode_batch(LPI);
   const int lane = (int)(threadIdx.x & (WAVE - 1));
   const int li = lane & (LPI - 1);       // quad index inside the element
   const int gbase = lane - li;           // first lane of this element's group
   const u64 gmask = (LPI == 64) ? ~0ull : ((1ull << LPI) - 1ull);
-  const int ipb = (int)blockDim.x / LPI;  // items per block
-  const int iib = (int)threadIdx.x / LPI;
-  const uint4 n4 = reinterpret_cast<const uint4*>(nw)[li];
-  const uint4 h4 = reinterpret_cast<const uint4*>(halfw)[li];
-  for (size_t base = (size_t)blockIdx.x * ipb; base < count; base += (size_t)gridDim.x * ipb) {
-    size_t item = base + iib;
-    bool active = item < count;
-    uint4 m4 = make_uint4(0u, 0u, 0u, 0u);
-    if (active) m4 = reinterpret_cast<const uint4*>(plain)[item * (size_t)LPI + li];
-    // lexicographic compare of this quad with floor(n/2), most significant word first
-    int cmp = 0;
-    if (m4.w != h4.w) cmp = m4.w > h4.w ? 1 : -1;
-    else if (m4.z != h4.z) cmp = m4.z > h4.z ? 1 : -1;
-    else if (m4.y != h4.y) cmp = m4.y > h4.y ? 1 : -1;
-    else if (m4.x != h4.x) cmp = m4.x > h4.x ? 1 : -1;
-    u64 gt = (__builtin_amdgcn_ballot_w64(cmp > 0) >> gbase) & gmask;
-    u64 lt = (__builtin_amdgcn_ballot_w64(cmp < 0) >> gbase) & gmask;
-    bool neg = gt > lt;  // higher lanes hold more significant words
-    // d = n - m, quad-local with borrow-in 0
-    u64 nlo = (u64)n4.x | ((u64)n4.y << 32), nhi = (u64)n4.z | ((u64)n4.w << 32);
-    u64 mlo = (u64)m4.x | ((u64)m4.y << 32), mhi = (u64)m4.z | ((u64)m4.w << 32);
-    u64 dlo = nlo - mlo;
-    u64 b0 = nlo < mlo ? 1ull : 0ull;
-    u64 dhi = nhi - mhi - b0;
-    bool gen = (nhi < mhi) || (nhi == mhi && b0);  // borrow out with borrow-in 0
-    bool prop = (dlo == 0ull && dhi == 0ull);      // a borrow-in would pass through
-    u64 G = (__builtin_amdgcn_ballot_w64(gen) >> gbase) & gmask;
-    u64 P = (__builtin_amdgcn_ballot_w64(prop) >> gbase) & gmask;
-    // carries of the addition U + V with U = G|P, V = G are the borrows into each lane
-    u64 U = G | P, V = G;
-    u64 bin = ((U + V) ^ U ^ V) >> li & 1ull;
-    if (bin) {
-      u64 t = dlo;
-      dlo = t - 1ull;
-      if (t == 0ull) dhi -= 1ull;
+  const int gpb = (int)blockDim.x / LPI;  // lane groups per block
+  const int gib = (int)threadIdx.x / LPI;
+  // this quad of n and of n - 2^64; the low two words of the element do not take part in the comparisons
+  uint4 n4 = reinterpret_cast<const uint4*>(nw)[li];
+  uint4 b4 = reinterpret_cast<const uint4*>(nbw)[li];
+  const u64 nlo = (u64)n4.x | ((u64)n4.y << 32);  // used on lane 0 only
+  const u32 keep = li == 0 ? 0u : ~0u;
+  n4.x &= keep, n4.y &= keep, b4.x &= keep, b4.y &= keep;
+  for (size_t base0 = (size_t)blockIdx.x * gpb * B; base0 < count; base0 += (size_t)gridDim.x * gpb * B) {
+    const size_t first = base0 + (size_t)gib * B;  // this group's elements: first .. first + B - 1
+    uint4 loaded[B];
+#pragma unroll
+    for (int u = 0; u < B; ++u) {
+      loaded[u] = make_uint4(0u, 0u, 0u, 0u);
+      if (first + u < count) {
+        typedef u32 quad_t __attribute__((vector_size(16)));
+        const quad_t* src = reinterpret_cast<const quad_t*>(plain) + ((first + u) * (size_t)LPI + li);
+        const quad_t v = HAFLO_DECODE_NONTEMPORAL ? __builtin_nontemporal_load(src) : *src;
+        loaded[u] = make_uint4(v[0], v[1], v[2], v[3]);
+      }
     }
-    u64 rlo = neg ? dlo : mlo;
-    u64 rhi = neg ? dhi : mhi;
-    // magnitude must fit 64 bits: everything above the low two words is zero
-    bool high_nonzero = (li == 0) ? (rhi != 0ull) : ((rlo | rhi) != 0ull);
-    u64 nz = (__builtin_amdgcn_ballot_w64(high_nonzero) >> gbase) & gmask;
-    if (active && li == 0) {
-      bool ok = (nz == 0ull) && (neg ? (rlo <= 0x8000000000000000ull) : (rlo < 0x8000000000000000ull));
-      long long q = 0;
-      if (ok) q = neg ? (long long)(0ull - rlo) : (long long)rlo;
-      if (qout) qout[item] = q;
-      if (vout) vout[item] = __builtin_ldexp((double)q, -scale_bits);
-      if (status) status[item] = ok ? HAFLO_ST_OK : HAFLO_ST_RANGE;
+    long long my_q = 0;  // lane u < B: value and validity of element first + u
+    bool my_ok = false;
+#pragma unroll
+    for (int u = 0; u < B; ++u) {
+      const uint4 m4 = loaded[u];
+      const u64 mlo = (u64)m4.x | ((u64)m4.y << 32);  // meaningful on lane 0
+      const u32 hx = m4.x & keep, hy = m4.y & keep;
+      const bool zero = (hx | hy | m4.z | m4.w) == 0u;
+      const bool like_n = ((hx ^ n4.x) | (hy ^ n4.y) | (m4.z ^ n4.z) | (m4.w ^ n4.w)) == 0u;
+      const bool like_b = ((hx ^ b4.x) | (hy ^ b4.y) | (m4.z ^ b4.z) | (m4.w ^ b4.w)) == 0u;
+      const bool all_zero = ((__builtin_amdgcn_ballot_w64(zero) >> gbase) & gmask) == gmask;
+      const bool all_n = ((__builtin_amdgcn_ballot_w64(like_n) >> gbase) & gmask) == gmask;
+      const bool all_b = ((__builtin_amdgcn_ballot_w64(like_b) >> gbase) & gmask) == gmask;
+      // lane 0: the low 64 bits of m and of n - m, and whether that subtraction borrows
+      const u64 dlo = nlo - mlo;
+      const bool borrow = nlo < mlo;
+      const bool near_n = borrow ? all_b : all_n;  // n - m = dlo exactly
+      const bool ok = all_zero ? (mlo < 0x8000000000000000ull) : (near_n && dlo <= 0x8000000000000000ull);
+      const long long q = !ok ? 0ll : (all_zero ? (long long)mlo : (long long)(0ull - dlo));
+      // hand lane 0's verdict to lane u
+      const u32 q_lo = (u32)__builtin_amdgcn_ds_bpermute(gbase << 2, (int)(u32)(u64)q);
+      const u32 q_hi = (u32)__builtin_amdgcn_ds_bpermute(gbase << 2, (int)(u32)((u64)q >> 32));
+      const u32 ok0 = (u32)__builtin_amdgcn_ds_bpermute(gbase << 2, ok ? 1 : 0);
+      if (li == u) {
+        my_q = (long long)((u64)q_lo | ((u64)q_hi << 32));
+        my_ok = ok0 != 0u;
+      }
+    }
+    const size_t item = first + (size_t)li;
+    if (li < B && item < count) {
+      if (qout) __builtin_nontemporal_store(my_q, qout + item);
+      if (vout) __builtin_nontemporal_store(__builtin_ldexp((double)my_q, -scale_bits), vout + item);
+      if (status) __builtin_nontemporal_store((u32)(my_ok ? HAFLO_ST_OK : HAFLO_ST_RANGE), status + item);
     }
   }
 }
@@ -312,7 +339,9 @@ int haflo_encode_f32(const haflo_ctx* ctx, const float* d_v, uint32_t scale_bits
   if (count == 0) return HAFLO_OK;
   int z = 2;
   while (z < ctx->lp && ctx->n.word(z) == 0) ++z;
-  const LaunchShape sh = launch_shape(ctx, count, 1, 8);
+  // the residues are written once and read by a later kernel: non-temporal stores from few, long-running
+  // wavefronts (a plain device fill is fastest the same way: more blocks per compute unit write slower)
+  const LaunchShape sh = launch_shape(ctx, count, 1, ctx->lp <= 32 ? 2 : 1);
   HAFLO_LAUNCH(k_encode, sh, (hipStream_t)stream, d_v, (const float*)nullptr, (int)scale_bits, ctx->d_n_words,
                ctx->lp, z, d_plain, d_status, count);
   return hip_status(hipGetLastError());
@@ -333,7 +362,7 @@ int haflo_fore_gradient(const haflo_ctx* ctx, const void* d_c_host, const float*
   char* guest = (char*)d_workspace + plain_bytes;
   int z = 2;
   while (z < ctx->lp && ctx->n.word(z) == 0) ++z;
-  const LaunchShape sh = launch_shape(ctx, count, 1, 8);
+  const LaunchShape sh = launch_shape(ctx, count, 1, ctx->lp <= 32 ? 2 : 1);
   HAFLO_LAUNCH(k_encode, sh, (hipStream_t)stream, d_logits_guest, d_label, (int)scale_bits, ctx->d_n_words, ctx->lp,
                z, plain, d_status, count);
   int rc = haflo_encrypt(ctx, plain, d_r, guest, count, guest + cipher_bytes, enc_bytes, stream);
@@ -359,10 +388,10 @@ int haflo_decode(const haflo_ctx* ctx, const uint32_t* d_plain, uint32_t scale_b
   if (!ctx || scale_bits > 1000 || (count && !d_plain)) return HAFLO_EINVAL;
   if (count == 0) return HAFLO_OK;
   const int lpi = ctx->lp / 4;
-  const LaunchShape sh = launch_shape(ctx, count, lpi, 16);
+  const LaunchShape sh = launch_shape(ctx, (count + decode_batch(lpi) - 1) / decode_batch(lpi), lpi, HAFLO_DECODE_BLOCKS_PER_CU);
   hipStream_t st = (hipStream_t)stream;
 #define DECODE(LPI)                                                                                        \
-  HAFLO_LAUNCH((k_decode<LPI>), sh, st, d_plain, ctx->d_n_words, ctx->d_halfn_words, (int)scale_bits,      \
+  HAFLO_LAUNCH((k_decode<LPI>), sh, st, d_plain, ctx->d_n_words, ctx->d_nb_words, (int)scale_bits,         \
                (long long*)d_q, d_v, d_status, count)
   switch (lpi) {
     case 4: DECODE(4); break;

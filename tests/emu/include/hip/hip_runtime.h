@@ -27,6 +27,8 @@
 #define __shared__ static
 #define __align__(n) __attribute__((aligned(n)))
 #define HIP_SYMBOL(x) x
+#define __builtin_nontemporal_store(v, p) (*(p) = (v))
+#define __builtin_nontemporal_load(p) (*(p))
 
 struct dim3 {
   unsigned x, y, z;

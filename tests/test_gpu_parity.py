@@ -952,8 +952,8 @@ def test_batch_with_partial_last_pass(api):
     pub.close()
 
 
-def test_edges_encode_decode(api):
-    bits = 1024
+@pytest.mark.parametrize("bits", [512, 1024, 2048, 4096])
+def test_edges_encode_decode(api, bits):
     ctx, sk = context(api, bits)
     pk = sk.public
     n = pk.n
