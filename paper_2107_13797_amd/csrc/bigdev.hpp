@@ -16,7 +16,8 @@
 //
 // Cross-lane traffic: ds_bpermute for broadcasts from a lane chosen at run time,
 // DPP moves for broadcasts from lane 0 of a group and for the exchange with the
-// neighbouring lane (groups never straddle a 16-lane DPP row, so T <= 16).
+// neighbouring lane (groups of up to 16 lanes never straddle a 16-lane DPP row;
+// a group of more lanes has the wavefront to itself).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -46,17 +47,27 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// Geometry of the lane group that owns one big integer.
+// Geometry of the lane group that owns one big integer. Up to 16 lanes, a power of two: groups tile a
+// 16-lane DPP row and every lane of the wavefront belongs to one. More than 16 lanes: one group per
+// wavefront on lanes 0 .. T-1 (any T up to 64), for batches so small that the latency of a single product
+// is what counts; the lanes above hold zeros (zero limbs of the operands and of the modulus keep every
+// column of theirs zero, so the top lane of the group receives zeros from above, as it does from the
+// first lane of a neighbouring group) and neither load nor store. Neighbour exchange then uses the DPP
+// shifts over the whole wavefront, and the quotient digit of lane 0 is read into a scalar register.
 template <int T>
 struct Grp {
-  static_assert(T == 1 || T == 2 || T == 4 || T == 8 || T == 16, "group must fit one DPP row");
+  static_assert(T >= 1 && T <= 64 && (T > 16 || (T & (T - 1)) == 0), "1, 2, 4, 8, 16 lanes, or one group per wavefront");
+  static constexpr bool kWhole = T > 16;           // one group per wavefront
+  static constexpr int kPitch = kWhole ? WAVE : T;  // lanes from one group to the next
   int k;          // this lane's chunk index inside the group
   int base_addr;  // ds_bpermute byte address of the group's lane 0
   __device__ __forceinline__ Grp() {
     int lane = (int)(threadIdx.x & (WAVE - 1));
-    k = lane & (T - 1);
+    k = lane & (kPitch - 1);
     base_addr = (lane - k) << 2;
   }
+  // false on the lanes of a whole-wavefront group that hold no limbs
+  __device__ __forceinline__ bool live() const { return !kWhole || k < T; }
   // value of `v` held by lane `src_k` of this group
   __device__ __forceinline__ u32 bcast(u32 v, int src_k) const {
     if (T == 1) return v;
@@ -65,29 +76,35 @@ struct Grp {
   // value of `v` held by lane 0 of this group, through DPP moves: a few VALU cycles instead of a round
   // trip through the LDS crossbar, which matters where the result is needed at once. A group that fills
   // a 16-lane row takes the row broadcast; smaller groups a quad broadcast, then a row shift by 4 lanes
-  // into the odd banks.
+  // into the odd banks; a whole-wavefront group reads lane 0 into a scalar register.
   __device__ __forceinline__ u32 bcast0(u32 v) const {
     if (T == 1) return v;
     int x = (int)v;
+    if (kWhole) return (u32)__builtin_amdgcn_readfirstlane(x);
     if (T == 16) return (u32)__builtin_amdgcn_update_dpp(x, x, 0x150 /* row_newbcast:0 */, 0xf, 0xf, false);
     x = __builtin_amdgcn_update_dpp(x, x, T == 2 ? 0xA0 /* quad_perm:[0,0,2,2] */ : 0x00 /* [0,0,0,0] */, 0xf, 0xf, false);
     if (T == 8) x = __builtin_amdgcn_update_dpp(x, x, 0x114 /* row_shr:4 */, 0xf, 0xA, false);
     return (u32)x;
   }
-  // v of the next-higher lane; 0 past the end of the 16-lane row. The top lane
-  // of a group that is not at a row end sees lane 0 of the next group.
+  // v of the next-higher lane; 0 past the end of the 16-lane row (of the wavefront for a whole-wavefront
+  // group). The top lane of a group that is not at a row end sees lane 0 of the next group.
   __device__ __forceinline__ u32 from_upper_raw(u32 v) const {
     if (T == 1) return 0u;
+    if (kWhole) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x130 /* wave_shl:1 */, 0xf, 0xf, true);
     return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x101 /* row_shl:1 */, 0xf, 0xf, true);
   }
   __device__ __forceinline__ u32 from_upper(u32 v) const {
     if (T == 1) return 0u;
     u32 r = from_upper_raw(v);
-    return (k == T - 1) ? 0u : r;
+    return (k >= T - 1) ? 0u : r;
   }
-  // v of the next-lower lane; 0 for the group's lane 0
+  // v of the next-lower lane; 0 for the group's lane 0 (and for the lanes without limbs)
   __device__ __forceinline__ u32 from_lower(u32 v) const {
     if (T == 1) return 0u;
+    if (kWhole) {
+      u32 r = (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x138 /* wave_shr:1 */, 0xf, 0xf, true);
+      return (k == 0 || k >= T) ? 0u : r;
+    }
     u32 r = (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x111 /* row_shr:1 */, 0xf, 0xf, true);
     return (k == 0) ? 0u : r;
   }
@@ -135,7 +152,8 @@ __device__ __forceinline__ void hi_normalise(u64 (&A)[LPT], const Grp<T>& g, u32
 template <int LPT, int T>
 struct BRegs {
   const u32 (&b)[LPT];
-  static constexpr int kAhead = 1;
+  // a step of few limbs is short: ask earlier, so that the crossbar's latency stays covered
+  static constexpr int kAhead = LPT <= 3 ? LPT : (LPT <= 8 && LPT % 2 == 0 ? 2 : 1);
   __device__ __forceinline__ u32 limb(int o, int rr, const Grp<T>& g) const {
     if (T == 1) return b[rr % LPT];
     // past the last limb this reads a lane of the next group (or wraps); that value is never used
@@ -424,14 +442,17 @@ __device__ __forceinline__ void mulwide(u32 (&lo)[LPT], u32 (&hi)[LPT], const u3
 template <int LPT, int T>
 __device__ __forceinline__ void load_limbs(u32 (&x)[LPT], const u32* p, const Grp<T>& g) {
   const u32* q = p + g.k * LPT;
+  const bool live = g.live();
 #pragma unroll
-  for (int j = 0; j < LPT; ++j) x[j] = q[j];
+  for (int j = 0; j < LPT; ++j) x[j] = live ? q[j] : 0u;
 }
 template <int LPT, int T>
 __device__ __forceinline__ void store_limbs(u32* p, const u32 (&x)[LPT], const Grp<T>& g) {
   u32* q = p + g.k * LPT;
+  if (g.live()) {
 #pragma unroll
-  for (int j = 0; j < LPT; ++j) q[j] = x[j];
+    for (int j = 0; j < LPT; ++j) q[j] = x[j];
+  }
 }
 template <int LPT>
 __device__ __forceinline__ void zero_limbs(u32 (&x)[LPT]) {
@@ -443,7 +464,7 @@ __device__ __forceinline__ void zero_limbs(u32 (&x)[LPT]) {
 template <int LPT, int T>
 __device__ __forceinline__ void load_limbs_below(u32 (&x)[LPT], const u32* p, int valid, const Grp<T>& g) {
 #pragma unroll
-  for (int j = 0; j < LPT; ++j) x[j] = (g.k * LPT + j < valid) ? p[g.k * LPT + j] : 0u;
+  for (int j = 0; j < LPT; ++j) x[j] = (g.live() && g.k * LPT + j < valid) ? p[g.k * LPT + j] : 0u;
 }
 
 // This lane's 29-bit limbs, counted from limb `first_limb` of the integer, cut out of an array
@@ -459,7 +480,7 @@ __device__ __forceinline__ void load_words_as_limbs(u32 (&x)[LPT], const u32* wp
     u32 lo = (wi < nwords) ? wp[wi] : 0u;
     u32 hi = (wi + 1 < nwords) ? wp[wi + 1] : 0u;
     u64 v = ((u64)hi << 32) | lo;
-    x[j] = (u32)(v >> sh) & LIMB_MASK;
+    x[j] = g.live() ? (u32)(v >> sh) & LIMB_MASK : 0u;
   }
 }
 

@@ -140,10 +140,12 @@ namespace haflo {
 // 256-lane blocks capped at blocks_per_cu per compute unit; a batch too small
 // to give every compute unit four wavefronts uses single-wavefront blocks so
 // that it still spreads over the chip.
+enum { kGeoPlain = 0, kGeoWide = 1, kGeoWave = 2 };  // lanes per big integer: as the modulus says, twice that, a wavefront
 struct LaunchShape {
   int blocks;
   int threads;
   int gpb;  // groups per block
+  int geo = kGeoPlain;
   size_t slots() const { return (size_t)blocks * gpb; }
 };
 inline LaunchShape launch_shape(const haflo_ctx* ctx, size_t groups, int t, int blocks_per_cu) {

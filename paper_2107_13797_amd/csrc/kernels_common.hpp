@@ -29,8 +29,8 @@ struct Batch {
   unsigned block, nblocks;  // this block's index among the blocks that share the batch
   __device__ __forceinline__ Batch() : Batch(blockIdx.x, gridDim.x) {}
   __device__ __forceinline__ Batch(unsigned block_, unsigned nblocks_) : block(block_), nblocks(nblocks_) {
-    gpb = (int)blockDim.x / T;
-    gib = (int)threadIdx.x / T;
+    gpb = (int)blockDim.x / Grp<T>::kPitch;
+    gib = (int)threadIdx.x / Grp<T>::kPitch;
   }
   __device__ __forceinline__ size_t first() const { return (size_t)block * gpb; }
   __device__ __forceinline__ size_t stride() const { return (size_t)nblocks * gpb; }
@@ -161,7 +161,15 @@ __device__ __forceinline__ void engine_run(const ModRef& M, const Prog& P, const
         if (op == ENG_MUL_C) src = io.constant[a];
         else src = table + (size_t)(op == ENG_MUL_TD ? (u32)(k >> a) & 15u : a) * NL;
         if (!(tab_ok || op == ENG_MUL_C)) src = io.constant[kConstR1];
-        montmul_mem<LPT, T>(acc, acc, src, mod.n, mod.n0inv, g);
+        if (Grp<T>::kWhole) {
+          // a lone wavefront cannot hide a load every few steps: the lanes fetch their limbs of the
+          // multiplier once (one latency per product) and the steps take them from registers
+          u32 t[LPT];
+          load_limbs<LPT, T>(t, src, g);
+          montmul<LPT, T>(acc, acc, t, mod.n, mod.n0inv, g);
+        } else {
+          montmul_mem<LPT, T>(acc, acc, src, mod.n, mod.n0inv, g);
+        }
       }
       if (op == ENG_MUL_T_ST && tab_ok) store_limbs<LPT, T>(table + (size_t)b * NL, acc, g);
     }
@@ -223,6 +231,18 @@ __global__ __launch_bounds__(kBlockThreads, 4) void k_engine_pair(EngineJob j0, 
     else if ((m).lpt == 9 && (m).t == 1) { CALL(9, 1); }          \
     else return HAFLO_EINVAL;                                     \
   } while (0)
+// The same dispatch for batches of at most one big integer per SIMD, where the latency of one product is all
+// that counts: one integer per wavefront on 18 to 48 lanes with 2 to 6 limbs each (steps of a dozen
+// instructions instead of two to four dozen). Moduli without such a geometry take the wide one.
+#define HAFLO_DISPATCH_GEOMETRY_WAVE(m, CALL)                     \
+  do {                                                            \
+    if ((m).nl == 36) { CALL(2, 18); }                            \
+    else if ((m).nl == 72) { CALL(2, 36); }                       \
+    else if ((m).nl == 144) { CALL(3, 48); }                      \
+    else if ((m).nl == 288) { CALL(6, 48); }                      \
+    else HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL);                   \
+  } while (0)
+inline bool haflo_has_wave_geometry(const haflo::ModHost& m) { return m.nl == 36 || m.nl == 72 || m.nl == 144 || m.nl == 288; }
 // true when so few big integers are in flight that the chip is mostly idle anyway
 namespace haflo {
 inline bool few_groups(const haflo_ctx* ctx, size_t groups, int per_cu = 8) {

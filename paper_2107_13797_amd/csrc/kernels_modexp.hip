@@ -167,14 +167,27 @@ __global__ __launch_bounds__(kBlockThreads) void k_enc_crt(ModRef MP2, ModRef MQ
   }
 }
 
-// A batch that leaves most of the chip idle is latency-bound: its integers are spread over twice
-// the lanes (9 limbs each), which shortens every product of the chain at 1.2 times the
-// instructions. Taken while the doubled batch still is at most two wavefronts per SIMD.
-bool engine_wide(const haflo_ctx* ctx, size_t count, const ModHost& m) {
-  return m.lpt == 18 && m.t < 16 && count * (size_t)m.t <= (size_t)ctx->num_cu * 256;
+// A batch that leaves most of the chip idle is latency-bound. Up to one element per SIMD, each gets a
+// wavefront to itself (a few limbs per lane: the shortest steps); beyond that, while twice the lanes still
+// are at most two wavefronts per SIMD, its integers are spread over twice the lanes (9 limbs each), which
+// shortens every product of the chain at 1.2 times the instructions. `jobs`: independent halves of one launch.
+int engine_geo(const haflo_ctx* ctx, size_t count, const ModHost& m, int jobs = 1) {
+  if (haflo_has_wave_geometry(m) && count * (size_t)jobs <= (size_t)ctx->num_cu * 4) return kGeoWave;
+  if (m.lpt == 18 && m.t < 16 && count * (size_t)m.t <= (size_t)ctx->num_cu * 256) return kGeoWide;
+  return kGeoPlain;
 }
-LaunchShape modexp_shape(const haflo_ctx* ctx, size_t count, const ModHost& m) {
-  return launch_shape(ctx, count, engine_wide(ctx, count, m) ? 2 * m.t : m.t, kModexpBlocksPerCu);
+LaunchShape modexp_shape(const haflo_ctx* ctx, size_t count, const ModHost& m, int jobs = 1) {
+  const int geo = engine_geo(ctx, count, m, jobs);
+  LaunchShape s;
+  if (geo == kGeoWave) {
+    s.blocks = (int)(count ? count : 1);
+    s.threads = 64;
+    s.gpb = 1;
+  } else {
+    s = launch_shape(ctx, count, geo == kGeoWide ? 2 * m.t : m.t, kModexpBlocksPerCu);
+  }
+  s.geo = geo;
+  return s;
 }
 
 EngineIO engine_io(const ModHost& m) {
@@ -198,9 +211,10 @@ bool to_inline(ProgInline& pi, const std::vector<uint32_t>& prog) {
 template <class Prog>
 int launch_engine(const ModHost& m, const LaunchShape& sh, hipStream_t st, const Prog& prog, const EngineIO& io,
                   size_t count) {
-  const bool wide = sh.gpb * m.t != sh.threads;  // the shape was made for twice the lanes per integer
 #define CALL(LPT, T) HAFLO_LAUNCH((k_engine<LPT, T, Prog>), sh, st, m.ref(), prog, io, count)
-  if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
+  if (sh.geo == kGeoWave) { HAFLO_DISPATCH_GEOMETRY_WAVE(m, CALL); }
+  else if (sh.geo == kGeoWide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); }
+  else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
   return hip_status(hipGetLastError());
 }
@@ -220,10 +234,11 @@ BatchSplit split_batch(const haflo_ctx* ctx, size_t count, const ModHost& m) {
   b.full = 0;
   b.tail = b.shape;
   const size_t slots = b.shape.slots();
-  if (engine_wide(ctx, count, m) || count <= slots || count % slots == 0) return b;
+  if (b.shape.geo != kGeoPlain || count <= slots || count % slots == 0) return b;
   b.full = count / slots * slots;
   const size_t rest = count - b.full;
-  const int t = engine_wide(ctx, rest, m) ? 2 * m.t : m.t;
+  b.tail.geo = engine_geo(ctx, rest, m);
+  const int t = b.tail.geo == kGeoWave ? 64 : (b.tail.geo == kGeoWide ? 2 * m.t : m.t);
   b.tail.threads = 64;
   b.tail.gpb = 64 / t;
   b.tail.blocks = (int)((rest + b.tail.gpb - 1) / b.tail.gpb);
@@ -267,8 +282,8 @@ size_t ws_encrypt(const haflo_ctx* ctx, size_t count) {
   // grid; for the last stage one table slot of N.nl limbs per lane group]
   size_t tl1 = (size_t)std::max(ctx->prog_enc_p.table_entries, ctx->prog_enc_q.table_entries);
   size_t tl2 = (size_t)std::max(ctx->prog_lift_p.table_entries, ctx->prog_lift_q.table_entries);
-  size_t low = 2 * modexp_shape(ctx, count, ctx->P).slots() * tl1 * ctx->P.nl;
-  size_t lift = 2 * modexp_shape(ctx, count, ctx->P2).slots() * tl2 * ctx->P2.nl;
+  size_t low = 2 * modexp_shape(ctx, count, ctx->P, 2).slots() * tl1 * ctx->P.nl;
+  size_t lift = 2 * modexp_shape(ctx, count, ctx->P2, 2).slots() * tl2 * ctx->P2.nl;
   size_t last = modexp_shape(ctx, count, ctx->N).slots() * (size_t)ctx->N.nl;
   return (2 * count * (size_t)ctx->P2.nl + count * (size_t)ctx->N.nl + std::max(std::max(low, lift), last)) * 4;
 }
@@ -285,7 +300,7 @@ size_t ws_decrypt(const haflo_ctx* ctx, size_t count) {
   if (!ctx->has_priv) return 0;
   size_t tl = (size_t)std::max(ctx->prog_dec_p.table_entries, ctx->prog_dec_q.table_entries);
   return (count * (size_t)ctx->N.nl + 2 * count * (size_t)ctx->P2.nl +
-          2 * modexp_shape(ctx, count, ctx->P2).slots() * tl * ctx->P2.nl) * 4;
+          2 * modexp_shape(ctx, count, ctx->P2, 2).slots() * tl * ctx->P2.nl) * 4;
 }
 
 // tables[i][d] = c_i^d, d < entries, for `count` internal ciphertexts (used by the matvec)
@@ -345,7 +360,7 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
     const ModHost& geo = stage ? h : l;
     const DevProg* progs[2] = {stage ? &ctx->prog_lift_p : &ctx->prog_enc_p, stage ? &ctx->prog_lift_q : &ctx->prog_enc_q};
     const int tl = std::max(progs[0]->table_entries, progs[1]->table_entries);
-    LaunchShape sh = modexp_shape(ctx, count, geo);
+    LaunchShape sh = modexp_shape(ctx, count, geo, 2);
     EngineJob job[2];
     for (int side = 0; side < 2; ++side) {
       const ModHost& ms = stage ? (side ? ctx->Q2 : ctx->P2) : (side ? ctx->Q : ctx->P);
@@ -368,7 +383,9 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
     const unsigned split = (unsigned)sh.blocks;
     sh.blocks *= 2;
 #define CALL(LPT, T) HAFLO_LAUNCH((k_engine_pair<LPT, T>), sh, st, job[0], job[1], split, count)
-    if (engine_wide(ctx, count, geo)) { HAFLO_DISPATCH_GEOMETRY_WIDE(geo, CALL); } else { HAFLO_DISPATCH_GEOMETRY(geo, CALL); }
+    if (sh.geo == kGeoWave) { HAFLO_DISPATCH_GEOMETRY_WAVE(geo, CALL); }
+    else if (sh.geo == kGeoWide) { HAFLO_DISPATCH_GEOMETRY_WIDE(geo, CALL); }
+    else { HAFLO_DISPATCH_GEOMETRY(geo, CALL); }
 #undef CALL
   }
   {
@@ -536,7 +553,7 @@ int decrypt_launches(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_pla
     // both prime-power branches in one launch: the first half of the grid works modulo p^2,
     // the second half modulo q^2, each half with its own table slots
     const ModHost& m = ctx->P2;
-    LaunchShape sh = modexp_shape(ctx, count, m);
+    LaunchShape sh = modexp_shape(ctx, count, m, 2);
     EngineJob job[2];
     for (int side = 0; side < 2; ++side) {
       const ModHost& ms = side ? ctx->Q2 : ctx->P2;
@@ -553,7 +570,9 @@ int decrypt_launches(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_pla
     const unsigned split = (unsigned)sh.blocks;
     sh.blocks *= 2;
 #define CALL(LPT, T) HAFLO_LAUNCH((k_engine_pair<LPT, T>), sh, st, job[0], job[1], split, count)
-    if (engine_wide(ctx, count, m)) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
+    if (sh.geo == kGeoWave) { HAFLO_DISPATCH_GEOMETRY_WAVE(m, CALL); }
+    else if (sh.geo == kGeoWide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); }
+    else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
   }
   {

@@ -92,6 +92,10 @@ uint32_t dpp(uint32_t old, uint32_t src, int ctrl, int row_mask, int bank_mask, 
   } else if (ctrl >= 0x111 && ctrl <= 0x11f) {  // row_shr:n - lane i reads lane i-n
     int s = pos - (ctrl - 0x110);
     if (s >= 0) from = row + s;
+  } else if (ctrl == 0x130) {  // wave_shl:1 - lane i reads lane i+1 of the wavefront
+    if (lane + 1 < kWave) from = lane + 1;
+  } else if (ctrl == 0x138) {  // wave_shr:1 - lane i reads lane i-1 of the wavefront
+    if (lane >= 1) from = lane - 1;
   } else if (ctrl >= 0x150 && ctrl <= 0x15f) {  // row_newbcast:n - every lane of a row reads its lane n
     from = row + (ctrl - 0x150);
   } else if (ctrl >= 0 && ctrl <= 0xff) {  // quad_perm
@@ -101,6 +105,11 @@ uint32_t dpp(uint32_t old, uint32_t src, int ctrl, int row_mask, int bank_mask, 
   }
   if (from < 0) return bound_ctrl ? 0u : old;
   return t[from];
+}
+
+uint32_t readlane(uint32_t v, int src_lane) {
+  const uint32_t* t = exchange(v);
+  return t[src_lane & (kWave - 1)];
 }
 
 uint64_t ballot(bool p) {

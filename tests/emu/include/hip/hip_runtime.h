@@ -63,6 +63,7 @@ void launch(dim3 grid, dim3 block, const std::function<void()>& body);
 uint32_t bpermute(int byte_addr, uint32_t v);
 uint32_t dpp(uint32_t old, uint32_t src, int ctrl, int row_mask, int bank_mask, bool bound_ctrl);
 uint64_t ballot(bool p);
+uint32_t readlane(uint32_t v, int src_lane);
 void barrier();
 void* dev_alloc(size_t bytes);
 void dev_free(void* p);
@@ -81,6 +82,9 @@ static inline int __builtin_amdgcn_update_dpp(int old, int src, int ctrl, int ro
                                               bool bound_ctrl) {
   return (int)hipemu::dpp((uint32_t)old, (uint32_t)src, ctrl, row_mask, bank_mask, bound_ctrl);
 }
+// every lane of an emulated wavefront is active, so the first active lane is lane 0
+static inline int __builtin_amdgcn_readfirstlane(int v) { return (int)hipemu::readlane((uint32_t)v, 0); }
+static inline int __builtin_amdgcn_readlane(int v, int lane) { return (int)hipemu::readlane((uint32_t)v, lane); }
 static inline uint64_t __builtin_amdgcn_ballot_w64(bool p) { return hipemu::ballot(p); }
 static inline void __builtin_amdgcn_sched_barrier(int) {}
 static inline void __builtin_amdgcn_sched_group_barrier(int, int, int) {}

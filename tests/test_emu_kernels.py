@@ -392,6 +392,48 @@ def test_wider_lane_groups(emu, bits):
     lib.haflo_ctx_destroy(ctx)
 
 
+@pytest.mark.parametrize("bits,count", [(1024, 2), (2048, 1)])
+def test_whole_wavefront_groups_encrypt_decrypt(emu, bits, count):
+    """Batches of at most one element per SIMD give every big integer a wavefront to itself (18 to 48
+    lanes with 2 or 3 limbs each, neighbour exchange across DPP rows, the quotient digit through a
+    scalar register): the full encryption program with the public key, the key owner's two-stage
+    route and the decryption through p^2 and q^2, against the oracle."""
+    lib = emu
+    p, q = oracle_key(bits)
+    sk = O.PrivateKey(p, q)
+    pk = sk.public
+    n = pk.n
+    lp, lc = bits // 32, bits // 16
+
+    def le(x, nbytes):
+        return (C.c_uint8 * nbytes).from_buffer_copy(x.to_bytes(nbytes, "little"))
+
+    own, pub = C.c_void_p(), C.c_void_p()
+    assert lib.haflo_ctx_create_private(le(p, bits // 16), le(q, bits // 16), bits, C.byref(own)) == 0
+    assert lib.haflo_ctx_create_public(le(n, bits // 8), bits, C.byref(pub)) == 0
+    cb = C.c_size_t()
+    lib.haflo_ctx_info(own, None, None, None, C.byref(cb), None)
+    nlw = cb.value // 4
+    rng = random.Random(bits + 1)
+    ms = [rng.randrange(n) for _ in range(count)]
+    ms[0] = n - 1
+    rs = [rng.randrange(1, n) for _ in range(count)]
+    want = [O.encrypt(pk, m, r) for m, r in zip(ms, rs)]
+    lc_out = zeros(lib, (count, lc))
+    for ctx in (pub, own):
+        d_c = zeros(lib, (count, nlw))
+        w, nb = ws(lib, ctx, _cabi.OP_ENCRYPT, count)
+        assert lib.haflo_encrypt(ctx, words(lib, ms, lp).p, words(lib, rs, lp).p, d_c.p, count, w.p, nb, None) == 0
+        assert lib.haflo_export_cipher(ctx, d_c.p, lc_out.p, count, None) == 0
+        assert synth.words_to_ints(lc_out.get()) == want
+    d_pl = zeros(lib, (count, lp))
+    w, nb = ws(lib, own, _cabi.OP_DECRYPT, count)
+    assert lib.haflo_decrypt(own, d_c.p, d_pl.p, count, w.p, nb, None) == 0
+    assert synth.words_to_ints(d_pl.get()) == ms
+    lib.haflo_ctx_destroy(own)
+    lib.haflo_ctx_destroy(pub)
+
+
 def test_bucket_matvec_four_lane_groups(emu, force_buckets):
     """The bucket method with 4 lanes per integer (1024-bit key), where several groups share a
     wave and chunks of different length keep them in lock step."""
