@@ -292,6 +292,178 @@ __device__ __forceinline__ void montmul_mem(u32 (&out)[LPT], const u32 (&a)[LPT]
   montmul_core<LPT, T>(out, a, src, n, n0inv, g);
 }
 
+// ---------------------------------------------------------------------------
+// Arithmetic modulo n^2 on pairs of residues modulo n
+// ---------------------------------------------------------------------------
+// A residue X modulo n^2 is held as two half-length integers, X = x0 + n x1 (x0, x1 lazy residues modulo
+// n, NL limbs each, R = 2^(29 NL) the Montgomery radix of n). For X Y = x0 y0 + n (x0 y1 + x1 y0) (mod n^2),
+// let m = x0 y0 (-1/n) mod R be the quotient of the Montgomery reduction of x0 y0 and t = (x0 y0 + m n) / R
+// its result; then x0 y0 = t R - m n, and
+//     Z = t + n z1,  z1 = (x0 y1 + x1 y0 - m) / R mod n,
+// satisfies Z R = X Y (mod n^2): a Montgomery product modulo n^2 with the half-length radix, from one
+// half-length Montgomery product (whose quotient digits are kept) and one half-length Montgomery reduction
+// of a sum of two products: 5 NL^2 limb products instead of the 8 NL^2 of a full-length product on 2 NL
+// limbs, and 3.6 NL^2 instead of 6.2 NL^2 for a squaring (x0^2 by sq_weight, 2 x0 x1 as one product with a
+// doubled limb). Both run in the same word-serial loop: step i adds a0 b0_i to window A and
+// a0 b1_i + a1 b0_i to window B, takes A's quotient digit q, hands its complement 2^29 - 1 - q to the
+// lowest column of B on lane 0 (the digits of R - 1 - m; a one in column 0 makes it R - m, and the -R that
+// is left turns into -1 after the division, which the final + (n - 1) absorbs), then takes B's digit.
+//   a0, a1, b0, b1: limbs < 2^29 + 2^8, values < 4n.  out0 < 2n, out1 < 2n (1 + 2^-30), limbs < 2^29 + 2^5.
+// Where two operands' limbs come from: registers (ds_bpermute) or two NL-limb arrays in memory, as for
+// the single product.
+template <int LPT, int T>
+struct BRegs2 {
+  const u32 (&b0)[LPT];
+  const u32 (&b1)[LPT];
+  static constexpr int kAhead = BRegs<LPT, T>::kAhead;
+  __device__ __forceinline__ u32 limb0(int o, int rr, const Grp<T>& g) const {
+    if (T == 1) return b0[rr % LPT];
+    return (u32)__builtin_amdgcn_ds_bpermute(g.base_addr + ((o + rr / LPT) << 2), (int)b0[rr % LPT]);
+  }
+  __device__ __forceinline__ u32 limb1(int o, int rr, const Grp<T>& g) const {
+    if (T == 1) return b1[rr % LPT];
+    return (u32)__builtin_amdgcn_ds_bpermute(g.base_addr + ((o + rr / LPT) << 2), (int)b1[rr % LPT]);
+  }
+};
+template <int LPT, int T>
+struct BMem2 {
+  const u32* p;  // [b0: NL limbs][b1: NL limbs]
+  static constexpr int kAhead = 0;
+  __device__ __forceinline__ u32 limb0(int o, int rr, const Grp<T>& g) const {
+    (void)g;
+    return p[o * LPT + rr];
+  }
+  __device__ __forceinline__ u32 limb1(int o, int rr, const Grp<T>& g) const {
+    (void)g;
+    return p[LPT * T + o * LPT + rr];
+  }
+};
+
+template <int LPT, int T, class BSrc, bool SQ>
+__device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT], const u32 (&a0)[LPT],
+                                             const u32 (&a1)[LPT], const BSrc& bsrc, const u32 (&n)[LPT], u32 n0inv,
+                                             const Grp<T>& g) {
+  static_assert(LPT <= 9, "a column of the second window takes three products per step");
+  const u32 eight = opaque_eight();
+  u64 A[LPT], B[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) {
+    A[j] = 0;
+    B[j] = 0;
+  }
+  if (g.k == 0) B[0] = 1;
+  const u32 first = (g.k == 0) ? 1u : 0u;  // the lane that holds the lowest column of the whole integer
+  constexpr int D = BSrc::kAhead;
+  constexpr int RING = D > 0 ? D : 1;
+  static_assert(LPT % RING == 0, "ring size");
+  u32 ring0[RING], ring1[RING];
+#pragma unroll
+  for (int d = 0; d < D; ++d) {
+    ring0[d] = bsrc.limb0(0, d, g);
+    ring1[d] = bsrc.limb1(0, d, g);
+  }
+#pragma unroll 1
+  for (int o = 0; o < T; ++o) {
+    static_for<0, LPT>([&](auto rc) {
+      constexpr int r = decltype(rc)::value;
+      u32 b0i, b1i;
+      if (D > 0) {
+        b0i = ring0[r % RING];
+        b1i = ring1[r % RING];
+        ring0[r % RING] = bsrc.limb0(o, r + D, g);
+        ring1[r % RING] = bsrc.limb1(o, r + D, g);
+      } else {
+        b0i = bsrc.limb0(o, r, g);
+        b1i = bsrc.limb1(o, r, g);
+      }
+      [[maybe_unused]] const u32 b0i2 = SQ ? b0i + b0i : b0i;
+      const u32 b1x = SQ ? b1i + b1i : b1i;  // squaring: 2 x0 x1 as x0 times the doubled limb of x1
+      // window A: a0 * b0 (for a squaring the products sq_weight selects)
+      auto product_a = [&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        constexpr int w = SQ ? sq_weight(LPT, j, r) : 1;
+        if constexpr (w == 1) A[j] = mad64(a0[j], b0i, A[j]);
+        else if constexpr (w == 2) A[j] = mad64(a0[j], b0i2, A[j]);
+      };
+      product_a(std::integral_constant<int, 0>{});
+      const u32 qa = g.bcast0(((u32)A[0] * n0inv) & LIMB_MASK);
+      static_for<1, LPT>(product_a);
+      // window B: a0 * b1 + a1 * b0, minus the quotient digit of A on the lowest column of the integer
+      B[0] = mad64(a0[0], b1x, B[0]);
+      if (!SQ) B[0] = mad64(a1[0], b0i, B[0]);
+      B[0] = mad64(LIMB_MASK - qa, first, B[0]);
+      const u32 qb = g.bcast0(((u32)B[0] * n0inv) & LIMB_MASK);
+#pragma unroll
+      for (int j = 1; j < LPT; ++j) {
+        B[j] = mad64(a0[j], b1x, B[j]);
+        if (!SQ) B[j] = mad64(a1[j], b0i, B[j]);
+      }
+      // both windows: add the multiple of n, hand the lowest column down, slide
+      const u64 ta = mad64(qa, n[0], A[0]);
+      const u64 tb = mad64(qb, n[0], B[0]);
+      const u32 recv_a = g.from_upper_raw((u32)ta & LIMB_MASK);
+      const u32 recv_b = g.from_upper_raw((u32)tb & LIMB_MASK);
+      if (LPT > 1) {
+        A[0] = mad64(qa, n[LPT > 1 ? 1 : 0], A[LPT > 1 ? 1 : 0]) + (ta >> LIMB_BITS);
+        B[0] = mad64(qb, n[LPT > 1 ? 1 : 0], B[LPT > 1 ? 1 : 0]) + (tb >> LIMB_BITS);
+#pragma unroll
+        for (int j = 2; j < LPT; ++j) {
+          A[j - 1] = mad64(qa, n[j], A[j]);
+          B[j - 1] = mad64(qb, n[j], B[j]);
+        }
+        A[LPT - 1] = (u64)recv_a;
+        B[LPT - 1] = (u64)recv_b;
+      } else {
+        A[0] = (u64)recv_a + (ta >> LIMB_BITS);
+        B[0] = (u64)recv_b + (tb >> LIMB_BITS);
+      }
+    });
+  }
+  // B holds (x0 y1 + x1 y0 - m) / R + 1 modulo n: add n - 1
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) B[j] += (u64)n[j];
+  B[0] -= (u64)first;  // n is odd, so its lowest limb is at least 1
+  hi_normalise<LPT, T>(A, g, eight);
+  hi_normalise<LPT, T>(B, g, eight);
+  u64 ca = 0, cb = 0;
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) {
+    const u64 va = A[j] + ca, vb = B[j] + cb;
+    out0[j] = (u32)va & LIMB_MASK;
+    out1[j] = (u32)vb & LIMB_MASK;
+    ca = va >> LIMB_BITS;
+    cb = vb >> LIMB_BITS;
+  }
+  if (T > 1) {
+    out0[0] += g.from_lower((u32)ca);
+    out1[0] += g.from_lower((u32)cb);
+  }
+}
+
+// (out0, out1) = (a0, a1) * (b0, b1) / R modulo n^2, b in registers (out may alias a and b)
+template <int LPT, int T>
+__device__ __forceinline__ void pairmul(u32 (&out0)[LPT], u32 (&out1)[LPT], const u32 (&a0)[LPT], const u32 (&a1)[LPT],
+                                        const u32 (&b0)[LPT], const u32 (&b1)[LPT], const u32 (&n)[LPT], u32 n0inv,
+                                        const Grp<T>& g) {
+  BRegs2<LPT, T> src = {b0, b1};
+  pairmul_core<LPT, T, BRegs2<LPT, T>, false>(out0, out1, a0, a1, src, n, n0inv, g);
+}
+// b = 2 NL limbs at `bmem` ([b0][b1]), the same array for every lane of the group
+template <int LPT, int T>
+__device__ __forceinline__ void pairmul_mem(u32 (&out0)[LPT], u32 (&out1)[LPT], const u32 (&a0)[LPT],
+                                            const u32 (&a1)[LPT], const u32* bmem, const u32 (&n)[LPT], u32 n0inv,
+                                            const Grp<T>& g) {
+  BMem2<LPT, T> src = {bmem};
+  pairmul_core<LPT, T, BMem2<LPT, T>, false>(out0, out1, a0, a1, src, n, n0inv, g);
+}
+// (out0, out1) = (a0, a1)^2 / R modulo n^2
+template <int LPT, int T>
+__device__ __forceinline__ void pairsqr(u32 (&out0)[LPT], u32 (&out1)[LPT], const u32 (&a0)[LPT], const u32 (&a1)[LPT],
+                                        const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
+  BRegs2<LPT, T> src = {a0, a1};
+  pairmul_core<LPT, T, BRegs2<LPT, T>, true>(out0, out1, a0, a1, src, n, n0inv, g);
+}
+
 // Full carry propagation of signed lazy limbs (|x[j]| < 2^30): afterwards every
 // limb is in [0, 2^29) and the return value (the same on all lanes of the
 // group) is the carry out of the top limb: 0 for a value in [0, 2^(29*NL)),

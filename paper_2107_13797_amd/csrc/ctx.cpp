@@ -242,6 +242,32 @@ static void build_prog_encrypt(DevProg& p, const Big& n, Uploader& up) {
   p.d_ins = up.put(p.host);
 }
 
+// The same on pairs of residues modulo n (engine_run_pairs): r -> r R -> (r R)^n = r^n R -> times (1 + m n)
+// (the pair (1, m)) = the ciphertext -> times R 2^(29 N.nl): its Montgomery form modulo n^2 at the radix of
+// the other operators. Constants: [0] R, [1] R^2, [4] R 2^(29 N.nl), all modulo n^2 and as pairs.
+static void build_prog_encrypt_pairs(DevProg& p, const HostSched& sched, Uploader& up) {
+  p.sched = sched;
+  p.host.clear();
+  p.host.push_back(eng_ins(ENG_LOAD_W, 1));
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstR2));
+  append_modexp(p.host, p.sched);
+  p.host.push_back(eng_ins(ENG_STORE_T, 0));
+  p.host.push_back(eng_ins(ENG_LOAD_W1, 0));
+  p.host.push_back(eng_ins(ENG_MUL_T, 0));
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstExtra));
+  p.table_entries = p.sched.table_len + 1;
+  p.d_ins = up.put(p.host);
+}
+
+// x < n^2 as the pair (x mod n, x div n), nl limbs each
+static std::vector<uint32_t> pair_limbs(const Big& x, const Big& n, int nl) {
+  const Big lo = Big::mod(x, n);
+  const Big hi = Big::div(x, n);
+  std::vector<uint32_t> v = to_limbs29(lo, nl), h = to_limbs29(hi, nl);
+  v.insert(v.end(), h.begin(), h.end());
+  return v;
+}
+
 // Key owner's encryption, one prime-power branch in two stages. With n = s t (s, t the primes,
 // gcd(t, s - 1) = 1) the n-th powers modulo s^2 are the subgroup of order s - 1, whose elements are
 // determined by their residues modulo s: the one that is a modulo s is a^s mod s^2. Hence
@@ -327,6 +353,22 @@ static int ctx_build(haflo_ctx* ctx, const Big& n, const Big* p, const Big* q, u
     Big r2 = Big::mod(Big::mul(r1, r1), ctx->nsq);
     Big k1 = Big::mod(Big::mul(n, r2), ctx->nsq);
     ctx->d_k1 = up.put(to_limbs29(k1, nl_n2));
+  }
+  {
+    // pair arithmetic modulo n^2: n at half the limbs, and the constants of the pair engine
+    const int nl_h = nl_n2 / 2;
+    build_modulus(ctx->Nh, n, nl_h, up);
+    const Big R = Big::pow2((size_t)kLimbBits * nl_h), RN = Big::pow2((size_t)kLimbBits * nl_n2);
+    const Big r1 = Big::mod(R, ctx->nsq);
+    const Big r2 = Big::mod(Big::mul(r1, r1), ctx->nsq);
+    const Big rx = Big::mod(Big::mul(r1, Big::mod(RN, ctx->nsq)), ctx->nsq);
+    std::vector<uint32_t> tab;
+    for (const Big* b : {&r1, &r2, &rx}) {
+      std::vector<uint32_t> l = pair_limbs(*b, n, nl_h);
+      tab.insert(tab.end(), l.begin(), l.end());
+    }
+    ctx->d_pair_consts = up.put(tab);
+    build_prog_encrypt_pairs(ctx->prog_enc_pairs, ctx->prog_enc.sched, up);
   }
   ctx->d_n_words = up.put(to_words(n, ctx->lp));
   ctx->d_nb_words = up.put(to_words(Big::sub(n, Big::pow2(64)), ctx->lp));

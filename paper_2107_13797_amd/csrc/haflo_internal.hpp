@@ -61,7 +61,8 @@ enum EngOp : uint32_t {
   ENG_LOAD_W = 13,   // acc = the element's 32-bit-word input a (0 or 1), cut into limbs
   ENG_LOAD_L = 14,   // acc = limbs [a*NL, (a+1)*NL) of the element's limb input
   ENG_LOAD_TD = 15,  // acc = table[(k >> a) & 15]
-  ENG_LOAD_WH = 16   // acc = limbs [NL, 2 NL) of the element's 32-bit-word input a: the part above ENG_LOAD_W's
+  ENG_LOAD_WH = 16,  // acc = limbs [NL, 2 NL) of the element's 32-bit-word input a: the part above ENG_LOAD_W's
+  ENG_LOAD_W1 = 17   // pair engine only: acc = 1 + n w for the element's 32-bit-word input a
 };
 enum { kConstR1 = 0, kConstR2 = 1, kConstR3 = 2, kConstOne = 3, kConstExtra = 4, kNumConst = 5 };
 inline uint32_t eng_ins(uint32_t op, uint32_t a = 0, uint32_t b = 0) { return op | (a << 8) | (b << 20); }
@@ -112,6 +113,9 @@ struct haflo_ctx {
   haflo::ModHost Nw;           // n, at the limb count (and Montgomery radix) of n^2
   haflo::ModHost P2, Q2;       // p^2, q^2 (private)
   haflo::ModHost P, Q;         // p, q (private)
+  haflo::ModHost Nh;           // n at half the limbs of n^2: the modulus of the pair arithmetic modulo n^2
+  uint32_t* d_pair_consts = nullptr;  // R, R^2 and R 2^(29 N.nl) modulo n^2 as pairs (N.nl limbs each), R = 2^(29 Nh.nl)
+  haflo::DevProg prog_enc_pairs;  // encryption with the public key on pairs modulo n
   haflo::DevProg prog_enc;     // encryption: r^n modulo n^2 and the (1 + m n) factor
   haflo::DevProg prog_dec_p;   // decryption branch: c^(p-1) modulo p^2
   haflo::DevProg prog_dec_q;   // decryption branch: c^(q-1) modulo q^2

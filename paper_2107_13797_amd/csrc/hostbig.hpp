@@ -160,6 +160,24 @@ class Big {
     }
     return r;
   }
+  // floor(a / m) by the same shift-and-subtract
+  static Big div(const Big& a, const Big& m) {
+    Big r, q;
+    q.w.assign((a.bits() + 31) / 32, 0);
+    for (size_t i = a.bits(); i-- > 0;) {
+      r = r.shl1();
+      if (a.bit(i)) {
+        if (r.w.empty()) r.w.push_back(1);
+        else r.w[0] |= 1;
+      }
+      if (r >= m) {
+        r = sub(r, m);
+        q.w[i / 32] |= 1u << (i % 32);
+      }
+    }
+    q.trim();
+    return q;
+  }
   static Big gcd(Big a, Big b) {
     if (a.is_zero()) return b;
     if (b.is_zero()) return a;

@@ -185,6 +185,83 @@ __global__ __launch_bounds__(kBlockThreads, 4) void k_engine(ModRef M, Prog P, E
   engine_run<LPT, T, Prog>(M, P, io, count, blockIdx.x, gridDim.x);
 }
 
+// The same engine on residues modulo n^2 held as pairs of residues modulo n (pairmul_core): `M` is the
+// modulus n with half the limbs of n^2, an element of the tables and of the constant arrays is
+// [x0: NL limbs][x1: NL limbs]. Only the instructions an exponentiation needs are understood: ENG_SQ,
+// ENG_MUL_T, ENG_MUL_T_ST, ENG_MUL_C, ENG_LOAD_T, ENG_STORE_T, ENG_LOAD_C, ENG_LOAD_W (the pair (w, 0)) and
+// ENG_LOAD_W1 (the pair (1, w), i.e. 1 + n w). When the program ends, acc must hold X 2^(29 * 2 NL) modulo
+// n^2 for the result X (the program's last product takes care of that factor); it is written to io.out as
+// the canonical integer x0 + n x1 on 2 NL limbs: the format of every other operator.
+template <int LPT, int T, class Prog>
+__device__ __forceinline__ void engine_run_pairs(const ModRef& M, const Prog& P, const EngineIO& io, size_t count,
+                                                 unsigned block, unsigned nblocks) {
+  constexpr int NL = LPT * T;  // limbs of n; an element has 2 NL
+  Grp<T> g;
+  Batch<T> bt(block, nblocks);
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    const bool active = base + bt.gib < count;
+    const size_t item = io.first + base + bt.gib;
+    u32* table = io.tables + bt.slot() * (size_t)io.table_entries * (2 * NL);
+    u32 x0[LPT], x1[LPT];
+    zero_limbs<LPT>(x0);
+    zero_limbs<LPT>(x1);
+#pragma unroll 1
+    for (int pc = 0; pc < P.len; ++pc) {
+      const u32 ins = P.at(pc);
+      const u32 op = ins & 0xFFu, a = (ins >> 8) & 0xFFFu, b = ins >> 20;
+      if (op == ENG_SQ) {
+        pairsqr<LPT, T>(x0, x1, x0, x1, mod.n, mod.n0inv, g);
+      } else if (op == ENG_MUL_T || op == ENG_MUL_T_ST || op == ENG_MUL_C) {
+        const u32* src = op == ENG_MUL_C ? io.constant[a] : table + (size_t)a * (2 * NL);
+        pairmul_mem<LPT, T>(x0, x1, x0, x1, src, mod.n, mod.n0inv, g);
+        if (op == ENG_MUL_T_ST) {
+          store_limbs<LPT, T>(table + (size_t)b * (2 * NL), x0, g);
+          store_limbs<LPT, T>(table + (size_t)b * (2 * NL) + NL, x1, g);
+        }
+      } else if (op == ENG_STORE_T) {
+        store_limbs<LPT, T>(table + (size_t)a * (2 * NL), x0, g);
+        store_limbs<LPT, T>(table + (size_t)a * (2 * NL) + NL, x1, g);
+      } else if (op == ENG_LOAD_T || op == ENG_LOAD_C) {
+        const u32* src = op == ENG_LOAD_C ? io.constant[a] : table + (size_t)a * (2 * NL);
+        load_limbs<LPT, T>(x0, src, g);
+        load_limbs<LPT, T>(x1, src + NL, g);
+      } else if (op == ENG_LOAD_W || op == ENG_LOAD_W1) {
+        u32 w[LPT];
+        if (active) load_words_as_limbs<LPT, T>(w, io.in_words[a] + item * (size_t)io.in_nwords, io.in_nwords, g, 0);
+        else zero_limbs<LPT>(w);
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+          x0[j] = op == ENG_LOAD_W ? w[j] : ((g.k == 0 && j == 0) ? 1u : 0u);
+          x1[j] = op == ENG_LOAD_W ? 0u : w[j];
+        }
+      }
+    }
+    // canonical halves (the second one may exceed 2n by a hair: two conditional subtractions), then the
+    // integer x0 + n x1 as low and high half
+    canonicalise<LPT, T>(x0, mod.n, g);
+    canonicalise<LPT, T>(x1, mod.n, g);
+    canonicalise<LPT, T>(x1, mod.n, g);
+    u32 lo[LPT], hi[LPT];
+    mulwide<LPT, T>(lo, hi, mod.n, x1, g);
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) lo[j] += x0[j];
+    const int carry = resolve<LPT, T>(lo, g);
+    if (g.k == 0) hi[0] += (u32)carry;
+    resolve<LPT, T>(hi, g);
+    if (active) {
+      store_limbs<LPT, T>(io.out + item * (size_t)(2 * NL), lo, g);
+      store_limbs<LPT, T>(io.out + item * (size_t)(2 * NL) + NL, hi, g);
+    }
+  }
+}
+
+template <int LPT, int T, class Prog>
+__global__ __launch_bounds__(kBlockThreads, 4) void k_engine_pairs(ModRef M, Prog P, EngineIO io, size_t count) {
+  engine_run_pairs<LPT, T, Prog>(M, P, io, count, blockIdx.x, gridDim.x);
+}
+
 // Two independent jobs of the same geometry in one launch (the two prime-power
 // branches of decryption): the first `split` blocks run job 0, the rest job 1.
 struct EngineJob {

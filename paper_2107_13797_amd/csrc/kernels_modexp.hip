@@ -245,6 +245,24 @@ BatchSplit split_batch(const haflo_ctx* ctx, size_t count, const ModHost& m) {
   return b;
 }
 
+// The pair engine (residues modulo n^2 as pairs modulo n) for the elements of full passes: `mh` is n at half
+// the limbs of n^2, spread over as many lanes per element as n^2 itself takes (9 limbs per lane).
+template <class Prog>
+int launch_engine_pairs(const ModHost& mh, const LaunchShape& sh, hipStream_t st, const Prog& prog,
+                        const EngineIO& io, size_t count) {
+#define CALL(T) HAFLO_LAUNCH((k_engine_pairs<9, T, Prog>), sh, st, mh.ref(), prog, io, count)
+  if (mh.lpt != 18) return HAFLO_EINVAL;
+  switch (mh.t) {
+    case 1: CALL(2); break;
+    case 2: CALL(4); break;
+    case 4: CALL(8); break;
+    case 8: CALL(16); break;
+    default: return HAFLO_EINVAL;
+  }
+#undef CALL
+  return hip_status(hipGetLastError());
+}
+
 template <class Prog>
 int launch_engine_batch(const haflo_ctx* ctx, const ModHost& m, hipStream_t st, const Prog& prog, EngineIO io,
                         size_t count) {
@@ -342,7 +360,23 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
     io.tables = (u32*)d_workspace;
     io.table_entries = ctx->prog_enc.table_entries;
     ProgPtr prog = {ctx->prog_enc.d_ins, (int)ctx->prog_enc.host.size()};
-    return launch_engine_batch(ctx, m, st, prog, io, count);
+    const BatchSplit b = split_batch(ctx, count, m);
+    if (b.shape.geo != kGeoPlain) return launch_engine(m, b.shape, st, prog, io, count);
+    // a batch that fills the chip: the pair arithmetic modulo n (5/8 of the limb products of a product,
+    // 0.57 of those of a squaring) for the full passes, the engine above for what is left over
+    EngineIO pio = io;
+    pio.constant[kConstR1] = ctx->d_pair_consts;
+    pio.constant[kConstR2] = ctx->d_pair_consts + m.nl;
+    pio.constant[kConstR3] = nullptr;
+    pio.constant[kConstOne] = nullptr;
+    pio.constant[kConstExtra] = ctx->d_pair_consts + 2 * m.nl;
+    pio.table_entries = ctx->prog_enc_pairs.table_entries;
+    ProgPtr pprog = {ctx->prog_enc_pairs.d_ins, (int)ctx->prog_enc_pairs.host.size()};
+    const size_t full = b.full ? b.full : count;
+    int rc = launch_engine_pairs(ctx->Nh, b.shape, st, pprog, pio, full);
+    if (rc != HAFLO_OK || full == count) return rc;
+    io.first = full;
+    return launch_engine(m, b.tail, st, prog, io, count - full);
   }
   // key owner: r^n modulo p^2 and q^2, each as (r^(n mod (s-1)) mod s)^s mod s^2 (a half-length
   // exponent on the quarter-size modulus, then a half-length exponent on the half-size one),

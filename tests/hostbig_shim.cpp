@@ -13,7 +13,7 @@ Big get(const uint8_t* p, size_t n) { return Big::from_bytes_le(p, n); }
 
 extern "C" {
 
-enum { OP_ADD = 0, OP_SUB, OP_MUL, OP_MOD, OP_GCD, OP_POWMOD, OP_INV_POW2, OP_SHL1, OP_SHR1, OP_LOW_BITS, OP_MONTMUL };
+enum { OP_ADD = 0, OP_SUB, OP_MUL, OP_MOD, OP_GCD, OP_POWMOD, OP_INV_POW2, OP_SHL1, OP_SHR1, OP_LOW_BITS, OP_MONTMUL, OP_DIV };
 
 // out (nout bytes, little-endian) = op(a, b, c); k is a small integer argument. Returns the bit
 // length of the result, or -1 for an unknown op.
@@ -32,6 +32,7 @@ long hostbig_op(int op, const uint8_t* a, size_t na, const uint8_t* b, size_t nb
     case OP_SHR1: r = x.shr1(); break;
     case OP_LOW_BITS: r = x.low_bits((size_t)k); break;
     case OP_MONTMUL: r = haflo::MontHost(z).mul(x, y); break;     // x y R^-1 mod z, R = 2^(32 words(z))
+    case OP_DIV: r = Big::div(x, y); break;
     default: return -1;
   }
   r.to_bytes_le(out, nout);

@@ -9,7 +9,7 @@ import pytest
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 OPS = {name: i for i, name in enumerate(
-    ["add", "sub", "mul", "mod", "gcd", "powmod", "inv_pow2", "shl1", "shr1", "low_bits", "montmul"])}
+    ["add", "sub", "mul", "mod", "gcd", "powmod", "inv_pow2", "shl1", "shr1", "low_bits", "montmul", "div"])}
 
 
 @pytest.fixture(scope="module")
@@ -60,6 +60,9 @@ def test_ring_operations(shim, bits):
         a, b = rng.choice(xs), rng.choice(xs)
         assert call(shim, "add", a, b) == a + b
         assert call(shim, "mul", a, b) == a * b
+        if b:
+            assert call(shim, "div", a, b) == a // b and call(shim, "mod", a, b) == a % b
+            assert call(shim, "div", a * b + b - 1, b) == a
         hi, lo = max(a, b), min(a, b)
         assert call(shim, "sub", hi, lo) == hi - lo
         assert shim.hostbig_cmp(_b(a), len(_b(a)), _b(b), len(_b(b))) == (a > b) - (a < b)
