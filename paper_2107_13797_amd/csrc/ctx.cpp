@@ -259,13 +259,65 @@ static void build_prog_encrypt_pairs(DevProg& p, const HostSched& sched, Uploade
   p.d_ins = up.put(p.host);
 }
 
-// x < n^2 as the pair (x mod n, x div n), nl limbs each
+// x < s^2 as the pair (x mod s, x div s), nl limbs each
 static std::vector<uint32_t> pair_limbs(const Big& x, const Big& n, int nl) {
   const Big lo = Big::mod(x, n);
   const Big hi = Big::div(x, n);
   std::vector<uint32_t> v = to_limbs29(lo, nl), h = to_limbs29(hi, nl);
   v.insert(v.end(), h.begin(), h.end());
   return v;
+}
+
+// The constants of the pair arithmetic modulo s^2 for the modulus `ms` = s (ModHost::d_pairs): R .. R^5 and 1
+// in their slots; `special` replaces the slots it names (operator-specific constants).
+static void build_pair_consts(ModHost& ms, const Big& s, const Big& s2,
+                              const std::vector<std::pair<int, Big>>& special, Uploader& up) {
+  std::vector<Big> c(kNumConst);
+  c[kConstR1] = Big::mod(Big::pow2((size_t)kLimbBits * ms.nl), s2);
+  c[kConstR2] = Big::mod(Big::mul(c[kConstR1], c[kConstR1]), s2);
+  c[kConstR3] = Big::mod(Big::mul(c[kConstR2], c[kConstR1]), s2);
+  c[kConstR4] = Big::mod(Big::mul(c[kConstR3], c[kConstR1]), s2);
+  c[kConstR5] = Big::mod(Big::mul(c[kConstR4], c[kConstR1]), s2);
+  c[kConstOne] = Big(1);
+  c[kConstExtra] = Big(1);
+  for (const std::pair<int, Big>& sp : special) c[sp.first] = sp.second;
+  std::vector<uint32_t> tab;
+  for (const Big& b : c) {
+    std::vector<uint32_t> l = pair_limbs(b, s, ms.nl);
+    tab.insert(tab.end(), l.begin(), l.end());
+  }
+  ms.d_pairs = up.put(tab);
+}
+
+// Decryption branch for a prime s on pairs modulo s: the canonical residue c modulo n^2 in four quarters,
+// c = c_0 + c_1 R + c_2 R^2 + c_3 R^3 (R = 2^(29 nl(s))), goes to the pair form of c R modulo s^2 as the sum
+// of the products of (c_k, 0) with R^(k+2), is raised to s - 1 and leaves the Montgomery domain. The result
+// is 1 + s L with L the quotient the decryption needs: the engine stores the second half of the pair.
+static void build_prog_decrypt_pairs(DevProg& p, const HostSched& sched, Uploader& up) {
+  p.sched = sched;
+  p.host.clear();
+  const uint32_t power[4] = {kConstR2, kConstR3, kConstR4, kConstR5};
+  for (uint32_t k = 0; k < 4; ++k) {
+    p.host.push_back(eng_ins(ENG_LOAD_L, k));
+    p.host.push_back(eng_ins(ENG_MUL_C, power[k]));
+    if (k) p.host.push_back(eng_ins(ENG_ADD_T, 0));
+    if (k < 3) p.host.push_back(eng_ins(ENG_STORE_T, 0));
+  }
+  append_modexp(p.host, p.sched);
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstOne));
+  p.table_entries = p.sched.table_len + 1;
+  p.d_ins = up.put(p.host);
+}
+// Key owner's encryption, second stage, on pairs modulo s: y (limb input, below s) to the power s modulo s^2
+static void build_prog_lift_pairs(DevProg& p, const HostSched& sched, Uploader& up) {
+  p.sched = sched;
+  p.host.clear();
+  p.host.push_back(eng_ins(ENG_LOAD_L, 0));
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstR2));
+  append_modexp(p.host, p.sched);
+  p.host.push_back(eng_ins(ENG_MUL_C, kConstOne));
+  p.table_entries = p.sched.table_len + 1;
+  p.d_ins = up.put(p.host);
 }
 
 // Key owner's encryption, one prime-power branch in two stages. With n = s t (s, t the primes,
@@ -358,16 +410,21 @@ static int ctx_build(haflo_ctx* ctx, const Big& n, const Big* p, const Big* q, u
     // pair arithmetic modulo n^2: n at half the limbs, and the constants of the pair engine
     const int nl_h = nl_n2 / 2;
     build_modulus(ctx->Nh, n, nl_h, up);
-    const Big R = Big::pow2((size_t)kLimbBits * nl_h), RN = Big::pow2((size_t)kLimbBits * nl_n2);
-    const Big r1 = Big::mod(R, ctx->nsq);
-    const Big r2 = Big::mod(Big::mul(r1, r1), ctx->nsq);
-    const Big rx = Big::mod(Big::mul(r1, Big::mod(RN, ctx->nsq)), ctx->nsq);
-    std::vector<uint32_t> tab;
-    for (const Big* b : {&r1, &r2, &rx}) {
-      std::vector<uint32_t> l = pair_limbs(*b, n, nl_h);
-      tab.insert(tab.end(), l.begin(), l.end());
-    }
-    ctx->d_pair_consts = up.put(tab);
+    const Big R = Big::mod(Big::pow2((size_t)kLimbBits * nl_h), ctx->nsq);
+    const Big RN = Big::mod(Big::pow2((size_t)kLimbBits * nl_n2), ctx->nsq);
+    // 1 / R_N modulo n^2: ((n^2 + 1) / 2)^(29 N.nl)
+    MontHost mn2(ctx->nsq);
+    const Big half = Big::add(ctx->nsq, Big(1)).shr1();
+    const Big rn_inv = mn2.powmod(half, Big((uint64_t)kLimbBits * (uint64_t)nl_n2));
+    const Big r2 = Big::mod(Big::mul(R, R), ctx->nsq), r3 = Big::mod(Big::mul(r2, R), ctx->nsq);
+    // out of the pair form: times R R_N from a plain pair, times R_N from a pair in Montgomery form; into it
+    // from a stored ciphertext W = w_lo + R w_hi (= c R_N): w_lo times R^2 / R_N plus w_hi times R^3 / R_N
+    build_pair_consts(ctx->Nh, n, ctx->nsq,
+                      {{kConstExtra, Big::mod(Big::mul(R, RN), ctx->nsq)},
+                       {kConstR3, RN},
+                       {kConstR4, Big::mod(Big::mul(r2, rn_inv), ctx->nsq)},
+                       {kConstR5, Big::mod(Big::mul(r3, rn_inv), ctx->nsq)}},
+                      up);
     build_prog_encrypt_pairs(ctx->prog_enc_pairs, ctx->prog_enc.sched, up);
   }
   ctx->d_n_words = up.put(to_words(n, ctx->lp));
@@ -385,6 +442,10 @@ static int ctx_build(haflo_ctx* ctx, const Big& n, const Big* p, const Big* q, u
     if (!up.ok) return HAFLO_ENOMEM;
     build_prog_decrypt(ctx->prog_dec_p, Big::sub(*p, Big(1)), up);
     build_prog_decrypt(ctx->prog_dec_q, Big::sub(*q, Big(1)), up);
+    build_pair_consts(ctx->P, *p, ctx->P2.mod, {}, up);
+    build_pair_consts(ctx->Q, *q, ctx->Q2.mod, {}, up);
+    build_prog_decrypt_pairs(ctx->prog_dec_pairs_p, ctx->prog_dec_p.sched, up);
+    build_prog_decrypt_pairs(ctx->prog_dec_pairs_q, ctx->prog_dec_q.sched, up);
     {
       Big pm1 = Big::sub(*p, Big(1)), qm1 = Big::sub(*q, Big(1));
       Big ordq = Big::mul(*q, qm1);  // |(Z/q^2)*|
@@ -392,6 +453,8 @@ static int ctx_build(haflo_ctx* ctx, const Big& n, const Big* p, const Big* q, u
       build_prog_encrypt_low(ctx->prog_enc_q, Big::mod(n, qm1), up);
       build_prog_encrypt_lift(ctx->prog_lift_p, *p, up);
       build_prog_encrypt_lift(ctx->prog_lift_q, *q, up);
+      build_prog_lift_pairs(ctx->prog_lift_pairs_p, ctx->prog_lift_p.sched, up);
+      build_prog_lift_pairs(ctx->prog_lift_pairs_q, ctx->prog_lift_q.sched, up);
       // (p^2)^-1 mod q^2 = (p^2)^(q(q-1)-1) mod q^2 (p is a unit there), kept in Montgomery form
       const Big& q2 = ctx->Q2.mod;
       MontHost mq2(q2);

@@ -64,7 +64,7 @@ enum EngOp : uint32_t {
   ENG_LOAD_WH = 16,  // acc = limbs [NL, 2 NL) of the element's 32-bit-word input a: the part above ENG_LOAD_W's
   ENG_LOAD_W1 = 17   // pair engine only: acc = 1 + n w for the element's 32-bit-word input a
 };
-enum { kConstR1 = 0, kConstR2 = 1, kConstR3 = 2, kConstOne = 3, kConstExtra = 4, kNumConst = 5 };
+enum { kConstR1 = 0, kConstR2 = 1, kConstR3 = 2, kConstOne = 3, kConstExtra = 4, kConstR4 = 5, kConstR5 = 6, kNumConst = 7 };
 inline uint32_t eng_ins(uint32_t op, uint32_t a = 0, uint32_t b = 0) { return op | (a << 8) | (b << 20); }
 
 // acc = acc^e for the plan `h`, using table slots [0, h.table_len] (the last one as scratch)
@@ -86,6 +86,10 @@ struct ModHost {
   int t = 0;    // lanes per big integer
   uint32_t n0inv = 0;
   uint32_t* d_tab = nullptr;  // device: n | r1 | r2 | r3 | one, nl limbs each
+  // Pair arithmetic modulo mod^2 (residues x0 + mod x1, see pairmul_core): kNumConst constants of 2 nl limbs
+  // each, [x0 | x1], indexed by kConst*: R, R^2, R^3, 1, an operator-specific one, R^4, R^5, all modulo
+  // mod^2 with R = 2^(29 nl). Null where the modulus is not used that way.
+  uint32_t* d_pairs = nullptr;
   ModRef ref() const {
     ModRef r;
     r.n = d_tab;
@@ -113,9 +117,13 @@ struct haflo_ctx {
   haflo::ModHost Nw;           // n, at the limb count (and Montgomery radix) of n^2
   haflo::ModHost P2, Q2;       // p^2, q^2 (private)
   haflo::ModHost P, Q;         // p, q (private)
-  haflo::ModHost Nh;           // n at half the limbs of n^2: the modulus of the pair arithmetic modulo n^2
-  uint32_t* d_pair_consts = nullptr;  // R, R^2 and R 2^(29 N.nl) modulo n^2 as pairs (N.nl limbs each), R = 2^(29 Nh.nl)
-  haflo::DevProg prog_enc_pairs;  // encryption with the public key on pairs modulo n
+  // n at half the limbs of n^2: the modulus of the pair arithmetic modulo n^2. Its operator-specific pair
+  // constants: [kConstExtra] R R_N, [kConstR3] R_N, [kConstR4] R^2 / R_N, [kConstR5] R^3 / R_N (R_N = 2^(29 N.nl),
+  // the radix of the stored ciphertexts): out of and into the pair form
+  haflo::ModHost Nh;
+  haflo::DevProg prog_enc_pairs;   // encryption with the public key on pairs modulo n
+  haflo::DevProg prog_dec_pairs_p, prog_dec_pairs_q;    // decryption branches on pairs modulo p, q
+  haflo::DevProg prog_lift_pairs_p, prog_lift_pairs_q;  // key owner's encryption, second stage, on pairs modulo p, q
   haflo::DevProg prog_enc;     // encryption: r^n modulo n^2 and the (1 + m n) factor
   haflo::DevProg prog_dec_p;   // decryption branch: c^(p-1) modulo p^2
   haflo::DevProg prog_dec_q;   // decryption branch: c^(q-1) modulo q^2

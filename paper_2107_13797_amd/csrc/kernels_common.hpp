@@ -96,6 +96,7 @@ struct EngineIO {
   int table_entries;
   int table_per_item;              // 1: slot = element index (tables are an output), 0: slot = lane group
   size_t first;                    // index of the launch's first element in the per-element arrays
+  int out_mode;                    // pair engine: what is stored, see kOut*
 };
 
 // The exponentiation engine: every lane group runs the batch-uniform program
@@ -185,17 +186,18 @@ __global__ __launch_bounds__(kBlockThreads, 4) void k_engine(ModRef M, Prog P, E
   engine_run<LPT, T, Prog>(M, P, io, count, blockIdx.x, gridDim.x);
 }
 
-// The same engine on residues modulo n^2 held as pairs of residues modulo n (pairmul_core): `M` is the
-// modulus n with half the limbs of n^2, an element of the tables and of the constant arrays is
-// [x0: NL limbs][x1: NL limbs]. Only the instructions an exponentiation needs are understood: ENG_SQ,
-// ENG_MUL_T, ENG_MUL_T_ST, ENG_MUL_C, ENG_LOAD_T, ENG_STORE_T, ENG_LOAD_C, ENG_LOAD_W (the pair (w, 0)) and
-// ENG_LOAD_W1 (the pair (1, w), i.e. 1 + n w). When the program ends, acc must hold X 2^(29 * 2 NL) modulo
-// n^2 for the result X (the program's last product takes care of that factor); it is written to io.out as
-// the canonical integer x0 + n x1 on 2 NL limbs: the format of every other operator.
+// The same engine on residues modulo s^2 held as pairs of residues modulo s (pairmul_core): `M` is the
+// modulus s with half the limbs of s^2; an element of the tables and of the constant arrays is
+// [x0: NL limbs][x1: NL limbs]. Instructions as above, with these readings: ENG_LOAD_W is the pair (w, 0),
+// ENG_LOAD_W1 the pair (1, w), i.e. 1 + s w; ENG_LOAD_L a takes limbs [a NL, (a + 1) NL) of the element's
+// limb input as (l, 0). When the program ends, acc holds the result X as a pair; io.out_mode says what is
+// stored: kOutInteger, the canonical integer x0 + s x1 on 2 NL limbs (low half, high half); kOutSecond, the
+// canonical x1 on NL limbs, for results that are 1 modulo s (x0 = 1), whose (X - 1) / s it is.
+enum { kOutInteger = 0, kOutSecond = 1 };
 template <int LPT, int T, class Prog>
 __device__ __forceinline__ void engine_run_pairs(const ModRef& M, const Prog& P, const EngineIO& io, size_t count,
                                                  unsigned block, unsigned nblocks) {
-  constexpr int NL = LPT * T;  // limbs of n; an element has 2 NL
+  constexpr int NL = LPT * T;  // limbs of s; an element has 2 NL
   Grp<T> g;
   Batch<T> bt(block, nblocks);
   ModRegs<LPT> mod;
@@ -204,6 +206,7 @@ __device__ __forceinline__ void engine_run_pairs(const ModRef& M, const Prog& P,
     const bool active = base + bt.gib < count;
     const size_t item = io.first + base + bt.gib;
     u32* table = io.tables + bt.slot() * (size_t)io.table_entries * (2 * NL);
+    const u64 k = (io.k64 && active) ? io.k64[item] : 0ull;
     u32 x0[LPT], x1[LPT];
     zero_limbs<LPT>(x0);
     zero_limbs<LPT>(x1);
@@ -213,8 +216,10 @@ __device__ __forceinline__ void engine_run_pairs(const ModRef& M, const Prog& P,
       const u32 op = ins & 0xFFu, a = (ins >> 8) & 0xFFFu, b = ins >> 20;
       if (op == ENG_SQ) {
         pairsqr<LPT, T>(x0, x1, x0, x1, mod.n, mod.n0inv, g);
-      } else if (op == ENG_MUL_T || op == ENG_MUL_T_ST || op == ENG_MUL_C) {
-        const u32* src = op == ENG_MUL_C ? io.constant[a] : table + (size_t)a * (2 * NL);
+      } else if (op == ENG_MUL_T || op == ENG_MUL_T_ST || op == ENG_MUL_C || op == ENG_MUL_TD) {
+        const u32* src;
+        if (op == ENG_MUL_C) src = io.constant[a];
+        else src = table + (size_t)(op == ENG_MUL_TD ? (u32)(k >> a) & 15u : a) * (2 * NL);
         pairmul_mem<LPT, T>(x0, x1, x0, x1, src, mod.n, mod.n0inv, g);
         if (op == ENG_MUL_T_ST) {
           store_limbs<LPT, T>(table + (size_t)b * (2 * NL), x0, g);
@@ -223,10 +228,28 @@ __device__ __forceinline__ void engine_run_pairs(const ModRef& M, const Prog& P,
       } else if (op == ENG_STORE_T) {
         store_limbs<LPT, T>(table + (size_t)a * (2 * NL), x0, g);
         store_limbs<LPT, T>(table + (size_t)a * (2 * NL) + NL, x1, g);
-      } else if (op == ENG_LOAD_T || op == ENG_LOAD_C) {
-        const u32* src = op == ENG_LOAD_C ? io.constant[a] : table + (size_t)a * (2 * NL);
-        load_limbs<LPT, T>(x0, src, g);
-        load_limbs<LPT, T>(x1, src + NL, g);
+      } else if (op == ENG_LOAD_T || op == ENG_LOAD_C || op == ENG_LOAD_TD || op == ENG_ADD_T || op == ENG_ADD_C) {
+        const u32* src;
+        if (op == ENG_LOAD_C || op == ENG_ADD_C) src = io.constant[a];
+        else src = table + (size_t)(op == ENG_LOAD_TD ? (u32)(k >> a) & 15u : a) * (2 * NL);
+        u32 t0[LPT], t1[LPT];
+        load_limbs<LPT, T>(t0, src, g);
+        load_limbs<LPT, T>(t1, src + NL, g);
+        if (op == ENG_ADD_T || op == ENG_ADD_C) {
+#pragma unroll
+          for (int j = 0; j < LPT; ++j) {
+            x0[j] += t0[j];
+            x1[j] += t1[j];
+          }
+          partial_norm<LPT, T>(x0, g);
+          partial_norm<LPT, T>(x1, g);
+        } else {
+#pragma unroll
+          for (int j = 0; j < LPT; ++j) {
+            x0[j] = t0[j];
+            x1[j] = t1[j];
+          }
+        }
       } else if (op == ENG_LOAD_W || op == ENG_LOAD_W1) {
         u32 w[LPT];
         if (active) load_words_as_limbs<LPT, T>(w, io.in_words[a] + item * (size_t)io.in_nwords, io.in_nwords, g, 0);
@@ -236,23 +259,44 @@ __device__ __forceinline__ void engine_run_pairs(const ModRef& M, const Prog& P,
           x0[j] = op == ENG_LOAD_W ? w[j] : ((g.k == 0 && j == 0) ? 1u : 0u);
           x1[j] = op == ENG_LOAD_W ? 0u : w[j];
         }
+      } else if (op == ENG_LOAD_L) {
+        const u32* src = io.in_limbs + item * (size_t)io.in_limbs_stride + (size_t)a * NL;
+        if (!active) zero_limbs<LPT>(x0);
+        else if (io.in_limbs_valid) load_limbs_below<LPT, T>(x0, src, io.in_limbs_valid - (int)a * NL, g);
+        else load_limbs<LPT, T>(x0, src, g);
+        zero_limbs<LPT>(x1);
       }
     }
-    // canonical halves (the second one may exceed 2n by a hair: two conditional subtractions), then the
-    // integer x0 + n x1 as low and high half
-    canonicalise<LPT, T>(x0, mod.n, g);
-    canonicalise<LPT, T>(x1, mod.n, g);
-    canonicalise<LPT, T>(x1, mod.n, g);
-    u32 lo[LPT], hi[LPT];
-    mulwide<LPT, T>(lo, hi, mod.n, x1, g);
+    // Canonical pair: x0 below s with what it exceeded s by carried into x1 (the value is x0 + s x1), then x1
+    // below s (it may exceed 2s by a hair after a product, or by more after the carry: two subtractions)
+    {
+      resolve<LPT, T>(x0, g);
+      s32 d[LPT];
 #pragma unroll
-    for (int j = 0; j < LPT; ++j) lo[j] += x0[j];
-    const int carry = resolve<LPT, T>(lo, g);
-    if (g.k == 0) hi[0] += (u32)carry;
-    resolve<LPT, T>(hi, g);
-    if (active) {
-      store_limbs<LPT, T>(io.out + item * (size_t)(2 * NL), lo, g);
-      store_limbs<LPT, T>(io.out + item * (size_t)(2 * NL) + NL, hi, g);
+      for (int j = 0; j < LPT; ++j) d[j] = (s32)x0[j] - (s32)mod.n[j];
+      const int top = resolve<LPT, T>(d, g);
+      if (top >= 0) {
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) x0[j] = (u32)d[j];
+        if (g.k == 0) x1[0] += 1u;
+      }
+    }
+    canonicalise<LPT, T>(x1, mod.n, g);
+    canonicalise<LPT, T>(x1, mod.n, g);
+    if (io.out_mode == kOutSecond) {
+      if (active) store_limbs<LPT, T>(io.out + item * (size_t)NL, x1, g);
+    } else {
+      u32 lo[LPT], hi[LPT];
+      mulwide<LPT, T>(lo, hi, mod.n, x1, g);
+#pragma unroll
+      for (int j = 0; j < LPT; ++j) lo[j] += x0[j];
+      const int carry = resolve<LPT, T>(lo, g);
+      if (g.k == 0) hi[0] += (u32)carry;
+      resolve<LPT, T>(hi, g);
+      if (active) {
+        store_limbs<LPT, T>(io.out + item * (size_t)(2 * NL), lo, g);
+        store_limbs<LPT, T>(io.out + item * (size_t)(2 * NL) + NL, hi, g);
+      }
     }
   }
 }
@@ -274,6 +318,14 @@ __global__ __launch_bounds__(kBlockThreads, 4) void k_engine_pair(EngineJob j0, 
                                                                   size_t count) {
   if (blockIdx.x < split) engine_run<LPT, T, ProgPtr>(j0.M, j0.P, j0.io, count, blockIdx.x, split);
   else engine_run<LPT, T, ProgPtr>(j1.M, j1.P, j1.io, count, blockIdx.x - split, gridDim.x - split);
+}
+
+// the same for the pair engine
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads, 4) void k_engine_pairs2(EngineJob j0, EngineJob j1, unsigned split,
+                                                                    size_t count) {
+  if (blockIdx.x < split) engine_run_pairs<LPT, T, ProgPtr>(j0.M, j0.P, j0.io, count, blockIdx.x, split);
+  else engine_run_pairs<LPT, T, ProgPtr>(j1.M, j1.P, j1.io, count, blockIdx.x - split, gridDim.x - split);
 }
 
 }  // namespace dev

@@ -50,22 +50,25 @@ __global__ __launch_bounds__(kBlockThreads) void k_dec_unmont(ModRef M, const u3
 
 // m_s = L_s(y) * h_s mod s for y = c^(s-1) mod s^2 (canonical, 2*NL limbs of
 // which only the low NL matter): L_s(y) = (y - 1)/s is an exact quotient below
-// s < 2^(29 NL), so it equals (y - 1) * s^-1 modulo 2^(29 NL).
+// s < 2^(29 NL), so it equals (y - 1) * s^-1 modulo 2^(29 NL). With `quotient` set,
+// ylow already holds L_s(y) (NL canonical limbs).
 template <int LPT, int T>
-__device__ __forceinline__ void crt_branch(u32 (&ms)[LPT], const u32* ylow, bool active, const ModRegs<LPT>& mod,
-                                           const u32* sinv, const u32* hsR, const Grp<T>& g) {
+__device__ __forceinline__ void crt_branch(u32 (&ms)[LPT], const u32* ylow, bool active, int quotient,
+                                           const ModRegs<LPT>& mod, const u32* sinv, const u32* hsR, const Grp<T>& g) {
   u32 x[LPT], t[LPT];
   if (active) load_limbs<LPT, T>(x, ylow, g);
   else zero_limbs<LPT>(x);
-  s32 d[LPT];
+  if (!quotient) {  // uniform over the launch
+    s32 d[LPT];
 #pragma unroll
-  for (int j = 0; j < LPT; ++j) d[j] = (s32)x[j];
-  if (g.k == 0) d[0] -= 1;
-  resolve<LPT, T>(d, g);  // modulo 2^(29 NL): a borrow out of the top is dropped
+    for (int j = 0; j < LPT; ++j) d[j] = (s32)x[j];
+    if (g.k == 0) d[0] -= 1;
+    resolve<LPT, T>(d, g);  // modulo 2^(29 NL): a borrow out of the top is dropped
 #pragma unroll
-  for (int j = 0; j < LPT; ++j) x[j] = (u32)d[j];
-  load_limbs<LPT, T>(t, sinv, g);
-  mullo<LPT, T>(x, x, t, g);
+    for (int j = 0; j < LPT; ++j) x[j] = (u32)d[j];
+    load_limbs<LPT, T>(t, sinv, g);
+    mullo<LPT, T>(x, x, t, g);
+  }
   load_limbs<LPT, T>(t, hsR, g);
   montmul<LPT, T>(ms, x, t, mod.n, mod.n0inv, g);
   canonicalise<LPT, T>(ms, mod.n, g);
@@ -78,7 +81,8 @@ __global__ __launch_bounds__(kBlockThreads) void k_dec_crt(ModRef MP, ModRef MQ,
                                                            const u32* __restrict__ qinv2, const u32* __restrict__ hpR,
                                                            const u32* __restrict__ hqR, const u32* __restrict__ pinvqR,
                                                            const u32* __restrict__ yp, const u32* __restrict__ yq,
-                                                           u32* __restrict__ plain, int lp, size_t count) {
+                                                           int quotients, u32* __restrict__ plain, int lp,
+                                                           size_t count) {
   constexpr int NL = LPT * T;
   __shared__ u32 stage[kBlockThreads * LPT * 2];
   Grp<T> g;
@@ -90,8 +94,9 @@ __global__ __launch_bounds__(kBlockThreads) void k_dec_crt(ModRef MP, ModRef MQ,
     size_t item = base + bt.gib;
     bool active = item < count;
     u32 a[LPT], b[LPT], t[LPT], u[LPT];
-    crt_branch<LPT, T>(a, yp + item * (size_t)(2 * NL), active, mp, pinv2, hpR, g);  // m_p
-    crt_branch<LPT, T>(b, yq + item * (size_t)(2 * NL), active, mq, qinv2, hqR, g);  // m_q
+    const size_t ystride = quotients ? NL : 2 * NL;
+    crt_branch<LPT, T>(a, yp + item * ystride, active, quotients, mp, pinv2, hpR, g);  // m_p
+    crt_branch<LPT, T>(b, yq + item * ystride, active, quotients, mq, qinv2, hqR, g);  // m_q
     // (m_q - m_p) mod q; m_p < p < 2q so one conditional subtraction reduces it
 #pragma unroll
     for (int j = 0; j < LPT; ++j) t[j] = a[j];
@@ -245,6 +250,33 @@ BatchSplit split_batch(const haflo_ctx* ctx, size_t count, const ModHost& m) {
   return b;
 }
 
+// `io` with the constants of the pair arithmetic modulo ms^2 in place of those of the plain engine
+EngineIO pair_io(const ModHost& ms, EngineIO io) {
+  for (int i = 0; i < kNumConst; ++i) io.constant[i] = ms.d_pairs + (size_t)i * 2 * ms.nl;
+  io.out_mode = kOutInteger;
+  return io;
+}
+
+// Two jobs of the pair engine in one launch (moduli p and q, 9 limbs per lane)
+int launch_engine_pairs2(const ModHost& mh, const LaunchShape& sh, hipStream_t st, const EngineJob& j0,
+                         const EngineJob& j1, unsigned split, size_t count) {
+#define CALL(T) HAFLO_LAUNCH((k_engine_pairs2<9, T>), sh, st, j0, j1, split, count)
+  if (mh.lpt == 9 && mh.t == 1) {
+    CALL(1);
+    return hip_status(hipGetLastError());
+  }
+  if (mh.lpt != 18) return HAFLO_EINVAL;
+  switch (mh.t) {
+    case 1: CALL(2); break;
+    case 2: CALL(4); break;
+    case 4: CALL(8); break;
+    case 8: CALL(16); break;
+    default: return HAFLO_EINVAL;
+  }
+#undef CALL
+  return hip_status(hipGetLastError());
+}
+
 // The pair engine (residues modulo n^2 as pairs modulo n) for the elements of full passes: `mh` is n at half
 // the limbs of n^2, spread over as many lanes per element as n^2 itself takes (9 limbs per lane).
 template <class Prog>
@@ -272,6 +304,32 @@ int launch_engine_batch(const haflo_ctx* ctx, const ModHost& m, hipStream_t st, 
   if (rc != HAFLO_OK) return rc;
   io.first = b.full;  // the table slots are free again once the first launch has finished (stream order)
   return launch_engine(m, b.tail, st, prog, io, count - b.full);
+}
+
+// A power of stored ciphertexts (`prog` begins with ENG_LOAD_L 0 and leaves the power in Montgomery form):
+// the full passes of a batch that fills the chip run the same program on pairs modulo n, with the element
+// taken into the pair form first and out of it at the end; what is left over runs as it is.
+int launch_power_batch(const haflo_ctx* ctx, hipStream_t st, const ProgInline& pi, const std::vector<uint32_t>& prog,
+                       EngineIO io, size_t count) {
+  const ModHost& m = ctx->N;
+  const BatchSplit b = split_batch(ctx, count, m);
+  std::vector<uint32_t> pp;
+  pp.push_back(eng_ins(ENG_LOAD_L, 1));
+  pp.push_back(eng_ins(ENG_MUL_C, kConstR5));
+  pp.push_back(eng_ins(ENG_STORE_T, 0));
+  pp.push_back(eng_ins(ENG_LOAD_L, 0));
+  pp.push_back(eng_ins(ENG_MUL_C, kConstR4));
+  pp.push_back(eng_ins(ENG_ADD_T, 0));
+  pp.insert(pp.end(), prog.begin() + 1, prog.end());
+  pp.push_back(eng_ins(ENG_MUL_C, kConstR3));
+  ProgInline ppi;
+  if (b.shape.geo != kGeoPlain || prog.empty() || prog[0] != eng_ins(ENG_LOAD_L, 0) || !to_inline(ppi, pp))
+    return launch_engine_batch(ctx, m, st, pi, io, count);
+  const size_t full = b.full ? b.full : count;
+  int rc = launch_engine_pairs(ctx->Nh, b.shape, st, ppi, pair_io(ctx->Nh, io), full);
+  if (rc != HAFLO_OK || full == count) return rc;
+  io.first = full;
+  return launch_engine(m, b.tail, st, pi, io, count - full);
 }
 
 }  // namespace
@@ -364,12 +422,7 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
     if (b.shape.geo != kGeoPlain) return launch_engine(m, b.shape, st, prog, io, count);
     // a batch that fills the chip: the pair arithmetic modulo n (5/8 of the limb products of a product,
     // 0.57 of those of a squaring) for the full passes, the engine above for what is left over
-    EngineIO pio = io;
-    pio.constant[kConstR1] = ctx->d_pair_consts;
-    pio.constant[kConstR2] = ctx->d_pair_consts + m.nl;
-    pio.constant[kConstR3] = nullptr;
-    pio.constant[kConstOne] = nullptr;
-    pio.constant[kConstExtra] = ctx->d_pair_consts + 2 * m.nl;
+    EngineIO pio = pair_io(ctx->Nh, io);
     pio.table_entries = ctx->prog_enc_pairs.table_entries;
     ProgPtr pprog = {ctx->prog_enc_pairs.d_ins, (int)ctx->prog_enc_pairs.host.size()};
     const size_t full = b.full ? b.full : count;
@@ -416,6 +469,20 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
     }
     const unsigned split = (unsigned)sh.blocks;
     sh.blocks *= 2;
+    if (stage == 1 && sh.geo == kGeoPlain) {
+      // a batch that fills the chip: the second stage on pairs modulo the primes (same result, the canonical
+      // integer modulo the prime's square, from about 0.6 of the limb products)
+      for (int side = 0; side < 2; ++side) {
+        const ModHost& ms = side ? ctx->Q : ctx->P;
+        const DevProg& dp = side ? ctx->prog_lift_pairs_q : ctx->prog_lift_pairs_p;
+        job[side].M = ms.ref();
+        job[side].P = ProgPtr{dp.d_ins, (int)dp.host.size()};
+        job[side].io = pair_io(ms, job[side].io);
+      }
+      int rc = launch_engine_pairs2(ctx->P, sh, st, job[0], job[1], split, count);
+      if (rc != HAFLO_OK) return rc;
+      continue;
+    }
 #define CALL(LPT, T) HAFLO_LAUNCH((k_engine_pair<LPT, T>), sh, st, job[0], job[1], split, count)
     if (sh.geo == kGeoWave) { HAFLO_DISPATCH_GEOMETRY_WAVE(geo, CALL); }
     else if (sh.geo == kGeoWide) { HAFLO_DISPATCH_GEOMETRY_WIDE(geo, CALL); }
@@ -507,7 +574,7 @@ int haflo_scalar_mul_u64(const haflo_ctx* ctx, const void* d_c, const uint64_t* 
   io.out = (u32*)d_out;
   io.tables = (u32*)d_workspace;
   io.table_entries = 16;
-  return launch_engine_batch(ctx, m, (hipStream_t)stream, pi, io, count);
+  return launch_power_batch(ctx, (hipStream_t)stream, pi, prog, io, count);
 }
 
 int haflo_scalar_mul_i64_bcast(const haflo_ctx* ctx, const void* d_c, int64_t k, void* d_out, size_t count,
@@ -537,7 +604,7 @@ int haflo_scalar_mul_i64_bcast(const haflo_ctx* ctx, const void* d_c, int64_t k,
   io.out = (u32*)d_out;
   io.tables = (u32*)d_workspace;
   io.table_entries = plan.table_len + 1;
-  return launch_engine_batch(ctx, m, st, pi, io, count);
+  return launch_power_batch(ctx, st, pi, prog, io, count);
 }
 
 int haflo_decrypt(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain, size_t count, void* d_workspace,
@@ -571,6 +638,7 @@ int haflo_decrypt_static(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d
 namespace {
 int decrypt_launches(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_plain, size_t count, void* d_workspace,
                      hipStream_t st) {
+  int pairs = 0;  // the branch results are the quotients L_s on P.nl limbs, not residues modulo s^2
   u32* canon29 = (u32*)d_workspace;
   u32* yp = canon29 + count * (size_t)ctx->N.nl;
   u32* yq = yp + count * (size_t)ctx->P2.nl;
@@ -603,18 +671,35 @@ int decrypt_launches(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_pla
     }
     const unsigned split = (unsigned)sh.blocks;
     sh.blocks *= 2;
+    if (sh.geo == kGeoPlain) {
+      // a batch that fills the chip: both branches on pairs modulo the primes; what comes out is the second
+      // half of the pair 1 + s L, the quotient L_s itself
+      for (int side = 0; side < 2; ++side) {
+        const ModHost& ms = side ? ctx->Q : ctx->P;
+        const DevProg& dp = side ? ctx->prog_dec_pairs_q : ctx->prog_dec_pairs_p;
+        job[side].M = ms.ref();
+        job[side].P = ProgPtr{dp.d_ins, (int)dp.host.size()};
+        job[side].io = pair_io(ms, job[side].io);
+        job[side].io.in_limbs_stride = ctx->N.nl;
+        job[side].io.out_mode = kOutSecond;
+      }
+      pairs = 1;
+      int rc = launch_engine_pairs2(ctx->P, sh, st, job[0], job[1], split, count);
+      if (rc != HAFLO_OK) return rc;
+    } else {
 #define CALL(LPT, T) HAFLO_LAUNCH((k_engine_pair<LPT, T>), sh, st, job[0], job[1], split, count)
-    if (sh.geo == kGeoWave) { HAFLO_DISPATCH_GEOMETRY_WAVE(m, CALL); }
-    else if (sh.geo == kGeoWide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); }
-    else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
+      if (sh.geo == kGeoWave) { HAFLO_DISPATCH_GEOMETRY_WAVE(m, CALL); }
+      else if (sh.geo == kGeoWide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); }
+      else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
 #undef CALL
+    }
   }
   {
     const ModHost& m = ctx->P;
     const LaunchShape sh = launch_shape(ctx, count, m.t, 8);
 #define CALL(LPT, T)                                                                                            \
   HAFLO_LAUNCH((k_dec_crt<LPT, T>), sh, st, ctx->P.ref(), ctx->Q.ref(), ctx->d_pinv, ctx->d_qinv, ctx->d_hp,    \
-               ctx->d_hq, ctx->d_pinvq, (const u32*)yp, (const u32*)yq, d_plain, ctx->lp, count)
+               ctx->d_hq, ctx->d_pinvq, (const u32*)yp, (const u32*)yq, pairs, d_plain, ctx->lp, count)
     HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
   }
