@@ -229,6 +229,7 @@ def main():
     mm, limbs = api.haflo_op_cost(pub, _cabi.OP_ENCRYPT)
     algo_mad = B * mm * montmul_mul32(limbs)
     achieved = algo_mad / (enc_ms * 1e-3)
+    executed = B * api.haflo_op_work(pub, _cabi.OP_ENCRYPT) / (enc_ms * 1e-3)
 
     # outside the timed steps: the key owner's encryption of the same batch (r^n through p^2 and
     # q^2, bit-identical ciphertexts), reported next to the headline, never inside it
@@ -277,8 +278,15 @@ def main():
                      "traffic_unit": "bytes per launch",
                      "traffic_source": "%s (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE on this launch shape); "
                                        "not measured in this run" % TRAFFIC_PROFILE,
-                     "squarings": "counted as general products; the kernel's squaring forms 10 of 18 limb "
-                                  "products per step",
+                     "accounting": "achieved counts every product of the exponentiation schedule as a word-serial "
+                                   "Montgomery product on 32-bit limbs, 2 L^2 + L multiply-adds, squarings included; the "
+                                   "kernel needs fewer: it works modulo n^2 on pairs of half-length residues (5/8 of the "
+                                   "limb products of a product, 0.57 of a squaring's) in 29-bit limbs",
+                     "executed": executed / 1e12,
+                     "frac_executed": executed / PEAK_MAD32_PER_S,
+                     "executed_note": "v_mad_u64_u32 the kernel really issues per second, in 10^12, and their share of "
+                                      "the same peak; a stream of nothing but this instruction sustains 0.69 of that "
+                                      "peak at the kernel's four wavefronts per SIMD (profiles/peak_microbench.md)",
                      "algorithmic": "%d Montgomery products x (2*%d^2+%d) mul32 per encryption" % (mm, limbs, limbs)},
     }
     if not args.no_cpu:

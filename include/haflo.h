@@ -142,6 +142,14 @@ int haflo_ctx_set_xtd_bucket_min_rows(haflo_ctx* ctx, size_t min_rows);
  * of p^2). Either output may be NULL. */
 int haflo_op_cost(const haflo_ctx* ctx, int op, uint64_t* montmuls, uint32_t* modulus_limbs);
 
+/* The multiply-adds (32x32+64-bit, on 29-bit limbs) the kernels really execute
+ * for one element of an operator on the path a chip-filling batch takes, all
+ * lanes together: the squarings leave out the symmetric half of their limb
+ * products and the arithmetic modulo n^2 (p^2, q^2) runs on pairs of half-length
+ * residues, so this is well below haflo_op_cost's products times (2 L^2 + L).
+ * Defined for HAFLO_OP_ENCRYPT on a public context and HAFLO_OP_DECRYPT. */
+int haflo_op_work(const haflo_ctx* ctx, int op, uint64_t* mads_executed);
+
 /* Workspace needed by an operator call of the given shape. For element-wise
  * operators `rows` is the element count and `cols` is ignored; for the matvecs
  * they are the matrix shape. Returns 0 for operators that need none and

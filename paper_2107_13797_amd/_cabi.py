@@ -23,6 +23,7 @@ PROTOTYPES = {
                                C.POINTER(c_size_t), C.POINTER(c_size_t)]),
     "haflo_ctx_set_xtd_bucket_min_rows": (c_int, [c_void_p, c_size_t]),
     "haflo_op_cost": (c_int, [c_void_p, c_int, C.POINTER(c_u64), C.POINTER(c_u32)]),
+    "haflo_op_work": (c_int, [c_void_p, c_int, C.POINTER(c_u64)]),
     "haflo_workspace_bytes": (c_size_t, [c_void_p, c_int, c_size_t, c_size_t]),
     "haflo_import_cipher": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "haflo_export_cipher": (c_int, [c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),

@@ -126,6 +126,13 @@ def haflo_workspace_bytes(ctx, op, rows, cols=0):
     return lib().haflo_workspace_bytes(ctx.handle, op, rows, cols)
 
 
+def haflo_op_work(ctx, op):
+    """32x32+64-bit multiply-adds the kernels execute per element of the operator (chip-filling batches)."""
+    w = C.c_uint64()
+    _check(lib().haflo_op_work(ctx.handle, op, C.byref(w)))
+    return w.value
+
+
 def haflo_op_cost(ctx, op):
     """(Montgomery products per element, 32-bit limbs of their modulus)."""
     mm, limbs = C.c_uint64(), C.c_uint32()

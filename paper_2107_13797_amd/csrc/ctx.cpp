@@ -643,4 +643,45 @@ int haflo_op_cost(const haflo_ctx* ctx, int op, uint64_t* montmuls, uint32_t* mo
   return HAFLO_OK;
 }
 
+// executed multiply-adds of one product on `nl` 29-bit limbs, all lanes of its group together
+namespace {
+uint64_t sq_products(int lpt) {  // limb products per step a squaring forms with lpt limbs per lane
+  uint64_t c = 0;
+  for (int j = 0; j < lpt; ++j) {
+    const int d = j;  // distance from the broadcast limb 0
+    if (d == 0 || (lpt % 2 == 0 && d == lpt / 2) || d <= (lpt - 1) / 2) ++c;
+  }
+  return c;
+}
+uint64_t plain_mul_mads(uint64_t nl, int lpt) { return nl * (nl / lpt) * (2 * (uint64_t)lpt) + nl; }
+uint64_t plain_sqr_mads(uint64_t nl, int lpt) { return nl * (nl / lpt) * (sq_products(lpt) + (uint64_t)lpt) + nl; }
+// the pair arithmetic runs with 9 limbs per lane: two windows, three (two for a squaring) products and two reductions
+uint64_t pair_mul_mads(uint64_t nl) { return nl * (nl / 9) * 45 + 2 * nl; }
+uint64_t pair_sqr_mads(uint64_t nl) { return nl * (nl / 9) * (sq_products(9) + 27) + 2 * nl; }
+}  // namespace
+
+int haflo_op_work(const haflo_ctx* ctx, int op, uint64_t* mads_executed) {
+  if (!ctx) return HAFLO_EINVAL;
+  uint64_t w = 0;
+  if (op == HAFLO_OP_ENCRYPT && !ctx->has_priv) {
+    // pairs modulo n: the power, three more products (into Montgomery form, the (1 + m n) factor, out of the
+    // pair form) and the plain product n x1 of the stored integer
+    const uint64_t nl = (uint64_t)ctx->Nh.nl;
+    w = ctx->prog_enc.sched.nsquare * pair_sqr_mads(nl) + (ctx->prog_enc.sched.nmul + 3) * pair_mul_mads(nl) + nl * nl;
+  } else if (op == HAFLO_OP_DECRYPT) {
+    if (!ctx->has_priv) return HAFLO_ENOPRIV;
+    // out of Montgomery form modulo n^2; per prime: four products into the pair form, the power, one out;
+    // then three half-size products and one plain product for the recombination
+    const uint64_t nl = (uint64_t)ctx->P.nl;
+    w = plain_mul_mads((uint64_t)ctx->N.nl, ctx->N.lpt);
+    for (const haflo::DevProg* dp : {&ctx->prog_dec_p, &ctx->prog_dec_q})
+      w += dp->sched.nsquare * pair_sqr_mads(nl) + (dp->sched.nmul + 5) * pair_mul_mads(nl);
+    w += 3 * plain_mul_mads(nl, ctx->P.lpt) + nl * nl;
+  } else {
+    return HAFLO_EINVAL;
+  }
+  if (mads_executed) *mads_executed = w;
+  return HAFLO_OK;
+}
+
 }  // extern "C"
