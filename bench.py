@@ -35,8 +35,8 @@ PEAK_MAD32_PER_S = 256 * 64 * 2.4e9
 # HBM bytes of the encryption launch at the profiled shape (2048-bit key, 65536 elements): rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE, each scaled by what the counter reads for a 1 GiB device copy. The figure is
 # transcribed from the profile named here, not measured by this run, and is reported for that shape only.
-TRAFFIC_PROFILE = "profiles/k_engine_encrypt_2048bit_b65536_pmc.md"
-TRAFFIC_BYTES_PROFILED = {(2048, 65536): (11430924 + 3085898) * 1024}
+TRAFFIC_PROFILE = "profiles/k_engine_pairs_encrypt_2048bit_b65536_pmc.md"
+TRAFFIC_BYTES_PROFILED = {(2048, 65536): (11693909 + 2581604) * 1024}
 
 
 def montmul_mul32(limbs):
@@ -271,7 +271,7 @@ def main():
                                        "algorithmic": "%d Montgomery-product equivalents x (2*%d^2+%d) mul32 per "
                                                       "encryption" % (mm_o, limbs_o, limbs_o)},
         "stage_ms": {k: v / args.steps for k, v in stage_ms.items()},
-        "roofline": {"bound": "alu", "kernel": "k_engine (encryption program, modulus n^2)", "achieved": achieved / 1e12,
+        "roofline": {"bound": "alu", "kernel": "k_engine_pairs (encryption program on pairs of residues modulo n)", "achieved": achieved / 1e12,
                      "peak": PEAK_MAD32_PER_S / 1e12, "unit": "TOP/s", "op": "32x32+64-bit integer multiply-add",
                      "frac": achieved / PEAK_MAD32_PER_S,
                      "traffic": TRAFFIC_BYTES_PROFILED.get((bits, B)),
@@ -285,7 +285,7 @@ def main():
                      "executed": executed / 1e12,
                      "frac_executed": executed / PEAK_MAD32_PER_S,
                      "executed_note": "v_mad_u64_u32 the kernel really issues per second, in 10^12, and their share of "
-                                      "the same peak; a stream of nothing but this instruction sustains 0.69 of that "
+                                      "the same peak; a stream of nothing but this instruction sustains 0.66 of that "
                                       "peak at the kernel's four wavefronts per SIMD (profiles/peak_microbench.md)",
                      "algorithmic": "%d Montgomery products x (2*%d^2+%d) mul32 per encryption" % (mm, limbs, limbs)},
     }

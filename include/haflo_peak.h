@@ -39,6 +39,26 @@ int haflo_peak_alu(int kind, int blocks, int iters, uint32_t* d_out, void* strea
 enum haflo_peak_hbm_kind { HAFLO_PEAK_FILL = 0, HAFLO_PEAK_COPY = 1, HAFLO_PEAK_READ = 2 };
 int haflo_peak_hbm(int kind, int blocks, void* d_dst, const void* d_src, size_t bytes, void* stream);
 
+/* Alternative limb widths for the Montgomery product, timed against the shipped
+ * 29-bit core: one big integer per lane, `iters` dependent products
+ * x <- x * y / R mod n (x <- x^2 / R for the squaring kind) per lane, R = 2 to the
+ * power (limbs * limb_bits). Every array is in the variant's own radix, least
+ * significant limb first: `limbs` uint32 per element for the integer kinds,
+ * `limbs` doubles (each an integer below 2^23) for HAFLO_LIMBS_23_FMA64; d_x, d_y,
+ * d_out hold `count` elements, d_n one (odd, below R / 2^10). n0inv = -1/n modulo
+ * 2^limb_bits. Operand limbs below 2^limb_bits, values below 2n; results are
+ * below 2n, limbs slightly above 2^limb_bits allowed (29-bit kinds), and are to
+ * be reduced modulo n by the caller. */
+enum haflo_peak_limb_kind {
+  HAFLO_LIMBS_29_MAD64 = 0,        /* the shipped core: v_mad_u64_u32 into 64-bit columns, 18 limbs */
+  HAFLO_LIMBS_29_MAD64_SQUARE = 1, /* its squaring, which leaves out the symmetric half (d_y unused) */
+  HAFLO_LIMBS_24_MUL24 = 2,        /* v_mul_u32_u24 + v_mul_hi_u32_u24 per limb product, 22 limbs */
+  HAFLO_LIMBS_23_FMA64 = 3         /* one FP64 FMA per limb product, 23 limbs held in doubles */
+};
+int haflo_peak_limbs(int kind, uint32_t* limbs, uint32_t* limb_bits);
+int haflo_peak_montmul_chain(int kind, const void* d_x, const void* d_y, const void* d_n, uint64_t n0inv, int iters,
+                             void* d_out, size_t count, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -82,7 +82,10 @@ PEAK_PROTOTYPES = {
     "haflo_peak_streams": (c_int, []),
     "haflo_peak_alu": (c_int, [c_int, c_int, c_int, c_void_p, c_void_p]),
     "haflo_peak_hbm": (c_int, [c_int, c_int, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "haflo_peak_limbs": (c_int, [c_int, C.POINTER(c_u32), C.POINTER(c_u32)]),
+    "haflo_peak_montmul_chain": (c_int, [c_int, c_void_p, c_void_p, c_void_p, c_u64, c_int, c_void_p, c_size_t, c_void_p]),
 }
+LIMBS_29_MAD64, LIMBS_29_MAD64_SQUARE, LIMBS_24_MUL24, LIMBS_23_FMA64 = 0, 1, 2, 3
 PEAK_MAD_U64_U32, PEAK_MUL_LO_HI, PEAK_MUL_U24, PEAK_FMA_F64, PEAK_ADD_U32 = 0, 1, 2, 3, 4
 PEAK_FILL, PEAK_COPY, PEAK_READ = 0, 1, 2
 

@@ -15,6 +15,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhaflo.so")
 PEAK_LIB = os.path.join(HERE, "libhaflo_peak.so")  # the roofline microbenchmarks, a library of their own
 SOURCES = ["ctx.cpp", "staging.cpp", "store.cpp", "kernels_basic.hip", "kernels_modexp.hip", "kernels_matvec.hip", "kernels_buckets.hip", "kernels_loss.hip"]
+PEAK_SOURCES = ["peak_microbench.hip", "limb_variants.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-x", "hip",
@@ -35,8 +36,8 @@ def _compile(src):
 def build_library(verbose=True):
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(4, os.cpu_count() or 1)) as pool:
-        objs = list(pool.map(_compile, SOURCES + ["peak_microbench.hip"]))
-    for lib, parts in ((LIB, objs[:-1]), (PEAK_LIB, objs[-1:])):
+        objs = list(pool.map(_compile, SOURCES + PEAK_SOURCES))
+    for lib, parts in ((LIB, objs[:len(SOURCES)]), (PEAK_LIB, objs[len(SOURCES):])):
         cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + parts
         res = subprocess.run(cmd, capture_output=True, text=True)
         if res.returncode != 0:
