@@ -210,16 +210,19 @@ __global__ __launch_bounds__(kScanThreads) void k_bk_scan_final(const u32* __res
 
 // Reduction round `round`. Key k owns items [off[k], off[k] + items_at(cnt[k], round)) and is cut into
 // choff[k+1] - choff[k] chunks of near-equal size; chunk q's product goes to out[q]. FIRST: item t is the
-// ciphertext of row sorted[t]; otherwise item t is in[t].
-template <int LPT, int T, bool FIRST>
-__global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u32* __restrict__ in,
+// ciphertext of row sorted[t]; otherwise item t is in[t]. PAIR: the items are pairs modulo M (see Elem);
+// `one` is the Montgomery one in the items' form.
+template <int LPT, int T, bool FIRST, bool PAIR>
+__global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u32* __restrict__ one,
+                                                            const u32* __restrict__ in,
                                                             const u32* __restrict__ sorted,
                                                             const u32* __restrict__ cnt,
                                                             const u32* __restrict__ off,
                                                             const u32* __restrict__ choff, size_t K,
                                                             int round, u32* __restrict__ stats,
                                                             u32* __restrict__ out) {
-  constexpr int NL = LPT * T;
+  using Ops = ElemOps<LPT, T, PAIR>;
+  constexpr int EL = Ops::kLimbs;
   constexpr int GW = WAVE / T;                 // lane groups per wavefront
   constexpr int IDX = (kChunk + T - 1) / T;    // row indices each lane keeps for its group's chunk
   Grp<T> g;
@@ -270,36 +273,77 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u
         for (int r = 1; r < IDX; ++r) v = ((int)(e / T) == r) ? idx[r] : v;
         at = g.bcast(v, (int)(e % T));
       }
-      return e < len ? in + at * (size_t)NL : M.r1;
+      return e < len ? in + at * (size_t)EL : one;
     };
-    u32 acc[LPT];
-    load_limbs<LPT, T>(acc, item(0), g);
+    typename Ops::E acc;
+    Ops::load(acc, item(0), g);
 #pragma unroll 1
     for (u32 e = 1; wave_any(e < len); ++e) {
-      // Touch the next item while this one is multiplied: the lanes of the group read words 72 bytes
-      // apart, which covers every cache line of the item; the value only has to stay live.
-      const u32 touch = item(e + 1)[g.k * LPT];
+      // Touch the next item while this one is multiplied: the lanes of the group read words one lane's
+      // share apart, which covers every cache line of the item; the value only has to stay live.
+      const u32 touch = Ops::touch(item(e + 1), g);
       // a group that has run out of items multiplies by one and stays in step with its wave
-      montmul_mem<LPT, T>(acc, acc, item(e), mod.n, mod.n0inv, g);
+      Ops::mul_mem(acc, item(e), mod, g);
       keep_live(touch);
     }
-    if (active) store_limbs<LPT, T>(out + (size_t)q * NL, acc, g);
+    if (active) Ops::store(out + (size_t)q * EL, acc, g);
     u32 drawn = 0;
     if (lane == 0) drawn = atomicAdd(next_chunk, (u32)GW);
     q0 = nwaves * (u32)GW + (u32)__builtin_amdgcn_ds_bpermute(0, (int)drawn);
   }
 }
 
+// Stored ciphertexts (Montgomery form modulo n^2 at the full radix R_N, NL = 2 LPT T limbs) into the pair
+// form modulo M = n (Montgomery form at the half radix R): W = w_lo + R w_hi goes to
+// (w_lo, 0) k_lo + (w_hi, 0) k_hi with the pair constants k_lo = R^2 / R_N and k_hi = R^3 / R_N. The result is
+// lazy (each half below 4n, limbs partially normalised), which is what a product takes.
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads, 4) void k_bk_to_pairs(ModRef M, const u32* __restrict__ k_lo,
+                                                                  const u32* __restrict__ k_hi,
+                                                                  const u32* __restrict__ in, size_t count,
+                                                                  u32* __restrict__ out) {
+  constexpr int NLH = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    const size_t it = base + bt.gib;
+    const bool active = it < count;
+    const u32* w = in + (active ? it : 0) * (size_t)(2 * NLH);
+    u32 a0[LPT], a1[LPT], b0[LPT], b1[LPT];
+    load_limbs<LPT, T>(a0, w, g);
+    load_limbs<LPT, T>(b0, w + NLH, g);
+    zero_limbs<LPT>(a1);
+    zero_limbs<LPT>(b1);
+    pairmul_mem<LPT, T>(a0, a1, a0, a1, k_lo, mod.n, mod.n0inv, g);
+    pairmul_mem<LPT, T>(b0, b1, b0, b1, k_hi, mod.n, mod.n0inv, g);
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+      a0[j] += b0[j];
+      a1[j] += b1[j];
+    }
+    partial_norm<LPT, T>(a0, g);
+    partial_norm<LPT, T>(a1, g);
+    if (active) {
+      store_limbs<LPT, T>(out + it * (size_t)(2 * NLH), a0, g);
+      store_limbs<LPT, T>(out + it * (size_t)(2 * NLH) + NLH, a1, g);
+    }
+  }
+}
+
 // Sub-products of one (position, column, sign): item g < 16: prod_l B[32 g + l]; item 16 + l: prod_h B[32 h + l].
 // B[k] is the single item left of key k after the last round that ran (one when the bucket is empty,
 // cnt[k] = 0): item offs_r[k] of that round's output arena, offs_r the offsets of the round after it.
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* __restrict__ arena0,
+template <int LPT, int T, bool PAIR>
+__global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* __restrict__ one,
+                                                          const u32* __restrict__ arena0,
                                                           const u32* __restrict__ arena1,
                                                           const u32* __restrict__ cnt, const u32* __restrict__ offs,
                                                           size_t K, const u32* __restrict__ stats, size_t combos,
                                                           u32* __restrict__ G) {
-  constexpr int NL = LPT * T;
+  using Ops = ElemOps<LPT, T, PAIR>;
+  constexpr int EL = Ops::kLimbs;
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
@@ -320,21 +364,21 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* _
     // factor e of this item, or null when its bucket is empty or the item is shorter
     auto locate = [&](int e) -> const u32* {
       const size_t key = key0 + (size_t)e * stride;
-      return (e < n && cnt[key] != 0u) ? B + (size_t)off[key] * NL : nullptr;
+      return (e < n && cnt[key] != 0u) ? B + (size_t)off[key] * EL : nullptr;
     };
-    u32 acc[LPT];
-    load_limbs<LPT, T>(acc, M.r1, g);
+    typename Ops::E acc;
+    Ops::load(acc, one, g);
     const u32* next = locate(0);
 #pragma unroll 1
     for (int e = 0; e < kLoCount; ++e) {
       // the next factor is located and touched while this one is multiplied
       const u32* cur = next;
       next = (e + 1 < kLoCount) ? locate(e + 1) : nullptr;
-      const u32 touch = (next ? next : M.r1)[g.k * LPT];
-      if (wave_any(cur != nullptr)) montmul_mem<LPT, T>(acc, acc, cur ? cur : M.r1, mod.n, mod.n0inv, g);
+      const u32 touch = Ops::touch(next ? next : one, g);
+      if (wave_any(cur != nullptr)) Ops::mul_mem(acc, cur ? cur : one, mod, g);
       keep_live(touch);
     }
-    if (active) store_limbs<LPT, T>(G + it * (size_t)NL, acc, g);
+    if (active) Ops::store(G + it * (size_t)EL, acc, g);
   }
 }
 
@@ -344,10 +388,12 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* _
 // the top (run *= G; acc *= run). Stage 2: prod_q A_q * (prod_q T_q^q)^8.
 constexpr int kSegLen = 8, kLoSegs = kLoCount / kSegLen, kHiSegs = kHiCount / kSegLen, kSegs = kLoSegs + kHiSegs;
 
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_bk_fold1(ModRef M, const u32* __restrict__ G, size_t combos,
+template <int LPT, int T, bool PAIR>
+__global__ __launch_bounds__(kBlockThreads) void k_bk_fold1(ModRef M, const u32* __restrict__ one,
+                                                            const u32* __restrict__ G, size_t combos,
                                                             u32* __restrict__ AT) {
-  constexpr int NL = LPT * T;
+  using Ops = ElemOps<LPT, T, PAIR>;
+  constexpr int EL = Ops::kLimbs;
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
@@ -361,30 +407,31 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_fold1(ModRef M, const u32*
     const bool is_hi = seg >= kLoSegs;
     // entry e of the segment's sequence: Glo[e], or Ghi[e + 1] (absent for e = 15)
     const int e0 = (is_hi ? seg - kLoSegs : seg) * kSegLen;
-    const u32* seq = G + (combo * kSubProducts + (is_hi ? 1 : kHiCount)) * (size_t)NL;
+    const u32* seq = G + (combo * kSubProducts + (is_hi ? 1 : kHiCount)) * (size_t)EL;
     const int limit = active ? (is_hi ? kHiCount - 1 : kLoCount) : 0;
-    auto entry = [&](int u) -> const u32* { return (e0 + u < limit) ? seq + (size_t)(e0 + u) * NL : M.r1; };
-    u32 run[LPT], acc[LPT];
-    load_limbs<LPT, T>(run, entry(kSegLen - 1), g);
-#pragma unroll
-    for (int jj = 0; jj < LPT; ++jj) acc[jj] = run[jj];
+    auto entry = [&](int u) -> const u32* { return (e0 + u < limit) ? seq + (size_t)(e0 + u) * EL : one; };
+    typename Ops::E run, acc;
+    Ops::load(run, entry(kSegLen - 1), g);
+    Ops::copy(acc, run);
 #pragma unroll 1
     for (int u = kSegLen - 2; u >= 0; --u) {
-      montmul_mem<LPT, T>(run, run, entry(u), mod.n, mod.n0inv, g);
-      montmul<LPT, T>(acc, acc, run, mod.n, mod.n0inv, g);
+      Ops::mul_mem(run, entry(u), mod, g);
+      Ops::mul(acc, run, mod, g);
     }
     if (active) {
-      store_limbs<LPT, T>(AT + (it * 2) * (size_t)NL, acc, g);
-      store_limbs<LPT, T>(AT + (it * 2 + 1) * (size_t)NL, run, g);
+      Ops::store(AT + (it * 2) * (size_t)EL, acc, g);
+      Ops::store(AT + (it * 2 + 1) * (size_t)EL, run, g);
     }
   }
 }
 
 // R[combo][0] = low part, R[combo][1] = high part
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_bk_fold2(ModRef M, const u32* __restrict__ AT, size_t combos,
+template <int LPT, int T, bool PAIR>
+__global__ __launch_bounds__(kBlockThreads) void k_bk_fold2(ModRef M, const u32* __restrict__ one,
+                                                            const u32* __restrict__ AT, size_t combos,
                                                             u32* __restrict__ R) {
-  constexpr int NL = LPT * T;
+  using Ops = ElemOps<LPT, T, PAIR>;
+  constexpr int EL = Ops::kLimbs;
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
@@ -396,31 +443,34 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_fold2(ModRef M, const u32*
     const size_t combo = active ? it >> 1 : 0;
     const bool is_hi = (it & 1) != 0;
     const int nseg = active ? (is_hi ? kHiSegs : kLoSegs) : 0;
-    const u32* mine = AT + ((combo * kSegs + (is_hi ? kLoSegs : 0)) * 2) * (size_t)NL;
-    auto a_of = [&](int q) -> const u32* { return q < nseg ? mine + (size_t)(2 * q) * NL : M.r1; };
-    auto t_of = [&](int q) -> const u32* { return q < nseg ? mine + (size_t)(2 * q + 1) * NL : M.r1; };
-    u32 run[LPT], acc[LPT];
-    load_limbs<LPT, T>(run, t_of(kLoSegs - 1), g);
-#pragma unroll
-    for (int jj = 0; jj < LPT; ++jj) acc[jj] = run[jj];
+    const u32* mine = AT + ((combo * kSegs + (is_hi ? kLoSegs : 0)) * 2) * (size_t)EL;
+    auto a_of = [&](int q) -> const u32* { return q < nseg ? mine + (size_t)(2 * q) * EL : one; };
+    auto t_of = [&](int q) -> const u32* { return q < nseg ? mine + (size_t)(2 * q + 1) * EL : one; };
+    typename Ops::E run, acc;
+    Ops::load(run, t_of(kLoSegs - 1), g);
+    Ops::copy(acc, run);
 #pragma unroll 1
     for (int q = kLoSegs - 2; q >= 1; --q) {
-      montmul_mem<LPT, T>(run, run, t_of(q), mod.n, mod.n0inv, g);
-      montmul<LPT, T>(acc, acc, run, mod.n, mod.n0inv, g);
+      Ops::mul_mem(run, t_of(q), mod, g);
+      Ops::mul(acc, run, mod, g);
     }
 #pragma unroll 1
-    for (int i = 0; i < 3; ++i) montsqr<LPT, T>(acc, acc, mod.n, mod.n0inv, g);  // ^8 = ^kSegLen
+    for (int i = 0; i < 3; ++i) Ops::sqr(acc, mod, g);  // ^8 = ^kSegLen
 #pragma unroll 1
-    for (int q = 0; q < kLoSegs; ++q) montmul_mem<LPT, T>(acc, acc, a_of(q), mod.n, mod.n0inv, g);
-    if (active) store_limbs<LPT, T>(R + it * (size_t)NL, acc, g);
+    for (int q = 0; q < kLoSegs; ++q) Ops::mul_mem(acc, a_of(q), mod, g);
+    if (active) Ops::store(R + it * (size_t)EL, acc, g);
   }
 }
 
-// P[j][sign] = prod_s (R_hi[s]^32 R_lo[s])^(1024^s), top position first.
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_bk_horner(ModRef M, const u32* __restrict__ R, size_t cols,
+// P[j][sign] = prod_s (R_hi[s]^32 R_lo[s])^(1024^s), top position first. PAIR: the result leaves the pair form
+// (`leave` = the pair constant R_N) and is stored as the canonical integer, the form of a stored ciphertext.
+template <int LPT, int T, bool PAIR>
+__global__ __launch_bounds__(kBlockThreads) void k_bk_horner(ModRef M, const u32* __restrict__ one,
+                                                             const u32* __restrict__ leave,
+                                                             const u32* __restrict__ R, size_t cols,
                                                              u32* __restrict__ P, const u32* __restrict__ stats) {
-  constexpr int NL = LPT * T;
+  using Ops = ElemOps<LPT, T, PAIR>;
+  constexpr int EL = Ops::kLimbs;
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
@@ -431,21 +481,32 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_horner(ModRef M, const u32
     const size_t it = base + bt.gib;
     const bool active = it < count;
     const size_t js = active ? it : 0;  // j * 2 + sign
-    u32 acc[LPT];
-    load_limbs<LPT, T>(acc, M.r1, g);
+    typename Ops::E acc;
+    Ops::load(acc, one, g);
 #pragma unroll 1
     for (int s = npos - 1; s >= 0; --s) {
-      const u32* r = R + (((size_t)s * cols * 2 + js) * 2) * (size_t)NL;  // [0] low part, [1] high part
+      const u32* r = R + (((size_t)s * cols * 2 + js) * 2) * (size_t)EL;  // [0] low part, [1] high part
 #pragma unroll 1
       for (int half = 1; half >= 0; --half) {
         if (s != npos - 1 || half != 1) {
 #pragma unroll 1
-          for (int i = 0; i < 5; ++i) montsqr<LPT, T>(acc, acc, mod.n, mod.n0inv, g);
+          for (int i = 0; i < 5; ++i) Ops::sqr(acc, mod, g);
         }
-        montmul_mem<LPT, T>(acc, acc, r + (size_t)half * NL, mod.n, mod.n0inv, g);
+        Ops::mul_mem(acc, r + (size_t)half * EL, mod, g);
       }
     }
-    if (active) store_limbs<LPT, T>(P + it * (size_t)NL, acc, g);
+    if constexpr (PAIR) {
+      Ops::mul_mem(acc, leave, mod, g);
+      pair_canonical<LPT, T>(acc.x0, acc.x1, mod.n, g);
+      u32 lo[LPT], hi[LPT];
+      pair_to_integer<LPT, T>(lo, hi, acc.x0, acc.x1, mod.n, g);
+      if (active) {
+        store_limbs<LPT, T>(P + it * (size_t)EL, lo, g);
+        store_limbs<LPT, T>(P + it * (size_t)EL + LPT * T, hi, g);
+      }
+    } else {
+      if (active) Ops::store(P + it * (size_t)EL, acc, g);
+    }
   }
 }
 
@@ -552,8 +613,8 @@ int seg_sum(const haflo_ctx* ctx, const uint32_t* d_c, const uint32_t* d_offsets
     // round 0 reads the elements where they are: a segment's items start at its first element
     const u32* off = r == 0 ? (const u32*)first : (const u32*)offs(r);
 #define CALL(LPT, T)                                                                                        \
-  HAFLO_LAUNCH((k_bk_round<LPT, T, false>), sh, st, m.ref(), items, (const u32*)nullptr, (const u32*)cnt, \
-               off, (const u32*)offs(r + 1), K, r, stats, out)
+  HAFLO_LAUNCH((k_bk_round<LPT, T, false, false>), sh, st, m.ref(), (const u32*)m.ref().r1, items,       \
+               (const u32*)nullptr, (const u32*)cnt, off, (const u32*)offs(r + 1), K, r, stats, out)
     HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
     items = out;
@@ -598,6 +659,8 @@ XtdBucketPlan xtd_bucket_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
   p.off_G = w;       w += combos * kSubProducts * nl;
   p.off_AT = w;      w += combos * kSegs * 2 * nl;
   p.off_R = w;       w += combos * 2 * nl;
+  p.pairs = haflo_has_pair_geometry(ctx->Nh);
+  p.off_pairs = w;   w += p.pairs ? rows * nl : 0;  // the ciphertexts in the pair form
   p.total = w;
   return p;
 }
@@ -629,63 +692,99 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
   HAFLO_LAUNCH(k_bk_scan_totals, scan, st, (const u32*)cnt, K, p.rounds + 1, totals, stats);
   HAFLO_LAUNCH(k_bk_scan_final, scan, st, (const u32*)cnt, K, p.rounds + 1, (const u32*)totals, offs(0));
   HAFLO_LAUNCH((k_bk_terms<true>), flat, st, d_X, rows, cols, cursor, (const u32*)offs(0), sorted, stats);
+  // The products run on pairs of residues modulo n (5/8 of the limb products of a full-length product) wherever
+  // the key size has that geometry: the ciphertexts are taken into the pair form once (two products each,
+  // against two products per matrix entry below), and the column results leave it in k_bk_horner.
+  const bool pairs = p.pairs;
+  const ModHost& mh = ctx->Nh;
+  const ModRef M = pairs ? mh.ref() : m.ref();
+  const int lanes = pairs ? 2 * mh.t : m.t;
+  const u32* one = pairs ? (const u32*)(mh.d_pairs + (size_t)kConstR1 * 2 * mh.nl) : (const u32*)m.ref().r1;
+  const u32* leave = pairs ? (const u32*)(mh.d_pairs + (size_t)kConstR3 * 2 * mh.nl) : (const u32*)nullptr;
   const u32* items = d_c;
+  if (pairs) {
+    u32* cp = ws + p.off_pairs;
+    const LaunchShape sh = launch_shape(ctx, rows, lanes, 8);
+#define CALL(LPT, T)                                                                                              \
+  HAFLO_LAUNCH((k_bk_to_pairs<LPT, T>), sh, st, M, (const u32*)(mh.d_pairs + (size_t)kConstR4 * 2 * mh.nl),     \
+               (const u32*)(mh.d_pairs + (size_t)kConstR5 * 2 * mh.nl), d_c, rows, cp)
+    HAFLO_DISPATCH_PAIRS(mh, CALL);
+#undef CALL
+    items = cp;
+  }
   for (int r = 0; r < p.rounds; ++r) {
     // upper bound of the chunks of this round: one lane group each, capped by the grid-stride loop
     size_t bound = rows * cols * kMaxPos;
     for (int i = 0; i <= r; ++i) bound = bound / kChunk + K;
-    const LaunchShape sh = launch_shape(ctx, bound, m.t, 3);
+    const LaunchShape sh = launch_shape(ctx, bound, lanes, 3);
     u32* out = ws + p.off_arena[r & 1];
-    if (r == 0) {
-#define CALL(LPT, T)                                                                                       \
-  HAFLO_LAUNCH((k_bk_round<LPT, T, true>), sh, st, m.ref(), items, (const u32*)sorted, (const u32*)cnt,  \
-               (const u32*)offs(0), (const u32*)offs(1), K, 0, stats, out)
-      HAFLO_DISPATCH_GEOMETRY(m, CALL);
+    const u32* srt = r == 0 ? (const u32*)sorted : (const u32*)nullptr;
+#define CALL_ROUND(LPT, T, FIRST, PAIR)                                                                  \
+  HAFLO_LAUNCH((k_bk_round<LPT, T, FIRST, PAIR>), sh, st, M, one, items, srt, (const u32*)cnt,          \
+               (const u32*)offs(r), (const u32*)offs(r + 1), K, r, stats, out)
+    if (pairs) {
+#define CALL(LPT, T) do { if (r == 0) CALL_ROUND(LPT, T, true, true); else CALL_ROUND(LPT, T, false, true); } while (0)
+      HAFLO_DISPATCH_PAIRS(mh, CALL);
 #undef CALL
     } else {
-#define CALL(LPT, T)                                                                                        \
-  HAFLO_LAUNCH((k_bk_round<LPT, T, false>), sh, st, m.ref(), items, (const u32*)nullptr, (const u32*)cnt, \
-               (const u32*)offs(r), (const u32*)offs(r + 1), K, r, stats, out)
+#define CALL(LPT, T) do { if (r == 0) CALL_ROUND(LPT, T, true, false); else CALL_ROUND(LPT, T, false, false); } while (0)
       HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
     }
+#undef CALL_ROUND
     items = out;
   }
   const size_t combos = cols * kMaxPos * 2;
   u32* G = ws + p.off_G;
   u32* AT = ws + p.off_AT;
   u32* R = ws + p.off_R;
+  // The tail kernels hold few integers: without the pair form they spread each over twice the lanes (the pair
+  // form already sits on those).
+  auto tail_shape = [&](size_t count, bool wide) { return launch_shape(ctx, count, pairs ? lanes : (wide ? haflo_wide_lanes(m) : m.t), 8); };
+#define TAIL(COUNT, WIDE)                                                    \
+  do {                                                                       \
+    const bool wide = (WIDE);                                                \
+    const LaunchShape sh = tail_shape((COUNT), wide);                        \
+    if (pairs) { HAFLO_DISPATCH_PAIRS(mh, CALL_P); }                         \
+    else if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL_N); }              \
+    else { HAFLO_DISPATCH_GEOMETRY(m, CALL_N); }                             \
+  } while (0)
   {
     // half of the items belong to unused digit positions and leave at once
-    const bool wide = haflo::few_groups(ctx, combos * kSubProducts, 64);
-    const LaunchShape sh = launch_shape(ctx, combos * kSubProducts, wide ? haflo_wide_lanes(m) : m.t, 8);
-#define CALL(LPT, T)                                                                                    \
-  HAFLO_LAUNCH((k_bk_sub<LPT, T>), sh, st, m.ref(), (const u32*)(ws + p.off_arena[0]),                 \
+#define CALL_P(LPT, T)                                                                                  \
+  HAFLO_LAUNCH((k_bk_sub<LPT, T, true>), sh, st, M, one, (const u32*)(ws + p.off_arena[0]),            \
                (const u32*)(ws + p.off_arena[1]), (const u32*)cnt, (const u32*)offs(0), K, (const u32*)stats, combos, G)
-    if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
-#undef CALL
+#define CALL_N(LPT, T)                                                                                  \
+  HAFLO_LAUNCH((k_bk_sub<LPT, T, false>), sh, st, M, one, (const u32*)(ws + p.off_arena[0]),           \
+               (const u32*)(ws + p.off_arena[1]), (const u32*)cnt, (const u32*)offs(0), K, (const u32*)stats, combos, G)
+    TAIL(combos * kSubProducts, haflo::few_groups(ctx, combos * kSubProducts, 64));
+#undef CALL_P
+#undef CALL_N
   }
   {
-    const bool wide = haflo::few_groups(ctx, combos * kSegs);
-    const LaunchShape sh = launch_shape(ctx, combos * kSegs, wide ? haflo_wide_lanes(m) : m.t, 8);
-#define CALL(LPT, T) HAFLO_LAUNCH((k_bk_fold1<LPT, T>), sh, st, m.ref(), (const u32*)G, combos, AT)
-    if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
-#undef CALL
+#define CALL_P(LPT, T) HAFLO_LAUNCH((k_bk_fold1<LPT, T, true>), sh, st, M, one, (const u32*)G, combos, AT)
+#define CALL_N(LPT, T) HAFLO_LAUNCH((k_bk_fold1<LPT, T, false>), sh, st, M, one, (const u32*)G, combos, AT)
+    TAIL(combos * kSegs, haflo::few_groups(ctx, combos * kSegs));
+#undef CALL_P
+#undef CALL_N
   }
   {
-    const bool wide = haflo::few_groups(ctx, combos * 2);
-    const LaunchShape sh = launch_shape(ctx, combos * 2, wide ? haflo_wide_lanes(m) : m.t, 8);
-#define CALL(LPT, T) HAFLO_LAUNCH((k_bk_fold2<LPT, T>), sh, st, m.ref(), (const u32*)AT, combos, R)
-    if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
-#undef CALL
+#define CALL_P(LPT, T) HAFLO_LAUNCH((k_bk_fold2<LPT, T, true>), sh, st, M, one, (const u32*)AT, combos, R)
+#define CALL_N(LPT, T) HAFLO_LAUNCH((k_bk_fold2<LPT, T, false>), sh, st, M, one, (const u32*)AT, combos, R)
+    TAIL(combos * 2, haflo::few_groups(ctx, combos * 2));
+#undef CALL_P
+#undef CALL_N
   }
   {
-    const bool wide = haflo::few_groups(ctx, cols * 2);
-    const LaunchShape sh = launch_shape(ctx, cols * 2, wide ? haflo_wide_lanes(m) : m.t, 8);
-#define CALL(LPT, T) HAFLO_LAUNCH((k_bk_horner<LPT, T>), sh, st, m.ref(), (const u32*)R, cols, d_P, (const u32*)stats)
-    if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
-#undef CALL
+#define CALL_P(LPT, T) \
+  HAFLO_LAUNCH((k_bk_horner<LPT, T, true>), sh, st, M, one, leave, (const u32*)R, cols, d_P, (const u32*)stats)
+#define CALL_N(LPT, T) \
+  HAFLO_LAUNCH((k_bk_horner<LPT, T, false>), sh, st, M, one, leave, (const u32*)R, cols, d_P, (const u32*)stats)
+    TAIL(cols * 2, haflo::few_groups(ctx, cols * 2));
+#undef CALL_P
+#undef CALL_N
   }
+#undef TAIL
   return hip_status(hipGetLastError());
 }
 

@@ -186,6 +186,36 @@ __global__ __launch_bounds__(kBlockThreads, 4) void k_engine(ModRef M, Prog P, E
   engine_run<LPT, T, Prog>(M, P, io, count, blockIdx.x, gridDim.x);
 }
 
+// Canonical pair: x0 below s with what it exceeded s by carried into x1 (the value is x0 + s x1), then x1
+// below s (it may exceed 2s by a hair after a product, or by more after the carry: two subtractions).
+// Input: a lazy pair as a product leaves it.
+template <int LPT, int T>
+__device__ __forceinline__ void pair_canonical(u32 (&x0)[LPT], u32 (&x1)[LPT], const u32 (&n)[LPT], const Grp<T>& g) {
+  resolve<LPT, T>(x0, g);
+  s32 d[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) d[j] = (s32)x0[j] - (s32)n[j];
+  const int top = resolve<LPT, T>(d, g);
+  if (top >= 0) {
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) x0[j] = (u32)d[j];
+    if (g.k == 0) x1[0] += 1u;
+  }
+  canonicalise<LPT, T>(x1, n, g);
+  canonicalise<LPT, T>(x1, n, g);
+}
+// The integer x0 + s x1 of a canonical pair, as its low and high NL limbs (canonical)
+template <int LPT, int T>
+__device__ __forceinline__ void pair_to_integer(u32 (&lo)[LPT], u32 (&hi)[LPT], const u32 (&x0)[LPT],
+                                                const u32 (&x1)[LPT], const u32 (&n)[LPT], const Grp<T>& g) {
+  mulwide<LPT, T>(lo, hi, n, x1, g);
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) lo[j] += x0[j];
+  const int carry = resolve<LPT, T>(lo, g);
+  if (g.k == 0) hi[0] += (u32)carry;
+  resolve<LPT, T>(hi, g);
+}
+
 // The same engine on residues modulo s^2 held as pairs of residues modulo s (pairmul_core): `M` is the
 // modulus s with half the limbs of s^2; an element of the tables and of the constant arrays is
 // [x0: NL limbs][x1: NL limbs]. Instructions as above, with these readings: ENG_LOAD_W is the pair (w, 0),
@@ -267,32 +297,12 @@ __device__ __forceinline__ void engine_run_pairs(const ModRef& M, const Prog& P,
         zero_limbs<LPT>(x1);
       }
     }
-    // Canonical pair: x0 below s with what it exceeded s by carried into x1 (the value is x0 + s x1), then x1
-    // below s (it may exceed 2s by a hair after a product, or by more after the carry: two subtractions)
-    {
-      resolve<LPT, T>(x0, g);
-      s32 d[LPT];
-#pragma unroll
-      for (int j = 0; j < LPT; ++j) d[j] = (s32)x0[j] - (s32)mod.n[j];
-      const int top = resolve<LPT, T>(d, g);
-      if (top >= 0) {
-#pragma unroll
-        for (int j = 0; j < LPT; ++j) x0[j] = (u32)d[j];
-        if (g.k == 0) x1[0] += 1u;
-      }
-    }
-    canonicalise<LPT, T>(x1, mod.n, g);
-    canonicalise<LPT, T>(x1, mod.n, g);
+    pair_canonical<LPT, T>(x0, x1, mod.n, g);
     if (io.out_mode == kOutSecond) {
       if (active) store_limbs<LPT, T>(io.out + item * (size_t)NL, x1, g);
     } else {
       u32 lo[LPT], hi[LPT];
-      mulwide<LPT, T>(lo, hi, mod.n, x1, g);
-#pragma unroll
-      for (int j = 0; j < LPT; ++j) lo[j] += x0[j];
-      const int carry = resolve<LPT, T>(lo, g);
-      if (g.k == 0) hi[0] += (u32)carry;
-      resolve<LPT, T>(hi, g);
+      pair_to_integer<LPT, T>(lo, hi, x0, x1, mod.n, g);
       if (active) {
         store_limbs<LPT, T>(io.out + item * (size_t)(2 * NL), lo, g);
         store_limbs<LPT, T>(io.out + item * (size_t)(2 * NL) + NL, hi, g);
@@ -328,6 +338,54 @@ __global__ __launch_bounds__(kBlockThreads, 4) void k_engine_pairs2(EngineJob j0
   else engine_run_pairs<LPT, T, ProgPtr>(j1.M, j1.P, j1.io, count, blockIdx.x - split, gridDim.x - split);
 }
 
+
+// What the reduction kernels multiply: a Montgomery residue of LPT T limbs, or (PAIR) a residue modulo the
+// square of the LPT T-limb modulus held as a pair, 2 LPT T limbs in memory ([x0][x1]), with pairmul_core's
+// products. The kernels are written once against this.
+template <int LPT, bool PAIR>
+struct Elem {
+  u32 x0[LPT];
+  u32 x1[PAIR ? LPT : 1];
+};
+template <int LPT, int T, bool PAIR>
+struct ElemOps {
+  static constexpr int kLimbs = (PAIR ? 2 : 1) * LPT * T;  // limbs of an element in memory
+  using E = Elem<LPT, PAIR>;
+  static __device__ __forceinline__ void load(E& e, const u32* p, const Grp<T>& g) {
+    load_limbs<LPT, T>(e.x0, p, g);
+    if constexpr (PAIR) load_limbs<LPT, T>(e.x1, p + LPT * T, g);
+  }
+  static __device__ __forceinline__ void store(u32* p, const E& e, const Grp<T>& g) {
+    store_limbs<LPT, T>(p, e.x0, g);
+    if constexpr (PAIR) store_limbs<LPT, T>(p + LPT * T, e.x1, g);
+  }
+  static __device__ __forceinline__ void copy(E& d, const E& s) {
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+      d.x0[j] = s.x0[j];
+      if constexpr (PAIR) d.x1[j] = s.x1[j];
+    }
+  }
+  // one word of every cache line of the element at p, so that it is on its way while something else runs
+  static __device__ __forceinline__ u32 touch(const u32* p, const Grp<T>& g) {
+    u32 v = p[g.k * LPT];
+    if constexpr (PAIR) v ^= p[LPT * T + g.k * LPT];
+    return v;
+  }
+  static __device__ __forceinline__ void mul_mem(E& acc, const u32* p, const ModRegs<LPT>& mod, const Grp<T>& g) {
+    if constexpr (PAIR) pairmul_mem<LPT, T>(acc.x0, acc.x1, acc.x0, acc.x1, p, mod.n, mod.n0inv, g);
+    else montmul_mem<LPT, T>(acc.x0, acc.x0, p, mod.n, mod.n0inv, g);
+  }
+  static __device__ __forceinline__ void mul(E& acc, const E& b, const ModRegs<LPT>& mod, const Grp<T>& g) {
+    if constexpr (PAIR) pairmul<LPT, T>(acc.x0, acc.x1, acc.x0, acc.x1, b.x0, b.x1, mod.n, mod.n0inv, g);
+    else montmul<LPT, T>(acc.x0, acc.x0, b.x0, mod.n, mod.n0inv, g);
+  }
+  static __device__ __forceinline__ void sqr(E& acc, const ModRegs<LPT>& mod, const Grp<T>& g) {
+    if constexpr (PAIR) pairsqr<LPT, T>(acc.x0, acc.x1, acc.x0, acc.x1, mod.n, mod.n0inv, g);
+    else montsqr<LPT, T>(acc.x0, acc.x0, mod.n, mod.n0inv, g);
+  }
+};
+
 }  // namespace dev
 }  // namespace haflo
 
@@ -360,6 +418,17 @@ __global__ __launch_bounds__(kBlockThreads, 4) void k_engine_pairs2(EngineJob j0
     else if ((m).lpt == 9 && (m).t == 1) { CALL(9, 1); }          \
     else return HAFLO_EINVAL;                                     \
   } while (0)
+// The pair arithmetic modulo the square of `mh` (18 limbs per lane as a plain modulus): 9 limbs of each half
+// per lane on twice the lanes. Expands `CALL(9, T)`.
+#define HAFLO_DISPATCH_PAIRS(mh, CALL)                            \
+  do {                                                            \
+    if ((mh).lpt == 18 && (mh).t == 1) { CALL(9, 2); }            \
+    else if ((mh).lpt == 18 && (mh).t == 2) { CALL(9, 4); }       \
+    else if ((mh).lpt == 18 && (mh).t == 4) { CALL(9, 8); }       \
+    else if ((mh).lpt == 18 && (mh).t == 8) { CALL(9, 16); }      \
+    else return HAFLO_EINVAL;                                     \
+  } while (0)
+inline bool haflo_has_pair_geometry(const haflo::ModHost& mh) { return mh.d_pairs && mh.lpt == 18 && mh.t <= 8; }
 // The same dispatch for batches of at most one big integer per SIMD, where the latency of one product is all
 // that counts: one integer per wavefront on 18 to 48 lanes with 2 to 6 limbs each (steps of a dozen
 // instructions instead of two to four dozen). Moduli without such a geometry take the wide one.
