@@ -61,29 +61,44 @@ __host__ __device__ inline int signed_digit_positions(unsigned maxmag) {
 // Returns the integer matrix with 2^29 (f', g') = (u f + v g, q f + r g); every
 // entry has magnitude at most 2^29 and each row sums to at most 2^29 in
 // magnitude.
+// The steps are taken in runs: all the halvings that g's trailing zeros allow at once (a count of
+// trailing zeros), then, g being odd, the combination of one odd step without its halving, which the
+// next run takes. The odd step is written with masks instead of selects - swap and negate,
+// (f, g) <- (g, -f) and the matrix rows likewise, when delta > 0, then g += f - so that it is straight-line
+// code on the scalar unit (a whole-wavefront group, where f0 and g0 are wave-uniform) as well as on the
+// vector unit. About half as many loop rounds as steps, none of them with a branch inside.
 __device__ __forceinline__ void divsteps29(int& delta, u32 f0, u32 g0, s32& u, s32& v, s32& q, s32& r) {
-  u = 1;
-  v = 0;
-  q = 0;
-  r = 1;
-#pragma unroll 1
-  for (int i = 0; i < LIMB_BITS; ++i) {
-    bool odd = (g0 & 1u) != 0u;
-    bool swp = odd && (delta > 0);
-    u32 nf = swp ? g0 : f0;
-    s32 nu = swp ? q : u;
-    s32 nv = swp ? r : v;
-    u32 ng = odd ? (swp ? g0 - f0 : g0 + f0) : g0;
-    s32 nq = odd ? (swp ? q - u : q + u) : q;
-    s32 nr = odd ? (swp ? r - v : r + v) : r;
-    delta = swp ? 1 - delta : 1 + delta;
-    f0 = nf;
-    g0 = ng >> 1;
-    u = nu * 2;
-    v = nv * 2;
-    q = nq;
-    r = nr;
+  s32 eta = -delta;  // the swap condition is eta < 0
+  u32 uu = 1, vv = 0, qq = 0, rr = 1;  // the matrix, in wrapping arithmetic
+  int left = LIMB_BITS;
+  for (;;) {
+    const int z = __builtin_ctz(g0 | (1u << left));  // bits [0, left) of g0 are exact, bit `left` ends the run
+    g0 >>= z;
+    uu <<= z;
+    vv <<= z;
+    eta -= z;
+    left -= z;
+    if (left == 0) break;
+    const u32 c = (u32)(eta >> 31);  // all ones: swap
+    u32 t = (f0 ^ g0) & c;
+    f0 ^= t;
+    g0 ^= t;
+    g0 = ((g0 ^ c) - c) + f0;
+    t = (uu ^ qq) & c;
+    uu ^= t;
+    qq ^= t;
+    qq = ((qq ^ c) - c) + uu;
+    t = (vv ^ rr) & c;
+    vv ^= t;
+    rr ^= t;
+    rr = ((rr ^ c) - c) + vv;
+    eta = (s32)(((u32)eta ^ c) - c);
   }
+  delta = -eta;
+  u = (s32)uu;
+  v = (s32)vv;
+  q = (s32)qq;
+  r = (s32)rr;
 }
 
 // Shared tail of the two linear updates: absorb the carry of the lane below,
@@ -129,7 +144,7 @@ __device__ __forceinline__ void invert_mont(u32 (&out)[LPT], const u32 (&a)[LPT]
 #pragma unroll
     for (int j = 0; j < LPT; ++j) any |= gg[j];
     if (!wave_any(any != 0)) break;
-    u32 f0 = g.bcast((u32)f[0], 0), g0 = g.bcast((u32)gg[0], 0);
+    u32 f0 = g.bcast0((u32)f[0]), g0 = g.bcast0((u32)gg[0]);
     s32 u, v, q, r;
     divsteps29(delta, f0, g0, u, v, q, r);
     {
@@ -151,8 +166,8 @@ __device__ __forceinline__ void invert_mont(u32 (&out)[LPT], const u32 (&a)[LPT]
       // multiples of m that clear the lowest limb of each combination
       u32 lowd = (u32)u * (u32)d[0] + (u32)v * (u32)e[0];
       u32 lowe = (u32)q * (u32)d[0] + (u32)r * (u32)e[0];
-      u32 kd = g.bcast((lowd * M.n0inv) & LIMB_MASK, 0);
-      u32 ke = g.bcast((lowe * M.n0inv) & LIMB_MASK, 0);
+      u32 kd = g.bcast0((lowd * M.n0inv) & LIMB_MASK);
+      u32 ke = g.bcast0((lowe * M.n0inv) & LIMB_MASK);
       s64 cd = 0, ce = 0;
       s32 nd[LPT], ne[LPT];
 #pragma unroll
@@ -169,7 +184,7 @@ __device__ __forceinline__ void invert_mont(u32 (&out)[LPT], const u32 (&a)[LPT]
     }
   }
   // f = +-1 now; the inverse is sign(f) * d modulo m
-  u32 f0 = g.bcast((u32)f[0], 0) & LIMB_MASK;
+  u32 f0 = g.bcast0((u32)f[0]) & LIMB_MASK;
   bool fneg = (f0 != 1u);
 #pragma unroll
   for (int j = 0; j < LPT; ++j) d[j] = fneg ? -d[j] : d[j];
@@ -812,17 +827,40 @@ int launch_maxmag(const haflo_ctx* ctx, const int32_t* X, size_t total, u32* wor
   return hip_status(hipGetLastError());
 }
 
+// Launch shape and geometry of a short, latency-bound kernel over `count` big integers modulo `m`: one
+// wavefront per integer while every integer can have a SIMD to itself, else twice the lanes per integer
+// while the chip is mostly idle, else the modulus's own geometry.
+LaunchShape latency_shape(const haflo_ctx* ctx, size_t count, const ModHost& m) {
+  LaunchShape sh;
+  if (haflo_has_wave_geometry(m) && count <= (size_t)ctx->num_cu * 4) {
+    sh.blocks = (int)(count ? count : 1);
+    sh.threads = 64;
+    sh.gpb = 1;
+    sh.geo = kGeoWave;
+    return sh;
+  }
+  const bool wide = haflo::few_groups(ctx, count);
+  sh = launch_shape(ctx, count, wide ? haflo_wide_lanes(m) : m.t, 8);
+  sh.geo = wide ? kGeoWide : kGeoPlain;
+  return sh;
+}
+#define HAFLO_DISPATCH_SHAPE(sh, m, CALL)                                    \
+  do {                                                                       \
+    if ((sh).geo == kGeoWave) { HAFLO_DISPATCH_GEOMETRY_WAVE(m, CALL); }     \
+    else if ((sh).geo == kGeoWide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } \
+    else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }                               \
+  } while (0)
+
 }  // namespace
 
 namespace haflo {
 
 int invert_batch(const haflo_ctx* ctx, const uint32_t* in, uint32_t* out, size_t count, hipStream_t st) {
   const ModHost& m = ctx->N;
-  const bool wide = haflo::few_groups(ctx, count);
-  const LaunchShape sh = launch_shape(ctx, count, wide ? haflo_wide_lanes(m) : m.t, 8);
+  const LaunchShape sh = latency_shape(ctx, count, m);
   const int nbatch = inverse_batches(ctx);
 #define CALL(LPT, T) HAFLO_LAUNCH((k_invert<LPT, T>), sh, st, m.ref(), ctx->Nw.ref(), in, out, count, nbatch)
-  if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
+  HAFLO_DISPATCH_SHAPE(sh, m, CALL);
 #undef CALL
   return hip_status(hipGetLastError());
 }
@@ -875,10 +913,9 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
     u32* P = ws + l.off_P;
     rc = xtd_buckets(ctx, (const u32*)d_c, d_X, rows, cols, ws + l.off_ws, P, st);
     if (rc != HAFLO_OK) return rc;
-    const bool wide = haflo::few_groups(ctx, cols);
-    const LaunchShape sh = launch_shape(ctx, cols, wide ? haflo_wide_lanes(m) : m.t, 8);
+    const LaunchShape sh = latency_shape(ctx, cols, m);
 #define CALL(LPT, T) HAFLO_LAUNCH((k_xtd_finish<LPT, T>), sh, st, m.ref(), ctx->Nw.ref(), cols, (const u32*)P, (u32*)d_out, nbatch)
-    if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
+    HAFLO_DISPATCH_SHAPE(sh, m, CALL);
 #undef CALL
   } else if (orientation == 0) {
     const XtdPlan p = xtd_plan(ctx, rows, cols);
@@ -906,10 +943,9 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
 #undef CALL
     }
     {
-      const bool wide = haflo::few_groups(ctx, cols);
-      const LaunchShape sh = launch_shape(ctx, cols, wide ? haflo_wide_lanes(m) : m.t, 8);
+      const LaunchShape sh = latency_shape(ctx, cols, m);
 #define CALL(LPT, T) HAFLO_LAUNCH((k_xtd_finish<LPT, T>), sh, st, m.ref(), ctx->Nw.ref(), cols, (const u32*)P, (u32*)d_out, nbatch)
-      if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
+      HAFLO_DISPATCH_SHAPE(sh, m, CALL);
 #undef CALL
     }
   } else {
