@@ -293,48 +293,12 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u
   }
 }
 
-// Stored ciphertexts (Montgomery form modulo n^2 at the full radix R_N, NL = 2 LPT T limbs) into the pair
-// form modulo M = n (Montgomery form at the half radix R): W = w_lo + R w_hi goes to
-// (w_lo, 0) k_lo + (w_hi, 0) k_hi with the pair constants k_lo = R^2 / R_N and k_hi = R^3 / R_N. The result is
-// lazy (each half below 4n, limbs partially normalised), which is what a product takes.
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads, 4) void k_bk_to_pairs(ModRef M, const u32* __restrict__ k_lo,
-                                                                  const u32* __restrict__ k_hi,
-                                                                  const u32* __restrict__ in, size_t count,
-                                                                  u32* __restrict__ out) {
-  constexpr int NLH = LPT * T;
-  Grp<T> g;
-  Batch<T> bt;
-  ModRegs<LPT> mod;
-  load_mod<LPT, T>(mod, M, g);
-  for (size_t base = bt.first(); base < count; base += bt.stride()) {
-    const size_t it = base + bt.gib;
-    const bool active = it < count;
-    const u32* w = in + (active ? it : 0) * (size_t)(2 * NLH);
-    u32 a0[LPT], a1[LPT], b0[LPT], b1[LPT];
-    load_limbs<LPT, T>(a0, w, g);
-    load_limbs<LPT, T>(b0, w + NLH, g);
-    zero_limbs<LPT>(a1);
-    zero_limbs<LPT>(b1);
-    pairmul_mem<LPT, T>(a0, a1, a0, a1, k_lo, mod.n, mod.n0inv, g);
-    pairmul_mem<LPT, T>(b0, b1, b0, b1, k_hi, mod.n, mod.n0inv, g);
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) {
-      a0[j] += b0[j];
-      a1[j] += b1[j];
-    }
-    partial_norm<LPT, T>(a0, g);
-    partial_norm<LPT, T>(a1, g);
-    if (active) {
-      store_limbs<LPT, T>(out + it * (size_t)(2 * NLH), a0, g);
-      store_limbs<LPT, T>(out + it * (size_t)(2 * NLH) + NLH, a1, g);
-    }
-  }
-}
-
 // Sub-products of one (position, column, sign): item g < 16: prod_l B[32 g + l]; item 16 + l: prod_h B[32 h + l].
 // B[k] is the single item left of key k after the last round that ran (one when the bucket is empty,
 // cnt[k] = 0): item offs_r[k] of that round's output arena, offs_r the offsets of the round after it.
+// An item's factors are split over kSubSplit neighbouring lane groups of a block, which multiply their
+// shares side by side and then combine them pairwise through LDS: a chain of 8 + 2 products instead of 32.
+constexpr int kSubSplit = 4;
 template <int LPT, int T, bool PAIR>
 __global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* __restrict__ one,
                                                           const u32* __restrict__ arena0,
@@ -344,6 +308,9 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* _
                                                           u32* __restrict__ G) {
   using Ops = ElemOps<LPT, T, PAIR>;
   constexpr int EL = Ops::kLimbs;
+  constexpr int GPB = kBlockThreads / Grp<T>::kPitch;
+  static_assert(GPB % kSubSplit == 0 && kSubSplit * Grp<T>::kPitch <= WAVE, "the groups of an item share a wavefront");
+  __shared__ u32 lds[(GPB / 2) * EL];
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
@@ -351,34 +318,52 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* _
   const int ran = rounds_run(stats[kStatMaxCount]);
   const u32* B = ((ran - 1) & 1) ? arena1 : arena0;
   const u32* off = offs + (size_t)ran * (K + 1);
-  const size_t count = combos * kSubProducts;
+  const size_t count = combos * kSubProducts * kSubSplit;
+  const int part = bt.gib % kSubSplit;
+  u32* slot = lds + (size_t)(bt.gib / kSubSplit * 2 + (part & 1)) * EL;
   for (size_t base = bt.first(); base < count; base += bt.stride()) {
-    const size_t it = base + bt.gib;
-    const bool active = it < count;
+    const size_t grp = base + bt.gib;
+    const bool active = grp < count;
+    const size_t it = grp / kSubSplit;
     const size_t combo = active ? it / kSubProducts : 0;
     const int sub = active ? (int)(it - combo * kSubProducts) : 0;
     const bool is_hi = sub < kHiCount;
     const size_t key0 = combo * kMags + (is_hi ? (size_t)sub * kLoCount : (size_t)(sub - kHiCount));
     const size_t stride = is_hi ? 1 : kLoCount;
-    const int n = active ? (is_hi ? kLoCount : kHiCount) : 0;
-    // factor e of this item, or null when its bucket is empty or the item is shorter
+    const int per = active ? (is_hi ? kLoCount : kHiCount) / kSubSplit : 0;  // factors of this group's share
+    const int e0 = part * per;
+    // factor e of this share, or null when its bucket is empty or the share is shorter
     auto locate = [&](int e) -> const u32* {
-      const size_t key = key0 + (size_t)e * stride;
-      return (e < n && cnt[key] != 0u) ? B + (size_t)off[key] * EL : nullptr;
+      const size_t key = key0 + (size_t)(e0 + e) * stride;
+      return (e < per && cnt[key] != 0u) ? B + (size_t)off[key] * EL : nullptr;
     };
     typename Ops::E acc;
     Ops::load(acc, one, g);
     const u32* next = locate(0);
+    bool any = false;
 #pragma unroll 1
-    for (int e = 0; e < kLoCount; ++e) {
+    for (int e = 0; e < kLoCount / kSubSplit; ++e) {
       // the next factor is located and touched while this one is multiplied
       const u32* cur = next;
-      next = (e + 1 < kLoCount) ? locate(e + 1) : nullptr;
+      next = (e + 1 < kLoCount / kSubSplit) ? locate(e + 1) : nullptr;
       const u32 touch = Ops::touch(next ? next : one, g);
       if (wave_any(cur != nullptr)) Ops::mul_mem(acc, cur ? cur : one, mod, g);
+      any = any || cur != nullptr;
       keep_live(touch);
     }
-    if (active) Ops::store(G + it * (size_t)EL, acc, g);
+    // shares 2, 3 hand theirs to shares 0, 1; then share 1 to share 0. Every group of a wavefront runs the
+    // products (the ones with nothing to take multiply by one), so that all lanes stay on the same path; the
+    // groups of an item sit in one wavefront, and a wavefront whose items are all empty (an unused digit
+    // position) skips them.
+    const bool work = wave_any(any);
+#pragma unroll 1
+    for (int half = kSubSplit / 2; half >= 1; half >>= 1) {
+      if (part >= half && part < 2 * half) Ops::store(slot, acc, g);
+      __syncthreads();
+      if (work) Ops::mul_mem(acc, part < half ? (const u32*)(slot + (size_t)(half == 1 ? 1 : 0) * EL) : one, mod, g);
+      __syncthreads();
+    }
+    if (active && part == 0) Ops::store(G + it * (size_t)EL, acc, g);
   }
 }
 
@@ -706,7 +691,7 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
     u32* cp = ws + p.off_pairs;
     const LaunchShape sh = launch_shape(ctx, rows, lanes, 8);
 #define CALL(LPT, T)                                                                                              \
-  HAFLO_LAUNCH((k_bk_to_pairs<LPT, T>), sh, st, M, (const u32*)(mh.d_pairs + (size_t)kConstR4 * 2 * mh.nl),     \
+  HAFLO_LAUNCH((k_to_pairs<LPT, T>), sh, st, M, (const u32*)(mh.d_pairs + (size_t)kConstR4 * 2 * mh.nl),     \
                (const u32*)(mh.d_pairs + (size_t)kConstR5 * 2 * mh.nl), d_c, rows, cp)
     HAFLO_DISPATCH_PAIRS(mh, CALL);
 #undef CALL
@@ -757,7 +742,7 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
 #define CALL_N(LPT, T)                                                                                  \
   HAFLO_LAUNCH((k_bk_sub<LPT, T, false>), sh, st, M, one, (const u32*)(ws + p.off_arena[0]),           \
                (const u32*)(ws + p.off_arena[1]), (const u32*)cnt, (const u32*)offs(0), K, (const u32*)stats, combos, G)
-    TAIL(combos * kSubProducts, haflo::few_groups(ctx, combos * kSubProducts, 64));
+    TAIL(combos * kSubProducts * kSubSplit, haflo::few_groups(ctx, combos * kSubProducts * kSubSplit, 64));
 #undef CALL_P
 #undef CALL_N
   }

@@ -386,6 +386,52 @@ struct ElemOps {
   }
 };
 
+
+// A stored ciphertext (Montgomery form modulo n^2 at the full radix R_N, 2 LPT T limbs at `w`) into the pair
+// form modulo n (Montgomery form at the half radix R): W = w_lo + R w_hi goes to
+// (w_lo, 0) k_lo + (w_hi, 0) k_hi with the pair constants k_lo = R^2 / R_N and k_hi = R^3 / R_N. The result is
+// lazy (each half below 4n, limbs partially normalised), which is what a product takes.
+template <int LPT, int T>
+__device__ __forceinline__ void to_pair(u32 (&x0)[LPT], u32 (&x1)[LPT], const u32* w, const u32* k_lo, const u32* k_hi,
+                                        const ModRegs<LPT>& mod, const Grp<T>& g) {
+  constexpr int NLH = LPT * T;
+  u32 b0[LPT], b1[LPT];
+  load_limbs<LPT, T>(x0, w, g);
+  load_limbs<LPT, T>(b0, w + NLH, g);
+  zero_limbs<LPT>(x1);
+  zero_limbs<LPT>(b1);
+  pairmul_mem<LPT, T>(x0, x1, x0, x1, k_lo, mod.n, mod.n0inv, g);
+  pairmul_mem<LPT, T>(b0, b1, b0, b1, k_hi, mod.n, mod.n0inv, g);
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) {
+    x0[j] += b0[j];
+    x1[j] += b1[j];
+  }
+  partial_norm<LPT, T>(x0, g);
+  partial_norm<LPT, T>(x1, g);
+}
+template <int LPT, int T>
+__global__ __launch_bounds__(kBlockThreads, 4) void k_to_pairs(ModRef M, const u32* __restrict__ k_lo,
+                                                               const u32* __restrict__ k_hi,
+                                                               const u32* __restrict__ in, size_t count,
+                                                               u32* __restrict__ out) {
+  constexpr int NLH = LPT * T;
+  Grp<T> g;
+  Batch<T> bt;
+  ModRegs<LPT> mod;
+  load_mod<LPT, T>(mod, M, g);
+  for (size_t base = bt.first(); base < count; base += bt.stride()) {
+    const size_t it = base + bt.gib;
+    const bool active = it < count;
+    u32 a0[LPT], a1[LPT];
+    to_pair<LPT, T>(a0, a1, in + (active ? it : 0) * (size_t)(2 * NLH), k_lo, k_hi, mod, g);
+    if (active) {
+      store_limbs<LPT, T>(out + it * (size_t)(2 * NLH), a0, g);
+      store_limbs<LPT, T>(out + it * (size_t)(2 * NLH) + NLH, a1, g);
+    }
+  }
+}
+
 }  // namespace dev
 }  // namespace haflo
 

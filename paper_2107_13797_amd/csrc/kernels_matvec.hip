@@ -284,8 +284,10 @@ __global__ __launch_bounds__(kBlockThreads) void k_maxmag(const int* __restrict_
     u32 mag = x < 0 ? 0u - (u32)x : (u32)x;
     m = mag > m ? mag : m;
   }
+  // the word only grows: a wavefront whose maximum is already there leaves it alone, so the atomics on the one
+  // address stay few
   const u32 best = wave_max(m);
-  if ((threadIdx.x & (WAVE - 1)) == 0 && best) atomicMax(maxmag, best);
+  if ((threadIdx.x & (WAVE - 1)) == 0 && best > *(volatile u32*)maxmag) atomicMax(maxmag, best);
 }
 __device__ __forceinline__ int bit_length(u32 v) { return v ? 32 - __builtin_clz(v) : 0; }
 
@@ -447,60 +449,78 @@ __global__ __launch_bounds__(kBlockThreads) void k_xtd_finish(ModRef M, ModRef M
 // ---------------------------------------------------------------------------
 
 // Positional tables T[j][sign][s][d] = b^(d 256^s), b = c_j or its inverse, d = 1..255, in two steps.
-// Step 1, one group per (j, sign, s): b^(256^s) by 8 s squarings, then the chains d = 1..16 and
-// d = 32, 48, .., 240. Step 2, one group per remaining entry: T[16 hi + lo] = T[16 hi] * T[lo].
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_xw_tables(ModRef M, const u32* __restrict__ bases,
+// Step 1, one group per (j, sign, s) and per entry d = 1..16 and d = 32, 48, .., 240: x = b^(256^s) by 8 s
+// squarings, for the multiples of 16 four more (x^16), then x^k, k <= 16, by binary exponentiation: a chain of
+// at most 8 s + 12 products, where one group per table would run 8 s + 29. Step 2, one group per remaining
+// entry: T[16 hi + lo] = T[16 hi] * T[lo].
+// PAIR: the tables are in the pair form modulo M (see Elem); the bases, stored ciphertexts, are taken into it
+// as they are loaded (k_lo, k_hi: see to_pair).
+constexpr int kXwStep1 = kWinLow + (kWinEntries / kWinLow - 2);  // 16 + 14 entries per table in step 1
+template <int LPT, int T, bool PAIR>
+__global__ __launch_bounds__(kBlockThreads) void k_xw_tables(ModRef M, const u32* __restrict__ k_lo,
+                                                             const u32* __restrict__ k_hi,
+                                                             const u32* __restrict__ bases,
                                                              const u32* __restrict__ invbases, size_t cols,
                                                              u32* __restrict__ tables,
                                                              const u32* __restrict__ maxmag) {
-  constexpr int NL = LPT * T;
+  using Ops = ElemOps<LPT, T, PAIR>;
+  constexpr int EL = Ops::kLimbs;
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
   const int npos = (bit_length(*maxmag) + kWin - 1) / kWin;
-  const size_t count = cols * 2 * (size_t)npos;
+  const size_t count = cols * 2 * (size_t)npos * (size_t)kXwStep1;
   for (size_t base = bt.first(); base < count; base += bt.stride()) {
     const size_t it = base + bt.gib;
     const bool active = it < count;
-    const size_t item = active ? it / (size_t)npos : 0;  // j * 2 + sign
-    const int s = active ? (int)(it - item * (size_t)npos) : 0;
+    const size_t tab = active ? it / (size_t)kXwStep1 : 0;  // (j * 2 + sign) * npos + s
+    const int e = active ? (int)(it - tab * (size_t)kXwStep1) : 0;
+    const size_t item = tab / (size_t)(npos ? npos : 1);    // j * 2 + sign
+    const int s = (int)(tab - item * (size_t)(npos ? npos : 1));
+    const bool multiple = e >= kWinLow;                     // entry 16 k, k = 2..15; else entry k, k = 1..16
+    const int k = multiple ? e - kWinLow + 2 : e + 1;
     const u32* src = (item & 1) ? invbases : bases;
-    u32 b[LPT], cur[LPT], step[LPT];
-    load_limbs<LPT, T>(b, src + (item >> 1) * (size_t)NL, g);
+    typename Ops::E x, acc, t;
+    if constexpr (PAIR) to_pair<LPT, T>(x.x0, x.x1, src + (item >> 1) * (size_t)EL, k_lo, k_hi, mod, g);
+    else Ops::load(x, src + (item >> 1) * (size_t)EL, g);
+    // every group of a wavefront runs the same products; the ones that do not need one discard it
+    const int nsq = kWin * s + (multiple ? 4 : 0);
 #pragma unroll 1
-    for (int i = 0; wave_any(i < kWin * s); ++i) {
-      u32 t[LPT];
-      montsqr<LPT, T>(t, b, mod.n, mod.n0inv, g);
-      if (i < kWin * s) {
-#pragma unroll
-        for (int jj = 0; jj < LPT; ++jj) b[jj] = t[jj];
+    for (int i = 0; wave_any(i < nsq); ++i) {
+      Ops::copy(t, x);
+      Ops::sqr(t, mod, g);
+      if (i < nsq) Ops::copy(x, t);
+    }
+    Ops::copy(acc, x);
+    bool started = false;
+#pragma unroll 1
+    for (int bit = 4; bit >= 0; --bit) {
+      if (wave_any(started)) {
+        Ops::copy(t, acc);
+        Ops::sqr(t, mod, g);
+        if (started) Ops::copy(acc, t);
       }
+      const bool set = ((k >> bit) & 1) != 0;
+      const bool need = set && started;
+      if (wave_any(need)) {
+        Ops::copy(t, acc);
+        Ops::mul(t, x, mod, g);
+        if (need) Ops::copy(acc, t);
+      }
+      started = started || set;
     }
-    u32* tb = tables + ((item * (size_t)kMaxPos + (size_t)s) * (size_t)kWinEntries) * NL;
-    if (active) store_limbs<LPT, T>(tb + NL, b, g);
-#pragma unroll
-    for (int jj = 0; jj < LPT; ++jj) cur[jj] = b[jj];
-#pragma unroll 1
-    for (int dgt = 2; dgt <= kWinLow; ++dgt) {
-      montmul<LPT, T>(cur, cur, b, mod.n, mod.n0inv, g);
-      if (active) store_limbs<LPT, T>(tb + (size_t)dgt * NL, cur, g);
-    }
-#pragma unroll
-    for (int jj = 0; jj < LPT; ++jj) step[jj] = cur[jj];  // b^16
-#pragma unroll 1
-    for (int dgt = 2 * kWinLow; dgt < kWinEntries; dgt += kWinLow) {
-      montmul<LPT, T>(cur, cur, step, mod.n, mod.n0inv, g);
-      if (active) store_limbs<LPT, T>(tb + (size_t)dgt * NL, cur, g);
-    }
+    u32* tb = tables + ((item * (size_t)kMaxPos + (size_t)s) * (size_t)kWinEntries) * EL;
+    if (active) Ops::store(tb + (size_t)(multiple ? kWinLow * k : k) * EL, acc, g);
   }
 }
 
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_xw_tables_fill(ModRef M, size_t cols, u32* __restrict__ tables,
+template <int LPT, int T, bool PAIR>
+__global__ __launch_bounds__(kBlockThreads) void k_xw_tables_fill(ModRef M, const u32* __restrict__ one, size_t cols,
+                                                                  u32* __restrict__ tables,
                                                                   const u32* __restrict__ maxmag) {
-  constexpr int NL = LPT * T;
+  using Ops = ElemOps<LPT, T, PAIR>;
+  constexpr int EL = Ops::kLimbs;
   constexpr int kHi = kWinEntries / kWinLow - 1, kLo = kWinLow - 1;  // 15 x 15 entries per table
   Grp<T> g;
   Batch<T> bt;
@@ -516,12 +536,11 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_tables_fill(ModRef M, size
     const int hi = e / kLo + 1, lo = e % kLo + 1;
     const size_t item = tab / (size_t)(npos ? npos : 1);
     const int s = (int)(tab - item * (size_t)(npos ? npos : 1));
-    u32* tb = tables + ((item * (size_t)kMaxPos + (size_t)s) * (size_t)kWinEntries) * NL;
-    u32 a[LPT];
-    if (active) load_limbs<LPT, T>(a, tb + (size_t)(hi * kWinLow) * NL, g);
-    else zero_limbs<LPT>(a);
-    montmul_mem<LPT, T>(a, a, active ? tb + (size_t)lo * NL : M.r1, mod.n, mod.n0inv, g);
-    if (active) store_limbs<LPT, T>(tb + (size_t)(hi * kWinLow + lo) * NL, a, g);
+    u32* tb = tables + ((item * (size_t)kMaxPos + (size_t)s) * (size_t)kWinEntries) * EL;
+    typename Ops::E a;
+    Ops::load(a, active ? tb + (size_t)(hi * kWinLow) * EL : one, g);
+    Ops::mul_mem(a, active ? tb + (size_t)lo * EL : one, mod, g);
+    if (active) Ops::store(tb + (size_t)(hi * kWinLow + lo) * EL, a, g);
   }
 }
 
@@ -634,15 +653,37 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_order_scan(u32* __restrict
 // its lazy partial product to partial[row][segment] for k_xw_combine. Work items are taken in the order
 // `order` (rows with the longest lists first): a wavefront takes the run of its own index first, then
 // runs drawn from a counter (zero at launch), so that long lists do not leave the rest of the chip waiting.
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads, 3) void k_xw_main(ModRef M, size_t rows, size_t list_stride,
-                                                           const u32* __restrict__ lists,
+// PAIR: the table entries are pairs modulo M (see Elem); a finished product leaves the pair form (`leave` = the
+// pair constant R_N) and is stored as the canonical integer, the form of a stored ciphertext.
+template <int LPT, int T, bool PAIR>
+__device__ __forceinline__ void xw_store_result(u32* dst, Elem<LPT, PAIR>& acc, bool active, const u32* leave,
+                                                const ModRegs<LPT>& mod, const Grp<T>& g) {
+  if constexpr (PAIR) {
+    pairmul_mem<LPT, T>(acc.x0, acc.x1, acc.x0, acc.x1, leave, mod.n, mod.n0inv, g);
+    pair_canonical<LPT, T>(acc.x0, acc.x1, mod.n, g);
+    u32 lo[LPT], hi[LPT];
+    pair_to_integer<LPT, T>(lo, hi, acc.x0, acc.x1, mod.n, g);
+    if (active) {
+      store_limbs<LPT, T>(dst, lo, g);
+      store_limbs<LPT, T>(dst + LPT * T, hi, g);
+    }
+  } else {
+    canonicalise<LPT, T>(acc.x0, mod.n, g);
+    if (active) store_limbs<LPT, T>(dst, acc.x0, g);
+  }
+}
+
+template <int LPT, int T, bool PAIR>
+__global__ __launch_bounds__(kBlockThreads, 3) void k_xw_main(ModRef M, const u32* __restrict__ one,
+                                                           const u32* __restrict__ leave, size_t rows,
+                                                           size_t list_stride, const u32* __restrict__ lists,
                                                            const u32* __restrict__ counts,
                                                            const u32* __restrict__ order,
                                                            const u32* __restrict__ tables, u32* __restrict__ next_item,
                                                            int seg_shift, u32* __restrict__ partial,
                                                            u32* __restrict__ out) {
-  constexpr int NL = LPT * T;
+  using Ops = ElemOps<LPT, T, PAIR>;
+  constexpr int EL = Ops::kLimbs;
   constexpr int GW = WAVE / T;
   Grp<T> g;
   ModRegs<LPT> mod;
@@ -660,22 +701,21 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_xw_main(ModRef M, size_t r
     const u32 cnt = active ? counts[row] : 0u;
     const u32 e0 = (u32)(((u64)cnt * seg) >> seg_shift), e1 = (u32)(((u64)cnt * (seg + 1u)) >> seg_shift);
     const u32* mine = lists + row * list_stride;
-    auto entry = [&](u32 e) -> const u32* { return (e < e1) ? tables + (size_t)mine[e] * NL : M.r1; };
-    u32 acc[LPT];
-    load_limbs<LPT, T>(acc, entry(e0), g);
+    auto entry = [&](u32 e) -> const u32* { return (e < e1) ? tables + (size_t)mine[e] * EL : one; };
+    typename Ops::E acc;
+    Ops::load(acc, entry(e0), g);
 #pragma unroll 1
     for (u32 e = e0 + 1; wave_any(e < e1); ++e) {
       // the next entry is looked up and touched while this one is multiplied; a group that has run out
       // of entries multiplies by one and stays in step with its wave
-      const u32 touch = entry(e + 1)[g.k * LPT];
-      montmul_mem<LPT, T>(acc, acc, entry(e), mod.n, mod.n0inv, g);
+      const u32 touch = Ops::touch(entry(e + 1), g);
+      Ops::mul_mem(acc, entry(e), mod, g);
       keep_live(touch);
     }
     if (seg_shift == 0) {
-      canonicalise<LPT, T>(acc, mod.n, g);
-      if (active) store_limbs<LPT, T>(out + row * (size_t)NL, acc, g);
+      xw_store_result<LPT, T, PAIR>(out + row * (size_t)EL, acc, active, leave, mod, g);
     } else if (active) {
-      store_limbs<LPT, T>(partial + ((row << seg_shift) + seg) * (size_t)NL, acc, g);
+      Ops::store(partial + ((row << seg_shift) + seg) * (size_t)EL, acc, g);
     }
     u32 drawn = 0;
     if (lane == 0) drawn = atomicAdd(next_item, (u32)GW);
@@ -684,10 +724,12 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_xw_main(ModRef M, size_t r
 }
 
 // out[row] = product of the row's 2^seg_shift partial products, canonical
-template <int LPT, int T>
-__global__ __launch_bounds__(kBlockThreads) void k_xw_combine(ModRef M, size_t rows, int seg_shift,
-                                                              const u32* __restrict__ partial, u32* __restrict__ out) {
-  constexpr int NL = LPT * T;
+template <int LPT, int T, bool PAIR>
+__global__ __launch_bounds__(kBlockThreads) void k_xw_combine(ModRef M, const u32* __restrict__ leave, size_t rows,
+                                                              int seg_shift, const u32* __restrict__ partial,
+                                                              u32* __restrict__ out) {
+  using Ops = ElemOps<LPT, T, PAIR>;
+  constexpr int EL = Ops::kLimbs;
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
@@ -695,14 +737,12 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_combine(ModRef M, size_t r
   for (size_t base = bt.first(); base < rows; base += bt.stride()) {
     const size_t row = base + bt.gib;
     const bool active = row < rows;
-    const u32* mine = partial + ((active ? row : 0) << seg_shift) * (size_t)NL;
-    u32 acc[LPT];
-    load_limbs<LPT, T>(acc, mine, g);
+    const u32* mine = partial + ((active ? row : 0) << seg_shift) * (size_t)EL;
+    typename Ops::E acc;
+    Ops::load(acc, mine, g);
 #pragma unroll 1
-    for (int sgm = 1; sgm < (1 << seg_shift); ++sgm)
-      montmul_mem<LPT, T>(acc, acc, mine + (size_t)sgm * NL, mod.n, mod.n0inv, g);
-    canonicalise<LPT, T>(acc, mod.n, g);
-    if (active) store_limbs<LPT, T>(out + row * (size_t)NL, acc, g);
+    for (int sgm = 1; sgm < (1 << seg_shift); ++sgm) Ops::mul_mem(acc, mine + (size_t)sgm * EL, mod, g);
+    xw_store_result<LPT, T, PAIR>(out + (active ? row : 0) * (size_t)EL, acc, active, leave, mod, g);
   }
 }
 
@@ -821,7 +861,7 @@ int launch_maxmag(const haflo_ctx* ctx, const int32_t* X, size_t total, u32* wor
   one.gpb = kBlockThreads;
   HAFLO_LAUNCH(k_zero_word, one, st, word, zero_words);
   if (total) {
-    LaunchShape sh = launch_shape(ctx, total, 1, 8);
+    LaunchShape sh = launch_shape(ctx, (total + 15) / 16, 1, 8);  // sixteen entries per lane: few wavefronts, few atomics
     HAFLO_LAUNCH(k_maxmag, sh, st, X, total, word);
   }
   return hip_status(hipGetLastError());
@@ -954,23 +994,41 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
     u32* tables = ws + p.off_tables;
     u32* lists = ws + p.off_nz;
     u32* cnt = ws + p.off_cnt;
+    // The tables and the row products are in the pair form modulo n (5/8 of the limb products of a full-length
+    // product) wherever the key size has that geometry; a row's result leaves it as it is stored.
+    const bool pairs = haflo_has_pair_geometry(ctx->Nh);
+    const ModHost& mh = ctx->Nh;
+    const ModRef M = pairs ? mh.ref() : m.ref();
+    const int lanes = pairs ? 2 * mh.t : m.t;
+    const u32* one = pairs ? (const u32*)(mh.d_pairs + (size_t)kConstR1 * 2 * mh.nl) : (const u32*)m.ref().r1;
+    const u32* leave = pairs ? (const u32*)(mh.d_pairs + (size_t)kConstR3 * 2 * mh.nl) : (const u32*)nullptr;
     if (cols) {
       rc = invert_batch(ctx, (const u32*)d_c, inv, cols, st);
       if (rc != HAFLO_OK) return rc;
       {
-        const size_t groups = cols * 2 * kMaxPos;
+        const size_t groups = cols * 2 * kMaxPos * kXwStep1;
         const bool wide = haflo::few_groups(ctx, groups, 32);
-        const LaunchShape sh = launch_shape(ctx, groups, wide ? haflo_wide_lanes(m) : m.t, 8);
-#define CALL(LPT, T) \
-  HAFLO_LAUNCH((k_xw_tables<LPT, T>), sh, st, m.ref(), (const u32*)d_c, (const u32*)inv, cols, tables, (const u32*)ws)
-        if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL); }
-#undef CALL
+        const LaunchShape sh = launch_shape(ctx, groups, pairs ? lanes : (wide ? haflo_wide_lanes(m) : m.t), 8);
+#define CALL_P(LPT, T)                                                                                           \
+  HAFLO_LAUNCH((k_xw_tables<LPT, T, true>), sh, st, M, (const u32*)(mh.d_pairs + (size_t)kConstR4 * 2 * mh.nl), \
+               (const u32*)(mh.d_pairs + (size_t)kConstR5 * 2 * mh.nl), (const u32*)d_c, (const u32*)inv, cols,  \
+               tables, (const u32*)ws)
+#define CALL_N(LPT, T)                                                                                  \
+  HAFLO_LAUNCH((k_xw_tables<LPT, T, false>), sh, st, M, (const u32*)nullptr, (const u32*)nullptr,      \
+               (const u32*)d_c, (const u32*)inv, cols, tables, (const u32*)ws)
+        if (pairs) { HAFLO_DISPATCH_PAIRS(mh, CALL_P); }
+        else if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL_N); }
+        else { HAFLO_DISPATCH_GEOMETRY(m, CALL_N); }
+#undef CALL_P
+#undef CALL_N
       }
       {
-        const LaunchShape sh = launch_shape(ctx, cols * 2 * kMaxPos * 225, m.t, 8);
-#define CALL(LPT, T) HAFLO_LAUNCH((k_xw_tables_fill<LPT, T>), sh, st, m.ref(), cols, tables, (const u32*)ws)
-        HAFLO_DISPATCH_GEOMETRY(m, CALL);
-#undef CALL
+        const LaunchShape sh = launch_shape(ctx, cols * 2 * kMaxPos * 225, lanes, 8);
+#define CALL_P(LPT, T) HAFLO_LAUNCH((k_xw_tables_fill<LPT, T, true>), sh, st, M, one, cols, tables, (const u32*)ws)
+#define CALL_N(LPT, T) HAFLO_LAUNCH((k_xw_tables_fill<LPT, T, false>), sh, st, M, one, cols, tables, (const u32*)ws)
+        if (pairs) { HAFLO_DISPATCH_PAIRS(mh, CALL_P); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL_N); }
+#undef CALL_P
+#undef CALL_N
       }
     }
     u32* bins = ws + kXwBinsAt;
@@ -978,31 +1036,36 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
     {
       const LaunchShape sh = launch_shape(ctx, rows, 64, 8);
       HAFLO_LAUNCH(k_xw_lists, sh, st, d_X, rows, cols, lists, cnt, (const u32*)ws);
-      LaunchShape per_row, one;
-      per_row.threads = one.threads = kBlockThreads;
-      per_row.gpb = one.gpb = kBlockThreads;
+      LaunchShape per_row, single;
+      per_row.threads = single.threads = kBlockThreads;
+      per_row.gpb = single.gpb = kBlockThreads;
       per_row.blocks = (int)std::min((rows + kBlockThreads - 1) / kBlockThreads, (size_t)ctx->num_cu * 8);
-      one.blocks = 1;
+      single.blocks = 1;
       HAFLO_LAUNCH(k_xw_order<false>, per_row, st, (const u32*)cnt, rows, cols, bins, order, (const u32*)ws);
-      HAFLO_LAUNCH(k_xw_order_scan, one, st, bins);
+      HAFLO_LAUNCH(k_xw_order_scan, single, st, bins);
       HAFLO_LAUNCH(k_xw_order<true>, per_row, st, (const u32*)cnt, rows, cols, bins, order, (const u32*)ws);
     }
     u32* partial = ws + p.off_partial;
     {
-      const LaunchShape sh = launch_shape(ctx, rows << p.seg_shift, m.t, 3);
-#define CALL(LPT, T)                                                                                          \
-  HAFLO_LAUNCH((k_xw_main<LPT, T>), sh, st, m.ref(), rows, cols * (size_t)kMaxPos, (const u32*)lists,         \
-               (const u32*)cnt, (const u32*)order, (const u32*)tables, ws + 1, p.seg_shift, partial,          \
-               (u32*)d_out)
-      HAFLO_DISPATCH_GEOMETRY(m, CALL);
-#undef CALL
+      const LaunchShape sh = launch_shape(ctx, rows << p.seg_shift, lanes, 3);
+#define CALL_ARGS M, one, leave, rows, cols * (size_t)kMaxPos, (const u32*)lists, (const u32*)cnt, (const u32*)order, \
+                  (const u32*)tables, ws + 1, p.seg_shift, partial, (u32*)d_out
+#define CALL_P(LPT, T) HAFLO_LAUNCH((k_xw_main<LPT, T, true>), sh, st, CALL_ARGS)
+#define CALL_N(LPT, T) HAFLO_LAUNCH((k_xw_main<LPT, T, false>), sh, st, CALL_ARGS)
+      if (pairs) { HAFLO_DISPATCH_PAIRS(mh, CALL_P); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL_N); }
+#undef CALL_P
+#undef CALL_N
+#undef CALL_ARGS
     }
     if (p.seg_shift) {
-      const LaunchShape sh = launch_shape(ctx, rows, m.t, 8);
-#define CALL(LPT, T) \
-  HAFLO_LAUNCH((k_xw_combine<LPT, T>), sh, st, m.ref(), rows, p.seg_shift, (const u32*)partial, (u32*)d_out)
-      HAFLO_DISPATCH_GEOMETRY(m, CALL);
-#undef CALL
+      const LaunchShape sh = launch_shape(ctx, rows, lanes, 8);
+#define CALL_P(LPT, T) \
+  HAFLO_LAUNCH((k_xw_combine<LPT, T, true>), sh, st, M, leave, rows, p.seg_shift, (const u32*)partial, (u32*)d_out)
+#define CALL_N(LPT, T) \
+  HAFLO_LAUNCH((k_xw_combine<LPT, T, false>), sh, st, M, leave, rows, p.seg_shift, (const u32*)partial, (u32*)d_out)
+      if (pairs) { HAFLO_DISPATCH_PAIRS(mh, CALL_P); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL_N); }
+#undef CALL_P
+#undef CALL_N
     }
   }
   return hip_status(hipGetLastError());
