@@ -377,7 +377,7 @@ def test_edges_scalar_mul(api, bits):
 
 
 @pytest.mark.parametrize("method", ["tables", "buckets"])
-@pytest.mark.parametrize("bits", [512, 2048])
+@pytest.mark.parametrize("bits", [512, 1024, 2048, 4096])
 def test_edges_matvec(api, bits, method):
     ctx, sk = context(api, bits)
     with xtd_method(api, ctx, method):
