@@ -28,7 +28,6 @@ namespace {
 constexpr int kWin = 8;                    // window width of the exponent digits
 constexpr int kWinEntries = 1 << kWin;     // table entries per base and position (entry 0 unused)
 constexpr int kMaxPos = (32 + kWin - 1) / kWin;  // digit positions of a 32-bit magnitude
-constexpr int kWinLow = 16;                // digit = kWinLow * hi + lo in the table construction
 
 // Orientation 0: signed 5-bit digits. |x| + c, c = 16 (32^S - 1) / 31, is read in base 32 and
 // each digit e is taken as d = e - 16 in [-16, 15], so |x| = sum d_s 32^s: the table holds only
@@ -448,21 +447,19 @@ __global__ __launch_bounds__(kBlockThreads) void k_xtd_finish(ModRef M, ModRef M
 // orientation 1: out[i] = prod_j c_j^X[i][j]
 // ---------------------------------------------------------------------------
 
-// Positional tables T[j][sign][s][d] = b^(d 256^s), b = c_j or its inverse, d = 1..255, in two steps.
-// Step 1, one group per (j, sign, s) and per entry d = 1..16 and d = 32, 48, .., 240: x = b^(256^s) by 8 s
-// squarings, for the multiples of 16 four more (x^16), then x^k, k <= 16, by binary exponentiation: a chain of
-// at most 8 s + 12 products, where one group per table would run 8 s + 29. Step 2, one group per remaining
-// entry: T[16 hi + lo] = T[16 hi] * T[lo].
+// Positional tables T[j][sign][s][d] = b^(d 256^s), b = c_j or its inverse, d = 1..255.
+// k_xw_positions, one group per (j, sign, s): T[1] = b^(256^s) by 8 s squarings. Then eight launches of
+// k_xw_level with B = 1, 2, 4, .., 128, one group per entry d in (B, 2 B]: T[d] = T[d - B] * T[B]. Every entry
+// costs one product and the chain is 8 s + 8 products long.
 // PAIR: the tables are in the pair form modulo M (see Elem); the bases, stored ciphertexts, are taken into it
 // as they are loaded (k_lo, k_hi: see to_pair).
-constexpr int kXwStep1 = kWinLow + (kWinEntries / kWinLow - 2);  // 16 + 14 entries per table in step 1
 template <int LPT, int T, bool PAIR>
-__global__ __launch_bounds__(kBlockThreads) void k_xw_tables(ModRef M, const u32* __restrict__ k_lo,
-                                                             const u32* __restrict__ k_hi,
-                                                             const u32* __restrict__ bases,
-                                                             const u32* __restrict__ invbases, size_t cols,
-                                                             u32* __restrict__ tables,
-                                                             const u32* __restrict__ maxmag) {
+__global__ __launch_bounds__(kBlockThreads) void k_xw_positions(ModRef M, const u32* __restrict__ k_lo,
+                                                                const u32* __restrict__ k_hi,
+                                                                const u32* __restrict__ bases,
+                                                                const u32* __restrict__ invbases, size_t cols,
+                                                                u32* __restrict__ tables,
+                                                                const u32* __restrict__ maxmag) {
   using Ops = ElemOps<LPT, T, PAIR>;
   constexpr int EL = Ops::kLimbs;
   Grp<T> g;
@@ -470,77 +467,53 @@ __global__ __launch_bounds__(kBlockThreads) void k_xw_tables(ModRef M, const u32
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
   const int npos = (bit_length(*maxmag) + kWin - 1) / kWin;
-  const size_t count = cols * 2 * (size_t)npos * (size_t)kXwStep1;
+  const size_t count = cols * 2 * (size_t)npos;
   for (size_t base = bt.first(); base < count; base += bt.stride()) {
     const size_t it = base + bt.gib;
     const bool active = it < count;
-    const size_t tab = active ? it / (size_t)kXwStep1 : 0;  // (j * 2 + sign) * npos + s
-    const int e = active ? (int)(it - tab * (size_t)kXwStep1) : 0;
-    const size_t item = tab / (size_t)(npos ? npos : 1);    // j * 2 + sign
-    const int s = (int)(tab - item * (size_t)(npos ? npos : 1));
-    const bool multiple = e >= kWinLow;                     // entry 16 k, k = 2..15; else entry k, k = 1..16
-    const int k = multiple ? e - kWinLow + 2 : e + 1;
+    const size_t item = active ? it / (size_t)npos : 0;  // j * 2 + sign
+    const int s = active ? (int)(it - item * (size_t)npos) : 0;
     const u32* src = (item & 1) ? invbases : bases;
-    typename Ops::E x, acc, t;
+    typename Ops::E x, t;
     if constexpr (PAIR) to_pair<LPT, T>(x.x0, x.x1, src + (item >> 1) * (size_t)EL, k_lo, k_hi, mod, g);
     else Ops::load(x, src + (item >> 1) * (size_t)EL, g);
-    // every group of a wavefront runs the same products; the ones that do not need one discard it
-    const int nsq = kWin * s + (multiple ? 4 : 0);
+    // every group of a wavefront runs the same squarings; the ones that are done discard theirs
 #pragma unroll 1
-    for (int i = 0; wave_any(i < nsq); ++i) {
+    for (int i = 0; wave_any(i < kWin * s); ++i) {
       Ops::copy(t, x);
       Ops::sqr(t, mod, g);
-      if (i < nsq) Ops::copy(x, t);
-    }
-    Ops::copy(acc, x);
-    bool started = false;
-#pragma unroll 1
-    for (int bit = 4; bit >= 0; --bit) {
-      if (wave_any(started)) {
-        Ops::copy(t, acc);
-        Ops::sqr(t, mod, g);
-        if (started) Ops::copy(acc, t);
-      }
-      const bool set = ((k >> bit) & 1) != 0;
-      const bool need = set && started;
-      if (wave_any(need)) {
-        Ops::copy(t, acc);
-        Ops::mul(t, x, mod, g);
-        if (need) Ops::copy(acc, t);
-      }
-      started = started || set;
+      if (i < kWin * s) Ops::copy(x, t);
     }
     u32* tb = tables + ((item * (size_t)kMaxPos + (size_t)s) * (size_t)kWinEntries) * EL;
-    if (active) Ops::store(tb + (size_t)(multiple ? kWinLow * k : k) * EL, acc, g);
+    if (active) Ops::store(tb + EL, x, g);
   }
 }
 
 template <int LPT, int T, bool PAIR>
-__global__ __launch_bounds__(kBlockThreads) void k_xw_tables_fill(ModRef M, const u32* __restrict__ one, size_t cols,
-                                                                  u32* __restrict__ tables,
-                                                                  const u32* __restrict__ maxmag) {
+__global__ __launch_bounds__(kBlockThreads) void k_xw_level(ModRef M, const u32* __restrict__ one, size_t cols, int B,
+                                                            u32* __restrict__ tables,
+                                                            const u32* __restrict__ maxmag) {
   using Ops = ElemOps<LPT, T, PAIR>;
   constexpr int EL = Ops::kLimbs;
-  constexpr int kHi = kWinEntries / kWinLow - 1, kLo = kWinLow - 1;  // 15 x 15 entries per table
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
   const int npos = (bit_length(*maxmag) + kWin - 1) / kWin;
-  const size_t count = cols * 2 * (size_t)npos * (size_t)(kHi * kLo);
+  const int per = B < kWinEntries - 1 - B ? B : kWinEntries - 1 - B;  // entries B + 1 .. min(2 B, 255)
+  const size_t count = cols * 2 * (size_t)npos * (size_t)per;
   for (size_t base = bt.first(); base < count; base += bt.stride()) {
     const size_t it = base + bt.gib;
     const bool active = it < count;
-    const size_t tab = active ? it / (size_t)(kHi * kLo) : 0;  // (j * 2 + sign) * npos + s
-    const int e = active ? (int)(it - tab * (size_t)(kHi * kLo)) : 0;
-    const int hi = e / kLo + 1, lo = e % kLo + 1;
+    const size_t tab = active ? it / (size_t)per : 0;  // (j * 2 + sign) * npos + s
+    const int d = B + 1 + (active ? (int)(it - tab * (size_t)per) : 0);
     const size_t item = tab / (size_t)(npos ? npos : 1);
     const int s = (int)(tab - item * (size_t)(npos ? npos : 1));
     u32* tb = tables + ((item * (size_t)kMaxPos + (size_t)s) * (size_t)kWinEntries) * EL;
     typename Ops::E a;
-    Ops::load(a, active ? tb + (size_t)(hi * kWinLow) * EL : one, g);
-    Ops::mul_mem(a, active ? tb + (size_t)lo * EL : one, mod, g);
-    if (active) Ops::store(tb + (size_t)(hi * kWinLow + lo) * EL, a, g);
+    Ops::load(a, active ? tb + (size_t)(d - B) * EL : one, g);
+    Ops::mul_mem(a, active ? tb + (size_t)B * EL : one, mod, g);
+    if (active) Ops::store(tb + (size_t)d * EL, a, g);
   }
 }
 
@@ -827,7 +800,7 @@ constexpr size_t kXwBinsAt = 64;
 // Segments per row: doubled while the chip would hold fewer than four wavefronts per SIMD, up to 8
 // and while a full row still gives every segment a few entries.
 int xw_seg_shift(const haflo_ctx* ctx, size_t rows, size_t cols) {
-  const size_t per_wave = (size_t)(64 / ctx->N.t), want_waves = (size_t)ctx->num_cu * 16;
+  const size_t per_wave = (size_t)(64 / ctx->N.t), want_waves = (size_t)ctx->num_cu * 32;
   int sh = 0;
   while (sh < 3 && (rows << sh) < want_waves * per_wave && cols >= ((size_t)4 << sh)) ++sh;
   return sh;
@@ -1006,15 +979,15 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
       rc = invert_batch(ctx, (const u32*)d_c, inv, cols, st);
       if (rc != HAFLO_OK) return rc;
       {
-        const size_t groups = cols * 2 * kMaxPos * kXwStep1;
+        const size_t groups = cols * 2 * kMaxPos;
         const bool wide = haflo::few_groups(ctx, groups, 32);
         const LaunchShape sh = launch_shape(ctx, groups, pairs ? lanes : (wide ? haflo_wide_lanes(m) : m.t), 8);
-#define CALL_P(LPT, T)                                                                                           \
-  HAFLO_LAUNCH((k_xw_tables<LPT, T, true>), sh, st, M, (const u32*)(mh.d_pairs + (size_t)kConstR4 * 2 * mh.nl), \
-               (const u32*)(mh.d_pairs + (size_t)kConstR5 * 2 * mh.nl), (const u32*)d_c, (const u32*)inv, cols,  \
+#define CALL_P(LPT, T)                                                                                              \
+  HAFLO_LAUNCH((k_xw_positions<LPT, T, true>), sh, st, M, (const u32*)(mh.d_pairs + (size_t)kConstR4 * 2 * mh.nl), \
+               (const u32*)(mh.d_pairs + (size_t)kConstR5 * 2 * mh.nl), (const u32*)d_c, (const u32*)inv, cols,     \
                tables, (const u32*)ws)
 #define CALL_N(LPT, T)                                                                                  \
-  HAFLO_LAUNCH((k_xw_tables<LPT, T, false>), sh, st, M, (const u32*)nullptr, (const u32*)nullptr,      \
+  HAFLO_LAUNCH((k_xw_positions<LPT, T, false>), sh, st, M, (const u32*)nullptr, (const u32*)nullptr,   \
                (const u32*)d_c, (const u32*)inv, cols, tables, (const u32*)ws)
         if (pairs) { HAFLO_DISPATCH_PAIRS(mh, CALL_P); }
         else if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL_N); }
@@ -1022,11 +995,15 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
 #undef CALL_P
 #undef CALL_N
       }
-      {
-        const LaunchShape sh = launch_shape(ctx, cols * 2 * kMaxPos * 225, lanes, 8);
-#define CALL_P(LPT, T) HAFLO_LAUNCH((k_xw_tables_fill<LPT, T, true>), sh, st, M, one, cols, tables, (const u32*)ws)
-#define CALL_N(LPT, T) HAFLO_LAUNCH((k_xw_tables_fill<LPT, T, false>), sh, st, M, one, cols, tables, (const u32*)ws)
-        if (pairs) { HAFLO_DISPATCH_PAIRS(mh, CALL_P); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL_N); }
+      for (int B = 1; B < kWinEntries; B *= 2) {
+        const size_t groups = cols * 2 * kMaxPos * (size_t)std::min(B, kWinEntries - 1 - B);
+        const bool wide = haflo::few_groups(ctx, groups, 32);
+        const LaunchShape sh = launch_shape(ctx, groups, pairs ? lanes : (wide ? haflo_wide_lanes(m) : m.t), 8);
+#define CALL_P(LPT, T) HAFLO_LAUNCH((k_xw_level<LPT, T, true>), sh, st, M, one, cols, B, tables, (const u32*)ws)
+#define CALL_N(LPT, T) HAFLO_LAUNCH((k_xw_level<LPT, T, false>), sh, st, M, one, cols, B, tables, (const u32*)ws)
+        if (pairs) { HAFLO_DISPATCH_PAIRS(mh, CALL_P); }
+        else if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL_N); }
+        else { HAFLO_DISPATCH_GEOMETRY(m, CALL_N); }
 #undef CALL_P
 #undef CALL_N
       }
