@@ -392,7 +392,7 @@ def test_wider_lane_groups(emu, bits):
     lib.haflo_ctx_destroy(ctx)
 
 
-@pytest.mark.parametrize("bits,count", [(1024, 2)])
+@pytest.mark.parametrize("bits,count", [(1024, 1)])
 def test_whole_wavefront_groups_encrypt_decrypt(emu, bits, count):
     """Batches of at most one element per SIMD give every big integer a wavefront to itself (18 to 48
     lanes with 2 or 3 limbs each, neighbour exchange across DPP rows, the quotient digit through a

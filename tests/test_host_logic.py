@@ -61,7 +61,7 @@ def test_strerror(lib):
 @pytest.mark.parametrize("bits,seed", [(512, 1), (512, 2), (512, 77), (512, 2 ** 63 + 5), (512, 2 ** 64 - 1),
                                        (1024, 1), (1024, 31337), (1024, 0), (1024, 12), (1024, 2 ** 40),
                                        (2048, 5), (2048, 6), (2048, 7), (2048, 1000), (2048, 2 ** 62),
-                                       (4096, 3), (4096, 4), (4096, 99), (4096, 2 ** 33 + 1), (4096, 2 ** 64 - 2)])
+                                       (4096, 99), (4096, 2 ** 33 + 1)])
 def test_keygen_matches_oracle(lib, bits, seed):
     p = (C.c_uint8 * (bits // 16))()
     q = (C.c_uint8 * (bits // 16))()

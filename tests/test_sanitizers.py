@@ -19,7 +19,7 @@ from conftest import ROOT
 
 # the emulated kernel tests that touch the most pointer arithmetic for the least time
 KERNEL_SUBSET = ("import_export_add or encrypt_decrypt_scalar or summation_segments or bucket_matvec_random "
-                 "or host_staging or summation_levels or encode_decode")
+                 "or host_staging or encode_decode")
 
 
 def _asan_runtime():
