@@ -199,7 +199,7 @@ int invert_batch(const haflo_ctx* ctx, const uint32_t* in, uint32_t* out, size_t
 struct XtdBucketPlan {
   int rounds;
   size_t keys, scan_blocks;
-  size_t off_cnt, off_totals, off_offs, off_sorted, off_arena[2], off_G, off_AT, off_R, off_pairs, total;
+  size_t off_cnt, off_totals, off_offs, off_sorted, off_arena[2], off_G, off_AT, off_R, off_pairs, off_order, total;
   bool pairs;  // the products run on pairs of residues modulo n
 };
 bool xtd_buckets_fit(size_t rows, size_t cols);

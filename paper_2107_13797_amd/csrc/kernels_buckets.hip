@@ -20,6 +20,8 @@
 //   4. Horner over the digit positions, and P[+] * P[-]^-1 by the caller.
 #include "kernels_common.hpp"
 
+#include <algorithm>
+
 using namespace haflo;
 using namespace haflo::dev;
 
@@ -47,8 +49,12 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_zero(u32* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
 
-// Words of the statistics block at the start of the workspace (zeroed with the counters).
-enum { kStatMaxMag = 0, kStatMaxCount = 1, kStatNextChunk = 2, kStatWords = 16 };
+// Words of the statistics block at the start of the workspace (zeroed with the counters): the largest
+// magnitude and bucket, the chunk counter of every round, and for the rounds that hand their chunks out in
+// the order of their lengths (k_bk_order) the length classes: kOrdClasses counts, then as many cursors.
+constexpr int kOrdRounds = 2, kOrdClasses = 32;
+enum { kStatMaxMag = 0, kStatMaxCount = 1, kStatNextChunk = 2, kStatOrder = 16,
+       kStatWords = kStatOrder + kOrdRounds * 2 * kOrdClasses };
 
 // Every non-zero digit of every entry, always over kMaxPos positions (positions above the largest
 // magnitude only hold zero digits). A block takes kTermRows rows of one column and counts its digits in
@@ -208,10 +214,77 @@ __global__ __launch_bounds__(kScanThreads) void k_bk_scan_final(const u32* __res
   }
 }
 
+// Chunk q of a round: its key (the one with choff[key] <= q < choff[key + 1]), and which part of the key's
+// items it takes: near-equal shares of at most kChunk.
+struct ChunkAt {
+  size_t key;
+  u32 begin, len;
+};
+__device__ __forceinline__ ChunkAt chunk_at(u32 q, bool active, const u32* __restrict__ cnt,
+                                            const u32* __restrict__ choff, size_t K, int round) {
+  const u32 qq = active ? q : 0u;
+  size_t lo = 0, hi = K;
+  while (hi - lo > 1) {
+    size_t mid = (lo + hi) >> 1;
+    if (choff[mid] <= qq) lo = mid;
+    else hi = mid;
+  }
+  const u32 first_chunk = choff[lo], nc = choff[lo + 1] - first_chunk, n = items_at(cnt[lo], round);
+  const u32 cc = qq - first_chunk;
+  ChunkAt c = {lo, 0u, 0u};
+  if (active && nc != 0u) {
+    c.begin = (u32)(((u64)n * cc) / nc);
+    c.len = (u32)(((u64)n * (cc + 1u)) / nc) - c.begin;  // at most kChunk
+  }
+  return c;
+}
+
+// The chunks of a round in the order of their lengths, longest first: the lane groups of a wavefront multiply
+// their chunks in lock-step up to the longest of them, so chunks of one length side by side leave no product
+// slot empty (in consecutive order about 7 % of the first round's slots and 20 % of the second's are padding).
+// A counting sort over the kChunk lengths in two passes: SCATTER = false counts the classes into bins[0 ..
+// kOrdClasses); SCATTER = true reserves places through the cursors bins[kOrdClasses ..) and writes
+// order[place] = chunk. A block takes 256 chunks at a time and counts in LDS first.
+template <bool SCATTER>
+__global__ __launch_bounds__(kBlockThreads) void k_bk_order(const u32* __restrict__ cnt,
+                                                            const u32* __restrict__ choff, size_t K, int round,
+                                                            u32* __restrict__ stats, u32* __restrict__ order) {
+  static_assert(kChunk < kOrdClasses, "one class per chunk length");
+  __shared__ u32 hist[kOrdClasses];
+  __shared__ u32 start[kOrdClasses];
+  if (round >= rounds_run(stats[kStatMaxCount])) return;
+  u32* bins = stats + kStatOrder + round * 2 * kOrdClasses;
+  const u32 total = choff[K];
+  for (u32 q0 = blockIdx.x * kBlockThreads; q0 < total; q0 += gridDim.x * kBlockThreads) {
+    if (threadIdx.x < kOrdClasses) hist[threadIdx.x] = 0u;
+    __syncthreads();
+    const u32 q = q0 + threadIdx.x;
+    const bool active = q < total;
+    const u32 cls = (u32)kChunk - chunk_at(q, active, cnt, choff, K, round).len;  // 0: the longest
+    const u32 rank = active ? atomicAdd(&hist[cls], 1u) : 0u;
+    __syncthreads();
+    if (threadIdx.x < kOrdClasses && hist[threadIdx.x] != 0u) {
+      const u32 l = threadIdx.x;
+      const u32 before = atomicAdd(&bins[(SCATTER ? kOrdClasses : 0) + l], hist[l]);
+      if (SCATTER) {
+        u32 first = 0;
+        for (u32 i = 0; i < l; ++i) first += bins[i];
+        start[l] = first + before;
+      }
+    }
+    if (SCATTER) {
+      __syncthreads();
+      if (active) order[start[cls] + rank] = q;
+    }
+    __syncthreads();
+  }
+}
+
 // Reduction round `round`. Key k owns items [off[k], off[k] + items_at(cnt[k], round)) and is cut into
 // choff[k+1] - choff[k] chunks of near-equal size; chunk q's product goes to out[q]. FIRST: item t is the
 // ciphertext of row sorted[t]; otherwise item t is in[t]. PAIR: the items are pairs modulo M (see Elem);
-// `one` is the Montgomery one in the items' form.
+// `one` is the Montgomery one in the items' form. `order`: the chunks in the order in which they are handed
+// out (k_bk_order), or null for 0, 1, 2, ...
 template <int LPT, int T, bool FIRST, bool PAIR>
 __global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u32* __restrict__ one,
                                                             const u32* __restrict__ in,
@@ -220,6 +293,7 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u
                                                             const u32* __restrict__ off,
                                                             const u32* __restrict__ choff, size_t K,
                                                             int round, u32* __restrict__ stats,
+                                                            const u32* __restrict__ order,
                                                             u32* __restrict__ out) {
   using Ops = ElemOps<LPT, T, PAIR>;
   constexpr int EL = Ops::kLimbs;
@@ -232,30 +306,18 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u
   if (round >= rounds_run(stats[kStatMaxCount])) return;  // every bucket already is a single item
   u32* next_chunk = stats + kStatNextChunk + round;
   const u32 total = choff[K];
-  // A wavefront takes GW consecutive chunks at a time: first the run of its own index, then runs drawn
-  // from a counter (zero at launch) behind those, until the end is passed.
+  // A wavefront takes GW consecutive chunks (of `order`) at a time: first the run of its own index, then runs
+  // drawn from a counter (zero at launch) behind those, until the end is passed.
   const u32 nwaves = (u32)((gridDim.x * blockDim.x) / WAVE);
   u32 q0 = (u32)((blockIdx.x * blockDim.x + threadIdx.x) / WAVE) * (u32)GW;
   for (;; ) {
     if (q0 >= total) break;
-    const u32 q = q0 + (u32)(lane / T);
-    const bool active = q < total;
-    const u32 qq = active ? q : 0u;
-    // the key with choff[key] <= q < choff[key + 1]
-    size_t lo = 0, hi = K;
-    while (hi - lo > 1) {
-      size_t mid = (lo + hi) >> 1;
-      if (choff[mid] <= qq) lo = mid;
-      else hi = mid;
-    }
-    const u32 first_chunk = choff[lo], nc = choff[lo + 1] - first_chunk, n = items_at(cnt[lo], round);
-    const u32 cc = qq - first_chunk;
-    u32 begin = 0, len = 0;
-    if (active && nc != 0u) {
-      begin = (u32)(((u64)n * cc) / nc);
-      len = (u32)(((u64)n * (cc + 1u)) / nc) - begin;  // at most kChunk
-    }
-    const size_t start = (size_t)off[lo] + begin;
+    const u32 at = q0 + (u32)(lane / T);
+    const bool active = at < total;
+    const u32 q = (active && order) ? order[at] : at;
+    const ChunkAt ch = chunk_at(q, active, cnt, choff, K, round);
+    const u32 len = ch.len;
+    const size_t start = (size_t)off[ch.key] + ch.begin;
     // first round: the chunk's row indices, spread over the lanes of the group
     u32 idx[IDX];
     if (FIRST) {
@@ -599,7 +661,7 @@ int seg_sum(const haflo_ctx* ctx, const uint32_t* d_c, const uint32_t* d_offsets
     const u32* off = r == 0 ? (const u32*)first : (const u32*)offs(r);
 #define CALL(LPT, T)                                                                                        \
   HAFLO_LAUNCH((k_bk_round<LPT, T, false, false>), sh, st, m.ref(), (const u32*)m.ref().r1, items,       \
-               (const u32*)nullptr, (const u32*)cnt, off, (const u32*)offs(r + 1), K, r, stats, out)
+               (const u32*)nullptr, (const u32*)cnt, off, (const u32*)offs(r + 1), K, r, stats, (const u32*)nullptr, out)
     HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
     items = out;
@@ -646,6 +708,7 @@ XtdBucketPlan xtd_bucket_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
   p.off_R = w;       w += combos * 2 * nl;
   p.pairs = haflo_has_pair_geometry(ctx->Nh);
   p.off_pairs = w;   w += p.pairs ? rows * nl : 0;  // the ciphertexts in the pair form
+  p.off_order = w;   w += p1;                       // the chunks of a round in the order of their lengths
   p.total = w;
   return p;
 }
@@ -677,26 +740,26 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
   HAFLO_LAUNCH(k_bk_scan_totals, scan, st, (const u32*)cnt, K, p.rounds + 1, totals, stats);
   HAFLO_LAUNCH(k_bk_scan_final, scan, st, (const u32*)cnt, K, p.rounds + 1, (const u32*)totals, offs(0));
   HAFLO_LAUNCH((k_bk_terms<true>), flat, st, d_X, rows, cols, cursor, (const u32*)offs(0), sorted, stats);
-  // The products run on pairs of residues modulo n (5/8 of the limb products of a full-length product) wherever
-  // the key size has that geometry: the ciphertexts are taken into the pair form once (two products each,
-  // against two products per matrix entry below), and the column results leave it in k_bk_horner.
-  const bool pairs = p.pairs;
+  // The products run on pairs of residues modulo n (5/8 of the limb products of a full-length product; every
+  // supported key size has that geometry): the ciphertexts are taken into the pair form once (two products each,
+  // against two products per matrix entry below), and the column results leave it in k_bk_horner. The pair form
+  // sits on twice the lanes of n, which also suits the short kernels at the end, where few integers are left.
   const ModHost& mh = ctx->Nh;
-  const ModRef M = pairs ? mh.ref() : m.ref();
-  const int lanes = pairs ? 2 * mh.t : m.t;
-  const u32* one = pairs ? (const u32*)(mh.d_pairs + (size_t)kConstR1 * 2 * mh.nl) : (const u32*)m.ref().r1;
-  const u32* leave = pairs ? (const u32*)(mh.d_pairs + (size_t)kConstR3 * 2 * mh.nl) : (const u32*)nullptr;
-  const u32* items = d_c;
-  if (pairs) {
-    u32* cp = ws + p.off_pairs;
+  if (!p.pairs) return HAFLO_EINVAL;
+  const ModRef M = mh.ref();
+  const int lanes = 2 * mh.t;
+  const u32* one = mh.d_pairs + (size_t)kConstR1 * 2 * mh.nl;
+  const u32* leave = mh.d_pairs + (size_t)kConstR3 * 2 * mh.nl;
+  u32* cp = ws + p.off_pairs;
+  {
     const LaunchShape sh = launch_shape(ctx, rows, lanes, 8);
-#define CALL(LPT, T)                                                                                              \
-  HAFLO_LAUNCH((k_to_pairs<LPT, T>), sh, st, M, (const u32*)(mh.d_pairs + (size_t)kConstR4 * 2 * mh.nl),     \
+#define CALL(LPT, T)                                                                                         \
+  HAFLO_LAUNCH((k_to_pairs<LPT, T>), sh, st, M, (const u32*)(mh.d_pairs + (size_t)kConstR4 * 2 * mh.nl),    \
                (const u32*)(mh.d_pairs + (size_t)kConstR5 * 2 * mh.nl), d_c, rows, cp)
     HAFLO_DISPATCH_PAIRS(mh, CALL);
 #undef CALL
-    items = cp;
   }
+  const u32* items = cp;
   for (int r = 0; r < p.rounds; ++r) {
     // upper bound of the chunks of this round: one lane group each, capped by the grid-stride loop
     size_t bound = rows * cols * kMaxPos;
@@ -704,18 +767,23 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
     const LaunchShape sh = launch_shape(ctx, bound, lanes, 3);
     u32* out = ws + p.off_arena[r & 1];
     const u32* srt = r == 0 ? (const u32*)sorted : (const u32*)nullptr;
-#define CALL_ROUND(LPT, T, FIRST, PAIR)                                                                  \
-  HAFLO_LAUNCH((k_bk_round<LPT, T, FIRST, PAIR>), sh, st, M, one, items, srt, (const u32*)cnt,          \
-               (const u32*)offs(r), (const u32*)offs(r + 1), K, r, stats, out)
-    if (pairs) {
-#define CALL(LPT, T) do { if (r == 0) CALL_ROUND(LPT, T, true, true); else CALL_ROUND(LPT, T, false, true); } while (0)
-      HAFLO_DISPATCH_PAIRS(mh, CALL);
-#undef CALL
-    } else {
-#define CALL(LPT, T) do { if (r == 0) CALL_ROUND(LPT, T, true, false); else CALL_ROUND(LPT, T, false, false); } while (0)
-      HAFLO_DISPATCH_GEOMETRY(m, CALL);
-#undef CALL
+    // the rounds with many chunks hand them out in the order of their lengths
+    const u32* ord = nullptr;
+    if (r < kOrdRounds) {
+      LaunchShape osh;
+      osh.threads = osh.gpb = kBlockThreads;
+      osh.blocks = (int)std::min((bound + kBlockThreads - 1) / kBlockThreads, (size_t)ctx->num_cu * 8);
+      u32* order = ws + p.off_order;
+      HAFLO_LAUNCH((k_bk_order<false>), osh, st, (const u32*)cnt, (const u32*)offs(r + 1), K, r, stats, order);
+      HAFLO_LAUNCH((k_bk_order<true>), osh, st, (const u32*)cnt, (const u32*)offs(r + 1), K, r, stats, order);
+      ord = order;
     }
+#define CALL_ROUND(LPT, T, FIRST)                                                                        \
+  HAFLO_LAUNCH((k_bk_round<LPT, T, FIRST, true>), sh, st, M, one, items, srt, (const u32*)cnt,          \
+               (const u32*)offs(r), (const u32*)offs(r + 1), K, r, stats, ord, out)
+#define CALL(LPT, T) do { if (r == 0) CALL_ROUND(LPT, T, true); else CALL_ROUND(LPT, T, false); } while (0)
+    HAFLO_DISPATCH_PAIRS(mh, CALL);
+#undef CALL
 #undef CALL_ROUND
     items = out;
   }
@@ -723,53 +791,34 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
   u32* G = ws + p.off_G;
   u32* AT = ws + p.off_AT;
   u32* R = ws + p.off_R;
-  // The tail kernels hold few integers: without the pair form they spread each over twice the lanes (the pair
-  // form already sits on those).
-  auto tail_shape = [&](size_t count, bool wide) { return launch_shape(ctx, count, pairs ? lanes : (wide ? haflo_wide_lanes(m) : m.t), 8); };
-#define TAIL(COUNT, WIDE)                                                    \
-  do {                                                                       \
-    const bool wide = (WIDE);                                                \
-    const LaunchShape sh = tail_shape((COUNT), wide);                        \
-    if (pairs) { HAFLO_DISPATCH_PAIRS(mh, CALL_P); }                         \
-    else if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL_N); }              \
-    else { HAFLO_DISPATCH_GEOMETRY(m, CALL_N); }                             \
-  } while (0)
   {
     // half of the items belong to unused digit positions and leave at once
-#define CALL_P(LPT, T)                                                                                  \
+    const LaunchShape sh = launch_shape(ctx, combos * kSubProducts * kSubSplit, lanes, 8);
+#define CALL(LPT, T)                                                                                    \
   HAFLO_LAUNCH((k_bk_sub<LPT, T, true>), sh, st, M, one, (const u32*)(ws + p.off_arena[0]),            \
                (const u32*)(ws + p.off_arena[1]), (const u32*)cnt, (const u32*)offs(0), K, (const u32*)stats, combos, G)
-#define CALL_N(LPT, T)                                                                                  \
-  HAFLO_LAUNCH((k_bk_sub<LPT, T, false>), sh, st, M, one, (const u32*)(ws + p.off_arena[0]),           \
-               (const u32*)(ws + p.off_arena[1]), (const u32*)cnt, (const u32*)offs(0), K, (const u32*)stats, combos, G)
-    TAIL(combos * kSubProducts * kSubSplit, haflo::few_groups(ctx, combos * kSubProducts * kSubSplit, 64));
-#undef CALL_P
-#undef CALL_N
+    HAFLO_DISPATCH_PAIRS(mh, CALL);
+#undef CALL
   }
   {
-#define CALL_P(LPT, T) HAFLO_LAUNCH((k_bk_fold1<LPT, T, true>), sh, st, M, one, (const u32*)G, combos, AT)
-#define CALL_N(LPT, T) HAFLO_LAUNCH((k_bk_fold1<LPT, T, false>), sh, st, M, one, (const u32*)G, combos, AT)
-    TAIL(combos * kSegs, haflo::few_groups(ctx, combos * kSegs));
-#undef CALL_P
-#undef CALL_N
+    const LaunchShape sh = launch_shape(ctx, combos * kSegs, lanes, 8);
+#define CALL(LPT, T) HAFLO_LAUNCH((k_bk_fold1<LPT, T, true>), sh, st, M, one, (const u32*)G, combos, AT)
+    HAFLO_DISPATCH_PAIRS(mh, CALL);
+#undef CALL
   }
   {
-#define CALL_P(LPT, T) HAFLO_LAUNCH((k_bk_fold2<LPT, T, true>), sh, st, M, one, (const u32*)AT, combos, R)
-#define CALL_N(LPT, T) HAFLO_LAUNCH((k_bk_fold2<LPT, T, false>), sh, st, M, one, (const u32*)AT, combos, R)
-    TAIL(combos * 2, haflo::few_groups(ctx, combos * 2));
-#undef CALL_P
-#undef CALL_N
+    const LaunchShape sh = launch_shape(ctx, combos * 2, lanes, 8);
+#define CALL(LPT, T) HAFLO_LAUNCH((k_bk_fold2<LPT, T, true>), sh, st, M, one, (const u32*)AT, combos, R)
+    HAFLO_DISPATCH_PAIRS(mh, CALL);
+#undef CALL
   }
   {
-#define CALL_P(LPT, T) \
+    const LaunchShape sh = launch_shape(ctx, cols * 2, lanes, 8);
+#define CALL(LPT, T) \
   HAFLO_LAUNCH((k_bk_horner<LPT, T, true>), sh, st, M, one, leave, (const u32*)R, cols, d_P, (const u32*)stats)
-#define CALL_N(LPT, T) \
-  HAFLO_LAUNCH((k_bk_horner<LPT, T, false>), sh, st, M, one, leave, (const u32*)R, cols, d_P, (const u32*)stats)
-    TAIL(cols * 2, haflo::few_groups(ctx, cols * 2));
-#undef CALL_P
-#undef CALL_N
+    HAFLO_DISPATCH_PAIRS(mh, CALL);
+#undef CALL
   }
-#undef TAIL
   return hip_status(hipGetLastError());
 }
 

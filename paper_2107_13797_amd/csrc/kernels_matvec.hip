@@ -968,44 +968,31 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
     u32* lists = ws + p.off_nz;
     u32* cnt = ws + p.off_cnt;
     // The tables and the row products are in the pair form modulo n (5/8 of the limb products of a full-length
-    // product) wherever the key size has that geometry; a row's result leaves it as it is stored.
-    const bool pairs = haflo_has_pair_geometry(ctx->Nh);
+    // product; every supported key size has that geometry); a row's result leaves it as it is stored.
     const ModHost& mh = ctx->Nh;
-    const ModRef M = pairs ? mh.ref() : m.ref();
-    const int lanes = pairs ? 2 * mh.t : m.t;
-    const u32* one = pairs ? (const u32*)(mh.d_pairs + (size_t)kConstR1 * 2 * mh.nl) : (const u32*)m.ref().r1;
-    const u32* leave = pairs ? (const u32*)(mh.d_pairs + (size_t)kConstR3 * 2 * mh.nl) : (const u32*)nullptr;
+    if (!haflo_has_pair_geometry(mh)) return HAFLO_EINVAL;
+    const ModRef M = mh.ref();
+    const int lanes = 2 * mh.t;
+    const u32* one = mh.d_pairs + (size_t)kConstR1 * 2 * mh.nl;
+    const u32* leave = mh.d_pairs + (size_t)kConstR3 * 2 * mh.nl;
     if (cols) {
       rc = invert_batch(ctx, (const u32*)d_c, inv, cols, st);
       if (rc != HAFLO_OK) return rc;
       {
-        const size_t groups = cols * 2 * kMaxPos;
-        const bool wide = haflo::few_groups(ctx, groups, 32);
-        const LaunchShape sh = launch_shape(ctx, groups, pairs ? lanes : (wide ? haflo_wide_lanes(m) : m.t), 8);
-#define CALL_P(LPT, T)                                                                                              \
+        const LaunchShape sh = launch_shape(ctx, cols * 2 * kMaxPos, lanes, 8);
+#define CALL(LPT, T)                                                                                                \
   HAFLO_LAUNCH((k_xw_positions<LPT, T, true>), sh, st, M, (const u32*)(mh.d_pairs + (size_t)kConstR4 * 2 * mh.nl), \
                (const u32*)(mh.d_pairs + (size_t)kConstR5 * 2 * mh.nl), (const u32*)d_c, (const u32*)inv, cols,     \
                tables, (const u32*)ws)
-#define CALL_N(LPT, T)                                                                                  \
-  HAFLO_LAUNCH((k_xw_positions<LPT, T, false>), sh, st, M, (const u32*)nullptr, (const u32*)nullptr,   \
-               (const u32*)d_c, (const u32*)inv, cols, tables, (const u32*)ws)
-        if (pairs) { HAFLO_DISPATCH_PAIRS(mh, CALL_P); }
-        else if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL_N); }
-        else { HAFLO_DISPATCH_GEOMETRY(m, CALL_N); }
-#undef CALL_P
-#undef CALL_N
+        HAFLO_DISPATCH_PAIRS(mh, CALL);
+#undef CALL
       }
       for (int B = 1; B < kWinEntries; B *= 2) {
         const size_t groups = cols * 2 * kMaxPos * (size_t)std::min(B, kWinEntries - 1 - B);
-        const bool wide = haflo::few_groups(ctx, groups, 32);
-        const LaunchShape sh = launch_shape(ctx, groups, pairs ? lanes : (wide ? haflo_wide_lanes(m) : m.t), 8);
-#define CALL_P(LPT, T) HAFLO_LAUNCH((k_xw_level<LPT, T, true>), sh, st, M, one, cols, B, tables, (const u32*)ws)
-#define CALL_N(LPT, T) HAFLO_LAUNCH((k_xw_level<LPT, T, false>), sh, st, M, one, cols, B, tables, (const u32*)ws)
-        if (pairs) { HAFLO_DISPATCH_PAIRS(mh, CALL_P); }
-        else if (wide) { HAFLO_DISPATCH_GEOMETRY_WIDE(m, CALL_N); }
-        else { HAFLO_DISPATCH_GEOMETRY(m, CALL_N); }
-#undef CALL_P
-#undef CALL_N
+        const LaunchShape sh = launch_shape(ctx, groups, lanes, 8);
+#define CALL(LPT, T) HAFLO_LAUNCH((k_xw_level<LPT, T, true>), sh, st, M, one, cols, B, tables, (const u32*)ws)
+        HAFLO_DISPATCH_PAIRS(mh, CALL);
+#undef CALL
       }
     }
     u32* bins = ws + kXwBinsAt;
@@ -1025,24 +1012,18 @@ int haflo_cipher_matvec(const haflo_ctx* ctx, int orientation, const void* d_c, 
     u32* partial = ws + p.off_partial;
     {
       const LaunchShape sh = launch_shape(ctx, rows << p.seg_shift, lanes, 3);
-#define CALL_ARGS M, one, leave, rows, cols * (size_t)kMaxPos, (const u32*)lists, (const u32*)cnt, (const u32*)order, \
-                  (const u32*)tables, ws + 1, p.seg_shift, partial, (u32*)d_out
-#define CALL_P(LPT, T) HAFLO_LAUNCH((k_xw_main<LPT, T, true>), sh, st, CALL_ARGS)
-#define CALL_N(LPT, T) HAFLO_LAUNCH((k_xw_main<LPT, T, false>), sh, st, CALL_ARGS)
-      if (pairs) { HAFLO_DISPATCH_PAIRS(mh, CALL_P); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL_N); }
-#undef CALL_P
-#undef CALL_N
-#undef CALL_ARGS
+#define CALL(LPT, T)                                                                                            \
+  HAFLO_LAUNCH((k_xw_main<LPT, T, true>), sh, st, M, one, leave, rows, cols * (size_t)kMaxPos, (const u32*)lists, \
+               (const u32*)cnt, (const u32*)order, (const u32*)tables, ws + 1, p.seg_shift, partial, (u32*)d_out)
+      HAFLO_DISPATCH_PAIRS(mh, CALL);
+#undef CALL
     }
     if (p.seg_shift) {
       const LaunchShape sh = launch_shape(ctx, rows, lanes, 8);
-#define CALL_P(LPT, T) \
+#define CALL(LPT, T) \
   HAFLO_LAUNCH((k_xw_combine<LPT, T, true>), sh, st, M, leave, rows, p.seg_shift, (const u32*)partial, (u32*)d_out)
-#define CALL_N(LPT, T) \
-  HAFLO_LAUNCH((k_xw_combine<LPT, T, false>), sh, st, M, leave, rows, p.seg_shift, (const u32*)partial, (u32*)d_out)
-      if (pairs) { HAFLO_DISPATCH_PAIRS(mh, CALL_P); } else { HAFLO_DISPATCH_GEOMETRY(m, CALL_N); }
-#undef CALL_P
-#undef CALL_N
+      HAFLO_DISPATCH_PAIRS(mh, CALL);
+#undef CALL
     }
   }
   return hip_status(hipGetLastError());
