@@ -30,7 +30,7 @@ namespace {
 constexpr int kDigitBits = 10;
 constexpr int kMags = 512;     // digit magnitudes 1..512
 constexpr int kMaxPos = 4;     // 1024^4 - offset(4) > 2^31
-constexpr int kChunkBits = 4, kChunk = 1 << kChunkBits;  // items per lane group and round
+constexpr int kChunkBits = 5, kChunk = 1 << kChunkBits;  // items per lane group and round
 constexpr int kLoCount = 32, kHiCount = 16, kSubProducts = kLoCount + kHiCount;  // m = 32 h + l + 1
 
 __host__ __device__ inline unsigned long long digit_offset(int npos) {
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_zero(u32* p, size_t n) {
 // Words of the statistics block at the start of the workspace (zeroed with the counters): the largest
 // magnitude and bucket, the chunk counter of every round, and for the rounds that hand their chunks out in
 // the order of their lengths (k_bk_order) the length classes: kOrdClasses counts, then as many cursors.
-constexpr int kOrdRounds = 2, kOrdClasses = 32;
+constexpr int kOrdRounds = 2, kOrdClasses = 64;
 enum { kStatMaxMag = 0, kStatMaxCount = 1, kStatNextChunk = 2, kStatOrder = 16,
        kStatWords = kStatOrder + kOrdRounds * 2 * kOrdClasses };
 
@@ -146,7 +146,7 @@ __host__ __device__ inline int rounds_run(u32 largest) {
 // (= its items at round r + 1). Two kernels: per-block totals, then every block adds up the totals
 // before it and scans its own kScanKeys keys. offs: (rounds + 1) arrays of K + 1 words.
 constexpr int kScanThreads = 256, kScanPer = 8, kScanKeys = kScanThreads * kScanPer;
-constexpr int kMaxComp = 9;  // kChunk^8 = 2^32 bounds the rounds
+constexpr int kMaxComp = 9;  // kChunk^7 > 2^32 bounds the rounds
 
 // sum over the block of v, returned to every thread (red: kScanThreads words)
 __device__ __forceinline__ u32 block_sum(u32 v, u32* red) {
@@ -241,7 +241,8 @@ __device__ __forceinline__ ChunkAt chunk_at(u32 q, bool active, const u32* __res
 
 // The chunks of a round in the order of their lengths, longest first: the lane groups of a wavefront multiply
 // their chunks in lock-step up to the longest of them, so chunks of one length side by side leave no product
-// slot empty (in consecutive order about 7 % of the first round's slots and 20 % of the second's are padding).
+// slot empty (in consecutive order about 15 % of the first round's slots and a third of the second's are
+// padding at 64 rows per bucket).
 // A counting sort over the kChunk lengths in two passes: SCATTER = false counts the classes into bins[0 ..
 // kOrdClasses); SCATTER = true reserves places through the cursors bins[kOrdClasses ..) and writes
 // order[place] = chunk. A block takes 256 chunks at a time and counts in LDS first.

@@ -302,7 +302,7 @@ def test_bucket_matvec_random(env, force_buckets):
 
 def test_bucket_matvec_heavy_buckets(env, force_buckets):
     """Columns of equal entries put every row into one bucket, which then takes several
-    reduction rounds (37 rows > 16 items per chunk); a zero column gives the encryption-free one."""
+    reduction rounds (37 rows > 32 items per chunk); a zero column gives the encryption-free one."""
     X = np.zeros((37, 4), dtype=np.int32)
     X[:, 0] = 1 << 16
     X[:, 1] = -3

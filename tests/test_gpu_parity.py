@@ -437,7 +437,7 @@ def _edges_matvec(api, bits, method, ctx, sk):
 @pytest.mark.parametrize("bits", [1024, 2048])
 def test_summation_segments(api, bits):
     """Homomorphic summation over slices: empty slices, single elements, a slice longer than
-    16^3 elements (four reduction rounds), one slice over everything, and many short ones; the
+    32^2 elements (three reduction rounds), one slice over everything, and many short ones; the
     ciphertexts against the oracle, every slice also through decryption against the plaintext sums."""
     ctx, sk = context(api, bits)
     pk = sk.public
