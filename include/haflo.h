@@ -343,7 +343,7 @@ int haflo_cipher_sum(const haflo_ctx* ctx, const void* d_c, size_t count, void* 
  * d_c: count internal elements, count < 2^32. d_offsets: nseg + 1 device
  * uint32, non-decreasing, last <= count; nseg < 2^24. Slices may be of any
  * length, from empty to the whole array: every slice is spread over the chip
- * in chunks of 32 elements and reduced in rounds. An offset that runs
+ * in chunks of 16 or 32 elements and reduced in rounds. An offset that runs
  * backwards or past count is the caller's error: that slice is clipped or
  * empty and HAFLO_ST_RANGE is OR-ed into d_status (one device uint32, or
  * NULL); nothing outside the array is read. d_out: nseg internal elements, may

@@ -198,6 +198,7 @@ int invert_batch(const haflo_ctx* ctx, const uint32_t* in, uint32_t* out, size_t
 // X^T [[d]] by the bucket method (kernels_buckets.hip). Workspace layout in 32-bit words.
 struct XtdBucketPlan {
   int rounds;
+  int chunk_bits;  // a reduction round multiplies chunks of at most 2^chunk_bits items
   size_t keys, scan_blocks;
   size_t off_cnt, off_totals, off_offs, off_sorted, off_arena[2], off_G, off_AT, off_R, off_pairs, off_order, total;
   bool pairs;  // the products run on pairs of residues modulo n
@@ -212,6 +213,7 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
 // Segmented summation through the bucket reduction rounds (kernels_buckets.hip). Workspace layout in 32-bit words.
 struct SegSumPlan {
   int rounds;
+  int chunk_bits;
   size_t scan_blocks, off_cnt, off_totals, off_offs, off_arena[2], total;
 };
 SegSumPlan seg_sum_plan(const haflo_ctx* ctx, size_t count, size_t nseg);

@@ -11,7 +11,7 @@
 //      one array sorted by bucket (atomics; the order inside a bucket is
 //      arbitrary and does not change the canonical result);
 //   2. reduce every bucket to its product in rounds: a round cuts each bucket's
-//      items into chunks of at most kChunk, one lane group multiplies one chunk,
+//      items into chunks of at most 16 or 32, one lane group multiplies one chunk,
 //      the chunk products are the next round's items. A bucket of any size (a
 //      column of equal entries puts all its rows into one) is spread over the
 //      whole chip, and the number of rounds is fixed by the row count;
@@ -30,7 +30,10 @@ namespace {
 constexpr int kDigitBits = 10;
 constexpr int kMags = 512;     // digit magnitudes 1..512
 constexpr int kMaxPos = 4;     // 1024^4 - offset(4) > 2^31
-constexpr int kChunkBits = 5, kChunk = 1 << kChunkBits;  // items per lane group and round
+// Items per lane group and round: 2^cb with cb chosen per call (chunk_bits): long chunks for matrices that fill
+// the chip many times over (fewer items for the later rounds), short ones where the longest chain of products is
+// what the call waits for.
+constexpr int kChunkBitsMin = 4, kChunkBitsMax = 5, kChunkMax = 1 << kChunkBitsMax;
 constexpr int kLoCount = 32, kHiCount = 16, kSubProducts = kLoCount + kHiCount;  // m = 32 h + l + 1
 
 __host__ __device__ inline unsigned long long digit_offset(int npos) {
@@ -127,17 +130,17 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_terms(const int* __restric
   }
 }
 
-// Items of a key with `c` rows at the start of round r: ceil(c / kChunk^r).
-__host__ __device__ inline u32 items_at(u32 c, int r) {
-  const int sh = kChunkBits * r;
+// Items of a key with `c` rows at the start of round r: ceil(c / 2^(cb r)).
+__host__ __device__ inline u32 items_at(u32 c, int r, int cb) {
+  const int sh = cb * r;
   return sh >= 32 ? (c != 0u) : (u32)(((u64)c + ((1ull << sh) - 1ull)) >> sh);
 }
 
 // Rounds that have work when the largest bucket holds `largest` rows: round 0, then every round that
 // still finds a key with more than one item.
-__host__ __device__ inline int rounds_run(u32 largest) {
+__host__ __device__ inline int rounds_run(u32 largest, int cb) {
   int r = 1;
-  while (items_at(largest, r) > 1u) ++r;
+  while (items_at(largest, r, cb) > 1u) ++r;
   return r;
 }
 
@@ -146,7 +149,7 @@ __host__ __device__ inline int rounds_run(u32 largest) {
 // (= its items at round r + 1). Two kernels: per-block totals, then every block adds up the totals
 // before it and scans its own kScanKeys keys. offs: (rounds + 1) arrays of K + 1 words.
 constexpr int kScanThreads = 256, kScanPer = 8, kScanKeys = kScanThreads * kScanPer;
-constexpr int kMaxComp = 9;  // kChunk^7 > 2^32 bounds the rounds
+constexpr int kMaxComp = 9;  // 16^8 = 2^32 bounds the rounds
 
 // sum over the block of v, returned to every thread (red: kScanThreads words)
 __device__ __forceinline__ u32 block_sum(u32 v, u32* red) {
@@ -161,7 +164,8 @@ __device__ __forceinline__ u32 block_sum(u32 v, u32* red) {
 }
 
 __global__ __launch_bounds__(kScanThreads) void k_bk_scan_totals(const u32* __restrict__ cnt, size_t K, int ncomp,
-                                                                u32* __restrict__ totals, u32* __restrict__ stats) {
+                                                                int cb, u32* __restrict__ totals,
+                                                                u32* __restrict__ stats) {
   __shared__ u32 red[kScanThreads];
   u32 mine[kMaxComp];
   for (int c = 0; c < kMaxComp; ++c) mine[c] = 0u;
@@ -170,7 +174,7 @@ __global__ __launch_bounds__(kScanThreads) void k_bk_scan_totals(const u32* __re
   for (int i = 0; i < kScanPer; ++i) {
     const u32 n = (k0 + i < K) ? cnt[k0 + i] : 0u;
     largest = n > largest ? n : largest;
-    for (int c = 0; c < ncomp; ++c) mine[c] += items_at(n, c);
+    for (int c = 0; c < ncomp; ++c) mine[c] += items_at(n, c, cb);
   }
   largest = wave_max(largest);
   if ((threadIdx.x & (WAVE - 1)) == 0 && largest) atomicMax(&stats[kStatMaxCount], largest);
@@ -181,7 +185,7 @@ __global__ __launch_bounds__(kScanThreads) void k_bk_scan_totals(const u32* __re
 }
 
 __global__ __launch_bounds__(kScanThreads) void k_bk_scan_final(const u32* __restrict__ cnt, size_t K, int ncomp,
-                                                               const u32* __restrict__ totals,
+                                                               int cb, const u32* __restrict__ totals,
                                                                u32* __restrict__ offs) {
   __shared__ u32 red[kScanThreads];
   __shared__ u32 scan[kScanThreads];
@@ -193,7 +197,7 @@ __global__ __launch_bounds__(kScanThreads) void k_bk_scan_final(const u32* __res
     for (unsigned b = threadIdx.x; b < blockIdx.x; b += kScanThreads) before += totals[(size_t)c * gridDim.x + b];
     before = block_sum(before, red);
     u32 mine = 0;
-    for (int i = 0; i < kScanPer; ++i) mine += items_at(n[i], c);
+    for (int i = 0; i < kScanPer; ++i) mine += items_at(n[i], c, cb);
     // Hillis-Steele inclusive scan of the per-thread sums
     scan[threadIdx.x] = mine;
     __syncthreads();
@@ -207,7 +211,7 @@ __global__ __launch_bounds__(kScanThreads) void k_bk_scan_final(const u32* __res
     u32* dst = offs + (size_t)c * (K + 1);
     for (int i = 0; i < kScanPer; ++i) {
       if (k0 + i < K) dst[k0 + i] = run;
-      run += items_at(n[i], c);
+      run += items_at(n[i], c, cb);
     }
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == kScanThreads - 1) dst[K] = run;
     __syncthreads();
@@ -215,13 +219,13 @@ __global__ __launch_bounds__(kScanThreads) void k_bk_scan_final(const u32* __res
 }
 
 // Chunk q of a round: its key (the one with choff[key] <= q < choff[key + 1]), and which part of the key's
-// items it takes: near-equal shares of at most kChunk.
+// items it takes: near-equal shares of at most 2^cb.
 struct ChunkAt {
   size_t key;
   u32 begin, len;
 };
 __device__ __forceinline__ ChunkAt chunk_at(u32 q, bool active, const u32* __restrict__ cnt,
-                                            const u32* __restrict__ choff, size_t K, int round) {
+                                            const u32* __restrict__ choff, size_t K, int round, int cb) {
   const u32 qq = active ? q : 0u;
   size_t lo = 0, hi = K;
   while (hi - lo > 1) {
@@ -229,12 +233,12 @@ __device__ __forceinline__ ChunkAt chunk_at(u32 q, bool active, const u32* __res
     if (choff[mid] <= qq) lo = mid;
     else hi = mid;
   }
-  const u32 first_chunk = choff[lo], nc = choff[lo + 1] - first_chunk, n = items_at(cnt[lo], round);
+  const u32 first_chunk = choff[lo], nc = choff[lo + 1] - first_chunk, n = items_at(cnt[lo], round, cb);
   const u32 cc = qq - first_chunk;
   ChunkAt c = {lo, 0u, 0u};
   if (active && nc != 0u) {
     c.begin = (u32)(((u64)n * cc) / nc);
-    c.len = (u32)(((u64)n * (cc + 1u)) / nc) - c.begin;  // at most kChunk
+    c.len = (u32)(((u64)n * (cc + 1u)) / nc) - c.begin;  // at most 2^cb
   }
   return c;
 }
@@ -243,17 +247,18 @@ __device__ __forceinline__ ChunkAt chunk_at(u32 q, bool active, const u32* __res
 // their chunks in lock-step up to the longest of them, so chunks of one length side by side leave no product
 // slot empty (in consecutive order about 15 % of the first round's slots and a third of the second's are
 // padding at 64 rows per bucket).
-// A counting sort over the kChunk lengths in two passes: SCATTER = false counts the classes into bins[0 ..
+// A counting sort over the 2^cb lengths in two passes: SCATTER = false counts the classes into bins[0 ..
 // kOrdClasses); SCATTER = true reserves places through the cursors bins[kOrdClasses ..) and writes
 // order[place] = chunk. A block takes 256 chunks at a time and counts in LDS first.
 template <bool SCATTER>
 __global__ __launch_bounds__(kBlockThreads) void k_bk_order(const u32* __restrict__ cnt,
                                                             const u32* __restrict__ choff, size_t K, int round,
-                                                            u32* __restrict__ stats, u32* __restrict__ order) {
-  static_assert(kChunk < kOrdClasses, "one class per chunk length");
+                                                            int cb, u32* __restrict__ stats,
+                                                            u32* __restrict__ order) {
+  static_assert(kChunkMax < kOrdClasses, "one class per chunk length");
   __shared__ u32 hist[kOrdClasses];
   __shared__ u32 start[kOrdClasses];
-  if (round >= rounds_run(stats[kStatMaxCount])) return;
+  if (round >= rounds_run(stats[kStatMaxCount], cb)) return;
   u32* bins = stats + kStatOrder + round * 2 * kOrdClasses;
   const u32 total = choff[K];
   for (u32 q0 = blockIdx.x * kBlockThreads; q0 < total; q0 += gridDim.x * kBlockThreads) {
@@ -261,7 +266,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_order(const u32* __restric
     __syncthreads();
     const u32 q = q0 + threadIdx.x;
     const bool active = q < total;
-    const u32 cls = (u32)kChunk - chunk_at(q, active, cnt, choff, K, round).len;  // 0: the longest
+    const u32 cls = (1u << cb) - chunk_at(q, active, cnt, choff, K, round, cb).len;  // 0: the longest
     const u32 rank = active ? atomicAdd(&hist[cls], 1u) : 0u;
     __syncthreads();
     if (threadIdx.x < kOrdClasses && hist[threadIdx.x] != 0u) {
@@ -281,7 +286,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_order(const u32* __restric
   }
 }
 
-// Reduction round `round`. Key k owns items [off[k], off[k] + items_at(cnt[k], round)) and is cut into
+// Reduction round `round`. Key k owns items [off[k], off[k] + items_at(cnt[k], round, cb)) and is cut into
 // choff[k+1] - choff[k] chunks of near-equal size; chunk q's product goes to out[q]. FIRST: item t is the
 // ciphertext of row sorted[t]; otherwise item t is in[t]. PAIR: the items are pairs modulo M (see Elem);
 // `one` is the Montgomery one in the items' form. `order`: the chunks in the order in which they are handed
@@ -293,18 +298,18 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u
                                                             const u32* __restrict__ cnt,
                                                             const u32* __restrict__ off,
                                                             const u32* __restrict__ choff, size_t K,
-                                                            int round, u32* __restrict__ stats,
+                                                            int round, int cb, u32* __restrict__ stats,
                                                             const u32* __restrict__ order,
                                                             u32* __restrict__ out) {
   using Ops = ElemOps<LPT, T, PAIR>;
   constexpr int EL = Ops::kLimbs;
   constexpr int GW = WAVE / T;                 // lane groups per wavefront
-  constexpr int IDX = (kChunk + T - 1) / T;    // row indices each lane keeps for its group's chunk
+  constexpr int IDX = (kChunkMax + T - 1) / T;  // row indices each lane keeps for its group's chunk
   Grp<T> g;
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
   const int lane = (int)(threadIdx.x & (WAVE - 1));
-  if (round >= rounds_run(stats[kStatMaxCount])) return;  // every bucket already is a single item
+  if (round >= rounds_run(stats[kStatMaxCount], cb)) return;  // every bucket already is a single item
   u32* next_chunk = stats + kStatNextChunk + round;
   const u32 total = choff[K];
   // A wavefront takes GW consecutive chunks (of `order`) at a time: first the run of its own index, then runs
@@ -316,7 +321,7 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u
     const u32 at = q0 + (u32)(lane / T);
     const bool active = at < total;
     const u32 q = (active && order) ? order[at] : at;
-    const ChunkAt ch = chunk_at(q, active, cnt, choff, K, round);
+    const ChunkAt ch = chunk_at(q, active, cnt, choff, K, round, cb);
     const u32 len = ch.len;
     const size_t start = (size_t)off[ch.key] + ch.begin;
     // first round: the chunk's row indices, spread over the lanes of the group
@@ -367,8 +372,8 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* _
                                                           const u32* __restrict__ arena0,
                                                           const u32* __restrict__ arena1,
                                                           const u32* __restrict__ cnt, const u32* __restrict__ offs,
-                                                          size_t K, const u32* __restrict__ stats, size_t combos,
-                                                          u32* __restrict__ G) {
+                                                          size_t K, int cb, const u32* __restrict__ stats,
+                                                          size_t combos, u32* __restrict__ G) {
   using Ops = ElemOps<LPT, T, PAIR>;
   constexpr int EL = Ops::kLimbs;
   constexpr int GPB = kBlockThreads / Grp<T>::kPitch;
@@ -378,7 +383,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* _
   Batch<T> bt;
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
-  const int ran = rounds_run(stats[kStatMaxCount]);
+  const int ran = rounds_run(stats[kStatMaxCount], cb);
   const u32* B = ((ran - 1) & 1) ? arena1 : arena0;
   const u32* off = offs + (size_t)ran * (K + 1);
   const size_t count = combos * kSubProducts * kSubSplit;
@@ -579,14 +584,14 @@ template <int LPT, int T>
 __global__ __launch_bounds__(kBlockThreads) void k_seg_finish(ModRef M, const u32* __restrict__ arena0,
                                                               const u32* __restrict__ arena1,
                                                               const u32* __restrict__ cnt, const u32* __restrict__ offs,
-                                                              size_t K, const u32* __restrict__ stats,
+                                                              size_t K, int cb, const u32* __restrict__ stats,
                                                               u32* __restrict__ out) {
   constexpr int NL = LPT * T;
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
   load_mod<LPT, T>(mod, M, g);
-  const int ran = rounds_run(stats[kStatMaxCount]);
+  const int ran = rounds_run(stats[kStatMaxCount], cb);
   const u32* B = ((ran - 1) & 1) ? arena1 : arena0;
   const u32* off = offs + (size_t)ran * (K + 1);
   for (size_t base = bt.first(); base < K; base += bt.stride()) {
@@ -599,10 +604,18 @@ __global__ __launch_bounds__(kBlockThreads) void k_seg_finish(ModRef M, const u3
   }
 }
 
-int rounds_for(size_t rows) {
+int rounds_for(size_t rows, int cb) {
   int r = 0;
-  for (size_t reach = 1; reach < rows; reach *= kChunk) ++r;
+  for (size_t reach = 1; reach < rows; reach <<= cb) ++r;
   return r < 1 ? 1 : r;
+}
+
+// Chunk size of a call with `items` factors in all: the long chunks once the first round has several full passes
+// of chunks over the lane groups the chip holds (then the later rounds' items are what is worth saving), the
+// short ones below that, where the call waits for its longest chain of products.
+int chunk_bits(const haflo_ctx* ctx, size_t items, int lanes) {
+  const size_t resident = (size_t)ctx->num_cu * 3 * (size_t)(kBlockThreads / lanes);
+  return (items >> kChunkBitsMax) >= 4 * resident ? kChunkBitsMax : kChunkBitsMin;
 }
 
 }  // namespace
@@ -612,11 +625,12 @@ namespace haflo {
 SegSumPlan seg_sum_plan(const haflo_ctx* ctx, size_t count, size_t nseg) {
   SegSumPlan p;
   const size_t nl = (size_t)ctx->N.nl;
-  p.rounds = rounds_for(count);
+  p.chunk_bits = chunk_bits(ctx, count, ctx->N.t);
+  p.rounds = rounds_for(count, p.chunk_bits);
   p.scan_blocks = (nseg + kScanKeys - 1) / kScanKeys;
-  size_t p1 = count / kChunk + nseg;
+  size_t p1 = (count >> p.chunk_bits) + nseg;
   if (p1 > count) p1 = count;
-  size_t p2 = p1 / kChunk + nseg;
+  size_t p2 = (p1 >> p.chunk_bits) + nseg;
   if (p2 > p1) p2 = p1;
   size_t w = 0;
   p.off_cnt = w;     w += kStatWords + 2 * nseg;  // statistics and chunk counters, lengths, first elements
@@ -633,6 +647,7 @@ int seg_sum(const haflo_ctx* ctx, const uint32_t* d_c, const uint32_t* d_offsets
             uint32_t* d_out, uint32_t* d_status, uint32_t* ws, hipStream_t st) {
   const ModHost& m = ctx->N;
   const SegSumPlan p = seg_sum_plan(ctx, count, nseg);
+  const int cb = p.chunk_bits;
   if (p.rounds + 1 > kMaxComp || kStatNextChunk + p.rounds > kStatWords) return HAFLO_EINVAL;
   const size_t K = nseg;
   u32* stats = ws + p.off_cnt;
@@ -650,19 +665,19 @@ int seg_sum(const haflo_ctx* ctx, const uint32_t* d_c, const uint32_t* d_offsets
   scan.gpb = kScanThreads;
   HAFLO_LAUNCH(k_bk_zero, one, st, stats, (size_t)kStatWords);
   HAFLO_LAUNCH(k_seg_counts, launch_shape(ctx, K, 1, 8), st, d_offsets, K, (u32)count, cnt, first, d_status);
-  HAFLO_LAUNCH(k_bk_scan_totals, scan, st, (const u32*)cnt, K, p.rounds + 1, totals, stats);
-  HAFLO_LAUNCH(k_bk_scan_final, scan, st, (const u32*)cnt, K, p.rounds + 1, (const u32*)totals, offs(0));
+  HAFLO_LAUNCH(k_bk_scan_totals, scan, st, (const u32*)cnt, K, p.rounds + 1, cb, totals, stats);
+  HAFLO_LAUNCH(k_bk_scan_final, scan, st, (const u32*)cnt, K, p.rounds + 1, cb, (const u32*)totals, offs(0));
   const u32* items = d_c;
   for (int r = 0; r < p.rounds; ++r) {
     size_t bound = count;
-    for (int i = 0; i <= r; ++i) bound = bound / kChunk + K;
+    for (int i = 0; i <= r; ++i) bound = (bound >> cb) + K;
     const LaunchShape sh = launch_shape(ctx, bound, m.t, 3);
     u32* out = ws + p.off_arena[r & 1];
     // round 0 reads the elements where they are: a segment's items start at its first element
     const u32* off = r == 0 ? (const u32*)first : (const u32*)offs(r);
 #define CALL(LPT, T)                                                                                        \
   HAFLO_LAUNCH((k_bk_round<LPT, T, false, false>), sh, st, m.ref(), (const u32*)m.ref().r1, items,       \
-               (const u32*)nullptr, (const u32*)cnt, off, (const u32*)offs(r + 1), K, r, stats, (const u32*)nullptr, out)
+               (const u32*)nullptr, (const u32*)cnt, off, (const u32*)offs(r + 1), K, r, cb, stats, (const u32*)nullptr, out)
     HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
     items = out;
@@ -671,7 +686,7 @@ int seg_sum(const haflo_ctx* ctx, const uint32_t* d_c, const uint32_t* d_offsets
     const LaunchShape sh = launch_shape(ctx, K, m.t, 8);
 #define CALL(LPT, T)                                                                          \
   HAFLO_LAUNCH((k_seg_finish<LPT, T>), sh, st, m.ref(), (const u32*)(ws + p.off_arena[0]),  \
-               (const u32*)(ws + p.off_arena[1]), (const u32*)cnt, (const u32*)offs(0), K, (const u32*)stats, d_out)
+               (const u32*)(ws + p.off_arena[1]), (const u32*)cnt, (const u32*)offs(0), K, cb, (const u32*)stats, d_out)
     HAFLO_DISPATCH_GEOMETRY(m, CALL);
 #undef CALL
   }
@@ -687,13 +702,15 @@ bool xtd_buckets_fit(size_t rows, size_t cols) {
 XtdBucketPlan xtd_bucket_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
   XtdBucketPlan p;
   const size_t nl = (size_t)ctx->N.nl;
-  p.rounds = rounds_for(rows);
+  p.pairs = haflo_has_pair_geometry(ctx->Nh);
+  p.chunk_bits = chunk_bits(ctx, rows * cols * 2, p.pairs ? 2 * ctx->Nh.t : ctx->N.t);  // two digits per entry as a rule
+  p.rounds = rounds_for(rows, p.chunk_bits);
   p.keys = cols * kMaxPos * 2 * kMags;
   p.scan_blocks = (p.keys + kScanKeys - 1) / kScanKeys;
   const size_t terms = rows * cols * kMaxPos;
-  size_t p1 = terms / kChunk + p.keys;
+  size_t p1 = (terms >> p.chunk_bits) + p.keys;
   if (p1 > terms) p1 = terms;
-  size_t p2 = p1 / kChunk + p.keys;
+  size_t p2 = (p1 >> p.chunk_bits) + p.keys;
   if (p2 > p1) p2 = p1;
   const size_t combos = cols * kMaxPos * 2;
   size_t w = 0;
@@ -707,7 +724,6 @@ XtdBucketPlan xtd_bucket_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
   p.off_G = w;       w += combos * kSubProducts * nl;
   p.off_AT = w;      w += combos * kSegs * 2 * nl;
   p.off_R = w;       w += combos * 2 * nl;
-  p.pairs = haflo_has_pair_geometry(ctx->Nh);
   p.off_pairs = w;   w += p.pairs ? rows * nl : 0;  // the ciphertexts in the pair form
   p.off_order = w;   w += p1;                       // the chunks of a round in the order of their lengths
   p.total = w;
@@ -718,6 +734,7 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
                 uint32_t* ws, uint32_t* d_P, hipStream_t st) {
   const ModHost& m = ctx->N;
   const XtdBucketPlan p = xtd_bucket_plan(ctx, rows, cols);
+  const int cb = p.chunk_bits;
   if (p.rounds + 1 > kMaxComp || kStatNextChunk + p.rounds > kStatWords) return HAFLO_EINVAL;
   const size_t K = p.keys;
   u32* stats = ws + p.off_cnt;
@@ -738,8 +755,8 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
   scan.gpb = kScanThreads;
   HAFLO_LAUNCH(k_bk_zero, fill, st, stats, kStatWords + 2 * K);
   HAFLO_LAUNCH((k_bk_terms<false>), flat, st, d_X, rows, cols, cnt, (const u32*)nullptr, (u32*)nullptr, stats);
-  HAFLO_LAUNCH(k_bk_scan_totals, scan, st, (const u32*)cnt, K, p.rounds + 1, totals, stats);
-  HAFLO_LAUNCH(k_bk_scan_final, scan, st, (const u32*)cnt, K, p.rounds + 1, (const u32*)totals, offs(0));
+  HAFLO_LAUNCH(k_bk_scan_totals, scan, st, (const u32*)cnt, K, p.rounds + 1, cb, totals, stats);
+  HAFLO_LAUNCH(k_bk_scan_final, scan, st, (const u32*)cnt, K, p.rounds + 1, cb, (const u32*)totals, offs(0));
   HAFLO_LAUNCH((k_bk_terms<true>), flat, st, d_X, rows, cols, cursor, (const u32*)offs(0), sorted, stats);
   // The products run on pairs of residues modulo n (5/8 of the limb products of a full-length product; every
   // supported key size has that geometry): the ciphertexts are taken into the pair form once (two products each,
@@ -764,7 +781,7 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
   for (int r = 0; r < p.rounds; ++r) {
     // upper bound of the chunks of this round: one lane group each, capped by the grid-stride loop
     size_t bound = rows * cols * kMaxPos;
-    for (int i = 0; i <= r; ++i) bound = bound / kChunk + K;
+    for (int i = 0; i <= r; ++i) bound = (bound >> cb) + K;
     const LaunchShape sh = launch_shape(ctx, bound, lanes, 3);
     u32* out = ws + p.off_arena[r & 1];
     const u32* srt = r == 0 ? (const u32*)sorted : (const u32*)nullptr;
@@ -775,13 +792,13 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
       osh.threads = osh.gpb = kBlockThreads;
       osh.blocks = (int)std::min((bound + kBlockThreads - 1) / kBlockThreads, (size_t)ctx->num_cu * 8);
       u32* order = ws + p.off_order;
-      HAFLO_LAUNCH((k_bk_order<false>), osh, st, (const u32*)cnt, (const u32*)offs(r + 1), K, r, stats, order);
-      HAFLO_LAUNCH((k_bk_order<true>), osh, st, (const u32*)cnt, (const u32*)offs(r + 1), K, r, stats, order);
+      HAFLO_LAUNCH((k_bk_order<false>), osh, st, (const u32*)cnt, (const u32*)offs(r + 1), K, r, cb, stats, order);
+      HAFLO_LAUNCH((k_bk_order<true>), osh, st, (const u32*)cnt, (const u32*)offs(r + 1), K, r, cb, stats, order);
       ord = order;
     }
 #define CALL_ROUND(LPT, T, FIRST)                                                                        \
   HAFLO_LAUNCH((k_bk_round<LPT, T, FIRST, true>), sh, st, M, one, items, srt, (const u32*)cnt,          \
-               (const u32*)offs(r), (const u32*)offs(r + 1), K, r, stats, ord, out)
+               (const u32*)offs(r), (const u32*)offs(r + 1), K, r, cb, stats, ord, out)
 #define CALL(LPT, T) do { if (r == 0) CALL_ROUND(LPT, T, true); else CALL_ROUND(LPT, T, false); } while (0)
     HAFLO_DISPATCH_PAIRS(mh, CALL);
 #undef CALL
@@ -797,7 +814,7 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
     const LaunchShape sh = launch_shape(ctx, combos * kSubProducts * kSubSplit, lanes, 8);
 #define CALL(LPT, T)                                                                                    \
   HAFLO_LAUNCH((k_bk_sub<LPT, T, true>), sh, st, M, one, (const u32*)(ws + p.off_arena[0]),            \
-               (const u32*)(ws + p.off_arena[1]), (const u32*)cnt, (const u32*)offs(0), K, (const u32*)stats, combos, G)
+               (const u32*)(ws + p.off_arena[1]), (const u32*)cnt, (const u32*)offs(0), K, cb, (const u32*)stats, combos, G)
     HAFLO_DISPATCH_PAIRS(mh, CALL);
 #undef CALL
   }

@@ -300,6 +300,26 @@ def test_bucket_matvec_random(env, force_buckets):
     _xtd_case(env, X, 21)
 
 
+def test_bucket_matvec_long_chunks(env, force_buckets):
+    """A matrix tall enough for the one-unit emulated chip to switch to chunks of 32 items (from 49152
+    exponent digits on): few magnitudes, so that buckets hold thousands of rows and three rounds run,
+    two of them with their chunks handed out by length. The ciphertexts are random units modulo n^2."""
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    rows, cols = 12500, 2
+    rng = random.Random(5)
+    cs = [rng.randrange(2, pk.nsq) for _ in range(rows)]
+    npr = np.random.default_rng(12)
+    X = npr.choice(np.array([1025, -1025, 3 * 1024 + 7, -(2 * 1024 + 7), 5 * 1024 - 3], dtype=np.int32), size=(rows, cols))
+    X[::500, 1] = 0
+    d_c = zeros(lib, (rows, nlw))
+    assert lib.haflo_import_cipher(ctx, words(lib, cs, BITS // 16).p, d_c.p, None, rows, None) == 0
+    w, nb = ws(lib, ctx, _cabi.OP_MATVEC_XT_D, rows, cols)
+    d_o = zeros(lib, (cols, nlw))
+    assert lib.haflo_cipher_matvec(ctx, 0, d_c.p, Dev(lib, X).p, rows, cols, d_o.p, w.p, nb, None) == 0
+    assert export(lib, ctx, d_o, cols) == O.matvec(pk, 0, cs, X.tolist())
+
+
 def test_bucket_matvec_heavy_buckets(env, force_buckets):
     """Columns of equal entries put every row into one bucket, which then takes several
     reduction rounds (37 rows > 32 items per chunk); a zero column gives the encryption-free one."""
