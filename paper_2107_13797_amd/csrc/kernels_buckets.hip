@@ -364,10 +364,11 @@ __global__ __launch_bounds__(kBlockThreads, 3) void k_bk_round(ModRef M, const u
 // Sub-products of one (position, column, sign): item g < 16: prod_l B[32 g + l]; item 16 + l: prod_h B[32 h + l].
 // B[k] is the single item left of key k after the last round that ran (one when the bucket is empty,
 // cnt[k] = 0): item offs_r[k] of that round's output arena, offs_r the offsets of the round after it.
-// An item's factors are split over kSubSplit neighbouring lane groups of a block, which multiply their
-// shares side by side and then combine them pairwise through LDS: a chain of 8 + 2 products instead of 32.
-constexpr int kSubSplit = 4;
-template <int LPT, int T, bool PAIR>
+// SPLIT = 4: an item's factors are split over four neighbouring lane groups of a block, which multiply their
+// shares side by side and then combine them pairwise through LDS: a chain of 8 + 2 products instead of 32, for
+// calls with so few items that the chain is what they wait for. SPLIT = 1: one group per item, no product slot
+// spent on combining, for calls whose items fill the chip.
+template <int LPT, int T, bool PAIR, int SPLIT>
 __global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* __restrict__ one,
                                                           const u32* __restrict__ arena0,
                                                           const u32* __restrict__ arena1,
@@ -377,8 +378,10 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* _
   using Ops = ElemOps<LPT, T, PAIR>;
   constexpr int EL = Ops::kLimbs;
   constexpr int GPB = kBlockThreads / Grp<T>::kPitch;
+  constexpr int kSubSplit = SPLIT;
+  static_assert(SPLIT == 1 || SPLIT == 4, "the pairwise combination below is written for four shares");
   static_assert(GPB % kSubSplit == 0 && kSubSplit * Grp<T>::kPitch <= WAVE, "the groups of an item share a wavefront");
-  __shared__ u32 lds[(GPB / 2) * EL];
+  __shared__ u32 lds[SPLIT > 1 ? (GPB / 2) * EL : 1];
   Grp<T> g;
   Batch<T> bt;
   ModRegs<LPT> mod;
@@ -416,20 +419,22 @@ __global__ __launch_bounds__(kBlockThreads) void k_bk_sub(ModRef M, const u32* _
       next = (e + 1 < kLoCount / kSubSplit) ? locate(e + 1) : nullptr;
       const u32 touch = Ops::touch(next ? next : one, g);
       if (wave_any(cur != nullptr)) Ops::mul_mem(acc, cur ? cur : one, mod, g);
-      any = any || cur != nullptr;
+      if (SPLIT > 1) any = any || cur != nullptr;
       keep_live(touch);
     }
     // shares 2, 3 hand theirs to shares 0, 1; then share 1 to share 0. Every group of a wavefront runs the
     // products (the ones with nothing to take multiply by one), so that all lanes stay on the same path; the
     // groups of an item sit in one wavefront, and a wavefront whose items are all empty (an unused digit
     // position) skips them.
-    const bool work = wave_any(any);
+    if constexpr (SPLIT > 1) {
+      const bool work = wave_any(any);
 #pragma unroll 1
-    for (int half = kSubSplit / 2; half >= 1; half >>= 1) {
-      if (part >= half && part < 2 * half) Ops::store(slot, acc, g);
-      __syncthreads();
-      if (work) Ops::mul_mem(acc, part < half ? (const u32*)(slot + (size_t)(half == 1 ? 1 : 0) * EL) : one, mod, g);
-      __syncthreads();
+      for (int half = kSubSplit / 2; half >= 1; half >>= 1) {
+        if (part >= half && part < 2 * half) Ops::store(slot, acc, g);
+        __syncthreads();
+        if (work) Ops::mul_mem(acc, part < half ? (const u32*)(slot + (size_t)(half == 1 ? 1 : 0) * EL) : one, mod, g);
+        __syncthreads();
+      }
     }
     if (active && part == 0) Ops::store(G + it * (size_t)EL, acc, g);
   }
@@ -811,12 +816,16 @@ int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, s
   u32* R = ws + p.off_R;
   {
     // half of the items belong to unused digit positions and leave at once
-    const LaunchShape sh = launch_shape(ctx, combos * kSubProducts * kSubSplit, lanes, 8);
-#define CALL(LPT, T)                                                                                    \
-  HAFLO_LAUNCH((k_bk_sub<LPT, T, true>), sh, st, M, one, (const u32*)(ws + p.off_arena[0]),            \
+    // one lane group per sub-product once those alone give every SIMD four wavefronts, else four
+    const bool split = combos * kSubProducts * (size_t)lanes < (size_t)ctx->num_cu * 16 * WAVE;
+    const LaunchShape sh = launch_shape(ctx, combos * kSubProducts * (split ? 4 : 1), lanes, 8);
+#define CALL_SUB(LPT, T, SPLIT)                                                                         \
+  HAFLO_LAUNCH((k_bk_sub<LPT, T, true, SPLIT>), sh, st, M, one, (const u32*)(ws + p.off_arena[0]),     \
                (const u32*)(ws + p.off_arena[1]), (const u32*)cnt, (const u32*)offs(0), K, cb, (const u32*)stats, combos, G)
+#define CALL(LPT, T) do { if (split) CALL_SUB(LPT, T, 4); else CALL_SUB(LPT, T, 1); } while (0)
     HAFLO_DISPATCH_PAIRS(mh, CALL);
 #undef CALL
+#undef CALL_SUB
   }
   {
     const LaunchShape sh = launch_shape(ctx, combos * kSegs, lanes, 8);
