@@ -666,6 +666,26 @@ def test_summation_segments(env, offsets):
     assert st.get()[0] == 0
 
 
+def test_summation_segments_long_chunks(env):
+    """An array long enough for the one-unit emulated chip to take chunks of 32 elements (from 49152
+    elements on): one slice of 40000 elements (four rounds), a short one, an empty one and the rest."""
+    lib, ctx, sk, nlw = env
+    pk = sk.public
+    rng = random.Random(79)
+    count = 49500
+    cs = [rng.randrange(1, pk.nsq) for _ in range(count)]
+    d_c = zeros(lib, (count, nlw))
+    assert lib.haflo_import_cipher(ctx, words(lib, cs, BITS // 16).p, d_c.p, None, count, None) == 0
+    offsets = [0, 40000, 40033, 40033, count]
+    nseg = len(offsets) - 1
+    w, nb = ws(lib, ctx, _cabi.OP_SUM_SEGMENTS, count, nseg)
+    d_s, st = zeros(lib, (nseg, nlw)), zeros(lib, (1,))
+    d_off = Dev(lib, np.array(offsets, dtype=np.uint32))
+    assert lib.haflo_cipher_sum_segments(ctx, d_c.p, count, d_off.p, nseg, d_s.p, st.p, w.p, nb, None) == 0
+    assert export(lib, ctx, d_s, nseg) == O.summation_segments(pk, cs, offsets)
+    assert st.get()[0] == 0
+
+
 def test_summation_segments_bad_offsets_and_arguments(env):
     """Offsets that run backwards or past the array are clipped and flagged; nothing outside the
     array is read (the emulated buffers end at a guard page)."""
