@@ -737,7 +737,6 @@ XtdBucketPlan xtd_bucket_plan(const haflo_ctx* ctx, size_t rows, size_t cols) {
 
 int xtd_buckets(const haflo_ctx* ctx, const uint32_t* d_c, const int32_t* d_X, size_t rows, size_t cols,
                 uint32_t* ws, uint32_t* d_P, hipStream_t st) {
-  const ModHost& m = ctx->N;
   const XtdBucketPlan p = xtd_bucket_plan(ctx, rows, cols);
   const int cb = p.chunk_bits;
   if (p.rounds + 1 > kMaxComp || kStatNextChunk + p.rounds > kStatWords) return HAFLO_EINVAL;
