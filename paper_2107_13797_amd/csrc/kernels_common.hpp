@@ -250,7 +250,16 @@ __device__ __forceinline__ void engine_run_pairs(const ModRef& M, const Prog& P,
         const u32* src;
         if (op == ENG_MUL_C) src = io.constant[a];
         else src = table + (size_t)(op == ENG_MUL_TD ? (u32)(k >> a) & 15u : a) * (2 * NL);
-        pairmul_mem<LPT, T>(x0, x1, x0, x1, src, mod.n, mod.n0inv, g);
+        if (Grp<T>::kWhole) {
+          // a lone wavefront cannot hide a load every few steps: the lanes fetch their limbs of the
+          // multiplier once and the steps take them from registers
+          u32 t0[LPT], t1[LPT];
+          load_limbs<LPT, T>(t0, src, g);
+          load_limbs<LPT, T>(t1, src + NL, g);
+          pairmul<LPT, T>(x0, x1, x0, x1, t0, t1, mod.n, mod.n0inv, g);
+        } else {
+          pairmul_mem<LPT, T>(x0, x1, x0, x1, src, mod.n, mod.n0inv, g);
+        }
         if (op == ENG_MUL_T_ST) {
           store_limbs<LPT, T>(table + (size_t)b * (2 * NL), x0, g);
           store_limbs<LPT, T>(table + (size_t)b * (2 * NL) + NL, x1, g);

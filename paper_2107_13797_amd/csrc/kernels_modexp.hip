@@ -283,6 +283,13 @@ template <class Prog>
 int launch_engine_pairs(const ModHost& mh, const LaunchShape& sh, hipStream_t st, const Prog& prog,
                         const EngineIO& io, size_t count) {
 #define CALL(T) HAFLO_LAUNCH((k_engine_pairs<9, T, Prog>), sh, st, mh.ref(), prog, io, count)
+  if (sh.geo == kGeoWave) {
+    // one pair per wavefront: 36 lanes of 2 limbs or 48 lanes of 3 limbs for each half
+    if (mh.nl == 72) HAFLO_LAUNCH((k_engine_pairs<2, 36, Prog>), sh, st, mh.ref(), prog, io, count);
+    else if (mh.nl == 144) HAFLO_LAUNCH((k_engine_pairs<3, 48, Prog>), sh, st, mh.ref(), prog, io, count);
+    else return HAFLO_EINVAL;
+    return hip_status(hipGetLastError());
+  }
   if (mh.lpt != 18) return HAFLO_EINVAL;
   switch (mh.t) {
     case 1: CALL(2); break;
@@ -419,7 +426,10 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
     io.table_entries = ctx->prog_enc.table_entries;
     ProgPtr prog = {ctx->prog_enc.d_ins, (int)ctx->prog_enc.host.size()};
     const BatchSplit b = split_batch(ctx, count, m);
-    if (b.shape.geo != kGeoPlain) return launch_engine(m, b.shape, st, prog, io, count);
+    // one integer per wavefront: from 2048-bit keys on the pair arithmetic pays there too (half the steps of a
+    // product, each with two accumulator windows: 4 % off the chain at 2048 bits, 11 % at 4096)
+    const bool wave_pairs = b.shape.geo == kGeoWave && (ctx->Nh.nl == 72 || ctx->Nh.nl == 144);
+    if (b.shape.geo != kGeoPlain && !wave_pairs) return launch_engine(m, b.shape, st, prog, io, count);
     // a batch that fills the chip: the pair arithmetic modulo n (5/8 of the limb products of a product,
     // 0.57 of those of a squaring) for the full passes, the engine above for what is left over
     EngineIO pio = pair_io(ctx->Nh, io);
