@@ -5,6 +5,7 @@ at a guard page) and lock-step convergence of the cross-lane code; it is not a
 parity claim for the GPU build, which tests/test_gpu_parity.py covers.
 """
 import ctypes as C
+import os
 import random
 
 import numpy as np
@@ -412,7 +413,12 @@ def test_wider_lane_groups(emu, bits):
     lib.haflo_ctx_destroy(ctx)
 
 
-@pytest.mark.parametrize("bits,count", [(1024, 1)])
+@pytest.mark.parametrize("bits,count", [
+    (1024, 1),
+    # the pair engine with one pair per wavefront (36 lanes, 2 limbs of each half): a minute and a half emulated
+    pytest.param(2048, 1, marks=pytest.mark.skipif(not os.environ.get("HAFLO_SLOW_TESTS"),
+                                                   reason="slow: set HAFLO_SLOW_TESTS=1")),
+])
 def test_whole_wavefront_groups_encrypt_decrypt(emu, bits, count):
     """Batches of at most one element per SIMD give every big integer a wavefront to itself (18 to 48
     lanes with 2 or 3 limbs each, neighbour exchange across DPP rows, the quotient digit through a
