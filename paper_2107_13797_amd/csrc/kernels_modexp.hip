@@ -261,6 +261,12 @@ EngineIO pair_io(const ModHost& ms, EngineIO io) {
 int launch_engine_pairs2(const ModHost& mh, const LaunchShape& sh, hipStream_t st, const EngineJob& j0,
                          const EngineJob& j1, unsigned split, size_t count) {
 #define CALL(T) HAFLO_LAUNCH((k_engine_pairs2<9, T>), sh, st, j0, j1, split, count)
+  if (sh.geo == kGeoWave) {
+    // one pair per wavefront: 36 lanes with 2 limbs of each half
+    if (mh.nl != 72) return HAFLO_EINVAL;
+    HAFLO_LAUNCH((k_engine_pairs2<2, 36>), sh, st, j0, j1, split, count);
+    return hip_status(hipGetLastError());
+  }
   if (mh.lpt == 9 && mh.t == 1) {
     CALL(1);
     return hip_status(hipGetLastError());
@@ -479,9 +485,10 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
     }
     const unsigned split = (unsigned)sh.blocks;
     sh.blocks *= 2;
-    if (stage == 1 && sh.geo == kGeoPlain) {
-      // a batch that fills the chip: the second stage on pairs modulo the primes (same result, the canonical
-      // integer modulo the prime's square, from about 0.6 of the limb products)
+    if (stage == 1 && (sh.geo == kGeoPlain || (sh.geo == kGeoWave && ctx->P.nl == 72))) {
+      // a batch that fills the chip (or, at a 4096-bit key, one integer per wavefront): the second stage on pairs
+      // modulo the primes (same result, the canonical integer modulo the prime's square, from about 0.6 of the
+      // limb products)
       for (int side = 0; side < 2; ++side) {
         const ModHost& ms = side ? ctx->Q : ctx->P;
         const DevProg& dp = side ? ctx->prog_lift_pairs_q : ctx->prog_lift_pairs_p;
@@ -681,9 +688,9 @@ int decrypt_launches(const haflo_ctx* ctx, const void* d_cipher, uint32_t* d_pla
     }
     const unsigned split = (unsigned)sh.blocks;
     sh.blocks *= 2;
-    if (sh.geo == kGeoPlain) {
-      // a batch that fills the chip: both branches on pairs modulo the primes; what comes out is the second
-      // half of the pair 1 + s L, the quotient L_s itself
+    if (sh.geo == kGeoPlain || (sh.geo == kGeoWave && ctx->P.nl == 72)) {
+      // a batch that fills the chip (or, at a 4096-bit key, one integer per wavefront): both branches on pairs
+      // modulo the primes; what comes out is the second half of the pair 1 + s L, the quotient L_s itself
       for (int side = 0; side < 2; ++side) {
         const ModHost& ms = side ? ctx->Q : ctx->P;
         const DevProg& dp = side ? ctx->prog_dec_pairs_q : ctx->prog_dec_pairs_p;
