@@ -557,17 +557,23 @@ def test_taylor_loss_sequence(api):
             assert flag == 1 and dev_to_ints(api.haflo_export_cipher(ctx, out)) == [want]
 
 
-@pytest.mark.parametrize("kind", ["int32_range", "one_hot", "sparse_small"])
+@pytest.mark.parametrize("kind", ["int32_range", "one_hot", "sparse_small", "many_columns"])
 def test_xtd_methods_agree_at_scale(api, kind):
     """Tall matrices beyond what the oracle can multiply: both X^T [[d]] methods must give the same
     canonical ciphertexts, and every output must decrypt to sum_i x_ij m_i mod n. The shapes put
-    up to 70000 rows into one bucket (five reduction rounds) and use all four digit positions."""
+    up to 70000 rows into one bucket (five reduction rounds) and use all four digit positions; the one
+    with many columns is large enough for the long chunks (32 items; four rounds for a full column)."""
     bits = 1024
     ctx, sk = context(api, bits)
     n = sk.public.n
-    rows, cols = 70001, 3
+    rows, cols = (70001, 48) if kind == "many_columns" else (70001, 3)
     rng = np.random.default_rng(91)
-    if kind == "int32_range":
+    if kind == "many_columns":
+        X = rng.integers(-(1 << 19), 1 << 19, size=(rows, cols), dtype=np.int64).astype(np.int32)
+        X[:, 0] = -(1 << 16)                      # one bucket with every row
+        X[:, 1] = np.where(rng.random(rows) < 0.5, 1023, -1025)
+        X[rng.random(X.shape) < 0.3] = 0
+    elif kind == "int32_range":
         X = rng.integers(-2 ** 31, 2 ** 31, size=(rows, cols), dtype=np.int64).astype(np.int32)
         X[0, 0], X[1, 0] = -2 ** 31, 2 ** 31 - 1
     elif kind == "one_hot":
