@@ -27,9 +27,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# MI355X: 256 compute units x 64 lanes x one v_mad_u64_u32 per lane per clock at 2.4 GHz
-# (32x32+64 integer multiply-add issues at the full VALU rate on gfx950: bench_peak.py measures it,
-# profiles/peak_microbench.md holds the figures).
+# MI355X: 256 compute units x 64 lanes x one instruction per lane and clock at 2.4 GHz, the nominal vector
+# rate. The 32x32+64 integer multiply-add itself reaches 0.66 - 0.74 of it (bench_peak.py measures that,
+# profiles/peak_microbench.md holds the figures); the nominal figure stays the denominator.
 PEAK_MAD32_PER_S = 256 * 64 * 2.4e9
 
 # HBM bytes of the encryption launch at the profiled shape (2048-bit key, 65536 elements): rocprofv3 --pmc
@@ -88,6 +88,45 @@ def _oracle_operators_one_core(p, q, seed):
     return res
 
 
+def _gmp_powm_one_core(n, rs, want_rn):
+    """Secondary CPU figure, never the checker: the same r^n mod n^2 with mpz_powm of the system's libgmp
+    through ctypes on one core (the paper's CPU column used gmpy2, which wraps the same routine).
+    -> dict, or None where the library is not there."""
+    import ctypes as C
+    try:
+        g = C.CDLL("libgmp.so.10")
+    except OSError:
+        return None
+
+    class Mpz(C.Structure):
+        _fields_ = [("alloc", C.c_int), ("size", C.c_int), ("d", C.c_void_p)]
+    for name in ("__gmpz_init", "__gmpz_clear", "__gmpz_set_str", "__gmpz_powm", "__gmpz_get_str"):
+        if not hasattr(g, name):
+            return None
+    g.__gmpz_set_str.argtypes = [C.POINTER(Mpz), C.c_char_p, C.c_int]
+    g.__gmpz_get_str.argtypes = [C.c_char_p, C.c_int, C.POINTER(Mpz)]
+    g.__gmpz_get_str.restype = C.c_char_p
+    base, exp, mod, out = Mpz(), Mpz(), Mpz(), Mpz()
+    for z in (base, exp, mod, out):
+        g.__gmpz_init(C.byref(z))
+    g.__gmpz_set_str(C.byref(exp), b"%x" % n, 16)
+    g.__gmpz_set_str(C.byref(mod), b"%x" % (n * n), 16)
+    buf = C.create_string_buffer((n * n).bit_length() // 4 + 8)
+    got, spent = [], 0.0
+    for r in rs:
+        g.__gmpz_set_str(C.byref(base), b"%x" % r, 16)
+        t0 = time.perf_counter()
+        g.__gmpz_powm(C.byref(out), C.byref(base), C.byref(exp), C.byref(mod))
+        spent += time.perf_counter() - t0
+        got.append(int(g.__gmpz_get_str(buf, 16, C.byref(out)), 16))
+    for z in (base, exp, mod, out):
+        g.__gmpz_clear(C.byref(z))
+    assert got == want_rn, "libgmp disagrees with python's pow"
+    return {"value": len(rs) / spent, "unit": "modexp/s", "cores": 1, "kind": "libgmp mpz_powm through ctypes; "
+            "a secondary figure, not the oracle and never the checker",
+            "sample": "%d of the same r^n mod n^2, %.1f s" % (len(rs), spent)}
+
+
 def cpu_baseline(p, q, ms, rs, want):
     """The oracle's encryption (the same r^n modexp the GPU headline counts) on all host cores and on
     one core, and the other operators on one core."""
@@ -112,6 +151,7 @@ def cpu_baseline(p, q, ms, rs, want):
                       "%.1f core-seconds" % (done, sum(t for t, _ in res)),
             "one_core": {"value": k1 / t1, "unit": "modexp/s", "cores": 1,
                          "sample": "the first %d of the same encryptions, %.1f s" % (k1, t1)},
+            "gmp_one_core": _gmp_powm_one_core(n, rs[:96], [pow(r, n, n * n) for r in rs[:96]]),
             "operators_one_core": _oracle_operators_one_core(p, q, 99),
             "operators_note": "python int oracle at the benchmark's key size, one core, instances per second "
                               "(the shape of the paper's one-core CPU column in its Table 2)"}
