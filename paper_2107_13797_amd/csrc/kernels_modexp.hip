@@ -176,13 +176,14 @@ __global__ __launch_bounds__(kBlockThreads) void k_enc_crt(ModRef MP2, ModRef MQ
 // wavefront to itself (a few limbs per lane: the shortest steps); beyond that, while twice the lanes still
 // are at most two wavefronts per SIMD, its integers are spread over twice the lanes (9 limbs each), which
 // shortens every product of the chain at 1.2 times the instructions. `jobs`: independent halves of one launch.
-int engine_geo(const haflo_ctx* ctx, size_t count, const ModHost& m, int jobs = 1) {
+// `nine`: take 9 limbs per lane (twice the lanes per integer) also for a batch that fills the chip.
+int engine_geo(const haflo_ctx* ctx, size_t count, const ModHost& m, int jobs = 1, bool nine = false) {
   if (haflo_has_wave_geometry(m) && count * (size_t)jobs <= (size_t)ctx->num_cu * 4) return kGeoWave;
-  if (m.lpt == 18 && m.t < 16 && count * (size_t)m.t <= (size_t)ctx->num_cu * 256) return kGeoWide;
+  if (m.lpt == 18 && m.t < 16 && (nine || count * (size_t)m.t <= (size_t)ctx->num_cu * 256)) return kGeoWide;
   return kGeoPlain;
 }
-LaunchShape modexp_shape(const haflo_ctx* ctx, size_t count, const ModHost& m, int jobs = 1) {
-  const int geo = engine_geo(ctx, count, m, jobs);
+LaunchShape modexp_shape(const haflo_ctx* ctx, size_t count, const ModHost& m, int jobs = 1, bool nine = false) {
+  const int geo = engine_geo(ctx, count, m, jobs, nine);
   LaunchShape s;
   if (geo == kGeoWave) {
     s.blocks = (int)(count ? count : 1);
@@ -371,7 +372,7 @@ size_t ws_encrypt(const haflo_ctx* ctx, size_t count) {
   // grid; for the last stage one table slot of N.nl limbs per lane group]
   size_t tl1 = (size_t)std::max(ctx->prog_enc_p.table_entries, ctx->prog_enc_q.table_entries);
   size_t tl2 = (size_t)std::max(ctx->prog_lift_p.table_entries, ctx->prog_lift_q.table_entries);
-  size_t low = 2 * modexp_shape(ctx, count, ctx->P, 2).slots() * tl1 * ctx->P.nl;
+  size_t low = 2 * modexp_shape(ctx, count, ctx->P, 2, true).slots() * tl1 * ctx->P.nl;
   size_t lift = 2 * modexp_shape(ctx, count, ctx->P2, 2).slots() * tl2 * ctx->P2.nl;
   size_t last = modexp_shape(ctx, count, ctx->N).slots() * (size_t)ctx->N.nl;
   return (2 * count * (size_t)ctx->P2.nl + count * (size_t)ctx->N.nl + std::max(std::max(low, lift), last)) * 4;
@@ -463,7 +464,8 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
     const ModHost& geo = stage ? h : l;
     const DevProg* progs[2] = {stage ? &ctx->prog_lift_p : &ctx->prog_enc_p, stage ? &ctx->prog_lift_q : &ctx->prog_enc_q};
     const int tl = std::max(progs[0]->table_entries, progs[1]->table_entries);
-    LaunchShape sh = modexp_shape(ctx, count, geo, 2);
+    // the first stage (plain residues modulo the primes) runs faster on 9 limbs per lane at any batch size
+    LaunchShape sh = modexp_shape(ctx, count, geo, 2, stage == 0);
     EngineJob job[2];
     for (int side = 0; side < 2; ++side) {
       const ModHost& ms = stage ? (side ? ctx->Q2 : ctx->P2) : (side ? ctx->Q : ctx->P);
