@@ -379,7 +379,7 @@ size_t ws_encrypt(const haflo_ctx* ctx, size_t count) {
 }
 // one table slot per resident lane group
 size_t ws_encrypt_obf(const haflo_ctx* ctx, size_t count) {
-  return launch_shape(ctx, count, ctx->N.t, 8).slots() * (size_t)ctx->N.nl * 4;
+  return launch_shape(ctx, count, haflo_wide_lanes(ctx->N), 8).slots() * (size_t)ctx->N.nl * 4;
 }
 // sized for the per-element variant (16 entries); the broadcast variant never needs more
 size_t ws_scalar_mul(const haflo_ctx* ctx, size_t count) {
@@ -565,7 +565,10 @@ int haflo_encrypt_with_obfuscator(const haflo_ctx* ctx, const uint32_t* d_plain,
   io.out = (u32*)d_cipher;
   io.tables = (u32*)d_workspace;
   io.table_entries = 1;
-  return launch_engine(m, launch_shape(ctx, count, m.t, 8), (hipStream_t)stream, pi, io, count);
+  // 9 limbs per lane: the 18-limb form of the engine spills registers
+  LaunchShape sh = launch_shape(ctx, count, haflo_wide_lanes(m), 8);
+  sh.geo = m.lpt == 18 && m.t < 16 ? kGeoWide : kGeoPlain;
+  return launch_engine(m, sh, (hipStream_t)stream, pi, io, count);
 }
 
 int haflo_scalar_mul_u64(const haflo_ctx* ctx, const void* d_c, const uint64_t* d_k, void* d_out, size_t count,
