@@ -408,7 +408,10 @@ int power_tables(const haflo_ctx* ctx, const uint32_t* d_c, uint32_t* d_tables, 
   io.tables = d_tables;
   io.table_entries = entries;
   io.table_per_item = 1;
-  return launch_engine(m, launch_shape(ctx, count, m.t, 8), st, pi, io, count);
+  // 9 limbs per lane: the 18-limb form of the engine spills registers
+  LaunchShape sh = launch_shape(ctx, count, haflo_wide_lanes(m), 8);
+  sh.geo = m.lpt == 18 && m.t < 16 ? kGeoWide : kGeoPlain;
+  return launch_engine(m, sh, st, pi, io, count);
 }
 }  // namespace haflo
 
