@@ -179,7 +179,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_enc_crt(ModRef MP2, ModRef MQ
 // `nine`: take 9 limbs per lane (twice the lanes per integer) also for a batch that fills the chip.
 int engine_geo(const haflo_ctx* ctx, size_t count, const ModHost& m, int jobs = 1, bool nine = false) {
   if (haflo_has_wave_geometry(m) && count * (size_t)jobs <= (size_t)ctx->num_cu * 4) return kGeoWave;
-  if (m.lpt == 18 && m.t < 16 && (nine || count * (size_t)m.t <= (size_t)ctx->num_cu * 256)) return kGeoWide;
+  if (m.lpt == 18 && m.t < 16 && (nine || count * (size_t)jobs * (size_t)m.t <= (size_t)ctx->num_cu * 256)) return kGeoWide;
   return kGeoPlain;
 }
 LaunchShape modexp_shape(const haflo_ctx* ctx, size_t count, const ModHost& m, int jobs = 1, bool nine = false) {
