@@ -349,7 +349,10 @@ def main():
             row = [x for x in rep[k] if x["op"].startswith("matvec")][0]
             out["xt_d_entries_per_s_cfg%d" % k] = row["rate"]
         out["configs_note"] = ("per operator: units, ms (one run after a warm-up, HIP events), units per second, "
-                               "fraction of the bounding roofline (alu: 39.3e12 mul32/s, hbm: 8 TB/s)")
+                               "fraction of the bounding roofline (alu: 39.3e12 mul32/s, hbm: 8 TB/s); frac counts every "
+                               "product of the schedule as a full-length Montgomery product (it can pass 1 where the "
+                               "kernels work on pairs of half-length residues), frac_executed the multiply-adds "
+                               "really issued")
     print(json.dumps(out))
 
 
