@@ -343,6 +343,7 @@ int launch_power_batch(const haflo_ctx* ctx, hipStream_t st, const ProgInline& p
   int rc = launch_engine_pairs(ctx->Nh, b.shape, st, ppi, pair_io(ctx->Nh, io), full);
   if (rc != HAFLO_OK || full == count) return rc;
   io.first = full;
+  if (b.tail.geo == kGeoPlain) return launch_engine_pairs(ctx->Nh, b.tail, st, ppi, pair_io(ctx->Nh, io), count - full);
   return launch_engine(m, b.tail, st, pi, io, count - full);
 }
 
@@ -448,6 +449,12 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
     const size_t full = b.full ? b.full : count;
     int rc = launch_engine_pairs(ctx->Nh, b.shape, st, pprog, pio, full);
     if (rc != HAFLO_OK || full == count) return rc;
+    // what is left over: on pairs as well while it still is a batch of many wavefronts, else the engine above
+    // in the geometry of a small batch
+    if (b.tail.geo == kGeoPlain) {
+      pio.first = full;
+      return launch_engine_pairs(ctx->Nh, b.tail, st, pprog, pio, count - full);
+    }
     io.first = full;
     return launch_engine(m, b.tail, st, prog, io, count - full);
   }

@@ -931,16 +931,18 @@ def test_encrypt_with_obfuscator_matches_encrypt(api):
         n, [ms[i] for i in idx], synth.words_to_ints(r_words[idx]))
 
 
-def test_batch_with_partial_last_pass(api):
-    """A batch a little larger than the resident lane groups is run as full passes plus a
-    remainder launch; elements on both sides of the cut and at the very end must be right."""
+@pytest.mark.parametrize("extra", ["few", "half_a_pass"])
+def test_batch_with_partial_last_pass(api, extra):
+    """A batch larger than the resident lane groups is run as full passes plus a remainder launch (a
+    small remainder in the geometry of a small batch, a large one on pairs like the full passes);
+    elements on both sides of the cut and at the very end must be right."""
     bits = 1024
     ctx, sk = context(api, bits)
     n = sk.public.n
     lp = bits // 32
     props = torch.cuda.get_device_properties(0)
     slots = props.multi_processor_count * 4 * (256 // 4)  # blocks per chip x lane groups per block
-    count = slots + 137
+    count = slots + (137 if extra == "few" else slots // 2 + 5)
     rng = np.random.default_rng(98)
     m_words = rng.integers(0, 2 ** 32, size=(count, lp), dtype=np.uint32)
     m_words[:, -1] &= 0x3FFFFFFF
