@@ -547,6 +547,13 @@ int haflo_encrypt(const haflo_ctx* ctx, const uint32_t* d_plain, const uint32_t*
   io.out = (u32*)d_cipher;
   io.tables = tables;
   io.table_entries = 1;
+  // three products per element: a batch that fills the chip takes 9 limbs per lane in one launch (the 18-limb
+  // form of the engine spills registers), smaller ones the geometries of small batches
+  if (m.lpt == 18 && m.t < 16 && engine_geo(ctx, count, m) == kGeoPlain) {
+    LaunchShape sh = launch_shape(ctx, count, 2 * m.t, kModexpBlocksPerCu);
+    sh.geo = kGeoWide;
+    return launch_engine(m, sh, st, pi, io, count);
+  }
   return launch_engine_batch(ctx, m, st, pi, io, count);
 }
 
