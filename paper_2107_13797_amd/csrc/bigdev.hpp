@@ -214,7 +214,9 @@ __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT
   u32 ring[RING];
 #pragma unroll
   for (int d = 0; d < D; ++d) ring[d] = bsrc.limb(0, d, g);
-#pragma unroll 1
+  // a whole-wavefront group has only 2 to 6 steps per lane: four lanes' worth per loop round, so that the sliding
+  // window and the ring of requested limbs need no register moves (11 % off a lone wavefront's chain)
+#pragma unroll(Grp<T>::kWhole ? 4 : 1)
   for (int o = 0; o < T; ++o) {
     static_for<0, LPT>([&](auto rc) {
       constexpr int r = decltype(rc)::value;
@@ -362,7 +364,7 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
     ring0[d] = bsrc.limb0(0, d, g);
     ring1[d] = bsrc.limb1(0, d, g);
   }
-#pragma unroll 1
+#pragma unroll(Grp<T>::kWhole ? 4 : 1)
   for (int o = 0; o < T; ++o) {
     static_for<0, LPT>([&](auto rc) {
       constexpr int r = decltype(rc)::value;
