@@ -152,10 +152,13 @@ __device__ __forceinline__ void hi_normalise(u64 (&A)[LPT], const Grp<T>& g, u32
 template <int LPT, int T>
 struct BRegs {
   const u32 (&b)[LPT];
-  // a step of few limbs is short: ask earlier, so that the crossbar's latency stays covered
-  static constexpr int kAhead = LPT <= 3 ? LPT : (LPT <= 8 && LPT % 2 == 0 ? 2 : 1);
+  // a step of few limbs is short: ask earlier, so that the crossbar's latency stays covered. A whole-wavefront
+  // group reads the limb into a scalar register instead (the lane index is wave-uniform): one instruction, no
+  // address register, nothing to wait for.
+  static constexpr int kAhead = Grp<T>::kWhole ? 0 : (LPT <= 3 ? LPT : (LPT <= 8 && LPT % 2 == 0 ? 2 : 1));
   __device__ __forceinline__ u32 limb(int o, int rr, const Grp<T>& g) const {
     if (T == 1) return b[rr % LPT];
+    if (Grp<T>::kWhole) return (u32)__builtin_amdgcn_readlane((int)b[rr % LPT], o + rr / LPT);
     // past the last limb this reads a lane of the next group (or wraps); that value is never used
     return (u32)__builtin_amdgcn_ds_bpermute(g.base_addr + ((o + rr / LPT) << 2), (int)b[rr % LPT]);
   }
@@ -320,10 +323,12 @@ struct BRegs2 {
   static constexpr int kAhead = BRegs<LPT, T>::kAhead;
   __device__ __forceinline__ u32 limb0(int o, int rr, const Grp<T>& g) const {
     if (T == 1) return b0[rr % LPT];
+    if (Grp<T>::kWhole) return (u32)__builtin_amdgcn_readlane((int)b0[rr % LPT], o + rr / LPT);
     return (u32)__builtin_amdgcn_ds_bpermute(g.base_addr + ((o + rr / LPT) << 2), (int)b0[rr % LPT]);
   }
   __device__ __forceinline__ u32 limb1(int o, int rr, const Grp<T>& g) const {
     if (T == 1) return b1[rr % LPT];
+    if (Grp<T>::kWhole) return (u32)__builtin_amdgcn_readlane((int)b1[rr % LPT], o + rr / LPT);
     return (u32)__builtin_amdgcn_ds_bpermute(g.base_addr + ((o + rr / LPT) << 2), (int)b1[rr % LPT]);
   }
 };
