@@ -121,6 +121,14 @@ __device__ __forceinline__ u32 opaque_eight() {
   return e;
 }
 
+// The limb mask in a vector register: an AND with it can carry a DPP lane shift on its other operand, which
+// a literal operand rules out.
+__device__ __forceinline__ u32 opaque_mask() {
+  u32 m = 0x1fffffffu;
+  asm volatile("" : "+v"(m));
+  return m;
+}
+
 // Keeps a loaded value (and so the load) alive up to this point without using it.
 __device__ __forceinline__ void keep_live(u32 v) { asm volatile("" ::"r"(v)); }
 
@@ -206,6 +214,7 @@ __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT
                                              const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
   static_assert(LPT <= 18, "a column must not collect more than 36 products");
   const u32 eight = opaque_eight();
+  [[maybe_unused]] const u32 maskv = opaque_mask();
   u64 A[LPT];
 #pragma unroll
   for (int j = 0; j < LPT; ++j) A[j] = 0;
@@ -219,7 +228,8 @@ __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT
   for (int d = 0; d < D; ++d) ring[d] = bsrc.limb(0, d, g);
   // a whole-wavefront group has only 2 to 6 steps per lane: four lanes' worth per loop round, so that the sliding
   // window and the ring of requested limbs need no register moves (11 % off a lone wavefront's chain)
-#pragma unroll(Grp<T>::kWhole ? 4 : 1)
+  constexpr int kLanesPerRound = Grp<T>::kWhole ? 4 : 1;
+#pragma unroll kLanesPerRound
   for (int o = 0; o < T; ++o) {
     static_for<0, LPT>([&](auto rc) {
       constexpr int r = decltype(rc)::value;
@@ -239,12 +249,17 @@ __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT
         else if constexpr (w == 2) A[j] = mad64(a[j], bi2, A[j]);
       };
       product(std::integral_constant<int, 0>{});
-      u32 qv = ((u32)A[0] * n0inv) & LIMB_MASK;
-      u32 q = g.bcast0(qv);
+      // the quotient digit: a whole-wavefront group takes the column into a scalar register first, so that the
+      // product and the mask are scalar instructions (the pair products measured slower that way and keep the
+      // vector form)
+      u32 q;
+      if constexpr (Grp<T>::kWhole) q = (g.bcast0((u32)A[0]) * n0inv) & LIMB_MASK;
+      else q = g.bcast0(((u32)A[0] * n0inv) & LIMB_MASK);
       static_for<1, LPT>(product);
       u64 t0 = mad64(q, n[0], A[0]);
-      u32 low = (u32)t0 & LIMB_MASK;  // 0 on lane 0 of every group, by the choice of q
-      u32 recv = g.from_upper_raw(low);
+      // the low 29 bits go to the lane below (0 on lane 0 of every group, by the choice of q); masked after
+      // the move, so that the mask rides on the DPP instruction
+      u32 recv = g.from_upper_raw((u32)t0) & maskv;
       u64 carry = t0 >> LIMB_BITS;
       if (LPT > 1) {
         A[0] = mad64(q, n[1], A[1]) + carry;
@@ -352,6 +367,7 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
                                              const Grp<T>& g) {
   static_assert(LPT <= 9, "a column of the second window takes three products per step");
   const u32 eight = opaque_eight();
+  [[maybe_unused]] const u32 maskv = opaque_mask();
   u64 A[LPT], B[LPT];
 #pragma unroll
   for (int j = 0; j < LPT; ++j) {
@@ -369,7 +385,8 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
     ring0[d] = bsrc.limb0(0, d, g);
     ring1[d] = bsrc.limb1(0, d, g);
   }
-#pragma unroll(Grp<T>::kWhole ? 4 : 1)
+  constexpr int kLanesPerRound = Grp<T>::kWhole ? 4 : 1;
+#pragma unroll kLanesPerRound
   for (int o = 0; o < T; ++o) {
     static_for<0, LPT>([&](auto rc) {
       constexpr int r = decltype(rc)::value;
@@ -408,8 +425,8 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
       // both windows: add the multiple of n, hand the lowest column down, slide
       const u64 ta = mad64(qa, n[0], A[0]);
       const u64 tb = mad64(qb, n[0], B[0]);
-      const u32 recv_a = g.from_upper_raw((u32)ta & LIMB_MASK);
-      const u32 recv_b = g.from_upper_raw((u32)tb & LIMB_MASK);
+      const u32 recv_a = g.from_upper_raw((u32)ta) & maskv;
+      const u32 recv_b = g.from_upper_raw((u32)tb) & maskv;
       if (LPT > 1) {
         A[0] = mad64(qa, n[LPT > 1 ? 1 : 0], A[LPT > 1 ? 1 : 0]) + (ta >> LIMB_BITS);
         B[0] = mad64(qb, n[LPT > 1 ? 1 : 0], B[LPT > 1 ? 1 : 0]) + (tb >> LIMB_BITS);
@@ -551,6 +568,7 @@ __device__ __forceinline__ void mul_plain(u32 (&lo)[LPT], u32 (&hi)[LPT], const 
                                           const Grp<T>& g) {
   static_assert(LPT <= 18, "a column must not collect more than 36 products");
   const u32 eight = opaque_eight();
+  [[maybe_unused]] const u32 maskv = opaque_mask();
   u64 A[LPT];
   u32 res[LPT];
 #pragma unroll
