@@ -375,7 +375,11 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
     B[j] = 0;
   }
   if (g.k == 0) B[0] = 1;
-  const u32 first = (g.k == 0) ? 1u : 0u;  // the lane that holds the lowest column of the whole integer
+  u32 first = (g.k == 0) ? 1u : 0u;  // the lane that holds the lowest column of the whole integer
+  // A lone wavefront is bound by its instruction count: hide that `first` is 0 or 1, so that the term it
+  // selects stays one multiply-add instead of a move, a select and a 64-bit add. Where several wavefronts
+  // share a SIMD the multiply-adds are the bottleneck and the compiler's three cheap instructions are right.
+  if constexpr (Grp<T>::kWhole) asm volatile("" : "+v"(first));
   constexpr int D = BSrc::kAhead;
   constexpr int RING = D > 0 ? D : 1;
   static_assert(LPT % RING == 0, "ring size");
