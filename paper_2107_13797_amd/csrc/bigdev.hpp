@@ -361,7 +361,8 @@ struct BMem2 {
   }
 };
 
-template <int LPT, int T, class BSrc, bool SQ>
+// B1X2: the source hands out the limbs of b1 already doubled (a squaring that doubled them once, outside the steps)
+template <int LPT, int T, class BSrc, bool SQ, bool B1X2 = false>
 __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT], const u32 (&a0)[LPT],
                                              const u32 (&a1)[LPT], const BSrc& bsrc, const u32 (&n)[LPT], u32 n0inv,
                                              const Grp<T>& g) {
@@ -405,7 +406,7 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
         b1i = bsrc.limb1(o, r, g);
       }
       [[maybe_unused]] const u32 b0i2 = SQ ? b0i + b0i : b0i;
-      const u32 b1x = SQ ? b1i + b1i : b1i;  // squaring: 2 x0 x1 as x0 times the doubled limb of x1
+      const u32 b1x = (SQ && !B1X2) ? b1i + b1i : b1i;  // squaring: 2 x0 x1 as x0 times the doubled limb of x1
       // window A: a0 * b0 (for a squaring the products sq_weight selects)
       auto product_a = [&](auto jc) {
         constexpr int j = decltype(jc)::value;
@@ -488,8 +489,17 @@ __device__ __forceinline__ void pairmul_mem(u32 (&out0)[LPT], u32 (&out1)[LPT], 
 template <int LPT, int T>
 __device__ __forceinline__ void pairsqr(u32 (&out0)[LPT], u32 (&out1)[LPT], const u32 (&a0)[LPT], const u32 (&a1)[LPT],
                                         const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
-  BRegs2<LPT, T> src = {a0, a1};
-  pairmul_core<LPT, T, BRegs2<LPT, T>, true>(out0, out1, a0, a1, src, n, n0inv, g);
+  if constexpr (Grp<T>::kWhole) {
+    // a lone wavefront pays for every instruction of a step: double x1 once, not limb by limb as it is read
+    u32 a1d[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) a1d[j] = a1[j] + a1[j];
+    BRegs2<LPT, T> src = {a0, a1d};
+    pairmul_core<LPT, T, BRegs2<LPT, T>, true, true>(out0, out1, a0, a1, src, n, n0inv, g);
+  } else {
+    BRegs2<LPT, T> src = {a0, a1};
+    pairmul_core<LPT, T, BRegs2<LPT, T>, true>(out0, out1, a0, a1, src, n, n0inv, g);
+  }
 }
 
 // Full carry propagation of signed lazy limbs (|x[j]| < 2^30): afterwards every
