@@ -253,7 +253,7 @@ __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT
       // product and the mask are scalar instructions (the pair products measured slower that way and keep the
       // vector form)
       u32 q;
-      if constexpr (Grp<T>::kWhole) q = (g.bcast0((u32)A[0]) * n0inv) & LIMB_MASK;
+      if constexpr (Grp<T>::kWhole) q = g.bcast0(((u32)A[0] * n0inv) & maskv);
       else q = g.bcast0(((u32)A[0] * n0inv) & LIMB_MASK);
       static_for<1, LPT>(product);
       u64 t0 = mad64(q, n[0], A[0]);
@@ -415,13 +415,13 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
         else if constexpr (w == 2) A[j] = mad64(a0[j], b0i2, A[j]);
       };
       product_a(std::integral_constant<int, 0>{});
-      const u32 qa = g.bcast0(((u32)A[0] * n0inv) & LIMB_MASK);
+      const u32 qa = g.bcast0(((u32)A[0] * n0inv) & (Grp<T>::kWhole ? maskv : LIMB_MASK));
       static_for<1, LPT>(product_a);
       // window B: a0 * b1 + a1 * b0, minus the quotient digit of A on the lowest column of the integer
       B[0] = mad64(a0[0], b1x, B[0]);
       if (!SQ) B[0] = mad64(a1[0], b0i, B[0]);
       B[0] = mad64(LIMB_MASK - qa, first, B[0]);
-      const u32 qb = g.bcast0(((u32)B[0] * n0inv) & LIMB_MASK);
+      const u32 qb = g.bcast0(((u32)B[0] * n0inv) & (Grp<T>::kWhole ? maskv : LIMB_MASK));
 #pragma unroll
       for (int j = 1; j < LPT; ++j) {
         B[j] = mad64(a0[j], b1x, B[j]);
