@@ -415,12 +415,15 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
         else if constexpr (w == 2) A[j] = mad64(a0[j], b0i2, A[j]);
       };
       product_a(std::integral_constant<int, 0>{});
-      const u32 qa = g.bcast0(((u32)A[0] * n0inv) & (Grp<T>::kWhole ? maskv : LIMB_MASK));
+      const u32 qav = ((u32)A[0] * n0inv) & (Grp<T>::kWhole ? maskv : LIMB_MASK);
+      const u32 qa = g.bcast0(qav);
       static_for<1, LPT>(product_a);
       // window B: a0 * b1 + a1 * b0, minus the quotient digit of A on the lowest column of the integer
       B[0] = mad64(a0[0], b1x, B[0]);
       if (!SQ) B[0] = mad64(a1[0], b0i, B[0]);
-      B[0] = mad64(LIMB_MASK - qa, first, B[0]);
+      // only the lowest lane's term counts, and that lane's own digit is the broadcast one: a whole-wavefront
+      // group takes it from the vector register, so that no scalar instruction waits on the broadcast
+      B[0] = mad64(Grp<T>::kWhole ? (qav ^ maskv) : LIMB_MASK - qa, first, B[0]);
       const u32 qb = g.bcast0(((u32)B[0] * n0inv) & (Grp<T>::kWhole ? maskv : LIMB_MASK));
 #pragma unroll
       for (int j = 1; j < LPT; ++j) {
