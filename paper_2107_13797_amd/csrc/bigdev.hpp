@@ -288,20 +288,86 @@ __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT
   if (T > 1) out[0] += g.from_lower((u32)c);
 }
 
+// The same product for a whole-wavefront group of at most 3 limbs per lane, with the column accumulators held
+// at 8 times their value, which puts the limb boundary of the lowest column on the 32-bit word boundary:
+// the quotient digit needs no mask ((8 x) * n0inv mod 2^32 = 8 q exactly), the 29 bits for the lane below are
+// the low word as it is, and the carry is the high word (times 8 again, folded into a multiply-add). A lone
+// wavefront is bound by its instruction count, and this step has 5 multiply-adds and 4 other instructions
+// where the plain one has 4 and 7. The operands enter shifted (a by 1 bit, b by 2; a by 2 for the doubled
+// products of a squaring): lazy limbs below 2^29 + 2^8 leave room for that, and a column of at most 6 products
+// stays below 2^64 / 8. Same result as montmul_core, bit for bit.
+template <int LPT, int T, bool SQ>
+__device__ __forceinline__ void montmul_whole_x8(u32 (&out)[LPT], const u32 (&a)[LPT], const u32 (&b)[LPT],
+                                                 const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
+  static_assert(Grp<T>::kWhole && LPT >= 2 && LPT <= 3, "6 products per column at most");
+  const u32 eight = opaque_eight();
+  u32 a2[LPT], b4[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) {
+    a2[j] = a[j] << 1;
+    b4[j] = b[j] << 2;  // for a squaring also a times 4: the multiplicand of the doubled products
+  }
+  u64 A[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) A[j] = 0;
+#pragma unroll 4
+  for (int o = 0; o < T; ++o) {
+    static_for<0, LPT>([&](auto rc) {
+      constexpr int r = decltype(rc)::value;
+      const u32 bi = (u32)__builtin_amdgcn_readlane((int)b4[r], o);
+      auto product = [&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        constexpr int w = SQ ? sq_weight(LPT, j, r) : 1;
+        if constexpr (w == 1) A[j] = mad64(a2[j], bi, A[j]);
+        else if constexpr (w == 2) A[j] = mad64(b4[j], bi, A[j]);
+      };
+      product(std::integral_constant<int, 0>{});
+      const u32 q8 = g.bcast0((u32)A[0] * n0inv);
+      static_for<1, LPT>(product);
+      const u64 t0 = mad64(q8, n[0], A[0]);
+      const u32 recv = g.from_upper_raw((u32)t0);
+      A[0] = mad64((u32)(t0 >> 32), eight, mad64(q8, n[1], A[1]));
+#pragma unroll
+      for (int j = 2; j < LPT; ++j) A[j - 1] = mad64(q8, n[j], A[j]);
+      A[LPT - 1] = (u64)recv;
+    });
+  }
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) A[j] >>= 3;
+  hi_normalise<LPT, T>(A, g, eight);
+  u64 c = 0;
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) {
+    u64 v = A[j] + c;
+    out[j] = (u32)v & LIMB_MASK;
+    c = v >> LIMB_BITS;
+  }
+  out[0] += g.from_lower((u32)c);
+}
+
+
 // b in registers (out may alias a and b)
 template <int LPT, int T>
 __device__ __forceinline__ void montmul(u32 (&out)[LPT], const u32 (&a)[LPT], const u32 (&b)[LPT],
                                         const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
-  BRegs<LPT, T> src = {b};
-  montmul_core<LPT, T>(out, a, src, n, n0inv, g);
+  if constexpr (Grp<T>::kWhole && LPT <= 3) {
+    montmul_whole_x8<LPT, T, false>(out, a, b, n, n0inv, g);
+  } else {
+    BRegs<LPT, T> src = {b};
+    montmul_core<LPT, T>(out, a, src, n, n0inv, g);
+  }
 }
 
 // out = a * a / 2^(29*NL) mod n with the symmetric half of the limb products left out (out may alias a)
 template <int LPT, int T>
 __device__ __forceinline__ void montsqr(u32 (&out)[LPT], const u32 (&a)[LPT], const u32 (&n)[LPT], u32 n0inv,
                                         const Grp<T>& g) {
-  BRegs<LPT, T> src = {a};
-  montmul_core<LPT, T, BRegs<LPT, T>, true>(out, a, src, n, n0inv, g);
+  if constexpr (Grp<T>::kWhole && LPT <= 3) {
+    montmul_whole_x8<LPT, T, true>(out, a, a, n, n0inv, g);
+  } else {
+    BRegs<LPT, T> src = {a};
+    montmul_core<LPT, T, BRegs<LPT, T>, true>(out, a, src, n, n0inv, g);
+  }
 }
 
 // b = NL limbs at `bmem`, the same array for every lane of the group
