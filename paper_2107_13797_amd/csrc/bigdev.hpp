@@ -538,13 +538,100 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
   }
 }
 
+// The pair product for a whole-wavefront group of 2 limbs per lane with both windows of column accumulators held
+// at 8 times their value (see montmul_whole_x8: no masks, the carries as multiply-adds): 11 multiply-adds and 9
+// other instructions per step where pairmul_core has 9 and 16. A column of the second window takes 3 products
+// per step for 2 steps (or 2, one of them doubled), which 8 times over still fits 64 bits; with 3 limbs per
+// lane it would not. Same result as pairmul_core, bit for bit.
+template <int T, bool SQ>
+__device__ __forceinline__ void pairmul_whole_x8(u32 (&out0)[2], u32 (&out1)[2], const u32 (&a0)[2], const u32 (&a1)[2],
+                                                 const u32 (&b0)[2], const u32 (&b1)[2], const u32 (&n)[2], u32 n0inv,
+                                                 const Grp<T>& g) {
+  static_assert(Grp<T>::kWhole, "one integer per wavefront");
+  constexpr int LPT = 2;
+  const u32 eight = opaque_eight();
+  // multiplicands times 2, multipliers times 4; a squaring forms 2 x0 x1 as (4 x0) (4 x1)
+  u32 a0s[LPT], a1s[LPT], b0q[LPT], b1q[LPT];
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) {
+    a0s[j] = a0[j] << 1;
+    a1s[j] = a1[j] << 1;
+    b0q[j] = b0[j] << 2;
+    b1q[j] = b1[j] << 2;
+  }
+  u64 A[LPT] = {0, 0}, B[LPT] = {0, 0};
+  if (g.k == 0) B[0] = 8;
+  u32 first = (g.k == 0) ? 1u : 0u;
+  asm volatile("" : "+v"(first));  // keeps the term below one multiply-add
+#pragma unroll 4
+  for (int o = 0; o < T; ++o) {
+    static_for<0, LPT>([&](auto rc) {
+      constexpr int r = decltype(rc)::value;
+      const u32 b0i = (u32)__builtin_amdgcn_readlane((int)b0q[r], o);
+      const u32 b1i = (u32)__builtin_amdgcn_readlane((int)b1q[r], o);
+      A[0] = mad64(a0s[0], b0i, A[0]);
+      const u32 qav = (u32)A[0] * n0inv;  // 8 q on the lowest lane, exactly
+      const u32 qa = g.bcast0(qav);
+      A[1] = mad64(a0s[1], b0i, A[1]);
+      if (SQ) {
+        B[0] = mad64(b0q[0], b1i, B[0]);
+      } else {
+        B[0] = mad64(a0s[0], b1i, B[0]);
+        B[0] = mad64(a1s[0], b0i, B[0]);
+      }
+      B[0] = mad64(qav ^ (LIMB_MASK << 3), first, B[0]);  // 8 (2^29 - 1 - q) on the lowest lane
+      const u32 qb = g.bcast0((u32)B[0] * n0inv);
+      if (SQ) {
+        B[1] = mad64(b0q[1], b1i, B[1]);
+      } else {
+        B[1] = mad64(a0s[1], b1i, B[1]);
+        B[1] = mad64(a1s[1], b0i, B[1]);
+      }
+      const u64 ta = mad64(qa, n[0], A[0]);
+      const u64 tb = mad64(qb, n[0], B[0]);
+      const u32 recv_a = g.from_upper_raw((u32)ta);
+      const u32 recv_b = g.from_upper_raw((u32)tb);
+      A[0] = mad64((u32)(ta >> 32), eight, mad64(qa, n[1], A[1]));
+      B[0] = mad64((u32)(tb >> 32), eight, mad64(qb, n[1], B[1]));
+      A[1] = (u64)recv_a;
+      B[1] = (u64)recv_b;
+    });
+  }
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) {
+    A[j] >>= 3;
+    B[j] >>= 3;
+  }
+  // from here on as in pairmul_core: B holds (x0 y1 + x1 y0 - m) / R + 1 modulo n, add n - 1
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) B[j] += (u64)n[j];
+  B[0] -= (u64)first;
+  hi_normalise<LPT, T>(A, g, eight);
+  hi_normalise<LPT, T>(B, g, eight);
+  u64 ca = 0, cb = 0;
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) {
+    const u64 va = A[j] + ca, vb = B[j] + cb;
+    out0[j] = (u32)va & LIMB_MASK;
+    out1[j] = (u32)vb & LIMB_MASK;
+    ca = va >> LIMB_BITS;
+    cb = vb >> LIMB_BITS;
+  }
+  out0[0] += g.from_lower((u32)ca);
+  out1[0] += g.from_lower((u32)cb);
+}
+
 // (out0, out1) = (a0, a1) * (b0, b1) / R modulo n^2, b in registers (out may alias a and b)
 template <int LPT, int T>
 __device__ __forceinline__ void pairmul(u32 (&out0)[LPT], u32 (&out1)[LPT], const u32 (&a0)[LPT], const u32 (&a1)[LPT],
                                         const u32 (&b0)[LPT], const u32 (&b1)[LPT], const u32 (&n)[LPT], u32 n0inv,
                                         const Grp<T>& g) {
-  BRegs2<LPT, T> src = {b0, b1};
-  pairmul_core<LPT, T, BRegs2<LPT, T>, false>(out0, out1, a0, a1, src, n, n0inv, g);
+  if constexpr (Grp<T>::kWhole && LPT == 2) {
+    pairmul_whole_x8<T, false>(out0, out1, a0, a1, b0, b1, n, n0inv, g);
+  } else {
+    BRegs2<LPT, T> src = {b0, b1};
+    pairmul_core<LPT, T, BRegs2<LPT, T>, false>(out0, out1, a0, a1, src, n, n0inv, g);
+  }
 }
 // b = 2 NL limbs at `bmem` ([b0][b1]), the same array for every lane of the group
 template <int LPT, int T>
@@ -558,7 +645,9 @@ __device__ __forceinline__ void pairmul_mem(u32 (&out0)[LPT], u32 (&out1)[LPT], 
 template <int LPT, int T>
 __device__ __forceinline__ void pairsqr(u32 (&out0)[LPT], u32 (&out1)[LPT], const u32 (&a0)[LPT], const u32 (&a1)[LPT],
                                         const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
-  if constexpr (Grp<T>::kWhole) {
+  if constexpr (Grp<T>::kWhole && LPT == 2) {
+    pairmul_whole_x8<T, true>(out0, out1, a0, a1, a0, a1, n, n0inv, g);
+  } else if constexpr (Grp<T>::kWhole) {
     // a lone wavefront pays for every instruction of a step: double x1 once, not limb by limb as it is read
     u32 a1d[LPT];
 #pragma unroll
