@@ -737,6 +737,32 @@ def test_random_operator_mixes(api):
         pub.close()
 
 
+@pytest.mark.parametrize("bits,counts", [(1024, (512, 513, 1024, 1025, 1500, 2048, 2049)), (2048, (512, 513, 1500, 2049)),
+                                         (4096, (1024, 1025))])
+def test_batch_sizes_around_the_geometry_switches(api, bits, counts):
+    """Batch sizes on both sides of the points where a launch changes the lanes it gives a big integer
+    (a wavefront each up to one or two elements per SIMD, then twice the lanes of the modulus, then its own
+    geometry): both encryption routes agree, sampled ciphertexts match the oracle, decryption returns
+    the plaintexts."""
+    own, sk = context(api, bits)
+    pk = sk.public
+    n = pk.n
+    lp = bits // 32
+    pub = api.haflo_ctx_create_public(n, bits)
+    rng = random.Random(bits)
+    for count in counts:
+        say("geometry switch", bits, count)
+        ms = [rng.randrange(n) for _ in range(count)]
+        rs = [rng.randrange(1, n) for _ in range(count)]
+        c = api.haflo_encrypt(pub, ints_to_dev(ms, lp), ints_to_dev(rs, lp))
+        assert torch.equal(c, api.haflo_encrypt(own, ints_to_dev(ms, lp), ints_to_dev(rs, lp)))
+        idx = sorted({0, count - 1, count // 2, max(0, count - 2)})
+        got = dev_to_ints(api.haflo_export_cipher(pub, c[torch.tensor(idx, device="cuda")].contiguous()))
+        assert got == [O.encrypt(pk, ms[i], rs[i]) for i in idx]
+        assert dev_to_ints(api.haflo_decrypt(own, c)) == ms
+    pub.close()
+
+
 def test_benchmark_workload_shape(api):
     """The step the benchmark times, at its size and launch configuration (2048-bit key, 65536 x 32,
     public-key encryption): sampled ciphertexts through encrypt -> add -> scalar_mul against the
