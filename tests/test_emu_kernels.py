@@ -377,7 +377,9 @@ def test_bucket_matvec_digit_boundaries(env, force_buckets, top):
 @pytest.mark.parametrize("bits", [1024, 2048, 4096])
 def test_wider_lane_groups(emu, bits):
     """The 4-, 8- and 16-lane geometries (1024/2048/4096-bit keys) on a few elements: Montgomery
-    form, addition, inverse and a short power, i.e. every cross-lane primitive."""
+    form and addition in the modulus's own lanes; the inverse and a short power, which a batch this
+    small runs with one integer per wavefront (single residues at 1024 bits, pairs from 2048 bits on,
+    with the accumulators of the 2- and 3-limb lanes held at 8 times their value)."""
     lib = emu
     p, q = oracle_key(bits)
     sk = O.PrivateKey(p, q)
