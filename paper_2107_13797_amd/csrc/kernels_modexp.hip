@@ -172,15 +172,15 @@ __global__ __launch_bounds__(kBlockThreads) void k_enc_crt(ModRef MP2, ModRef MQ
   }
 }
 
-// A batch that leaves most of the chip idle is latency-bound. Up to one element per SIMD (two where a launch
-// holds a single job), each gets a wavefront to itself (a few limbs per lane: the shortest steps); beyond that, while twice the lanes still
+// A batch that leaves most of the chip idle is latency-bound. Up to two chains per SIMD, each gets a
+// wavefront to itself (a few limbs per lane: the shortest steps); beyond that, while twice the lanes still
 // are at most two wavefronts per SIMD, its integers are spread over twice the lanes (9 limbs each), which
 // shortens every product of the chain at 1.2 times the instructions. `jobs`: independent halves of one launch.
 // `nine`: take 9 limbs per lane (twice the lanes per integer) also for a batch that fills the chip.
 int engine_geo(const haflo_ctx* ctx, size_t count, const ModHost& m, int jobs = 1, bool nine = false) {
-  // one chain per SIMD; a single job still gains with two (measured: 2048 encryptions at a 1024-bit key 4.4 ms
-  // against 5.2 ms at nine limbs per lane; three per SIMD lose, and so do two with two jobs each)
-  if (haflo_has_wave_geometry(m) && count * (size_t)jobs <= (size_t)ctx->num_cu * 4 * (jobs == 1 ? 2 : 1)) return kGeoWave;
+  // up to two chains per SIMD (measured: 2048 encryptions at a 1024-bit key 4.4 ms against 5.2 ms at nine limbs
+  // per lane, 1024 decryptions 0.91 against 1.37 ms; three per SIMD no longer gain)
+  if (haflo_has_wave_geometry(m) && count * (size_t)jobs <= (size_t)ctx->num_cu * 4 * 2) return kGeoWave;
   if (m.lpt == 18 && m.t < 16 && (nine || count * (size_t)jobs * (size_t)m.t <= (size_t)ctx->num_cu * 256)) return kGeoWide;
   return kGeoPlain;
 }
