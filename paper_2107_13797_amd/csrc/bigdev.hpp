@@ -86,6 +86,15 @@ struct Grp {
     if (T == 8) x = __builtin_amdgcn_update_dpp(x, x, 0x114 /* row_shr:4 */, 0xf, 0xA, false);
     return (u32)x;
   }
+  // bcast0(v & m) with the mask `m` (in a vector register) riding on the first DPP move of the broadcast
+  __device__ __forceinline__ u32 bcast0_masked(u32 v, u32 m) const {
+    if (T == 1 || kWhole) return bcast0(v & m);
+    int x = (int)v;
+    if (T == 16) return (u32)__builtin_amdgcn_update_dpp(0, x, 0x150 /* row_newbcast:0 */, 0xf, 0xf, true) & m;
+    x = (int)((u32)__builtin_amdgcn_update_dpp(0, x, T == 2 ? 0xA0 /* quad_perm:[0,0,2,2] */ : 0x00 /* [0,0,0,0] */, 0xf, 0xf, true) & m);
+    if (T == 8) x = __builtin_amdgcn_update_dpp(x, x, 0x114 /* row_shr:4 */, 0xf, 0xA, false);
+    return (u32)x;
+  }
   // v of the next-higher lane; 0 past the end of the 16-lane row (of the wavefront for a whole-wavefront
   // group). The top lane of a group that is not at a row end sees lane 0 of the next group.
   __device__ __forceinline__ u32 from_upper_raw(u32 v) const {
@@ -254,7 +263,7 @@ __device__ __forceinline__ void montmul_core(u32 (&out)[LPT], const u32 (&a)[LPT
       // vector form)
       u32 q;
       if constexpr (Grp<T>::kWhole) q = g.bcast0(((u32)A[0] * n0inv) & maskv);
-      else q = g.bcast0(((u32)A[0] * n0inv) & LIMB_MASK);
+      else q = g.bcast0_masked((u32)A[0] * n0inv, maskv);
       static_for<1, LPT>(product);
       u64 t0 = mad64(q, n[0], A[0]);
       // the low 29 bits go to the lane below (0 on lane 0 of every group, by the choice of q); masked after
@@ -481,8 +490,8 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
         else if constexpr (w == 2) A[j] = mad64(a0[j], b0i2, A[j]);
       };
       product_a(std::integral_constant<int, 0>{});
-      const u32 qav = ((u32)A[0] * n0inv) & (Grp<T>::kWhole ? maskv : LIMB_MASK);
-      const u32 qa = g.bcast0(qav);
+      const u32 qav = Grp<T>::kWhole ? ((u32)A[0] * n0inv) & maskv : 0u;  // used by whole-wavefront groups only
+      const u32 qa = Grp<T>::kWhole ? g.bcast0(qav) : g.bcast0_masked((u32)A[0] * n0inv, maskv);
       static_for<1, LPT>(product_a);
       // window B: a0 * b1 + a1 * b0, minus the quotient digit of A on the lowest column of the integer
       B[0] = mad64(a0[0], b1x, B[0]);
@@ -490,7 +499,7 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
       // only the lowest lane's term counts, and that lane's own digit is the broadcast one: a whole-wavefront
       // group takes it from the vector register, so that no scalar instruction waits on the broadcast
       B[0] = mad64(Grp<T>::kWhole ? (qav ^ maskv) : LIMB_MASK - qa, first, B[0]);
-      const u32 qb = g.bcast0(((u32)B[0] * n0inv) & (Grp<T>::kWhole ? maskv : LIMB_MASK));
+      const u32 qb = g.bcast0_masked((u32)B[0] * n0inv, maskv);
 #pragma unroll
       for (int j = 1; j < LPT; ++j) {
         B[j] = mad64(a0[j], b1x, B[j]);
