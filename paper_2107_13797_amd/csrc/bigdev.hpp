@@ -455,7 +455,7 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
   // A lone wavefront is bound by its instruction count: hide that `first` is 0 or 1, so that the term it
   // selects stays one multiply-add instead of a move, a select and a 64-bit add. Where several wavefronts
   // share a SIMD the multiply-adds are the bottleneck and the compiler's three cheap instructions are right.
-  if constexpr (Grp<T>::kWhole) asm volatile("" : "+v"(first));
+  if constexpr (T > 1) asm volatile("" : "+v"(first));
   constexpr int D = BSrc::kAhead;
   constexpr int RING = D > 0 ? D : 1;
   static_assert(LPT % RING == 0, "ring size");
@@ -656,8 +656,8 @@ __device__ __forceinline__ void pairsqr(u32 (&out0)[LPT], u32 (&out1)[LPT], cons
                                         const u32 (&n)[LPT], u32 n0inv, const Grp<T>& g) {
   if constexpr (Grp<T>::kWhole && LPT == 2) {
     pairmul_whole_x8<T, true>(out0, out1, a0, a1, a0, a1, n, n0inv, g);
-  } else if constexpr (Grp<T>::kWhole) {
-    // a lone wavefront pays for every instruction of a step: double x1 once, not limb by limb as it is read
+  } else if constexpr (T > 1) {
+    // double x1 once, not limb by limb as it is read
     u32 a1d[LPT];
 #pragma unroll
     for (int j = 0; j < LPT; ++j) a1d[j] = a1[j] + a1[j];
