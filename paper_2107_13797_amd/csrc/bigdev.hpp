@@ -452,9 +452,9 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
   }
   if (g.k == 0) B[0] = 1;
   u32 first = (g.k == 0) ? 1u : 0u;  // the lane that holds the lowest column of the whole integer
-  // A lone wavefront is bound by its instruction count: hide that `first` is 0 or 1, so that the term it
-  // selects stays one multiply-add instead of a move, a select and a 64-bit add. Where several wavefronts
-  // share a SIMD the multiply-adds are the bottleneck and the compiler's three cheap instructions are right.
+  // Hide that `first` is 0 or 1, so that the term it selects stays one multiply-add instead of a move, a
+  // select and a 64-bit add: these kernels are bound by vector issue slots, one per instruction whatever it
+  // is, at one wavefront per SIMD and at four alike (measured on both).
   if constexpr (T > 1) asm volatile("" : "+v"(first));
   constexpr int D = BSrc::kAhead;
   constexpr int RING = D > 0 ? D : 1;
