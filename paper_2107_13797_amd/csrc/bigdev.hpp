@@ -459,6 +459,13 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
     B[j] = 0;
   }
   if (g.k == 0) B[0] = 1;
+  // a squaring doubles x0 once as the multiplicand of its doubled products, instead of the broadcast limb per step
+  constexpr bool kDoubledA0 = SQ && T > 1 && !Grp<T>::kWhole;
+  [[maybe_unused]] u32 a0d[LPT];
+  if constexpr (kDoubledA0) {
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) a0d[j] = a0[j] + a0[j];
+  }
   u32 first = (g.k == 0) ? 1u : 0u;  // the lane that holds the lowest column of the whole integer
   // Hide that `first` is 0 or 1, so that the term it selects stays one multiply-add instead of a move, a
   // select and a 64-bit add: these kernels are bound by vector issue slots, one per instruction whatever it
@@ -488,14 +495,14 @@ __device__ __forceinline__ void pairmul_core(u32 (&out0)[LPT], u32 (&out1)[LPT],
         b0i = bsrc.limb0(o, r, g);
         b1i = bsrc.limb1(o, r, g);
       }
-      [[maybe_unused]] const u32 b0i2 = SQ ? b0i + b0i : b0i;
+      [[maybe_unused]] const u32 b0i2 = (SQ && !kDoubledA0) ? b0i + b0i : b0i;
       const u32 b1x = (SQ && !B1X2) ? b1i + b1i : b1i;  // squaring: 2 x0 x1 as x0 times the doubled limb of x1
       // window A: a0 * b0 (for a squaring the products sq_weight selects)
       auto product_a = [&](auto jc) {
         constexpr int j = decltype(jc)::value;
         constexpr int w = SQ ? sq_weight(LPT, j, r) : 1;
         if constexpr (w == 1) A[j] = mad64(a0[j], b0i, A[j]);
-        else if constexpr (w == 2) A[j] = mad64(a0[j], b0i2, A[j]);
+        else if constexpr (w == 2) A[j] = kDoubledA0 ? mad64(a0d[j], b0i, A[j]) : mad64(a0[j], b0i2, A[j]);
       };
       product_a(std::integral_constant<int, 0>{});
       const u32 qav = Grp<T>::kWhole ? ((u32)A[0] * n0inv) & maskv : 0u;  // used by whole-wavefront groups only
